@@ -1,0 +1,123 @@
+/*
+ * rattn.h - C ABI of librattn: the RAttention token-mixing layer on one MI355X (gfx950).
+ *
+ * The layer (paper Sec. 3.1-3.2) maps shared q/k/v to
+ *     o_t = RMS_s(x^s_t) + RMS_r(x^r_t)
+ * where x^s is sliding-window softmax attention over the last `window` keys (Sec. 2.1)
+ * and x^r = phi(q_t) S_{t-window} is residual linear attention over every older key
+ * (Eq. 4), S_t = sum_{s<=t} phi(k_s)^T v_s, phi = softmax over the head features, with
+ * group-query sharing of k/v (Sec. 3.1) and separate per-head RMS gains (Sec. 3.2).
+ *
+ * Conventions
+ *  - Positions are 0-based.  `window` = W >= 1 counts the keys the softmax branch sees
+ *    INCLUDING the current one: query t attends keys max(0,t-W+1)..t and the linear
+ *    branch covers keys 0..t-W.  The paper's symbol is w = W-1.  W >= T leaves the
+ *    linear branch empty (its output and RMS are exactly 0) = causal attention.
+ *  - Layer tensors are contiguous [B, T, H, D], D fastest.  Query head h reads KV head
+ *    h / (Hq/Hkv).  D is 64 or 128.
+ *  - dtype is the element type of q,k,v,o,dO,dq,dk,dv (and of the decode ring buffers).
+ *    Accumulators, linear-attention states, softmax/RMS statistics and gains are fp32.
+ *  - Every pointer is a DEVICE pointer unless stated otherwise.  The caller owns all
+ *    buffers; the library never allocates, frees or synchronises.  All work is enqueued
+ *    on `stream` (a hipStream_t passed as void*; NULL = the default stream).  Outputs are
+ *    overwritten, never accumulated into.
+ *  - Errors: every call returns a rattn_status; arguments are validated on the host
+ *    before anything is launched, so a failed call has launched nothing.
+ *    rattn_last_error() returns a thread-local human-readable detail string.
+ *  - Results are deterministic for fixed inputs and parameters (no floating-point atomics).
+ */
+#ifndef RATTN_H
+#define RATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  RATTN_OK = 0,
+  RATTN_ERR_INVALID_ARG = -1,   /* NULL pointer, non-positive size, Hq % Hkv != 0, eps <= 0 ... */
+  RATTN_ERR_UNSUPPORTED = -2,   /* D not in {64,128}, unknown dtype                             */
+  RATTN_ERR_WORKSPACE = -3,     /* workspace_bytes smaller than rattn_workspace_bytes reports   */
+  RATTN_ERR_HIP = -4            /* a HIP launch failed; detail in rattn_last_error()            */
+} rattn_status;
+
+typedef enum { RATTN_F32 = 0, RATTN_BF16 = 1 } rattn_dtype;
+
+typedef struct {
+  int32_t B, T, Hq, Hkv, D;
+  int32_t window;        /* W >= 1 (see conventions)                                                   */
+  int32_t chunk;         /* linear-branch chunk hint for Eqs. 2-3 (0 = library chooses); the result
+                            does not depend on it beyond rounding                                      */
+  int32_t dtype;         /* rattn_dtype                                                                */
+  float softmax_scale;   /* multiplies q.k in the softmax branch only (the paper's formula is 1.0)     */
+  float rms_eps;         /* > 0                                                                        */
+  int32_t save_for_bwd;  /* rattn_fwd also fills `saved` (needed by rattn_bwd)                         */
+} rattn_params;
+
+/* Sizes in bytes of the scratch `workspace` rattn_fwd / rattn_bwd need and of the opaque
+ * `saved` buffer rattn_fwd fills for rattn_bwd.  Any of the three out pointers (HOST) may
+ * be NULL.  Sizes depend on every field of *p except save_for_bwd. */
+rattn_status rattn_workspace_bytes(const rattn_params* p, size_t* fwd_bytes, size_t* bwd_bytes,
+                                   size_t* saved_bytes);
+
+/* Forward of the layer (Sec. 2.1 softmax branch, Eqs. 2-4 linear branch in chunkwise form
+ * with phi computed in-kernel, Sec. 3.2 combination).
+ *   q [B,T,Hq,D]; k,v [B,T,Hkv,D]; o [B,T,Hq,D]
+ *   gamma_swa, gamma_rla: fp32 [Hq,D] RMS gains of the two branches, NULL = all ones
+ *   saved: opaque, saved_bytes large, written iff p->save_for_bwd (else may be NULL);
+ *          holds the pre-norm branch outputs and the softmax / RMS row statistics
+ *   workspace: fwd_bytes of scratch (16-byte aligned), contents undefined on return */
+rattn_status rattn_fwd(const rattn_params* p, const void* q, const void* k, const void* v,
+                       const float* gamma_swa, const float* gamma_rla, void* o, void* saved,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward of the layer: gradients of sum(o * dO) w.r.t. q, k, v and the gains.
+ * Derived from Sec. 2.1, Eq. 4 and Sec. 3.2 (the linear-branch state gradients are the
+ * reverse-time counterpart of Eqs. 2-3; chunk states are recomputed, not saved).
+ *   saved: as written by rattn_fwd with the same params and inputs
+ *   dq [B,T,Hq,D]; dk,dv [B,T,Hkv,D] (summed over the query heads of each group)
+ *   dgamma_swa, dgamma_rla: fp32 [Hq,D], each may be NULL (then not computed) */
+rattn_status rattn_bwd(const rattn_params* p, const void* q, const void* k, const void* v,
+                       const float* gamma_swa, const float* gamma_rla, const void* saved,
+                       const void* dO, void* dq, void* dk, void* dv, float* dgamma_swa,
+                       float* dgamma_rla, void* workspace, size_t workspace_bytes, void* stream);
+
+typedef struct {
+  int32_t N;             /* sequences in the batch                                   */
+  int32_t Hq, Hkv, D;
+  int32_t window;        /* W >= 1: ring capacity in tokens                          */
+  int32_t dtype;         /* of q, k_new, v_new, rings, o                             */
+  float softmax_scale;
+  float rms_eps;
+} rattn_decode_params;
+
+/* One generated token per sequence with constant memory (Sec. 2.1: a cache of the last W
+ * keys; Sec. 2.2: a fixed D x D state; Eq. 4).  For sequence n with pos[n] = p:
+ *   1. if p >= W the key/value leaving the window (token p-W, stored in slot p % W) is
+ *      folded into the state: state += phi(k_old)^T v_old;
+ *   2. slot p % W of the rings is overwritten with (k_new, v_new);
+ *   3. x^s = softmax attention of each query head over the min(p+1, W) valid slots,
+ *      x^r = phi(q) state, o = RMS_s(x^s) + RMS_r(x^r).
+ *   q [N,Hq,D]; k_new,v_new [N,Hkv,D]; pos int32 [N] (device), 0-based index of the new
+ *   token, >= 0; k_ring,v_ring [N,Hkv,W,D] updated in place, token s lives in slot s % W;
+ *   state fp32 [N,Hkv,D,D] (row = feature of phi(k), column = value feature), updated in
+ *   place; o [N,Hq,D].  No workspace. */
+rattn_status rattn_decode_step(const rattn_decode_params* p, const void* q, const void* k_new,
+                               const void* v_new, const int32_t* pos, void* k_ring, void* v_ring,
+                               float* state, const float* gamma_swa, const float* gamma_rla,
+                               void* o, void* stream);
+
+/* Static description of a status code. */
+const char* rattn_status_string(rattn_status s);
+/* Detail of the last failure on the calling thread ("" if none). HOST string, library-owned. */
+const char* rattn_last_error(void);
+/* Library version, e.g. "0.1". */
+const char* rattn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RATTN_H */

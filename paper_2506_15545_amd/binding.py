@@ -1,0 +1,188 @@
+"""ctypes binding of librattn.so: same entry-point names as include/rattn.h.
+
+Only argument marshalling happens here (shape checks, buffer allocation through torch,
+raw device pointers, the current HIP stream).  Every arithmetic step of the layer runs in
+the library's kernels; there is no fallback: a missing library raises.
+"""
+import ctypes
+import os
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "librattn.so")
+
+RATTN_F32, RATTN_BF16 = 0, 1
+_DTYPES = {torch.float32: RATTN_F32, torch.bfloat16: RATTN_BF16}
+
+EXPORTS = ["rattn_workspace_bytes", "rattn_fwd", "rattn_bwd", "rattn_decode_step",
+           "rattn_status_string", "rattn_last_error", "rattn_version"]
+
+
+class RattnParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("T", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+                ("D", ctypes.c_int32), ("window", ctypes.c_int32), ("chunk", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("rms_eps", ctypes.c_float),
+                ("save_for_bwd", ctypes.c_int32)]
+
+
+class RattnDecodeParams(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("D", ctypes.c_int32),
+                ("window", ctypes.c_int32), ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+                ("rms_eps", ctypes.c_float)]
+
+
+class RattnError(RuntimeError):
+    def __init__(self, status, detail):
+        super().__init__(f"librattn status {status}: {detail}")
+        self.status = status
+        self.detail = detail
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (python -m paper_2506_15545_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, sz = ctypes.c_void_p, ctypes.c_size_t
+    L.rattn_workspace_bytes.restype = ctypes.c_int
+    L.rattn_workspace_bytes.argtypes = [ctypes.POINTER(RattnParams)] + [ctypes.POINTER(sz)] * 3
+    L.rattn_fwd.restype = ctypes.c_int
+    L.rattn_fwd.argtypes = [ctypes.POINTER(RattnParams)] + [vp] * 8 + [sz, vp]
+    L.rattn_bwd.restype = ctypes.c_int
+    L.rattn_bwd.argtypes = [ctypes.POINTER(RattnParams)] + [vp] * 13 + [sz, vp]
+    L.rattn_decode_step.restype = ctypes.c_int
+    L.rattn_decode_step.argtypes = [ctypes.POINTER(RattnDecodeParams)] + [vp] * 11
+    L.rattn_status_string.restype = ctypes.c_char_p
+    L.rattn_status_string.argtypes = [ctypes.c_int]
+    L.rattn_last_error.restype = ctypes.c_char_p
+    L.rattn_version.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def _check(status):
+    if status != 0:
+        raise RattnError(status, lib().rattn_last_error().decode())
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_params(q, k, window, chunk=0, softmax_scale=1.0, rms_eps=1e-6, save_for_bwd=False):
+    B, T, Hq, D = q.shape
+    return RattnParams(B, T, Hq, k.shape[2], D, window, chunk, _DTYPES[q.dtype], softmax_scale, rms_eps,
+                       1 if save_for_bwd else 0)
+
+
+def rattn_workspace_bytes(params):
+    """(fwd_bytes, bwd_bytes, saved_bytes) for a RattnParams."""
+    f, b, s = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib().rattn_workspace_bytes(ctypes.byref(params), ctypes.byref(f), ctypes.byref(b), ctypes.byref(s)))
+    return f.value, b.value, s.value
+
+
+def _check_layer(q, k, v):
+    for name, t in (("q", q), ("k", k), ("v", v)):
+        if not (t.is_cuda and t.is_contiguous() and t.dim() == 4):
+            raise ValueError(f"{name} must be a contiguous 4-d device tensor [B,T,H,D]")
+    if k.shape != v.shape or k.shape[0] != q.shape[0] or k.shape[1] != q.shape[1] or k.shape[3] != q.shape[3]:
+        raise ValueError("q/k/v shapes do not match")
+    if q.dtype not in _DTYPES or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v must share dtype float32 or bfloat16")
+
+
+def _gain(g, Hq, D, dev):
+    if g is None:
+        return None
+    g = g.to(device=dev, dtype=torch.float32).contiguous()
+    if g.shape != (Hq, D):
+        raise ValueError("gains must be [Hq, D]")
+    return g
+
+
+def _bytes(n, dev):
+    return torch.empty(max(int(n), 16), dtype=torch.uint8, device=dev)
+
+
+def rattn_fwd(q, k, v, window, gamma_swa=None, gamma_rla=None, chunk=0, softmax_scale=1.0, rms_eps=1e-6,
+              save_for_bwd=False, out=None, saved=None, workspace=None):
+    """o = RMS(SWA(q,k,v)) + RMS(RLA(q,k,v)); returns o, or (o, saved) when save_for_bwd.
+
+    out / saved / workspace may be passed in to reuse buffers (uint8 tensors for the latter two)."""
+    _check_layer(q, k, v)
+    p = make_params(q, k, window, chunk, softmax_scale, rms_eps, save_for_bwd)
+    fwd_b, _, saved_b = rattn_workspace_bytes(p)
+    dev = q.device
+    o = torch.empty_like(q) if out is None else out
+    ws = _bytes(fwd_b, dev) if workspace is None else workspace
+    sv = None
+    if save_for_bwd:
+        sv = _bytes(saved_b, dev) if saved is None else saved
+    gs = _gain(gamma_swa, q.shape[2], q.shape[3], dev)
+    gr = _gain(gamma_rla, q.shape[2], q.shape[3], dev)
+    _check(lib().rattn_fwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(gs), _ptr(gr), _ptr(o), _ptr(sv),
+                           _ptr(ws), ws.numel(), _stream()))
+    return (o, sv) if save_for_bwd else o
+
+
+def rattn_bwd(q, k, v, saved, dO, window, gamma_swa=None, gamma_rla=None, chunk=0, softmax_scale=1.0,
+              rms_eps=1e-6, want_dgamma=True, workspace=None, out=None):
+    """(dq, dk, dv, dgamma_swa, dgamma_rla) for upstream gradient dO; `saved` from rattn_fwd."""
+    _check_layer(q, k, v)
+    if dO.shape != q.shape or dO.dtype != q.dtype or not dO.is_contiguous():
+        raise ValueError("dO must match q")
+    p = make_params(q, k, window, chunk, softmax_scale, rms_eps, True)
+    _, bwd_b, saved_b = rattn_workspace_bytes(p)
+    if saved is None or saved.numel() < saved_b:
+        raise ValueError("saved buffer missing or too small")
+    dev = q.device
+    ws = _bytes(bwd_b, dev) if workspace is None else workspace
+    if out is None:
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    else:
+        dq, dk, dv = out
+    dgs = dgr = None
+    if want_dgamma:
+        dgs = torch.empty(q.shape[2], q.shape[3], dtype=torch.float32, device=dev)
+        dgr = torch.empty_like(dgs)
+    gs = _gain(gamma_swa, q.shape[2], q.shape[3], dev)
+    gr = _gain(gamma_rla, q.shape[2], q.shape[3], dev)
+    _check(lib().rattn_bwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(gs), _ptr(gr), _ptr(saved), _ptr(dO),
+                           _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dgs), _ptr(dgr), _ptr(ws), ws.numel(), _stream()))
+    return dq, dk, dv, dgs, dgr
+
+
+def rattn_decode_step(q, k_new, v_new, pos, k_ring, v_ring, state, gamma_swa=None, gamma_rla=None,
+                      softmax_scale=1.0, rms_eps=1e-6, out=None):
+    """One decode step; k_ring, v_ring, state are updated in place; returns o [N,Hq,D]."""
+    N, Hq, D = q.shape
+    Hkv, W = k_ring.shape[1], k_ring.shape[2]
+    for name, t in (("q", q), ("k_new", k_new), ("v_new", v_new), ("k_ring", k_ring), ("v_ring", v_ring),
+                    ("state", state), ("pos", pos)):
+        if not (t.is_cuda and t.is_contiguous()):
+            raise ValueError(f"{name} must be a contiguous device tensor")
+    if k_new.shape != (N, Hkv, D) or v_new.shape != (N, Hkv, D) or k_ring.shape != (N, Hkv, W, D) \
+            or v_ring.shape != k_ring.shape or state.shape != (N, Hkv, D, D) or pos.shape != (N,):
+        raise ValueError("decode tensor shapes do not match")
+    if state.dtype != torch.float32 or pos.dtype != torch.int32:
+        raise ValueError("state must be float32 and pos int32")
+    if q.dtype not in _DTYPES or any(t.dtype != q.dtype for t in (k_new, v_new, k_ring, v_ring)):
+        raise ValueError("q, k_new, v_new and the rings must share dtype float32 or bfloat16")
+    p = RattnDecodeParams(N, Hq, Hkv, D, W, _DTYPES[q.dtype], softmax_scale, rms_eps)
+    o = torch.empty_like(q) if out is None else out
+    gs = _gain(gamma_swa, Hq, D, q.device)
+    gr = _gain(gamma_rla, Hq, D, q.device)
+    _check(lib().rattn_decode_step(ctypes.byref(p), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(pos), _ptr(k_ring),
+                                   _ptr(v_ring), _ptr(state), _ptr(gs), _ptr(gr), _ptr(o), _stream()))
+    return o

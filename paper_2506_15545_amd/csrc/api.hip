@@ -1,0 +1,211 @@
+// C ABI of librattn: argument validation, workspace layout, path selection, launches.
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "kernels.hpp"
+#include "rattn.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+rattn_status fail(rattn_status s, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return s;
+}
+
+inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+struct Layout {
+  rattn::LayerDims dm;
+  size_t esize;
+  // saved
+  size_t sv_xs, sv_xr, sv_lse, sv_rs, sv_rr, saved_bytes;
+  // generic forward / backward workspace
+  size_t gf_states, gen_fwd_bytes;
+  size_t gb_states, gb_rstates, gb_dxs, gb_dxr, gb_delta, gb_dgpart, gen_bwd_bytes;
+  int RB;
+  size_t fwd_bytes, bwd_bytes;
+};
+
+rattn_status make_layout(const rattn_params* p, Layout* L) {
+  if (!p) return fail(RATTN_ERR_INVALID_ARG, "params is NULL");
+  if (p->B < 1 || p->T < 1 || p->Hq < 1 || p->Hkv < 1)
+    return fail(RATTN_ERR_INVALID_ARG, "B, T, Hq, Hkv must be >= 1 (got %d, %d, %d, %d)", p->B, p->T, p->Hq, p->Hkv);
+  if (p->Hq % p->Hkv != 0)
+    return fail(RATTN_ERR_INVALID_ARG, "Hq (%d) must be a multiple of Hkv (%d)", p->Hq, p->Hkv);
+  if (p->B > 65535 || p->Hq > 65535)
+    return fail(RATTN_ERR_UNSUPPORTED, "B and Hq must be <= 65535 (got %d, %d)", p->B, p->Hq);
+  if (p->D != 64 && p->D != 128) return fail(RATTN_ERR_UNSUPPORTED, "head_dim D must be 64 or 128 (got %d)", p->D);
+  if (p->window < 1) return fail(RATTN_ERR_INVALID_ARG, "window must be >= 1 (got %d)", p->window);
+  if (p->chunk < 0) return fail(RATTN_ERR_INVALID_ARG, "chunk must be >= 0 (got %d)", p->chunk);
+  if (p->dtype != RATTN_F32 && p->dtype != RATTN_BF16) return fail(RATTN_ERR_UNSUPPORTED, "unknown dtype %d", p->dtype);
+  if (!(p->rms_eps > 0.f)) return fail(RATTN_ERR_INVALID_ARG, "rms_eps must be > 0");
+  if (!(p->softmax_scale == p->softmax_scale) || p->softmax_scale == 0.f)
+    return fail(RATTN_ERR_INVALID_ARG, "softmax_scale must be a non-zero number");
+  if ((long long)p->B * p->T >= (1ll << 31) / 4 || (long long)p->B * p->T * p->Hq * p->D >= (1ll << 40))
+    return fail(RATTN_ERR_UNSUPPORTED, "tensor too large for 32-bit row indexing");
+
+  rattn::LayerDims& dm = L->dm;
+  dm.B = p->B; dm.T = p->T; dm.Hq = p->Hq; dm.Hkv = p->Hkv; dm.D = p->D;
+  dm.W = p->window; dm.G = p->Hq / p->Hkv;
+  dm.C = p->chunk > 0 ? p->chunk : 64;
+  const int Tp = p->T > p->window ? p->T - p->window : 0;
+  dm.nst = Tp > 0 ? (Tp - 1) / dm.C + 1 : 0;
+  dm.scale = p->softmax_scale; dm.eps = p->rms_eps;
+  L->esize = p->dtype == RATTN_F32 ? 4 : 2;
+
+  const size_t nq = (size_t)dm.B * dm.T * dm.Hq * dm.D;
+  const size_t nrow = (size_t)dm.B * dm.Hq * dm.T;
+  size_t off = 0;
+  L->sv_xs = off; off += align_up(nq * L->esize);
+  L->sv_xr = off; off += align_up(nq * L->esize);
+  L->sv_lse = off; off += align_up(nrow * 4);
+  L->sv_rs = off; off += align_up(nrow * 4);
+  L->sv_rr = off; off += align_up(nrow * 4);
+  L->saved_bytes = off;
+
+  const size_t nstate = (size_t)dm.B * dm.Hkv * dm.nst * dm.D * dm.D;
+  L->gf_states = 0;
+  L->gen_fwd_bytes = align_up(nstate * 4);
+
+  const long long rows = (long long)dm.B * dm.T;
+  L->RB = (int)(rows / 4 < 1 ? 1 : (rows / 4 > 256 ? 256 : rows / 4));
+  off = 0;
+  L->gb_states = off; off += align_up(nstate * 4);
+  L->gb_rstates = off; off += align_up(nstate * 4);
+  L->gb_dxs = off; off += align_up(nq * 4);
+  L->gb_dxr = off; off += align_up(nq * 4);
+  L->gb_delta = off; off += align_up(nrow * 4);
+  L->gb_dgpart = off; off += align_up((size_t)2 * L->RB * dm.Hq * dm.D * 4);
+  L->gen_bwd_bytes = off;
+
+  L->fwd_bytes = L->gen_fwd_bytes;
+  L->bwd_bytes = L->gen_bwd_bytes;
+  return RATTN_OK;
+}
+
+rattn::SavedPtrs saved_views(const Layout& L, void* saved) {
+  rattn::SavedPtrs sv = {nullptr, nullptr, nullptr, nullptr, nullptr};
+  if (saved) {
+    char* s = (char*)saved;
+    sv.xs = s + L.sv_xs; sv.xr = s + L.sv_xr;
+    sv.lse = (float*)(s + L.sv_lse); sv.rs = (float*)(s + L.sv_rs); sv.rr = (float*)(s + L.sv_rr);
+  }
+  return sv;
+}
+
+rattn_status check_launch(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(RATTN_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+  return RATTN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* rattn_status_string(rattn_status s) {
+  switch (s) {
+    case RATTN_OK: return "ok";
+    case RATTN_ERR_INVALID_ARG: return "invalid argument";
+    case RATTN_ERR_UNSUPPORTED: return "unsupported configuration";
+    case RATTN_ERR_WORKSPACE: return "workspace too small";
+    case RATTN_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+const char* rattn_last_error(void) { return g_err; }
+const char* rattn_version(void) { return "0.1"; }
+
+rattn_status rattn_workspace_bytes(const rattn_params* p, size_t* fwd_bytes, size_t* bwd_bytes, size_t* saved_bytes) {
+  Layout L;
+  rattn_status s = make_layout(p, &L);
+  if (s != RATTN_OK) return s;
+  if (fwd_bytes) *fwd_bytes = L.fwd_bytes;
+  if (bwd_bytes) *bwd_bytes = L.bwd_bytes;
+  if (saved_bytes) *saved_bytes = L.saved_bytes;
+  return RATTN_OK;
+}
+
+rattn_status rattn_fwd(const rattn_params* p, const void* q, const void* k, const void* v, const float* gamma_swa,
+                       const float* gamma_rla, void* o, void* saved, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+  Layout L;
+  rattn_status s = make_layout(p, &L);
+  if (s != RATTN_OK) return s;
+  if (!q || !k || !v || !o) return fail(RATTN_ERR_INVALID_ARG, "q, k, v, o must be non-NULL");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(saved) || !aligned16(workspace))
+    return fail(RATTN_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+  if (p->save_for_bwd && !saved) return fail(RATTN_ERR_INVALID_ARG, "save_for_bwd set but saved is NULL");
+  if (L.fwd_bytes > 0 && (!workspace || workspace_bytes < L.fwd_bytes))
+    return fail(RATTN_ERR_WORKSPACE, "forward needs %zu workspace bytes, got %zu", L.fwd_bytes, workspace_bytes);
+  hipStream_t st = (hipStream_t)stream;
+  rattn::SavedPtrs sv = saved_views(L, p->save_for_bwd ? saved : nullptr);
+  rattn::generic_fwd(L.dm, p->dtype, q, k, v, gamma_swa, gamma_rla, o, sv, (float*)((char*)workspace + L.gf_states), st);
+  return check_launch("rattn_fwd");
+}
+
+rattn_status rattn_bwd(const rattn_params* p, const void* q, const void* k, const void* v, const float* gamma_swa,
+                       const float* gamma_rla, const void* saved, const void* dO, void* dq, void* dk, void* dv,
+                       float* dgamma_swa, float* dgamma_rla, void* workspace, size_t workspace_bytes, void* stream) {
+  Layout L;
+  rattn_status s = make_layout(p, &L);
+  if (s != RATTN_OK) return s;
+  if (!q || !k || !v || !saved || !dO || !dq || !dk || !dv)
+    return fail(RATTN_ERR_INVALID_ARG, "q, k, v, saved, dO, dq, dk, dv must be non-NULL");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(saved) || !aligned16(dO) || !aligned16(dq) ||
+      !aligned16(dk) || !aligned16(dv) || !aligned16(workspace))
+    return fail(RATTN_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+  if (!workspace || workspace_bytes < L.bwd_bytes)
+    return fail(RATTN_ERR_WORKSPACE, "backward needs %zu workspace bytes, got %zu", L.bwd_bytes, workspace_bytes);
+  hipStream_t st = (hipStream_t)stream;
+  rattn::SavedPtrs sv = saved_views(L, const_cast<void*>(saved));
+  char* w = (char*)workspace;
+  rattn::GenericBwdWs ws;
+  ws.states = (float*)(w + L.gb_states); ws.rstates = (float*)(w + L.gb_rstates);
+  ws.dxs = (float*)(w + L.gb_dxs); ws.dxr = (float*)(w + L.gb_dxr);
+  ws.delta = (float*)(w + L.gb_delta); ws.dgpart = (float*)(w + L.gb_dgpart);
+  ws.RB = L.RB;
+  rattn::generic_bwd(L.dm, p->dtype, q, k, v, gamma_swa, gamma_rla, sv, dO, dq, dk, dv, dgamma_swa, dgamma_rla, ws, st);
+  return check_launch("rattn_bwd");
+}
+
+rattn_status rattn_decode_step(const rattn_decode_params* p, const void* q, const void* k_new, const void* v_new,
+                               const int32_t* pos, void* k_ring, void* v_ring, float* state, const float* gamma_swa,
+                               const float* gamma_rla, void* o, void* stream) {
+  if (!p) return fail(RATTN_ERR_INVALID_ARG, "params is NULL");
+  if (p->N < 1 || p->Hq < 1 || p->Hkv < 1)
+    return fail(RATTN_ERR_INVALID_ARG, "N, Hq, Hkv must be >= 1 (got %d, %d, %d)", p->N, p->Hq, p->Hkv);
+  if (p->Hq % p->Hkv != 0)
+    return fail(RATTN_ERR_INVALID_ARG, "Hq (%d) must be a multiple of Hkv (%d)", p->Hq, p->Hkv);
+  if (p->D != 64 && p->D != 128) return fail(RATTN_ERR_UNSUPPORTED, "head_dim D must be 64 or 128 (got %d)", p->D);
+  if (p->window < 1) return fail(RATTN_ERR_INVALID_ARG, "window must be >= 1 (got %d)", p->window);
+  if (p->dtype != RATTN_F32 && p->dtype != RATTN_BF16) return fail(RATTN_ERR_UNSUPPORTED, "unknown dtype %d", p->dtype);
+  if (!(p->rms_eps > 0.f)) return fail(RATTN_ERR_INVALID_ARG, "rms_eps must be > 0");
+  if (!(p->softmax_scale == p->softmax_scale) || p->softmax_scale == 0.f)
+    return fail(RATTN_ERR_INVALID_ARG, "softmax_scale must be a non-zero number");
+  if (p->N > 65535) return fail(RATTN_ERR_UNSUPPORTED, "N must be <= 65535 (got %d)", p->N);
+  if ((long long)p->N * p->Hkv * p->window * p->D >= (1ll << 40))
+    return fail(RATTN_ERR_UNSUPPORTED, "ring buffers too large");
+  if (!q || !k_new || !v_new || !pos || !k_ring || !v_ring || !state || !o)
+    return fail(RATTN_ERR_INVALID_ARG, "q, k_new, v_new, pos, k_ring, v_ring, state, o must be non-NULL");
+  if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(k_ring) || !aligned16(v_ring) ||
+      !aligned16(state) || !aligned16(o))
+    return fail(RATTN_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+  rattn::DecodeDims dd;
+  dd.N = p->N; dd.Hq = p->Hq; dd.Hkv = p->Hkv; dd.D = p->D; dd.W = p->window; dd.G = p->Hq / p->Hkv;
+  dd.scale = p->softmax_scale; dd.eps = p->rms_eps;
+  rattn::decode_step(dd, p->dtype, q, k_new, v_new, pos, k_ring, v_ring, state, gamma_swa, gamma_rla, o,
+                     (hipStream_t)stream);
+  return check_launch("rattn_decode_step");
+}
+
+}  // extern "C"

@@ -1,0 +1,49 @@
+// Host-side declarations shared by the C ABI (api.hip) and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace rattn {
+
+struct LayerDims {
+  int B, T, Hq, Hkv, D, W, C, G;
+  int nst;  // number of chunk states per (batch, kv head): ceil(max(T-W,0) / C)
+  float scale, eps;
+};
+
+// views into the opaque `saved` buffer: pre-norm branch outputs (I/O dtype, [B,T,Hq,D]) and the
+// row statistics (fp32, [B,Hq,T]): log-sum-exp of the softmax branch and the two RMS reciprocals
+struct SavedPtrs {
+  void* xs;
+  void* xr;
+  float* lse;
+  float* rs;
+  float* rr;
+};
+
+struct GenericBwdWs {
+  float* states;   // [B,Hkv,nst,D,D]
+  float* rstates;  // [B,Hkv,nst,D,D]
+  float* dxs;      // [B,T,Hq,D]
+  float* dxr;      // [B,T,Hq,D]
+  float* delta;    // [B,Hq,T]
+  float* dgpart;   // [2,RB,Hq,D]
+  int RB;
+};
+
+void generic_fwd(const LayerDims& dm, int dtype, const void* q, const void* k, const void* v, const float* gs,
+                 const float* gr, void* o, const SavedPtrs& sv, float* states, hipStream_t st);
+void generic_bwd(const LayerDims& dm, int dtype, const void* q, const void* k, const void* v, const float* gs,
+                 const float* gr, const SavedPtrs& sv, const void* dO, void* dq, void* dk, void* dv, float* dgs,
+                 float* dgr, const GenericBwdWs& ws, hipStream_t st);
+
+struct DecodeDims {
+  int N, Hq, Hkv, D, W, G;
+  float scale, eps;
+};
+void decode_step(const DecodeDims& dd, int dtype, const void* q, const void* k_new, const void* v_new,
+                 const int32_t* pos, void* k_ring, void* v_ring, float* state, const float* gs, const float* gr,
+                 void* o, hipStream_t st);
+
+}  // namespace rattn

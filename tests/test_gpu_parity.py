@@ -1,0 +1,179 @@
+"""GPU parity: librattn (through the C ABI binding) against the fp64 oracle, element by element,
+on seeded synthetic inputs.  Tolerances: max-abs 1e-4 for fp32 tensors and 2e-2 for bf16 tensors,
+relative to unit-scale outputs (outputs are RMS-normalised; gradients are divided by the RMS of
+the oracle gradient)."""
+import math
+import numpy as np
+import pytest
+import torch
+
+from oracle import rattn_oracle as orc
+from paper_2506_15545_amd import binding as rb
+from paper_2506_15545_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def np64(t):
+    return t.detach().cpu().to(torch.float64).numpy()
+
+
+def dev(t):
+    return None if t is None else t.cuda()
+
+
+def maxerr(got, ref):
+    return float(np.max(np.abs(np64(got) - ref)))
+
+
+def rel_rms_err(got, ref):
+    rms = math.sqrt(float(np.mean(ref ** 2))) + 1e-30
+    return float(np.max(np.abs(np64(got) - ref))) / rms
+
+
+def run_fwd_case(B, T, Hq, Hkv, D, W, dtype, seed, chunk=0, scale=None, gains=False, std=1.0, eps=1e-6):
+    x = synth.make_random_layer(B, T, Hq, Hkv, D, dtype, seed, std=std, with_gains=gains)
+    scale = 1.0 / math.sqrt(D) if scale is None else scale
+    gs, gr = x.get("gamma_swa"), x.get("gamma_rla")
+    print(f"fwd case B={B} T={T} Hq={Hq} Hkv={Hkv} D={D} W={W} {dtype} chunk={chunk} seed={seed}", flush=True)
+    o = rb.rattn_fwd(dev(x["q"]), dev(x["k"]), dev(x["v"]), W, dev(gs), dev(gr), chunk=chunk, softmax_scale=scale,
+                     rms_eps=eps)
+    torch.cuda.synchronize()
+    ref = orc.fwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), W, scale=scale, eps=eps,
+                        gamma_swa=None if gs is None else np64(gs), gamma_rla=None if gr is None else np64(gr))
+    # gains scale the output; keep the bar relative to unit-scale rows
+    gmax = 1.0 if gs is None else max(float(gs.abs().max()), float(gr.abs().max()), 1.0)
+    err = maxerr(o, ref["o"])
+    assert err <= TOL[dtype] * gmax, f"max abs err {err}"
+    return err
+
+
+def test_config1_tiny_f32_against_explicit_loops():
+    cfg = synth.CONFIGS["tiny_f32"]
+    q, k, v = synth.make_layer_inputs(cfg)
+    o = rb.rattn_fwd(q.cuda(), k.cuda(), v.cuda(), cfg.W, chunk=cfg.chunk, softmax_scale=cfg.scale)
+    ref = orc.fwd_loops(np64(q), np64(k), np64(v), cfg.W, scale=cfg.scale)
+    assert maxerr(o, ref["o"]) <= 1e-4
+
+
+@pytest.mark.parametrize("B,T,Hq,Hkv,D,W,chunk", [
+    (1, 1, 1, 1, 64, 1, 0),          # single token
+    (2, 77, 4, 2, 64, 5, 0),         # ragged T, small window, GQA 2
+    (1, 130, 3, 1, 128, 33, 16),     # GQA 3, window not a multiple of anything
+    (1, 200, 2, 2, 128, 64, 64),     # window = chunk
+    (1, 150, 2, 1, 64, 1, 7),        # window 1 (softmax over the token itself), odd chunk
+    (1, 96, 2, 2, 64, 96, 0),        # window = T: linear branch empty
+    (1, 96, 2, 2, 64, 500, 0),       # window > T
+    (2, 300, 4, 4, 128, 100, 100),   # long intra-chunk part (> 64 keys)
+])
+def test_fwd_f32_shapes(B, T, Hq, Hkv, D, W, chunk):
+    run_fwd_case(B, T, Hq, Hkv, D, W, "f32", seed=100 + T, chunk=chunk, gains=True)
+
+
+def test_fwd_f32_paper_formula_scale_one():
+    run_fwd_case(1, 120, 2, 1, 64, 16, "f32", seed=5, scale=1.0, std=0.125)
+
+
+@pytest.mark.parametrize("B,T,Hq,Hkv,D,W", [
+    (1, 200, 4, 2, 128, 48),
+    (2, 333, 2, 1, 64, 20),
+    (1, 256, 2, 2, 128, 256),
+])
+def test_fwd_bf16_shapes(B, T, Hq, Hkv, D, W):
+    run_fwd_case(B, T, Hq, Hkv, D, W, "bf16", seed=200 + T, gains=True)
+
+
+def test_chunk_hint_does_not_change_result():
+    x = synth.make_random_layer(1, 180, 2, 1, 64, "f32", 7)
+    outs = [rb.rattn_fwd(dev(x["q"]), dev(x["k"]), dev(x["v"]), 20, chunk=c, softmax_scale=0.125) for c in (0, 16, 33, 128)]
+    for o in outs[1:]:
+        assert float((o - outs[0]).abs().max()) < 2e-5
+
+
+def run_bwd_case(B, T, Hq, Hkv, D, W, dtype, seed, chunk=0, gains=True):
+    x = synth.make_random_layer(B, T, Hq, Hkv, D, dtype, seed, with_dO=True, with_gains=gains)
+    scale = 1.0 / math.sqrt(D)
+    gs, gr = x.get("gamma_swa"), x.get("gamma_rla")
+    print(f"bwd case B={B} T={T} Hq={Hq} Hkv={Hkv} D={D} W={W} {dtype} chunk={chunk} seed={seed}", flush=True)
+    q, k, v, dO = dev(x["q"]), dev(x["k"]), dev(x["v"]), dev(x["dO"])
+    o, saved = rb.rattn_fwd(q, k, v, W, dev(gs), dev(gr), chunk=chunk, softmax_scale=scale, save_for_bwd=True)
+    dq, dk, dv, dgs, dgr = rb.rattn_bwd(q, k, v, saved, dO, W, dev(gs), dev(gr), chunk=chunk, softmax_scale=scale)
+    torch.cuda.synchronize()
+    ref = orc.bwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), np64(x["dO"]), W, scale=scale,
+                        gamma_swa=None if gs is None else np64(gs), gamma_rla=None if gr is None else np64(gr))
+    tol = TOL[dtype]
+    for name, got in (("dq", dq), ("dk", dk), ("dv", dv), ("dgamma_swa", dgs), ("dgamma_rla", dgr)):
+        if np.all(ref[name] == 0):
+            assert float(got.abs().max()) == 0.0, name
+            continue
+        e = rel_rms_err(got, ref[name])
+        assert e <= tol, f"{name}: rel err {e}"
+
+
+@pytest.mark.parametrize("B,T,Hq,Hkv,D,W,chunk", [
+    (1, 1, 1, 1, 64, 1, 0),
+    (2, 77, 4, 2, 64, 5, 0),
+    (1, 130, 3, 1, 128, 33, 16),
+    (1, 150, 2, 1, 64, 1, 7),
+    (1, 96, 2, 2, 64, 96, 0),
+    (1, 260, 2, 2, 128, 70, 100),
+])
+def test_bwd_f32_shapes(B, T, Hq, Hkv, D, W, chunk):
+    run_bwd_case(B, T, Hq, Hkv, D, W, "f32", seed=300 + T, chunk=chunk)
+
+
+def test_bwd_config1_tiny_f32():
+    cfg = synth.CONFIGS["tiny_f32"]
+    q, k, v, dO = synth.make_layer_inputs(cfg, with_dO=True)
+    o, saved = rb.rattn_fwd(q.cuda(), k.cuda(), v.cuda(), cfg.W, chunk=cfg.chunk, softmax_scale=cfg.scale, save_for_bwd=True)
+    dq, dk, dv, _, _ = rb.rattn_bwd(q.cuda(), k.cuda(), v.cuda(), saved, dO.cuda(), cfg.W, chunk=cfg.chunk,
+                                    softmax_scale=cfg.scale)
+    ref = orc.bwd_dense(np64(q), np64(k), np64(v), np64(dO), cfg.W, scale=cfg.scale)
+    for name, got in (("dq", dq), ("dk", dk), ("dv", dv)):
+        assert rel_rms_err(got, ref[name]) <= 1e-4, name
+
+
+@pytest.mark.parametrize("B,T,Hq,Hkv,D,W", [(1, 200, 4, 2, 128, 48), (2, 140, 2, 1, 64, 20)])
+def test_bwd_bf16_shapes(B, T, Hq, Hkv, D, W):
+    run_bwd_case(B, T, Hq, Hkv, D, W, "bf16", seed=400 + T)
+
+
+# ------------------------------------------------------------------------------ decode
+@pytest.mark.parametrize("dtype,D,Hq,Hkv,W,T", [("f32", 64, 4, 2, 8, 30), ("f32", 128, 3, 1, 5, 12),
+                                                 ("bf16", 128, 8, 2, 16, 40), ("f32", 64, 6, 1, 50, 20)])
+def test_decode_chain_reproduces_forward(dtype, D, Hq, Hkv, W, T):
+    N = 3
+    x = synth.make_random_layer(N, T, Hq, Hkv, D, dtype, 500 + T, with_gains=True)
+    scale = 1.0 / math.sqrt(D)
+    gs, gr = x["gamma_swa"], x["gamma_rla"]
+    ref = orc.fwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), W, scale=scale, gamma_swa=np64(gs), gamma_rla=np64(gr))["o"]
+    dt = synth.torch_dtype(dtype)
+    kr = torch.zeros(N, Hkv, W, D, dtype=dt, device="cuda"); vr = torch.zeros_like(kr)
+    S = torch.zeros(N, Hkv, D, D, dtype=torch.float32, device="cuda")
+    q, k, v = dev(x["q"]), dev(x["k"]), dev(x["v"])
+    gmax = max(float(gs.abs().max()), float(gr.abs().max()), 1.0)
+    for t in range(T):
+        pos = torch.full((N,), t, dtype=torch.int32, device="cuda")
+        o = rb.rattn_decode_step(q[:, t].contiguous(), k[:, t].contiguous(), v[:, t].contiguous(), pos, kr, vr, S,
+                                 dev(gs), dev(gr), softmax_scale=scale)
+        assert maxerr(o, ref[:, t]) <= TOL[dtype] * gmax, f"step {t}"
+        assert torch.equal(kr[:, :, t % W], k[:, t])
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_decode_step_random_positions(dtype):
+    cfg = synth.DECODE_CONFIGS["decode_b128_w512"]
+    cfg = synth.DecodeConfig("small", 6, 8, 2, 128, 64, dtype, 11, 0, 300, cfg.scale)
+    pos = [0, 5, 63, 64, 65, 300]       # before the ring fills, at the edge, after
+    x = synth.make_decode_inputs(cfg, pos=pos)
+    o_ref, kr_ref, vr_ref, S_ref = orc.decode_step(np64(x["q"]), np64(x["k_new"]), np64(x["v_new"]), pos,
+                                                   np64(x["k_ring"]), np64(x["v_ring"]), np64(x["state"]), cfg.W,
+                                                   scale=cfg.scale)
+    d = {k_: v_.cuda() for k_, v_ in x.items()}
+    o = rb.rattn_decode_step(d["q"], d["k_new"], d["v_new"], d["pos"], d["k_ring"], d["v_ring"], d["state"],
+                             softmax_scale=cfg.scale)
+    assert maxerr(o, o_ref) <= TOL[dtype]
+    assert np.array_equal(np64(d["k_ring"]), kr_ref) and np.array_equal(np64(d["v_ring"]), vr_ref)
+    assert float(np.max(np.abs(np64(d["state"]) - S_ref))) <= 1e-5 * max(1.0, float(np.abs(S_ref).max()))
