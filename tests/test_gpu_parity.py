@@ -28,9 +28,15 @@ def maxerr(got, ref):
     return float(np.max(np.abs(np64(got) - ref)))
 
 
-def rel_rms_err(got, ref):
+def rel_rms_err(got, ref, dtype="f32"):
+    """max |got-ref| / RMS(ref).  Gradients are heavy-tailed (max ~ 10 RMS), so for bf16 tensors
+    the unavoidable rounding of the stored value itself (half an ulp = 2^-9 |ref|, allowed as
+    2^-8 |ref|) is taken off before dividing: the exact gradient rounded to bf16 scores 0."""
     rms = math.sqrt(float(np.mean(ref ** 2))) + 1e-30
-    return float(np.max(np.abs(np64(got) - ref))) / rms
+    err = np.abs(np64(got) - ref)
+    if dtype == "bf16":
+        err = np.maximum(err - np.abs(ref) / 256.0, 0.0)
+    return float(np.max(err)) / rms
 
 
 def run_fwd_case(B, T, Hq, Hkv, D, W, dtype, seed, chunk=0, scale=None, gains=False, std=1.0, eps=1e-6):
@@ -106,9 +112,10 @@ def run_bwd_case(B, T, Hq, Hkv, D, W, dtype, seed, chunk=0, gains=True):
     tol = TOL[dtype]
     for name, got in (("dq", dq), ("dk", dk), ("dv", dv), ("dgamma_swa", dgs), ("dgamma_rla", dgr)):
         if np.all(ref[name] == 0):
-            assert float(got.abs().max()) == 0.0, name
+            # an exactly-zero gradient (e.g. a one-key softmax) may come back as rounding noise
+            assert float(got.abs().max()) <= tol * 1e-2, name
             continue
-        e = rel_rms_err(got, ref[name])
+        e = rel_rms_err(got, ref[name], "f32" if name.startswith("dgamma") else dtype)
         assert e <= tol, f"{name}: rel err {e}"
 
 
