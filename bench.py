@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused SWA+RLA layer on one MI355X.
+
+A step = rattn_fwd (saving for backward) + rattn_bwd on the 3B-scale layer
+(B=4, Hq=24, Hkv=8, T=4096, D=128, W=512, bf16), inputs resident in HBM.  `value` is the
+algorithmic TFLOP/s of fwd+bwd: exact in-window (t,s) pairs plus the chunked linear-attention
+products at nominal chunk 64, no recomputation and no masked-tile waste counted.
+Prints ONE JSON line (see the design doc for the field definitions).
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA = 2.5e15     # dense bf16 MFMA FLOP/s, MI355X
+PEAK_FP32_VALU = 157.3e12   # fp32 vector FLOP/s
+PEAK_HBM = 8.0e12           # bytes/s
+NOMINAL_CHUNK = 64
+
+
+def swa_pairs(T, W):
+    return W * T - W * (W - 1) // 2 if W <= T else T * (T + 1) // 2
+
+
+def layer_flops(B, T, Hq, Hkv, D, W, C=NOMINAL_CHUNK):
+    """Algorithmic FLOPs of the layer, split by the kernels' responsibilities."""
+    P = swa_pairs(T, W)
+    Tp = max(T - W, 0)
+    f = {}
+    f["fwd_swa"] = B * Hq * 4 * D * P
+    f["fwd_rla_out"] = B * Hq * (2 * Tp * D * D + 4 * D * Tp * (C + 1) // 2)
+    f["fwd_state"] = B * Hkv * 2 * Tp * D * D
+    f["bwd_swa"] = B * Hq * 10 * D * P
+    f["bwd_rla_q"] = B * Hq * (4 * Tp * D * D + 10 * D * Tp * (C + 1) // 2)
+    f["bwd_rla_kv"] = B * Hkv * 4 * Tp * D * D
+    f["fwd"] = f["fwd_swa"] + f["fwd_rla_out"] + f["fwd_state"]
+    f["bwd"] = f["bwd_swa"] + f["bwd_rla_q"] + f["bwd_rla_kv"]
+    return f
+
+
+def kernel_algorithmic_flops(name, fl):
+    """Algorithmic FLOPs one launch of a named kernel is responsible for (None = not a contraction)."""
+    table = {
+        "gen_fwd_kernel": fl["fwd_swa"] + fl["fwd_rla_out"],
+        "gen_scan_kernel": fl["fwd_state"],
+        "gen_bwd_dq_kernel": 0.4 * fl["bwd_swa"] + 0.5 * fl["bwd_rla_q"],
+        "gen_bwd_dkv_kernel": 0.6 * fl["bwd_swa"] + 0.5 * fl["bwd_rla_q"] + 0.5 * fl["bwd_rla_kv"],
+        "fwd_fused_kernel": fl["fwd_swa"] + fl["fwd_rla_out"],
+        "rla_state_kernel": fl["fwd_state"],
+        "bwd_dq_kernel": 0.4 * fl["bwd_swa"] + 0.5 * fl["bwd_rla_q"],
+        "bwd_dkv_kernel": 0.6 * fl["bwd_swa"] + 0.5 * fl["bwd_rla_q"] + 0.5 * fl["bwd_rla_kv"],
+    }
+    return table.get(name)
+
+
+def decode_bytes(N, Hkv, Hq, D, W, esize, nvalid_sum=None):
+    ring = 2 * N * Hkv * W * D * esize if nvalid_sum is None else 2 * nvalid_sum * Hkv * D * esize
+    state = 2 * N * Hkv * D * D * 4
+    vec = N * (2 * Hq + 4 * Hkv) * D * esize  # q, o, k_new, v_new, ring slot write
+    return ring + state + vec
+
+
+def cpu_baseline(cfg, heads):
+    """The fp64 oracle, as it stands, on a bounded sample: fwd+bwd of `heads` query heads of batch 0
+    over the full sequence (heads are independent, so FLOP/s carries over to the whole tensor)."""
+    import numpy as np
+    import torch
+    from oracle import rattn_oracle as orc
+    from paper_2506_15545_amd import synth
+    q, k, v, dO = synth.make_layer_inputs(cfg, with_dO=True, B=1)
+    f64 = lambda t: t.to(torch.float64).numpy()
+    q, k, v, dO = f64(q), f64(k), f64(v), f64(dO)
+    t0 = time.perf_counter()
+    orc.fwd_dense(q, k, v, cfg.W, scale=cfg.scale, heads=heads, batches=[0])
+    orc.bwd_dense(q, k, v, dO, cfg.W, scale=cfg.scale, heads=heads, batches=[0])
+    dt = time.perf_counter() - t0
+    fl = layer_flops(1, cfg.T, len(heads), 0, cfg.D, cfg.W)
+    flops = fl["fwd"] + fl["bwd"]
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"fp64 numpy oracle fwd+bwd, {len(heads)} query head(s) of batch 0, full T={cfg.T}, "
+                      f"{dt:.1f} s wall", "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--cpu-heads", type=int, default=3)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2506_15545_amd import binding as rb, synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    rb.lib()
+    torch.cuda.set_device(0)
+
+    cfg = synth.CONFIGS["layer3b_t4096_w512"]
+    q, k, v, dO = (t.cuda() for t in synth.make_layer_inputs(cfg, with_dO=True))
+    p = rb.make_params(q, k, cfg.W, 0, cfg.scale, 1e-6, True)
+    fwd_b, bwd_b, saved_b = rb.rattn_workspace_bytes(p)
+    ws = torch.empty(max(fwd_b, bwd_b, 16), dtype=torch.uint8, device="cuda")
+    saved = torch.empty(saved_b, dtype=torch.uint8, device="cuda")
+    o = torch.empty_like(q)
+    grads = (torch.empty_like(q), torch.empty_like(k), torch.empty_like(v))
+
+    def step():
+        rb.rattn_fwd(q, k, v, cfg.W, softmax_scale=cfg.scale, save_for_bwd=True, out=o, saved=saved, workspace=ws)
+        rb.rattn_bwd(q, k, v, saved, dO, cfg.W, softmax_scale=cfg.scale, want_dgamma=False, workspace=ws, out=grads)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    rb.rattn_profile_enable(True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    recs = rb.rattn_profile_records()
+    rb.rattn_profile_enable(False)
+
+    fl = layer_flops(cfg.B, cfg.T, cfg.Hq, cfg.Hkv, cfg.D, cfg.W)
+    total = fl["fwd"] + fl["bwd"]
+    value = total / (ms_per_step * 1e-3) / 1e12
+
+    # per-kernel averages from the library's own HIP events (recorded on the launch stream)
+    agg = {}
+    for name, ms in recs:
+        a = agg.setdefault(name, [0.0, 0])
+        a[0] += ms; a[1] += 1
+    kernels = {n: {"avg_ms": s / c, "launches_per_step": c / args.steps} for n, (s, c) in agg.items()}
+    dom = max(kernels, key=lambda n: kernels[n]["avg_ms"] * kernels[n]["launches_per_step"])
+    dom_fl = kernel_algorithmic_flops(dom, fl)
+    mfma_path = not dom.startswith("gen_")
+    peak = PEAK_BF16_MFMA if mfma_path else PEAK_FP32_VALU
+    achieved = (dom_fl or 0.0) / (kernels[dom]["avg_ms"] * 1e-3)
+    roofline = {"bound": "mfma" if mfma_path else "alu", "kernel": dom, "achieved": achieved / 1e12,
+                "peak": peak / 1e12, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                "avg_ms": kernels[dom]["avg_ms"]}
+    fwd_ms = sum(kernels[n]["avg_ms"] * kernels[n]["launches_per_step"] for n in kernels
+                 if "bwd" not in n and n not in ("gen_scan_kernel(x2)",))
+    bwd_ms = sum(kernels[n]["avg_ms"] * kernels[n]["launches_per_step"] for n in kernels) - fwd_ms
+
+    out = {
+        "metric": "fused SWA+RLA fwd+bwd TFLOP/s & % MFMA peak @T=4096,w=512,d=128",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "T": cfg.T, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "D": cfg.D,
+                   "W": cfg.W, "step": "rattn_fwd(save_for_bwd)+rattn_bwd"},
+        "frac_mfma_peak": value * 1e12 / PEAK_BF16_MFMA,
+        "tokens_per_s": cfg.B * cfg.T / (ms_per_step * 1e-3),
+        "fwd": {"ms": fwd_ms, "tflops": fl["fwd"] / (fwd_ms * 1e-3) / 1e12,
+                "frac_mfma_peak": fl["fwd"] / (fwd_ms * 1e-3) / PEAK_BF16_MFMA},
+        "bwd": {"ms": bwd_ms, "tflops": fl["bwd"] / (bwd_ms * 1e-3) / 1e12,
+                "frac_mfma_peak": fl["bwd"] / (bwd_ms * 1e-3) / PEAK_BF16_MFMA},
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+
+    if not args.no_decode:
+        dcfg = synth.DECODE_CONFIGS["decode_b128_w512"]
+        d = {n: t.cuda() for n, t in synth.make_decode_inputs(dcfg).items()}
+        od = torch.empty_like(d["q"])
+        dstep = lambda: rb.rattn_decode_step(d["q"], d["k_new"], d["v_new"], d["pos"], d["k_ring"], d["v_ring"],
+                                             d["state"], softmax_scale=dcfg.scale, out=od)
+        for _ in range(5):
+            dstep()
+        torch.cuda.synchronize()
+        rb.rattn_profile_enable(True)
+        nd = 50
+        for _ in range(nd):
+            dstep()
+        torch.cuda.synchronize()
+        drecs = [ms for n, ms in rb.rattn_profile_records() if n == "decode_kernel"]
+        rb.rattn_profile_enable(False)
+        us = sum(drecs) / len(drecs) * 1e3
+        nbytes = decode_bytes(dcfg.N, dcfg.Hkv, dcfg.Hq, dcfg.D, dcfg.W, 2)
+        out["decode"] = {"workload": dcfg.name, "us_per_step": us, "algorithmic_bytes": nbytes,
+                         "achieved_GBps": nbytes / (us * 1e-6) / 1e9, "frac_hbm_peak": nbytes / (us * 1e-6) / PEAK_HBM,
+                         "tokens_per_s": dcfg.N / (us * 1e-6)}
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, list(range(args.cpu_heads)))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -110,6 +110,16 @@ rattn_status rattn_decode_step(const rattn_decode_params* p, const void* q, cons
                                float* state, const float* gamma_swa, const float* gamma_rla,
                                void* o, void* stream);
 
+/* Per-kernel timing (tracing aid; off by default).  While enabled, every kernel the library
+ * launches is bracketed by a pair of HIP events recorded on the launch stream.  Records pile up
+ * until rattn_profile_reset().  rattn_profile_get waits for record `idx` to finish and returns
+ * its kernel name (library-owned HOST string) and duration in milliseconds; it returns
+ * RATTN_ERR_INVALID_ARG for an index outside [0, rattn_profile_count()).  Not thread-safe. */
+void rattn_profile_enable(int on);
+void rattn_profile_reset(void);
+int rattn_profile_count(void);
+rattn_status rattn_profile_get(int idx, const char** name, float* ms);
+
 /* Static description of a status code. */
 const char* rattn_status_string(rattn_status s);
 /* Detail of the last failure on the calling thread ("" if none). HOST string, library-owned. */

@@ -15,7 +15,8 @@ RATTN_F32, RATTN_BF16 = 0, 1
 _DTYPES = {torch.float32: RATTN_F32, torch.bfloat16: RATTN_BF16}
 
 EXPORTS = ["rattn_workspace_bytes", "rattn_fwd", "rattn_bwd", "rattn_decode_step",
-           "rattn_status_string", "rattn_last_error", "rattn_version"]
+           "rattn_status_string", "rattn_last_error", "rattn_version",
+           "rattn_profile_enable", "rattn_profile_reset", "rattn_profile_count", "rattn_profile_get"]
 
 
 class RattnParams(ctypes.Structure):
@@ -62,6 +63,12 @@ def lib():
     L.rattn_status_string.argtypes = [ctypes.c_int]
     L.rattn_last_error.restype = ctypes.c_char_p
     L.rattn_version.restype = ctypes.c_char_p
+    L.rattn_profile_enable.restype = None
+    L.rattn_profile_enable.argtypes = [ctypes.c_int]
+    L.rattn_profile_reset.restype = None
+    L.rattn_profile_count.restype = ctypes.c_int
+    L.rattn_profile_get.restype = ctypes.c_int
+    L.rattn_profile_get.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float)]
     _lib = L
     return L
 
@@ -186,3 +193,22 @@ def rattn_decode_step(q, k_new, v_new, pos, k_ring, v_ring, state, gamma_swa=Non
     _check(lib().rattn_decode_step(ctypes.byref(p), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(pos), _ptr(k_ring),
                                    _ptr(v_ring), _ptr(state), _ptr(gs), _ptr(gr), _ptr(o), _stream()))
     return o
+
+
+def rattn_profile_enable(on):
+    lib().rattn_profile_enable(1 if on else 0)
+
+
+def rattn_profile_reset():
+    lib().rattn_profile_reset()
+
+
+def rattn_profile_records():
+    """[(kernel name, milliseconds)] of every launch since the last reset (waits for them)."""
+    L = lib()
+    out = []
+    for i in range(L.rattn_profile_count()):
+        name, ms = ctypes.c_char_p(), ctypes.c_float()
+        _check(L.rattn_profile_get(i, ctypes.byref(name), ctypes.byref(ms)))
+        out.append((name.value.decode(), ms.value))
+    return out

@@ -4,8 +4,30 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <vector>
+
 #include "kernels.hpp"
 #include "rattn.h"
+
+namespace rattn {
+namespace {
+struct ProfRec { const char* name; hipEvent_t a, b; };
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+}  // namespace
+void prof_begin(const char* name, hipStream_t st) {
+  if (!g_prof_on) return;
+  ProfRec r;
+  r.name = name;
+  if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+  hipEventRecord(r.a, st);
+  g_prof.push_back(r);
+}
+void prof_end(hipStream_t st) {
+  if (!g_prof_on || g_prof.empty()) return;
+  hipEventRecord(g_prof.back().b, st);
+}
+}  // namespace rattn
 
 namespace {
 
@@ -123,6 +145,26 @@ const char* rattn_status_string(rattn_status s) {
 }
 
 const char* rattn_last_error(void) { return g_err; }
+
+void rattn_profile_reset(void) {
+  for (auto& r : rattn::g_prof) { hipEventDestroy(r.a); hipEventDestroy(r.b); }
+  rattn::g_prof.clear();
+}
+void rattn_profile_enable(int on) {
+  rattn_profile_reset();
+  rattn::g_prof_on = on != 0;
+}
+int rattn_profile_count(void) { return (int)rattn::g_prof.size(); }
+rattn_status rattn_profile_get(int idx, const char** name, float* ms) {
+  if (idx < 0 || idx >= (int)rattn::g_prof.size()) return fail(RATTN_ERR_INVALID_ARG, "profile index %d out of range", idx);
+  const auto& r = rattn::g_prof[idx];
+  if (hipEventSynchronize(r.b) != hipSuccess) return fail(RATTN_ERR_HIP, "hipEventSynchronize failed");
+  float t = 0.f;
+  if (hipEventElapsedTime(&t, r.a, r.b) != hipSuccess) return fail(RATTN_ERR_HIP, "hipEventElapsedTime failed");
+  if (name) *name = r.name;
+  if (ms) *ms = t;
+  return RATTN_OK;
+}
 const char* rattn_version(void) { return "0.1"; }
 
 rattn_status rattn_workspace_bytes(const rattn_params* p, size_t* fwd_bytes, size_t* bwd_bytes, size_t* saved_bytes) {

@@ -8,11 +8,6 @@
 
 namespace rattn {
 
-template <typename IO, int D> struct WRow {  // one row spread over a wave, element d in lane d%64, reg d/64
-  static constexpr int EPL = D / 64;
-  float x[EPL];
-};
-
 // grid (Hkv, N), 256 threads.
 template <typename IO, int D>
 __global__ __launch_bounds__(256) void decode_kernel(const IO* __restrict__ q, const IO* __restrict__ k_new,
@@ -201,6 +196,7 @@ void decode_step(const DecodeDims& dd, int dtype, const void* q, const void* k_n
                  const int32_t* pos, void* k_ring, void* v_ring, float* state, const float* gs, const float* gr,
                  void* o, hipStream_t st) {
   dim3 grid(dd.Hkv, dd.N);
+  ProfScope ps("decode_kernel", st);
 #define RATTN_DECODE(IO, DD)                                                                                   \
   decode_kernel<IO, DD><<<grid, 256, 0, st>>>((const IO*)q, (const IO*)k_new, (const IO*)v_new, pos, (IO*)k_ring, \
                                               (IO*)v_ring, state, gs, gr, (IO*)o, dd)

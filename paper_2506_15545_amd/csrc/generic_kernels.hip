@@ -538,10 +538,13 @@ __global__ __launch_bounds__(256) void gen_bwd_dkv_kernel(const IO* __restrict__
 template <typename IO, int D>
 static void launch_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, const float* gs,
                        const float* gr, void* o, const SavedPtrs& sv, float* states, hipStream_t st) {
-  if (dm.nst > 0)
+  if (dm.nst > 0) {
+    ProfScope ps("gen_scan_kernel", st);
     gen_scan_kernel<IO, IO, D, false><<<dim3(D / 16, dm.Hkv, dm.B), 256, 0, st>>>(
         (const IO*)k, (const IO*)v, states, dm.T, dm.Hkv, 1, 0, dm.T - dm.W, dm.C, dm.nst);
+  }
   dim3 grid((dm.T + 4 * GEN_QPW - 1) / (4 * GEN_QPW), dm.Hq, dm.B);
+  ProfScope ps("gen_fwd_kernel", st);
   gen_fwd_kernel<IO, D><<<grid, 256, 0, st>>>((const IO*)q, (const IO*)k, (const IO*)v, gs, gr, states, (IO*)o,
                                               (IO*)sv.xs, (IO*)sv.xr, sv.lse, sv.rs, sv.rr, dm);
 }
@@ -550,23 +553,31 @@ template <typename IO, int D>
 static void launch_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, const float* gs,
                        const float* gr, const SavedPtrs& sv, const void* dO, void* dq, void* dk, void* dv,
                        float* dgs, float* dgr, const GenericBwdWs& ws, hipStream_t st) {
-  gen_bwd_prep_kernel<IO, D><<<dim3(ws.RB, dm.Hq), 256, 0, st>>>((const IO*)dO, (const IO*)sv.xs, (const IO*)sv.xr,
-                                                                 sv.rs, sv.rr, gs, gr, ws.dxs, ws.dxr, ws.delta,
-                                                                 ws.dgpart, dm);
+  {
+    ProfScope ps("gen_bwd_prep_kernel", st);
+    gen_bwd_prep_kernel<IO, D><<<dim3(ws.RB, dm.Hq), 256, 0, st>>>((const IO*)dO, (const IO*)sv.xs,
+                                                                   (const IO*)sv.xr, sv.rs, sv.rr, gs, gr, ws.dxs,
+                                                                   ws.dxr, ws.delta, ws.dgpart, dm);
+  }
   if (dgs || dgr) {
     const int HD = dm.Hq * D;
     gen_dgamma_reduce_kernel<<<(HD + 255) / 256, 256, 0, st>>>(ws.dgpart, dgs, dgr, ws.RB, HD);
   }
   if (dm.nst > 0) {
+    ProfScope ps("gen_scan_kernel(x2)", st);
     gen_scan_kernel<IO, IO, D, false><<<dim3(D / 16, dm.Hkv, dm.B), 256, 0, st>>>(
         (const IO*)k, (const IO*)v, ws.states, dm.T, dm.Hkv, 1, 0, dm.T - dm.W, dm.C, dm.nst);
     gen_scan_kernel<IO, float, D, true><<<dim3(D / 16, dm.Hkv, dm.B), 256, 0, st>>>(
         (const IO*)q, ws.dxr, ws.rstates, dm.T, dm.Hq, dm.G, dm.W, dm.T - dm.W, dm.C, dm.nst);
   }
   dim3 gq((dm.T + 4 * GEN_QPW - 1) / (4 * GEN_QPW), dm.Hq, dm.B);
-  gen_bwd_dq_kernel<IO, D><<<gq, 256, 0, st>>>((const IO*)q, (const IO*)k, (const IO*)v, ws.dxs, ws.dxr, ws.delta,
-                                               sv.lse, ws.states, (IO*)dq, dm);
+  {
+    ProfScope ps("gen_bwd_dq_kernel", st);
+    gen_bwd_dq_kernel<IO, D><<<gq, 256, 0, st>>>((const IO*)q, (const IO*)k, (const IO*)v, ws.dxs, ws.dxr, ws.delta,
+                                                 sv.lse, ws.states, (IO*)dq, dm);
+  }
   dim3 gk((dm.T + 4 * GEN_QPW - 1) / (4 * GEN_QPW), dm.Hkv, dm.B);
+  ProfScope ps("gen_bwd_dkv_kernel", st);
   gen_bwd_dkv_kernel<IO, D><<<gk, 256, 0, st>>>((const IO*)q, (const IO*)k, (const IO*)v, ws.dxs, ws.dxr, ws.delta,
                                                 sv.lse, ws.rstates, (IO*)dk, (IO*)dv, dm);
 }

@@ -6,6 +6,15 @@
 
 namespace rattn {
 
+// per-kernel event timing (see rattn_profile_* in rattn.h); no-ops while profiling is off
+void prof_begin(const char* name, hipStream_t st);
+void prof_end(hipStream_t st);
+struct ProfScope {
+  hipStream_t st;
+  ProfScope(const char* name, hipStream_t s) : st(s) { prof_begin(name, s); }
+  ~ProfScope() { prof_end(st); }
+};
+
 struct LayerDims {
   int B, T, Hq, Hkv, D, W, C, G;
   int nst;  // number of chunk states per (batch, kv head): ceil(max(T-W,0) / C)
