@@ -53,8 +53,16 @@ struct Layout {
   size_t gf_states, gen_fwd_bytes;
   size_t gb_states, gb_rstates, gb_dxs, gb_dxr, gb_delta, gb_dgpart, gen_bwd_bytes;
   int RB;
+  // MFMA forward workspace
+  bool fast_fwd;
+  size_t ff_u, ff_states, fast_fwd_bytes;
   size_t fwd_bytes, bwd_bytes;
 };
+
+bool force_generic() {
+  const char* e = getenv("RATTN_FORCE_GENERIC");
+  return e && e[0] && e[0] != '0';
+}
 
 rattn_status make_layout(const rattn_params* p, Layout* L) {
   if (!p) return fail(RATTN_ERR_INVALID_ARG, "params is NULL");
@@ -108,7 +116,16 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
   L->gb_dgpart = off; off += align_up((size_t)2 * L->RB * dm.Hq * dm.D * 4);
   L->gen_bwd_bytes = off;
 
-  L->fwd_bytes = L->gen_fwd_bytes;
+  L->fast_fwd = rattn::fast_fwd_supported(dm, p->dtype);
+  L->ff_u = L->ff_states = L->fast_fwd_bytes = 0;
+  if (L->fast_fwd) {
+    const rattn::FastFwdPlan pl = rattn::fast_fwd_plan(dm);
+    L->ff_u = 0;
+    L->ff_states = align_up(pl.u_bytes);
+    L->fast_fwd_bytes = L->ff_states + align_up(pl.state_bytes);
+  }
+  // the general-shape kernels stay selectable (RATTN_FORCE_GENERIC=1), so size for both
+  L->fwd_bytes = L->gen_fwd_bytes > L->fast_fwd_bytes ? L->gen_fwd_bytes : L->fast_fwd_bytes;
   L->bwd_bytes = L->gen_bwd_bytes;
   return RATTN_OK;
 }
@@ -191,7 +208,11 @@ rattn_status rattn_fwd(const rattn_params* p, const void* q, const void* k, cons
     return fail(RATTN_ERR_WORKSPACE, "forward needs %zu workspace bytes, got %zu", L.fwd_bytes, workspace_bytes);
   hipStream_t st = (hipStream_t)stream;
   rattn::SavedPtrs sv = saved_views(L, p->save_for_bwd ? saved : nullptr);
-  rattn::generic_fwd(L.dm, p->dtype, q, k, v, gamma_swa, gamma_rla, o, sv, (float*)((char*)workspace + L.gf_states), st);
+  if (L.fast_fwd && !force_generic())
+    rattn::fast_fwd(L.dm, q, k, v, gamma_swa, gamma_rla, o, sv, (float*)((char*)workspace + L.ff_u),
+                    (char*)workspace + L.ff_states, st);
+  else
+    rattn::generic_fwd(L.dm, p->dtype, q, k, v, gamma_swa, gamma_rla, o, sv, (float*)((char*)workspace + L.gf_states), st);
   return check_launch("rattn_fwd");
 }
 

@@ -1,0 +1,483 @@
+// MFMA forward of the RAttention layer for bf16, D = 128, T % 128 == 0, W % 64 == 0 (or W >= T).
+//
+// One work-group (4 waves) owns 128 consecutive queries of one head; wave w owns 32 of them.
+// Everything is computed TRANSPOSED so that a lane always owns one query (column) of the MFMA
+// results and all row statistics are lane-local (plus one exchange with lane^32):
+//   softmax branch (Sec. 2.1):  S^T = K Q^T  ->  online softmax  ->  O^T += V^T P^T
+//   linear branch (Eqs. 2-4) :  X^T = St Qf^T  +  V^T (M^T .* (Kf Qf^T)),  St = S_[j]^T (bf16, from the
+//                               state pre-pass), Qf/Kf = phi(Q)/phi(K) computed on the operand registers
+//   combination (Sec. 3.2)   :  o = gs * x_s * r_s + gr * x_r * r_r, transposed through LDS for
+//                               coalesced stores
+// K/V tiles (64 keys) stream through a double buffer in LDS with direct-to-LDS loads; the linear
+// branch runs first (its normalised result is carried as packed bf16), then the softmax branch walks
+// its key tiles from the diagonal downwards, so every row's running maximum is finite from the start.
+#include "common.hpp"
+#include "kernels.hpp"
+#include "mfma.hpp"
+
+namespace rattn {
+
+namespace {
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+struct FastFwdArgs {
+  const uint16_t *q, *k, *v;
+  const float *gs, *gr;
+  uint16_t *o, *xs_out, *xr_out;
+  float *lse_out, *rs_out, *rr_out;
+  const uint16_t* states;  // [B,Hkv,nstf,128 (value d),128 (feature f)] bf16: S^T at key position base+128*i
+  int B, T, Hq, Hkv, G, W, nstf, ntile;
+  float scale_log2, eps;
+};
+
+// softmax over the 128 features of the row whose two halves sit in lanes l and l^32 (64 values each)
+__device__ __forceinline__ void phi_rows(float (&x)[64], bf16x8_t (&op)[8]) {
+  float m = x[0];
+#pragma unroll
+  for (int i = 1; i < 64; ++i) m = fmaxf(m, x[i]);
+  m = fmaxf(m, xhalf(m));
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 64; ++i) { x[i] = exp2f((x[i] - m) * LOG2E); s += x[i]; }
+  s += xhalf(s);
+  const float inv = 1.f / s;
+#pragma unroll
+  for (int i = 0; i < 64; ++i) x[i] *= inv;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) op[c] = pack_bf16x8(&x[8 * c]);
+}
+
+// Write a [128 queries x 128] bf16 tile held transposed in accumulators (lane = query column, register
+// (dt,i) = feature 32dt + 8(i/4) + 4h + i%4) to global rows of stride `row_stride`, through LDS.
+// vals[dt][i] must already be final.  All 256 threads call it; smem[0..32K) is used.
+__device__ __forceinline__ void store_tile_transposed(unsigned char* smem, const float (&vals)[4][16], uint16_t* dst,
+                                                      size_t row_stride, int w, int lane) {
+  const int r32 = lane & 31, h = lane >> 5;
+  const int row = 32 * w + r32;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      f32x4_t f = {vals[dt][4 * i4], vals[dt][4 * i4 + 1], vals[dt][4 * i4 + 2], vals[dt][4 * i4 + 3]};
+      bf16x4_t pk = __builtin_convertvector(f, bf16x4_t);
+      const int c = 4 * dt + i4;
+      *reinterpret_cast<bf16x4_t*>(smem + row * ROW_BYTES + ((c ^ (row & 15)) << 4) + 8 * h) = pk;
+    }
+  __syncthreads();
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int id = tid + 256 * i;
+    const int r = id >> 4, p = id & 15;
+    const int c = p ^ (r & 15);
+    const uint4 val = *reinterpret_cast<const uint4*>(smem + r * ROW_BYTES + (p << 4));
+    *reinterpret_cast<uint4*>(dst + (size_t)r * row_stride + c * 8) = val;
+  }
+  __syncthreads();
+}
+
+template <bool MASKED>
+__device__ __forceinline__ void swa_subtile(const unsigned char* kt, const unsigned char* vt, int ks, int ka, int myq,
+                                            int W, float scale_log2, const bf16x8_t (&qop)[8], f32x16_t (&oacc)[4],
+                                            float& m, float& l, int lane) {
+  const int r32 = lane & 31, h = lane >> 5;
+  f32x16_t s = {0};
+#pragma unroll
+  for (int dk = 0; dk < 8; ++dk) s = mfma32(lds_row_chunk(kt, 32 * ks + r32, 2 * dk + h), qop[dk], s);
+  float x[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    x[i] = s[i] * scale_log2;
+    if (MASKED) {
+      const int key = ka + 8 * (i >> 2) + 4 * h + (i & 3);
+      const bool ok = key <= myq && key > myq - W;
+      x[i] = ok ? x[i] : -INFINITY;
+    }
+  }
+  float mx = x[0];
+#pragma unroll
+  for (int i = 1; i < 16; ++i) mx = fmaxf(mx, x[i]);
+  mx = fmaxf(mx, xhalf(mx));
+  const float m_new = fmaxf(m, mx);
+  const float alpha = exp2f(m - m_new);
+  float ps = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { x[i] = exp2f(x[i] - m_new); ps += x[i]; }
+  l = l * alpha + ps;
+  m = m_new;
+  if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) oacc[dt] *= alpha;
+  }
+  bf16x8_t pop[2] = {pack_bf16x8(&x[0]), pack_bf16x8(&x[8])};
+#pragma unroll
+  for (int mf = 0; mf < 2; ++mf) {
+    const int k0 = 32 * ks + 16 * mf + 4 * h;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) oacc[dt] = mfma32(lds_tr_pair(vt, k0, k0 + 8, 32 * dt, lane), pop[mf], oacc[dt]);
+  }
+}
+
+__global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
+  __shared__ __align__(16) unsigned char smem[65536];
+  const int lane = lane_id(), w = wave_id();
+  const int r32 = lane & 31, h = lane >> 5;
+  const int T = a.T, W = a.W, Hq = a.Hq, Hkv = a.Hkv, G = a.G;
+
+  // work id: consecutive ids share a KV head (its G query heads, then the next query tile); each XCD
+  // (blockIdx % 8) gets one contiguous range of ids so K/V tiles are reused out of its own L2
+  const int total = gridDim.x;
+  const int bid = blockIdx.x;
+  int wid = (total % 8 == 0) ? (bid % 8) * (total / 8) + bid / 8 : bid;
+  const int hh = wid % G; wid /= G;
+  const int qt = wid % a.ntile; wid /= a.ntile;
+  const int g = wid % Hkv;
+  const int b = wid / Hkv;
+  const int hq = g * G + hh;
+  const int t0 = qt * 128;
+  const size_t qstride = (size_t)Hq * 128, kstride = (size_t)Hkv * 128;
+  const size_t qtile_off = ((size_t)(b * T + t0) * Hq + hq) * 128;
+  const uint16_t* kbase = a.k + ((size_t)b * T * Hkv + g) * 128;
+  const uint16_t* vbase = a.v + ((size_t)b * T * Hkv + g) * 128;
+  const int myq = t0 + 32 * w + r32;
+  const size_t stat_off = (size_t)(b * Hq + hq) * T + myq;
+
+  bf16x8_t qop[8];
+  {
+    const uint16_t* qp = a.q + qtile_off + (size_t)(32 * w + r32) * qstride + 8 * h;
+#pragma unroll
+    for (int dk = 0; dk < 8; ++dk) qop[dk] = *reinterpret_cast<const bf16x8_t*>(qp + 16 * dk);
+  }
+
+  // ------------------------------------------------------------------ linear branch
+  bf16x2_t yr[4][8];  // x_r * r_r, packed
+  float rr_val = rsqrtf(a.eps);
+  // key tile of the intra-chunk part starts at j0 = t0 - W; when W % 128 == 64 the first query tile that
+  // reaches past the window has j0 = -64: no state yet (S = 0) and only its upper 64 keys exist
+  const int j0 = t0 - W;
+  if (j0 > -128) {
+    const bool has_state = j0 >= 0;
+    bf16x8_t qfop[8];
+    {
+      float x[64];
+#pragma unroll
+      for (int dk = 0; dk < 8; ++dk) unpack_bf16x8(qop[dk], &x[8 * dk]);
+      phi_rows(x, qfop);
+    }
+    f32x16_t xr[4] = {{0}, {0}, {0}, {0}};
+    if (has_state) {
+      const uint16_t* sbase = a.states + ((size_t)(b * Hkv + g) * a.nstf + j0 / 128) * 16384;
+      tile_load_async<false, 8>(sbase, 128, smem, w * 8, lane);
+      tile_load_async<true, 4>(vbase + (size_t)j0 * kstride, kstride, smem + 32768, w * 4, lane);
+    }
+    tile_load_async<true, 4>(vbase + (size_t)(j0 + 64) * kstride, kstride, smem + 49152, w * 4, lane);
+    wait_vmem();
+    __syncthreads();
+    if (has_state) {
+#pragma unroll
+      for (int kf = 0; kf < 8; ++kf)
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+          xr[dt] = mfma32(lds_row_chunk(smem, 32 * dt + r32, 2 * kf + h), qfop[kf], xr[dt]);
+    }
+    __syncthreads();
+    if (has_state) tile_load_async<false, 4>(kbase + (size_t)j0 * kstride, kstride, smem, w * 4, lane);
+    tile_load_async<false, 4>(kbase + (size_t)(j0 + 64) * kstride, kstride, smem + 16384, w * 4, lane);
+    wait_vmem();
+    __syncthreads();
+    for (int u = has_state ? 0 : 2; u <= w; ++u) {
+      const unsigned char* kt = smem + (u >> 1) * 16384;
+      const unsigned char* vt = smem + 32768 + (u >> 1) * 16384;
+      const int ks = u & 1;
+      bf16x8_t kfop[8];
+      {
+        float x[64];
+#pragma unroll
+        for (int dk = 0; dk < 8; ++dk) unpack_bf16x8(lds_row_chunk(kt, 32 * ks + r32, 2 * dk + h), &x[8 * dk]);
+        phi_rows(x, kfop);
+      }
+      f32x16_t c = {0};
+#pragma unroll
+      for (int dk = 0; dk < 8; ++dk) c = mfma32(kfop[dk], qfop[dk], c);
+      float cv[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key_local = 32 * u + 8 * (i >> 2) + 4 * h + (i & 3);
+        cv[i] = (u == w && key_local > 32 * w + r32) ? 0.f : c[i];
+      }
+      bf16x8_t cop[2] = {pack_bf16x8(&cv[0]), pack_bf16x8(&cv[8])};
+#pragma unroll
+      for (int mf = 0; mf < 2; ++mf) {
+        const int k0 = 32 * ks + 16 * mf + 4 * h;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) xr[dt] = mfma32(lds_tr_pair(vt, k0, k0 + 8, 32 * dt, lane), cop[mf], xr[dt]);
+      }
+    }
+    __syncthreads();
+    float ss = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) ss += xr[dt][i] * xr[dt][i];
+    ss += xhalf(ss);
+    rr_val = rsqrtf(ss * (1.f / 128.f) + a.eps);
+    if (a.xr_out) {
+      float vals[4][16];
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) vals[dt][i] = xr[dt][i];
+      store_tile_transposed(smem, vals, a.xr_out + qtile_off, qstride, w, lane);
+    }
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        f32x2_t f = {xr[dt][2 * i] * rr_val, xr[dt][2 * i + 1] * rr_val};
+        yr[dt][i] = __builtin_convertvector(f, bf16x2_t);
+      }
+  } else {
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        f32x2_t f = {0.f, 0.f};
+        yr[dt][i] = __builtin_convertvector(f, bf16x2_t);
+      }
+    if (a.xr_out) {
+      const int tid = threadIdx.x;
+      const uint4 z = make_uint4(0, 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int id = tid + 256 * i;
+        *reinterpret_cast<uint4*>(a.xr_out + qtile_off + (size_t)(id >> 4) * qstride + (id & 15) * 8) = z;
+      }
+    }
+  }
+
+  // ------------------------------------------------------------------ softmax branch
+  f32x16_t oacc[4] = {{0}, {0}, {0}, {0}};
+  float m = -INFINITY, l = 0.f;
+  const int kt_lo = max(0, t0 - W);
+  const int ntiles = (t0 + 128 - kt_lo) / 64;
+  {
+    const int kt0 = kt_lo + 64 * (ntiles - 1);
+    tile_load_async<false, 4>(kbase + (size_t)kt0 * kstride, kstride, smem, w * 4, lane);
+    tile_load_async<true, 4>(vbase + (size_t)kt0 * kstride, kstride, smem + 32768, w * 4, lane);
+    wait_vmem();
+    __syncthreads();
+  }
+  const int qa = t0 + 32 * w, qb = qa + 31;
+  for (int n = 0; n < ntiles; ++n) {
+    const int it = ntiles - 1 - n;
+    const int cur = n & 1;
+    if (n + 1 < ntiles) {
+      const int ktn = kt_lo + 64 * (it - 1);
+      tile_load_async<false, 4>(kbase + (size_t)ktn * kstride, kstride, smem + (cur ^ 1) * 16384, w * 4, lane);
+      tile_load_async<true, 4>(vbase + (size_t)ktn * kstride, kstride, smem + 32768 + (cur ^ 1) * 16384, w * 4, lane);
+    }
+    const unsigned char* kt = smem + cur * 16384;
+    const unsigned char* vt = smem + 32768 + cur * 16384;
+    const int kt0 = kt_lo + 64 * it;
+#pragma unroll
+    for (int ks = 1; ks >= 0; --ks) {
+      const int ka = kt0 + 32 * ks;
+      const bool need = ka <= qb && ka + 31 >= qa - W + 1;
+      if (need) {
+        const bool full = ka + 31 <= qa && ka >= qb - W + 1;
+        if (full) swa_subtile<false>(kt, vt, ks, ka, myq, W, a.scale_log2, qop, oacc, m, l, lane);
+        else swa_subtile<true>(kt, vt, ks, ka, myq, W, a.scale_log2, qop, oacc, m, l, lane);
+      }
+    }
+    wait_vmem();
+    __syncthreads();
+  }
+
+  // ------------------------------------------------------------------ combination
+  l += xhalf(l);
+  const float inv_l = 1.f / l;
+  float ss = 0.f;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) {
+    oacc[dt] *= inv_l;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) ss += oacc[dt][i] * oacc[dt][i];
+  }
+  ss += xhalf(ss);
+  const float rs_val = rsqrtf(ss * (1.f / 128.f) + a.eps);
+  if (a.xs_out) {
+    float vals[4][16];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) vals[dt][i] = oacc[dt][i];
+    store_tile_transposed(smem, vals, a.xs_out + qtile_off, qstride, w, lane);
+    if (h == 0) {
+      a.lse_out[stat_off] = (m + log2f(l)) * LN2;
+      a.rs_out[stat_off] = rs_val;
+      a.rr_out[stat_off] = rr_val;
+    }
+  }
+  {
+    float vals[4][16];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int d0 = 32 * dt + 8 * i4 + 4 * h;
+        float4 g1 = make_float4(1.f, 1.f, 1.f, 1.f), g2 = g1;
+        if (a.gs) g1 = *reinterpret_cast<const float4*>(a.gs + hq * 128 + d0);
+        if (a.gr) g2 = *reinterpret_cast<const float4*>(a.gr + hq * 128 + d0);
+        const float ga[4] = {g1.x, g1.y, g1.z, g1.w}, gb[4] = {g2.x, g2.y, g2.z, g2.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = 4 * i4 + e;
+          const float y = (float)yr[dt][i >> 1][i & 1];
+          vals[dt][i] = ga[e] * oacc[dt][i] * rs_val + gb[e] * y;
+        }
+      }
+    store_tile_transposed(smem, vals, a.o + qtile_off, qstride, w, lane);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// State pre-pass, step 1 (Eq. 2, chunk-local part): U_c^T = V_c^T phi(K_c) for one chunk of 64 or
+// 128 tokens of one KV head, fp32 [128 (d)][128 (f)].  grid (nchunks, Hkv, B), 256 threads.
+// Chunk 0 is the 64-token head chunk when `base` = 64; the others are 128 tokens starting at
+// base + 128*(c - (base > 0)).
+__global__ __launch_bounds__(256) void rla_chunk_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                                                        float* __restrict__ U, int T, int Hkv, int base) {
+  __shared__ __align__(16) unsigned char smem[65536];
+  unsigned char* Kt = smem;
+  unsigned char* Vt = smem + 32768;
+  const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z, nchunks = gridDim.x;
+  const int lane = lane_id(), w = wave_id(), tid = threadIdx.x;
+  const int r32 = lane & 31, h = lane >> 5;
+  const int hb = base > 0 ? 1 : 0;
+  const int lo = (hb && c == 0) ? 0 : base + 128 * (c - hb);
+  const int ntok = (hb && c == 0) ? 64 : 128;
+  const size_t kstride = (size_t)Hkv * 128;
+  const uint16_t* kb = k + ((size_t)(b * T + lo) * Hkv + g) * 128;
+  const uint16_t* vb = v + ((size_t)(b * T + lo) * Hkv + g) * 128;
+  tile_load_async<true, 4>(kb, kstride, Kt, w * 4, lane);
+  tile_load_async<true, 4>(vb, kstride, Vt, w * 4, lane);
+  if (ntok == 128) {
+    tile_load_async<true, 4>(kb, kstride, Kt, 16 + w * 4, lane);
+    tile_load_async<true, 4>(vb, kstride, Vt, 16 + w * 4, lane);
+  }
+  wait_vmem();
+  __syncthreads();
+  // phi(K) in place: two threads per token row, 64 features each
+  {
+    const int row = tid >> 1, half = tid & 1;
+    if (row < ntok) {
+      float x[64];
+      unsigned char* rp = Kt + row * ROW_BYTES;
+      const int sw = (row & 3) << 2;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) unpack_bf16x8(*reinterpret_cast<const bf16x8_t*>(rp + (((8 * half + j) ^ sw) << 4)), &x[8 * j]);
+      float m = x[0];
+#pragma unroll
+      for (int i = 1; i < 64; ++i) m = fmaxf(m, x[i]);
+      m = fmaxf(m, __shfl_xor(m, 1, 64));
+      float s = 0.f;
+#pragma unroll
+      for (int i = 0; i < 64; ++i) { x[i] = exp2f((x[i] - m) * LOG2E); s += x[i]; }
+      s += __shfl_xor(s, 1, 64);
+      const float inv = 1.f / s;
+#pragma unroll
+      for (int i = 0; i < 64; ++i) x[i] *= inv;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) *reinterpret_cast<bf16x8_t*>(rp + (((8 * half + j) ^ sw) << 4)) = pack_bf16x8(&x[8 * j]);
+    }
+  }
+  __syncthreads();
+  f32x16_t acc[4] = {{0}, {0}, {0}, {0}};
+  for (int ks = 0; ks < ntok / 16; ++ks) {
+    const int k0 = 16 * ks + 8 * h;
+    const bf16x8_t aop = lds_tr_pair(Vt, k0, k0 + 4, 32 * w, lane);
+#pragma unroll
+    for (int ft = 0; ft < 4; ++ft) acc[ft] = mfma32(aop, lds_tr_pair(Kt, k0, k0 + 4, 32 * ft, lane), acc[ft]);
+  }
+  float* out = U + ((size_t)(b * Hkv + g) * nchunks + c) * 16384;
+#pragma unroll
+  for (int ft = 0; ft < 4; ++ft)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int d = 32 * w + 8 * (i >> 2) + 4 * h + (i & 3);
+      out[(size_t)d * 128 + 32 * ft + r32] = acc[ft][i];
+    }
+}
+
+// State pre-pass, step 2 (Eq. 2, inter-chunk scan): states[i] = sum of the chunks before key position
+// base + 128*i, accumulated in fp32, stored as bf16 (the MFMA operand precision).  Every state
+// element scans independently.  grid (16, Hkv, B), 256 threads, 4 elements per thread.
+__global__ __launch_bounds__(256) void rla_scan_kernel(const float* __restrict__ U, uint16_t* __restrict__ states,
+                                                       int nchunks, int nstf, int base) {
+  const int g = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
+  const int e4 = (blockIdx.x * 256 + threadIdx.x) * 4;
+  const float* Ub = U + (size_t)(b * Hkv + g) * nchunks * 16384 + e4;
+  uint16_t* Sb = states + (size_t)(b * Hkv + g) * nstf * 16384 + e4;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  int c = 0;
+  if (base > 0) { acc = *reinterpret_cast<const float4*>(Ub); c = 1; }
+  for (int i = 0; i < nstf; ++i) {
+    f32x4_t f = {acc.x, acc.y, acc.z, acc.w};
+    *reinterpret_cast<bf16x4_t*>(Sb + (size_t)i * 16384) = __builtin_convertvector(f, bf16x4_t);
+    if (i + 1 < nstf) {
+      const float4 u = *reinterpret_cast<const float4*>(Ub + (size_t)c * 16384);
+      acc.x += u.x; acc.y += u.y; acc.z += u.z; acc.w += u.w;
+      ++c;
+    }
+  }
+}
+
+}  // namespace
+
+bool fast_fwd_supported(const LayerDims& dm, int dtype) {
+  if (dtype != 1 || dm.D != 128 || dm.T % 128 != 0) return false;
+  if (!(dm.scale > 0.f)) return false;
+  if (dm.W < dm.T && dm.W % 64 != 0) return false;
+  return true;
+}
+
+FastFwdPlan fast_fwd_plan(const LayerDims& dm) {
+  FastFwdPlan p;
+  p.W = dm.W >= dm.T ? dm.T : dm.W;
+  p.base = p.W % 128;
+  p.nstf = dm.T / 128 - (p.W + 127) / 128;
+  if (p.nstf < 0) p.nstf = 0;
+  p.nchunks = p.nstf > 0 ? (p.nstf - 1) + (p.base > 0 ? 1 : 0) : 0;
+  p.u_bytes = (size_t)dm.B * dm.Hkv * p.nchunks * 16384 * 4;
+  p.state_bytes = (size_t)dm.B * dm.Hkv * p.nstf * 16384 * 2;
+  return p;
+}
+
+void fast_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, const float* gs, const float* gr,
+              void* o, const SavedPtrs& sv, float* U, void* states, hipStream_t st) {
+  const FastFwdPlan pl = fast_fwd_plan(dm);
+  if (pl.nstf > 0) {
+    if (pl.nchunks > 0) {
+      ProfScope ps("rla_chunk_kernel", st);
+      rla_chunk_kernel<<<dim3(pl.nchunks, dm.Hkv, dm.B), 256, 0, st>>>((const uint16_t*)k, (const uint16_t*)v, U, dm.T,
+                                                                       dm.Hkv, pl.base);
+    }
+    ProfScope ps("rla_scan_kernel", st);
+    rla_scan_kernel<<<dim3(16, dm.Hkv, dm.B), 256, 0, st>>>(U, (uint16_t*)states, pl.nchunks, pl.nstf, pl.base);
+  }
+  FastFwdArgs a;
+  a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
+  a.gs = gs; a.gr = gr;
+  a.o = (uint16_t*)o; a.xs_out = (uint16_t*)sv.xs; a.xr_out = (uint16_t*)sv.xr;
+  a.lse_out = sv.lse; a.rs_out = sv.rs; a.rr_out = sv.rr;
+  a.states = (const uint16_t*)states;
+  a.B = dm.B; a.T = dm.T; a.Hq = dm.Hq; a.Hkv = dm.Hkv; a.G = dm.G; a.W = pl.W; a.nstf = pl.nstf;
+  a.ntile = dm.T / 128;
+  a.scale_log2 = dm.scale * LOG2E; a.eps = dm.eps;
+  ProfScope ps("fwd_fused_kernel", st);
+  fwd_fused_kernel<<<dim3(a.ntile * dm.Hq * dm.B), 256, 0, st>>>(a);
+}
+
+}  // namespace rattn

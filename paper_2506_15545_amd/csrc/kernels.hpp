@@ -47,6 +47,19 @@ void generic_bwd(const LayerDims& dm, int dtype, const void* q, const void* k, c
                  const float* gr, const SavedPtrs& sv, const void* dO, void* dq, void* dk, void* dv, float* dgs,
                  float* dgr, const GenericBwdWs& ws, hipStream_t st);
 
+// MFMA forward path (bf16, D = 128, T % 128 == 0, W % 64 == 0 or W >= T)
+struct FastFwdPlan {
+  int W;        // effective window (min(W, T))
+  int base;     // key position of state 0 (0 or 64); state i sits at base + 128*i
+  int nstf;     // number of states per (batch, kv head) = query tiles that have a linear branch
+  int nchunks;  // chunk-local products needed to build them
+  size_t u_bytes, state_bytes;
+};
+bool fast_fwd_supported(const LayerDims& dm, int dtype);
+FastFwdPlan fast_fwd_plan(const LayerDims& dm);
+void fast_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, const float* gs, const float* gr,
+              void* o, const SavedPtrs& sv, float* U, void* states, hipStream_t st);
+
 struct DecodeDims {
   int N, Hq, Hkv, D, W, G;
   float scale, eps;

@@ -1,0 +1,101 @@
+"""GPU parity of the MFMA kernels (bf16, D=128, T % 128 == 0, W % 64 == 0 or W >= T) against the
+fp64 oracle, on shapes that span several query tiles, both state alignments (W % 128 == 0 and 64),
+the causal degenerate case and GQA; plus agreement with the general-shape kernels."""
+import math
+import os
+import numpy as np
+import pytest
+import torch
+
+from oracle import rattn_oracle as orc
+from paper_2506_15545_amd import binding as rb
+from paper_2506_15545_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def np64(t):
+    return t.detach().cpu().to(torch.float64).numpy()
+
+
+def bf16_err(got, ref):
+    """max |got-ref| after taking off the storage rounding of a bf16 value (2^-8 |ref|)."""
+    e = np.abs(np64(got) - ref)
+    return float(np.max(np.maximum(e - np.abs(ref) / 256.0, 0.0)))
+
+
+CASES = [
+    # B, T, Hq, Hkv, W
+    (1, 128, 2, 1, 64),      # one query tile, state alignment 64
+    (1, 256, 2, 2, 128),     # two tiles, aligned states
+    (2, 512, 4, 2, 128),
+    (1, 1024, 3, 1, 192),    # GQA 3, W % 128 == 64
+    (1, 768, 2, 1, 512),
+    (1, 384, 2, 2, 384),     # W == T: causal attention, no linear branch
+    (1, 256, 2, 1, 4096),    # W > T
+    (1, 640, 6, 2, 64),      # smallest window
+]
+
+
+@pytest.mark.parametrize("B,T,Hq,Hkv,W", CASES)
+def test_fast_fwd_matches_oracle(B, T, Hq, Hkv, W):
+    D = 128
+    x = synth.make_random_layer(B, T, Hq, Hkv, D, "bf16", 900 + T + W, with_gains=True)
+    scale = 1.0 / math.sqrt(D)
+    gs, gr = x["gamma_swa"], x["gamma_rla"]
+    print(f"fast fwd case B={B} T={T} Hq={Hq} Hkv={Hkv} W={W}", flush=True)
+    q, k, v = x["q"].cuda(), x["k"].cuda(), x["v"].cuda()
+    o, saved = rb.rattn_fwd(q, k, v, W, gs.cuda(), gr.cuda(), softmax_scale=scale, save_for_bwd=True)
+    torch.cuda.synchronize()
+    ref = orc.fwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), W, scale=scale, gamma_swa=np64(gs), gamma_rla=np64(gr))
+    gmax = max(float(gs.abs().max()), float(gr.abs().max()), 1.0)
+    assert bf16_err(o, ref["o"]) <= 2e-2 * gmax
+    # saved tensors: pre-norm branch outputs and row statistics
+    n = B * T * Hq * D
+    xs = saved[:2 * n].view(torch.bfloat16).view(B, T, Hq, D)
+    off = (2 * n + 255) // 256 * 256
+    xr = saved[off:off + 2 * n].view(torch.bfloat16).view(B, T, Hq, D)
+    s_rms = math.sqrt(float(np.mean(ref["xs"] ** 2)))
+    assert bf16_err(xs, ref["xs"]) <= 2e-2 * s_rms
+    r_rms = math.sqrt(float(np.mean(ref["xr"] ** 2)))
+    if r_rms > 0:
+        assert bf16_err(xr, ref["xr"]) <= 2e-2 * r_rms
+    else:
+        assert float(xr.float().abs().max()) == 0.0
+    off2 = 2 * off
+    nrow = B * Hq * T
+    stat_stride = (4 * nrow + 255) // 256 * 256
+    lse = saved[off2:off2 + 4 * nrow].view(torch.float32).view(B, Hq, T)
+    rs = saved[off2 + stat_stride:off2 + stat_stride + 4 * nrow].view(torch.float32).view(B, Hq, T)
+    rr = saved[off2 + 2 * stat_stride:off2 + 2 * stat_stride + 4 * nrow].view(torch.float32).view(B, Hq, T)
+    assert float(np.max(np.abs(np64(lse) - ref["lse"]))) <= 2e-2
+    assert float(np.max(np.abs(np64(rs) / ref["rs"] - 1.0))) <= 2e-2
+    assert float(np.max(np.abs(np64(rr) / ref["rr"] - 1.0))) <= 2e-2
+
+
+def test_fast_and_general_kernels_agree():
+    B, T, Hq, Hkv, D, W = 2, 1024, 4, 2, 128, 256
+    x = synth.make_random_layer(B, T, Hq, Hkv, D, "bf16", 77)
+    q, k, v = x["q"].cuda(), x["k"].cuda(), x["v"].cuda()
+    scale = 1.0 / math.sqrt(D)
+    o_fast = rb.rattn_fwd(q, k, v, W, softmax_scale=scale)
+    os.environ["RATTN_FORCE_GENERIC"] = "1"
+    try:
+        o_gen = rb.rattn_fwd(q, k, v, W, softmax_scale=scale)
+    finally:
+        del os.environ["RATTN_FORCE_GENERIC"]
+    torch.cuda.synchronize()
+    assert float((o_fast.float() - o_gen.float()).abs().max()) <= 4e-2
+    rb.rattn_profile_enable(True)
+    rb.rattn_fwd(q, k, v, W, softmax_scale=scale)
+    names = [n for n, _ in rb.rattn_profile_records()]
+    rb.rattn_profile_enable(False)
+    assert "fwd_fused_kernel" in names and "gen_fwd_kernel" not in names
+
+
+def test_fast_fwd_is_deterministic():
+    x = synth.make_random_layer(1, 512, 4, 2, 128, "bf16", 5)
+    q, k, v = x["q"].cuda(), x["k"].cuda(), x["v"].cuda()
+    a = rb.rattn_fwd(q, k, v, 128, softmax_scale=0.09)
+    b = rb.rattn_fwd(q, k, v, 128, softmax_scale=0.09)
+    assert torch.equal(a, b)
