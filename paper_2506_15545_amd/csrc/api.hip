@@ -56,6 +56,7 @@ struct Layout {
   // MFMA forward workspace
   bool fast_fwd;
   size_t ff_u, ff_states, fast_fwd_bytes;
+  size_t fb_dxs, fb_dxr, fb_delta, fb_u, fb_states, fb_rstates, fb_dgpart, fast_bwd_bytes;
   size_t fwd_bytes, bwd_bytes;
 };
 
@@ -124,9 +125,22 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
     L->ff_states = align_up(pl.u_bytes);
     L->fast_fwd_bytes = L->ff_states + align_up(pl.state_bytes);
   }
+  L->fast_bwd_bytes = 0;
+  if (L->fast_fwd) {
+    const rattn::FastBwdPlan bp = rattn::fast_bwd_plan(dm);
+    off = 0;
+    L->fb_dxs = off; off += align_up(nq * 2);
+    L->fb_dxr = off; off += align_up(nq * 2);
+    L->fb_delta = off; off += align_up(nrow * 4);
+    L->fb_u = off; off += align_up(bp.u_bytes);
+    L->fb_states = off; off += align_up(bp.fwd.state_bytes);
+    L->fb_rstates = off; off += align_up(bp.rstate_bytes);
+    L->fb_dgpart = off; off += align_up((size_t)2 * bp.RB * dm.Hq * dm.D * 4);
+    L->fast_bwd_bytes = off;
+  }
   // the general-shape kernels stay selectable (RATTN_FORCE_GENERIC=1), so size for both
   L->fwd_bytes = L->gen_fwd_bytes > L->fast_fwd_bytes ? L->gen_fwd_bytes : L->fast_fwd_bytes;
-  L->bwd_bytes = L->gen_bwd_bytes;
+  L->bwd_bytes = L->gen_bwd_bytes > L->fast_bwd_bytes ? L->gen_bwd_bytes : L->fast_bwd_bytes;
   return RATTN_OK;
 }
 
@@ -232,6 +246,13 @@ rattn_status rattn_bwd(const rattn_params* p, const void* q, const void* k, cons
   hipStream_t st = (hipStream_t)stream;
   rattn::SavedPtrs sv = saved_views(L, const_cast<void*>(saved));
   char* w = (char*)workspace;
+  if (L.fast_fwd && !force_generic()) {
+    rattn::FastBwdWs fw;
+    fw.dxs = w + L.fb_dxs; fw.dxr = w + L.fb_dxr; fw.delta = (float*)(w + L.fb_delta); fw.U = (float*)(w + L.fb_u);
+    fw.states = w + L.fb_states; fw.rstates = w + L.fb_rstates; fw.dgpart = (float*)(w + L.fb_dgpart);
+    rattn::fast_bwd(L.dm, q, k, v, gamma_swa, gamma_rla, sv, dO, dq, dk, dv, dgamma_swa, dgamma_rla, fw, st);
+    return check_launch("rattn_bwd");
+  }
   rattn::GenericBwdWs ws;
   ws.states = (float*)(w + L.gb_states); ws.rstates = (float*)(w + L.gb_rstates);
   ws.dxs = (float*)(w + L.gb_dxs); ws.dxr = (float*)(w + L.gb_dxr);

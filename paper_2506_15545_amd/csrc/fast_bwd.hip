@@ -1,0 +1,531 @@
+// MFMA backward of the RAttention layer (same shape class as the MFMA forward: bf16, D = 128,
+// T % 128 == 0, W % 64 == 0 or W >= T).  No floating-point atomics: dq is produced by a kernel that
+// owns query tiles, dk/dv by a kernel that owns key tiles (and visits the G query heads of its KV
+// head in turn); both recompute the attention probabilities from the saved log-sum-exp.
+//
+//   prep : through the two RMS norms (Sec. 3.2): dx_s, dx_r (bf16 MFMA operands), delta = <dx_s, x_s>,
+//          dgamma partials
+//   states: S_[j] (Eq. 2, recomputed) and the reverse-time states R_[j] = sum_{later chunks} phi(q)^T dx_r
+//   dq   : transposed, lane = query:  dQ^T = scale * K^T dS^T,  dS = P .* (dP - delta),  dP^T = V dXs^T
+//          linear branch: dphi(Q)^T = S dXr^T + Kf^T (M^T .* (V dXr^T)), then the softmax Jacobian of phi
+//   dkv  : transposed, lane = key:   dV^T = dXs^T P + dXr^T C + R^T Kf^T,
+//          dK^T = scale * Q^T dS + J_phi(Qf^T dC + R V^T)
+#include "common.hpp"
+#include "kernels.hpp"
+#include "mfma.hpp"
+
+namespace rattn {
+
+namespace {
+
+struct FastBwdArgs {
+  const uint16_t *q, *k, *v, *dxs, *dxr;
+  const float *lse, *delta;
+  const uint16_t *states, *rstates;
+  uint16_t *dq, *dk, *dv;
+  int B, T, Hq, Hkv, G, W, nstf, nk, ntile;
+  float scale, scale_log2;
+};
+
+// ------------------------------------------------------------------------------------------------
+// grid (RB, Hq), 256 threads; a wave takes one (b,t) row of head h at a time, lane owns features
+// 2*lane, 2*lane+1.
+__global__ __launch_bounds__(256) void bwd_prep_kernel(const uint16_t* __restrict__ dO, const uint16_t* __restrict__ xs_in,
+                                                       const uint16_t* __restrict__ xr_in, const float* __restrict__ rs_in,
+                                                       const float* __restrict__ rr_in, const float* __restrict__ gs,
+                                                       const float* __restrict__ gr, uint16_t* __restrict__ dxs,
+                                                       uint16_t* __restrict__ dxr, float* __restrict__ delta,
+                                                       float* __restrict__ dgpart, int B, int T, int Hq) {
+  __shared__ float red[2][4][128];
+  const int h = blockIdx.y, RB = gridDim.x, lane = lane_id(), w = wave_id();
+  const int rows = B * T;
+  float g1[2] = {1.f, 1.f}, g2[2] = {1.f, 1.f}, dg1[2] = {0.f, 0.f}, dg2[2] = {0.f, 0.f};
+  if (gs) { g1[0] = gs[h * 128 + 2 * lane]; g1[1] = gs[h * 128 + 2 * lane + 1]; }
+  if (gr) { g2[0] = gr[h * 128 + 2 * lane]; g2[1] = gr[h * 128 + 2 * lane + 1]; }
+  for (int r = blockIdx.x * 4 + w; r < rows; r += RB * 4) {
+    const int b = r / T, t = r % T;
+    const size_t off = ((size_t)r * Hq + h) * 128 + 2 * lane;
+    const size_t so = (size_t)(b * Hq + h) * T + t;
+    const uint32_t udy = *reinterpret_cast<const uint32_t*>(dO + off);
+    const uint32_t uxs = *reinterpret_cast<const uint32_t*>(xs_in + off);
+    const uint32_t uxr = *reinterpret_cast<const uint32_t*>(xr_in + off);
+    const float dy[2] = {__uint_as_float(udy << 16), __uint_as_float(udy & 0xffff0000u)};
+    const float xs[2] = {__uint_as_float(uxs << 16), __uint_as_float(uxs & 0xffff0000u)};
+    const float xr[2] = {__uint_as_float(uxr << 16), __uint_as_float(uxr & 0xffff0000u)};
+    const float r_s = rs_in[so], r_r = rr_in[so];
+    float m1 = 0.f, m2 = 0.f;
+#pragma unroll
+    for (int e = 0; e < 2; ++e) { m1 += g1[e] * dy[e] * xs[e]; m2 += g2[e] * dy[e] * xr[e]; }
+    m1 = wave_sum(m1) * (1.f / 128.f); m2 = wave_sum(m2) * (1.f / 128.f);
+    float a[2], c[2], dl = 0.f;
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      a[e] = r_s * g1[e] * dy[e] - xs[e] * r_s * r_s * r_s * m1;
+      c[e] = r_r * g2[e] * dy[e] - xr[e] * r_r * r_r * r_r * m2;
+      dl += a[e] * xs[e];
+      dg1[e] += dy[e] * xs[e] * r_s;
+      dg2[e] += dy[e] * xr[e] * r_r;
+    }
+    f32x2_t fa = {a[0], a[1]}, fc = {c[0], c[1]};
+    *reinterpret_cast<bf16x2_t*>(dxs + off) = __builtin_convertvector(fa, bf16x2_t);
+    *reinterpret_cast<bf16x2_t*>(dxr + off) = __builtin_convertvector(fc, bf16x2_t);
+    dl = wave_sum(dl);
+    if (lane == 0) delta[so] = dl;
+  }
+#pragma unroll
+  for (int e = 0; e < 2; ++e) { red[0][w][2 * lane + e] = dg1[e]; red[1][w][2 * lane + e] = dg2[e]; }
+  __syncthreads();
+  {
+    const int which = threadIdx.x >> 7, d = threadIdx.x & 127;
+    const float s = red[which][0][d] + red[which][1][d] + red[which][2][d] + red[which][3][d];
+    dgpart[((size_t)(which * RB + blockIdx.x) * Hq + h) * 128 + d] = s;
+  }
+}
+
+__global__ void dgamma_reduce_kernel(const float* __restrict__ dgpart, float* __restrict__ dgs, float* __restrict__ dgr,
+                                     int RB, int HD) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= HD) return;
+  float s1 = 0.f, s2 = 0.f;
+  for (int r = 0; r < RB; ++r) { s1 += dgpart[(size_t)r * HD + i]; s2 += dgpart[(size_t)(RB + r) * HD + i]; }
+  if (dgs) dgs[i] = s1;
+  if (dgr) dgr[i] = s2;
+}
+
+// row `src` (128 bf16) re-read in accumulator layout: lane keeps features 32ft + 8*i4 + 4h + e -> x[ft*16 + 4*i4 + e];
+// phi of that row (the row's other half sits in lane ^ 32)
+__device__ __forceinline__ void phi_row_clayout(const uint16_t* src, int h, float (&x)[64]) {
+#pragma unroll
+  for (int ft = 0; ft < 4; ++ft)
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      const bf16x4_t v = *reinterpret_cast<const bf16x4_t*>(src + 32 * ft + 8 * i4 + 4 * h);
+      f32x4_t f = __builtin_convertvector(v, f32x4_t);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x[ft * 16 + 4 * i4 + e] = f[e];
+    }
+  float m = x[0];
+#pragma unroll
+  for (int i = 1; i < 64; ++i) m = fmaxf(m, x[i]);
+  m = fmaxf(m, xhalf(m));
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 64; ++i) { x[i] = exp2f((x[i] - m) * LOG2E); s += x[i]; }
+  s += xhalf(s);
+  const float inv = 1.f / s;
+#pragma unroll
+  for (int i = 0; i < 64; ++i) x[i] *= inv;
+}
+
+// acc <- f .* (acc - <acc, f>)   (softmax Jacobian applied to a gradient held in accumulator layout)
+__device__ __forceinline__ void phi_jacobian(f32x16_t (&acc)[4], const float (&f)[64]) {
+  float inner = 0.f;
+#pragma unroll
+  for (int ft = 0; ft < 4; ++ft)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) inner += acc[ft][i] * f[ft * 16 + i];
+  inner += xhalf(inner);
+#pragma unroll
+  for (int ft = 0; ft < 4; ++ft)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[ft][i] = f[ft * 16 + i] * (acc[ft][i] - inner);
+}
+
+__device__ __forceinline__ void load_bop(const uint16_t* rowp, int h, bf16x8_t (&op)[8]) {
+#pragma unroll
+  for (int c = 0; c < 8; ++c) op[c] = *reinterpret_cast<const bf16x8_t*>(rowp + 16 * c + 8 * h);
+}
+
+// ------------------------------------------------------------------------------------------------
+template <bool MASKED>
+__device__ __forceinline__ void dq_subtile(const unsigned char* kt, const unsigned char* vt, int ks, int ka, int myq,
+                                           int W, float scale, float scale_log2, float lse2, float dl,
+                                           const bf16x8_t (&qop)[8], const bf16x8_t (&dxsop)[8], f32x16_t (&acc)[4],
+                                           int lane) {
+  const int r32 = lane & 31, h = lane >> 5;
+  f32x16_t s = {0}, dp = {0};
+#pragma unroll
+  for (int c = 0; c < 8; ++c) s = mfma32(lds_row_chunk(kt, 32 * ks + r32, 2 * c + h), qop[c], s);
+#pragma unroll
+  for (int c = 0; c < 8; ++c) dp = mfma32(lds_row_chunk(vt, 32 * ks + r32, 2 * c + h), dxsop[c], dp);
+  float ds[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    float p = exp2f(s[i] * scale_log2 - lse2);
+    if (MASKED) {
+      const int key = ka + 8 * (i >> 2) + 4 * h + (i & 3);
+      p = (key <= myq && key > myq - W) ? p : 0.f;
+    }
+    ds[i] = p * (dp[i] - dl) * scale;
+  }
+  bf16x8_t dsop[2] = {pack_bf16x8(&ds[0]), pack_bf16x8(&ds[8])};
+#pragma unroll
+  for (int mf = 0; mf < 2; ++mf) {
+    const int k0 = 32 * ks + 16 * mf + 4 * h;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) acc[dt] = mfma32(lds_tr_pair(kt, k0, k0 + 8, 32 * dt, lane), dsop[mf], acc[dt]);
+  }
+}
+
+// grid (ntile * Hq * B), 256 threads: 128 queries of one head, wave w owns 32.
+__global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
+  __shared__ __align__(16) unsigned char smem[65536];
+  const int lane = lane_id(), w = wave_id();
+  const int r32 = lane & 31, h = lane >> 5;
+  const int T = a.T, W = a.W, Hq = a.Hq, Hkv = a.Hkv, G = a.G;
+  const int total = gridDim.x, bid = blockIdx.x;
+  int wid = (total % 8 == 0) ? (bid % 8) * (total / 8) + bid / 8 : bid;
+  const int hh = wid % G; wid /= G;
+  const int qt = wid % a.ntile; wid /= a.ntile;
+  const int g = wid % Hkv;
+  const int b = wid / Hkv;
+  const int hq = g * G + hh;
+  const int t0 = qt * 128;
+  const size_t qstride = (size_t)Hq * 128, kstride = (size_t)Hkv * 128;
+  const size_t qtile_off = ((size_t)(b * T + t0) * Hq + hq) * 128;
+  const size_t myrow_off = qtile_off + (size_t)(32 * w + r32) * qstride;
+  const uint16_t* kbase = a.k + ((size_t)b * T * Hkv + g) * 128;
+  const uint16_t* vbase = a.v + ((size_t)b * T * Hkv + g) * 128;
+  const int myq = t0 + 32 * w + r32;
+  const size_t stat_off = (size_t)(b * Hq + hq) * T + myq;
+
+  bf16x8_t qop[8];
+  load_bop(a.q + myrow_off, h, qop);
+  f32x16_t acc[4] = {{0}, {0}, {0}, {0}};
+
+  // ---- linear branch: d phi(q)
+  const int j0 = t0 - W;
+  if (j0 > -128) {
+    const bool has_state = j0 >= 0;
+    bf16x8_t dxrop[8];
+    load_bop(a.dxr + myrow_off, h, dxrop);
+    if (has_state) {
+      const uint16_t* sbase = a.states + ((size_t)(b * Hkv + g) * a.nstf + j0 / 128) * 16384;
+      tile_load_async<8>(sbase, 128, smem, w * 8, lane);
+      tile_load_async<4>(vbase + (size_t)j0 * kstride, kstride, smem + 32768, w * 4, lane);
+    }
+    tile_load_async<4>(vbase + (size_t)(j0 + 64) * kstride, kstride, smem + 49152, w * 4, lane);
+    wait_vmem();
+    __syncthreads();
+    if (has_state) {
+#pragma unroll
+      for (int kd = 0; kd < 8; ++kd) {
+        const int k0 = 16 * kd + 8 * h;
+#pragma unroll
+        for (int ft = 0; ft < 4; ++ft) acc[ft] = mfma32(lds_tr_pair(smem, k0, k0 + 4, 32 * ft, lane), dxrop[kd], acc[ft]);
+      }
+    }
+    __syncthreads();
+    if (has_state) tile_load_async<4>(kbase + (size_t)j0 * kstride, kstride, smem, w * 4, lane);
+    tile_load_async<4>(kbase + (size_t)(j0 + 64) * kstride, kstride, smem + 16384, w * 4, lane);
+    wait_vmem();
+    __syncthreads();
+    if (has_state) phi_tile_inplace(smem, 128);
+    else phi_tile_inplace(smem + 16384, 64);
+    __syncthreads();
+    for (int u = has_state ? 0 : 2; u <= w; ++u) {
+      const unsigned char* kt = smem + (u >> 1) * 16384;
+      const unsigned char* vt = smem + 32768 + (u >> 1) * 16384;
+      const int ks = u & 1;
+      f32x16_t c = {0};
+#pragma unroll
+      for (int kd = 0; kd < 8; ++kd) c = mfma32(lds_row_chunk(vt, 32 * ks + r32, 2 * kd + h), dxrop[kd], c);
+      float cv[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key_local = 32 * u + 8 * (i >> 2) + 4 * h + (i & 3);
+        cv[i] = (u == w && key_local > 32 * w + r32) ? 0.f : c[i];
+      }
+      bf16x8_t cop[2] = {pack_bf16x8(&cv[0]), pack_bf16x8(&cv[8])};
+#pragma unroll
+      for (int mf = 0; mf < 2; ++mf) {
+        const int k0 = 32 * ks + 16 * mf + 4 * h;
+#pragma unroll
+        for (int ft = 0; ft < 4; ++ft) acc[ft] = mfma32(lds_tr_pair(kt, k0, k0 + 8, 32 * ft, lane), cop[mf], acc[ft]);
+      }
+    }
+    __syncthreads();
+    float qf[64];
+    phi_row_clayout(a.q + myrow_off, h, qf);
+    phi_jacobian(acc, qf);
+  }
+
+  // ---- softmax branch
+  bf16x8_t dxsop[8];
+  load_bop(a.dxs + myrow_off, h, dxsop);
+  const float lse2 = a.lse[stat_off] * LOG2E;
+  const float dl = a.delta[stat_off];
+  const int kt_lo = max(0, t0 - W);
+  const int ntiles = (t0 + 128 - kt_lo) / 64;
+  {
+    const int kt0 = kt_lo + 64 * (ntiles - 1);
+    tile_load_async<4>(kbase + (size_t)kt0 * kstride, kstride, smem, w * 4, lane);
+    tile_load_async<4>(vbase + (size_t)kt0 * kstride, kstride, smem + 32768, w * 4, lane);
+    wait_vmem();
+    __syncthreads();
+  }
+  const int qa = t0 + 32 * w, qb = qa + 31;
+  for (int n = 0; n < ntiles; ++n) {
+    const int it = ntiles - 1 - n;
+    const int cur = n & 1;
+    if (n + 1 < ntiles) {
+      const int ktn = kt_lo + 64 * (it - 1);
+      tile_load_async<4>(kbase + (size_t)ktn * kstride, kstride, smem + (cur ^ 1) * 16384, w * 4, lane);
+      tile_load_async<4>(vbase + (size_t)ktn * kstride, kstride, smem + 32768 + (cur ^ 1) * 16384, w * 4, lane);
+    }
+    const unsigned char* kt = smem + cur * 16384;
+    const unsigned char* vt = smem + 32768 + cur * 16384;
+    const int kt0 = kt_lo + 64 * it;
+#pragma unroll
+    for (int ks = 1; ks >= 0; --ks) {
+      const int ka = kt0 + 32 * ks;
+      const bool need = ka <= qb && ka + 31 >= qa - W + 1;
+      if (need) {
+        const bool full = ka + 31 <= qa && ka >= qb - W + 1;
+        if (full) dq_subtile<false>(kt, vt, ks, ka, myq, W, a.scale, a.scale_log2, lse2, dl, qop, dxsop, acc, lane);
+        else dq_subtile<true>(kt, vt, ks, ka, myq, W, a.scale, a.scale_log2, lse2, dl, qop, dxsop, acc, lane);
+      }
+    }
+    wait_vmem();
+    __syncthreads();
+  }
+  float vals[4][16];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) vals[dt][i] = acc[dt][i];
+  store_tile_transposed(smem, vals, a.dq + qtile_off, qstride, w, lane);
+}
+
+// ------------------------------------------------------------------------------------------------
+template <bool MASKED>
+__device__ __forceinline__ void dkv_subtile(const unsigned char* qt, const unsigned char* dxt, int qs, int qa, int mykey,
+                                            int W, float scale, float scale_log2, const float* lse_row,
+                                            const float* delta_row, const bf16x8_t (&kop)[8], const bf16x8_t (&vop)[8],
+                                            f32x16_t (&dk)[4], f32x16_t (&dv)[4], int lane) {
+  const int r32 = lane & 31, h = lane >> 5;
+  f32x16_t s = {0}, dp = {0};
+#pragma unroll
+  for (int c = 0; c < 8; ++c) s = mfma32(lds_row_chunk(qt, 32 * qs + r32, 2 * c + h), kop[c], s);
+#pragma unroll
+  for (int c = 0; c < 8; ++c) dp = mfma32(lds_row_chunk(dxt, 32 * qs + r32, 2 * c + h), vop[c], dp);
+  float pv[16], ds[16];
+#pragma unroll
+  for (int i4 = 0; i4 < 4; ++i4) {
+    const int qrow = qa + 8 * i4 + 4 * h;
+    const float4 ls = *reinterpret_cast<const float4*>(lse_row + qrow);
+    const float4 dl = *reinterpret_cast<const float4*>(delta_row + qrow);
+    const float lsa[4] = {ls.x, ls.y, ls.z, ls.w}, dla[4] = {dl.x, dl.y, dl.z, dl.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int i = 4 * i4 + e;
+      float p = exp2f(s[i] * scale_log2 - lsa[e] * LOG2E);
+      if (MASKED) {
+        const int query = qrow + e;
+        p = (mykey <= query && query - mykey < W) ? p : 0.f;
+      }
+      pv[i] = p;
+      ds[i] = p * (dp[i] - dla[e]) * scale;
+    }
+  }
+  bf16x8_t pop[2] = {pack_bf16x8(&pv[0]), pack_bf16x8(&pv[8])};
+  bf16x8_t dsop[2] = {pack_bf16x8(&ds[0]), pack_bf16x8(&ds[8])};
+#pragma unroll
+  for (int mf = 0; mf < 2; ++mf) {
+    const int k0 = 32 * qs + 16 * mf + 4 * h;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+      dv[dt] = mfma32(lds_tr_pair(dxt, k0, k0 + 8, 32 * dt, lane), pop[mf], dv[dt]);
+      dk[dt] = mfma32(lds_tr_pair(qt, k0, k0 + 8, 32 * dt, lane), dsop[mf], dk[dt]);
+    }
+  }
+}
+
+// grid (ntile * Hkv * B), 256 threads: 128 keys of one KV head, wave w owns 32 (lane = key).
+__global__ __launch_bounds__(256, 2) void bwd_dkv_kernel(FastBwdArgs a) {
+  __shared__ __align__(16) unsigned char smem[65536];
+  const int lane = lane_id(), w = wave_id();
+  const int r32 = lane & 31, h = lane >> 5;
+  const int T = a.T, W = a.W, Hq = a.Hq, Hkv = a.Hkv, G = a.G;
+  const int total = gridDim.x, bid = blockIdx.x;
+  int wid = (total % 8 == 0) ? (bid % 8) * (total / 8) + bid / 8 : bid;
+  const int kti = wid % a.ntile; wid /= a.ntile;
+  const int g = wid % Hkv;
+  const int b = wid / Hkv;
+  const int s0 = kti * 128;
+  const int Tp = T - W;
+  const size_t qstride = (size_t)Hq * 128, kstride = (size_t)Hkv * 128;
+  const size_t ktile_off = ((size_t)(b * T + s0) * Hkv + g) * 128;
+  const size_t myrow_off = ktile_off + (size_t)(32 * w + r32) * kstride;
+  const int mykey = s0 + 32 * w + r32;
+
+  bf16x8_t kop[8], vop[8];
+  load_bop(a.k + myrow_off, h, kop);
+  load_bop(a.v + myrow_off, h, vop);
+  f32x16_t dk[4] = {{0}, {0}, {0}, {0}}, dv[4] = {{0}, {0}, {0}, {0}};
+
+  // ---- linear branch (dk accumulates d phi(k) here, turned into dk by the Jacobian at the end)
+  if (s0 < Tp) {
+    const int nq = min(128, Tp - s0);  // query rows t = s0 + W + [0, nq) pair with this key tile
+    bf16x8_t kfop[8];
+    {
+      float x[64];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) unpack_bf16x8(kop[c], &x[8 * c]);
+      phi_rows(x, kfop);
+    }
+    const uint16_t* rbase = a.rstates + ((size_t)(b * Hkv + g) * a.nk + kti) * 16384;
+    tile_load_async<8>(rbase, 128, smem, w * 8, lane);
+    wait_vmem();
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const int k0 = 16 * c + 8 * h;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        dv[t] = mfma32(lds_row_chunk(smem, 32 * t + r32, 2 * c + h), kfop[c], dv[t]);
+        dk[t] = mfma32(lds_tr_pair(smem, k0, k0 + 4, 32 * t, lane), vop[c], dk[t]);
+      }
+    }
+    for (int hh = 0; hh < G; ++hh) {
+      const size_t qoff = ((size_t)(b * T + s0 + W) * Hq + g * G + hh) * 128;
+      __syncthreads();
+      tile_load_async<4>(a.q + qoff, qstride, smem, w * 4, lane);
+      tile_load_async<4>(a.dxr + qoff, qstride, smem + 32768, w * 4, lane);
+      if (nq == 128) {
+        tile_load_async<4>(a.q + qoff, qstride, smem, 16 + w * 4, lane);
+        tile_load_async<4>(a.dxr + qoff, qstride, smem + 32768, 16 + w * 4, lane);
+      }
+      wait_vmem();
+      __syncthreads();
+      phi_tile_inplace(smem, nq);
+      __syncthreads();
+      for (int u = w; u < nq / 32; ++u) {
+        f32x16_t c = {0}, dc = {0};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) c = mfma32(lds_row_chunk(smem, 32 * u + r32, 2 * e + h), kfop[e], c);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dc = mfma32(lds_row_chunk(smem + 32768, 32 * u + r32, 2 * e + h), vop[e], dc);
+        float cv[16], dcv[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int q_local = 32 * u + 8 * (i >> 2) + 4 * h + (i & 3);
+          const bool keep = !(u == w && 32 * w + r32 > q_local);
+          cv[i] = keep ? c[i] : 0.f;
+          dcv[i] = keep ? dc[i] : 0.f;
+        }
+        bf16x8_t cop[2] = {pack_bf16x8(&cv[0]), pack_bf16x8(&cv[8])};
+        bf16x8_t dcop[2] = {pack_bf16x8(&dcv[0]), pack_bf16x8(&dcv[8])};
+#pragma unroll
+        for (int mf = 0; mf < 2; ++mf) {
+          const int k0 = 32 * u + 16 * mf + 4 * h;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            dv[t] = mfma32(lds_tr_pair(smem + 32768, k0, k0 + 8, 32 * t, lane), cop[mf], dv[t]);
+            dk[t] = mfma32(lds_tr_pair(smem, k0, k0 + 8, 32 * t, lane), dcop[mf], dk[t]);
+          }
+        }
+      }
+    }
+    __syncthreads();
+    float kf[64];
+    phi_row_clayout(a.k + myrow_off, h, kf);
+    phi_jacobian(dk, kf);
+  }
+
+  // ---- softmax branch: query tiles of 64 rows from s0 up to the last row that still sees these keys
+  const int n_qt = (min(s0 + 128 + W, T) - s0) / 64;
+  const int nsteps = G * n_qt;
+  const int ka = s0 + 32 * w;
+  auto issue = [&](int step, int buf) {
+    const int hh = step / n_qt, n = step % n_qt;
+    const size_t qoff = ((size_t)(b * T + s0 + 64 * n) * Hq + g * G + hh) * 128;
+    tile_load_async<4>(a.q + qoff, qstride, smem + buf * 16384, w * 4, lane);
+    tile_load_async<4>(a.dxs + qoff, qstride, smem + 32768 + buf * 16384, w * 4, lane);
+  };
+  issue(0, 0);
+  wait_vmem();
+  __syncthreads();
+  for (int step = 0; step < nsteps; ++step) {
+    const int cur = step & 1;
+    if (step + 1 < nsteps) issue(step + 1, cur ^ 1);
+    const int hh = step / n_qt, n = step % n_qt;
+    const int hq = g * G + hh;
+    const float* lse_row = a.lse + (size_t)(b * Hq + hq) * T;
+    const float* delta_row = a.delta + (size_t)(b * Hq + hq) * T;
+    const unsigned char* qtile = smem + cur * 16384;
+    const unsigned char* dxt = smem + 32768 + cur * 16384;
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs) {
+      const int qa = s0 + 64 * n + 32 * qs;
+      const bool need = qa + 31 >= ka && qa <= ka + 31 + W - 1;
+      if (need) {
+        const bool full = qa >= ka + 31 && qa + 31 <= ka + W - 1;
+        if (full) dkv_subtile<false>(qtile, dxt, qs, qa, mykey, W, a.scale, a.scale_log2, lse_row, delta_row, kop, vop, dk, dv, lane);
+        else dkv_subtile<true>(qtile, dxt, qs, qa, mykey, W, a.scale, a.scale_log2, lse_row, delta_row, kop, vop, dk, dv, lane);
+      }
+    }
+    wait_vmem();
+    __syncthreads();
+  }
+  float vals[4][16];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) vals[dt][i] = dk[dt][i];
+  store_tile_transposed(smem, vals, a.dk + ktile_off, kstride, w, lane);
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) vals[dt][i] = dv[dt][i];
+  store_tile_transposed(smem, vals, a.dv + ktile_off, kstride, w, lane);
+}
+
+}  // namespace
+
+FastBwdPlan fast_bwd_plan(const LayerDims& dm) {
+  FastBwdPlan p;
+  p.fwd = fast_fwd_plan(dm);
+  const int Tp = dm.T - p.fwd.W;
+  p.nk = Tp > 0 ? (Tp + 127) / 128 : 0;
+  const int nch = p.fwd.nchunks > p.nk - 1 ? p.fwd.nchunks : p.nk - 1;
+  p.u_bytes = (size_t)dm.B * dm.Hkv * (nch > 0 ? nch : 0) * 16384 * 4;
+  p.rstate_bytes = (size_t)dm.B * dm.Hkv * p.nk * 16384 * 2;
+  p.RB = 512;
+  return p;
+}
+
+void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, const float* gs, const float* gr,
+              const SavedPtrs& sv, const void* dO, void* dq, void* dk, void* dv, float* dgs, float* dgr,
+              const FastBwdWs& ws, hipStream_t st) {
+  const FastBwdPlan pl = fast_bwd_plan(dm);
+  {
+    ProfScope ps("bwd_prep_kernel", st);
+    bwd_prep_kernel<<<dim3(pl.RB, dm.Hq), 256, 0, st>>>((const uint16_t*)dO, (const uint16_t*)sv.xs, (const uint16_t*)sv.xr,
+                                                        sv.rs, sv.rr, gs, gr, (uint16_t*)ws.dxs, (uint16_t*)ws.dxr,
+                                                        ws.delta, ws.dgpart, dm.B, dm.T, dm.Hq);
+  }
+  if (dgs || dgr) {
+    const int HD = dm.Hq * 128;
+    dgamma_reduce_kernel<<<(HD + 255) / 256, 256, 0, st>>>(ws.dgpart, dgs, dgr, pl.RB, HD);
+  }
+  rla_forward_states(dm, pl.fwd, k, v, ws.U, ws.states, st);
+  rla_reverse_states(dm, pl.fwd.W, pl.nk, q, ws.dxr, ws.U, ws.rstates, st);
+  FastBwdArgs a;
+  a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
+  a.dxs = (const uint16_t*)ws.dxs; a.dxr = (const uint16_t*)ws.dxr;
+  a.lse = sv.lse; a.delta = ws.delta;
+  a.states = (const uint16_t*)ws.states; a.rstates = (const uint16_t*)ws.rstates;
+  a.dq = (uint16_t*)dq; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv;
+  a.B = dm.B; a.T = dm.T; a.Hq = dm.Hq; a.Hkv = dm.Hkv; a.G = dm.G; a.W = pl.fwd.W;
+  a.nstf = pl.fwd.nstf; a.nk = pl.nk; a.ntile = dm.T / 128;
+  a.scale = dm.scale; a.scale_log2 = dm.scale * LOG2E;
+  {
+    ProfScope ps("bwd_dq_kernel", st);
+    bwd_dq_kernel<<<dim3(a.ntile * dm.Hq * dm.B), 256, 0, st>>>(a);
+  }
+  ProfScope ps("bwd_dkv_kernel", st);
+  bwd_dkv_kernel<<<dim3(a.ntile * dm.Hkv * dm.B), 256, 0, st>>>(a);
+}
+
+}  // namespace rattn

@@ -19,9 +19,6 @@ namespace rattn {
 
 namespace {
 
-constexpr float LOG2E = 1.4426950408889634f;
-constexpr float LN2 = 0.6931471805599453f;
-
 struct FastFwdArgs {
   const uint16_t *q, *k, *v;
   const float *gs, *gr;
@@ -31,52 +28,6 @@ struct FastFwdArgs {
   int B, T, Hq, Hkv, G, W, nstf, ntile;
   float scale_log2, eps;
 };
-
-// softmax over the 128 features of the row whose two halves sit in lanes l and l^32 (64 values each)
-__device__ __forceinline__ void phi_rows(float (&x)[64], bf16x8_t (&op)[8]) {
-  float m = x[0];
-#pragma unroll
-  for (int i = 1; i < 64; ++i) m = fmaxf(m, x[i]);
-  m = fmaxf(m, xhalf(m));
-  float s = 0.f;
-#pragma unroll
-  for (int i = 0; i < 64; ++i) { x[i] = exp2f((x[i] - m) * LOG2E); s += x[i]; }
-  s += xhalf(s);
-  const float inv = 1.f / s;
-#pragma unroll
-  for (int i = 0; i < 64; ++i) x[i] *= inv;
-#pragma unroll
-  for (int c = 0; c < 8; ++c) op[c] = pack_bf16x8(&x[8 * c]);
-}
-
-// Write a [128 queries x 128] bf16 tile held transposed in accumulators (lane = query column, register
-// (dt,i) = feature 32dt + 8(i/4) + 4h + i%4) to global rows of stride `row_stride`, through LDS.
-// vals[dt][i] must already be final.  All 256 threads call it; smem[0..32K) is used.
-__device__ __forceinline__ void store_tile_transposed(unsigned char* smem, const float (&vals)[4][16], uint16_t* dst,
-                                                      size_t row_stride, int w, int lane) {
-  const int r32 = lane & 31, h = lane >> 5;
-  const int row = 32 * w + r32;
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int i4 = 0; i4 < 4; ++i4) {
-      f32x4_t f = {vals[dt][4 * i4], vals[dt][4 * i4 + 1], vals[dt][4 * i4 + 2], vals[dt][4 * i4 + 3]};
-      bf16x4_t pk = __builtin_convertvector(f, bf16x4_t);
-      const int c = 4 * dt + i4;
-      *reinterpret_cast<bf16x4_t*>(smem + row * ROW_BYTES + ((c ^ (row & 15)) << 4) + 8 * h) = pk;
-    }
-  __syncthreads();
-  const int tid = threadIdx.x;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int id = tid + 256 * i;
-    const int r = id >> 4, p = id & 15;
-    const int c = p ^ (r & 15);
-    const uint4 val = *reinterpret_cast<const uint4*>(smem + r * ROW_BYTES + (p << 4));
-    *reinterpret_cast<uint4*>(dst + (size_t)r * row_stride + c * 8) = val;
-  }
-  __syncthreads();
-}
 
 template <bool MASKED>
 __device__ __forceinline__ void swa_subtile(const unsigned char* kt, const unsigned char* vt, int ks, int ka, int myq,
@@ -169,10 +120,10 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
     f32x16_t xr[4] = {{0}, {0}, {0}, {0}};
     if (has_state) {
       const uint16_t* sbase = a.states + ((size_t)(b * Hkv + g) * a.nstf + j0 / 128) * 16384;
-      tile_load_async<false, 8>(sbase, 128, smem, w * 8, lane);
-      tile_load_async<true, 4>(vbase + (size_t)j0 * kstride, kstride, smem + 32768, w * 4, lane);
+      tile_load_async<8>(sbase, 128, smem, w * 8, lane);
+      tile_load_async<4>(vbase + (size_t)j0 * kstride, kstride, smem + 32768, w * 4, lane);
     }
-    tile_load_async<true, 4>(vbase + (size_t)(j0 + 64) * kstride, kstride, smem + 49152, w * 4, lane);
+    tile_load_async<4>(vbase + (size_t)(j0 + 64) * kstride, kstride, smem + 49152, w * 4, lane);
     wait_vmem();
     __syncthreads();
     if (has_state) {
@@ -183,8 +134,8 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
           xr[dt] = mfma32(lds_row_chunk(smem, 32 * dt + r32, 2 * kf + h), qfop[kf], xr[dt]);
     }
     __syncthreads();
-    if (has_state) tile_load_async<false, 4>(kbase + (size_t)j0 * kstride, kstride, smem, w * 4, lane);
-    tile_load_async<false, 4>(kbase + (size_t)(j0 + 64) * kstride, kstride, smem + 16384, w * 4, lane);
+    if (has_state) tile_load_async<4>(kbase + (size_t)j0 * kstride, kstride, smem, w * 4, lane);
+    tile_load_async<4>(kbase + (size_t)(j0 + 64) * kstride, kstride, smem + 16384, w * 4, lane);
     wait_vmem();
     __syncthreads();
     for (int u = has_state ? 0 : 2; u <= w; ++u) {
@@ -264,8 +215,8 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
   const int ntiles = (t0 + 128 - kt_lo) / 64;
   {
     const int kt0 = kt_lo + 64 * (ntiles - 1);
-    tile_load_async<false, 4>(kbase + (size_t)kt0 * kstride, kstride, smem, w * 4, lane);
-    tile_load_async<true, 4>(vbase + (size_t)kt0 * kstride, kstride, smem + 32768, w * 4, lane);
+    tile_load_async<4>(kbase + (size_t)kt0 * kstride, kstride, smem, w * 4, lane);
+    tile_load_async<4>(vbase + (size_t)kt0 * kstride, kstride, smem + 32768, w * 4, lane);
     wait_vmem();
     __syncthreads();
   }
@@ -275,8 +226,8 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
     const int cur = n & 1;
     if (n + 1 < ntiles) {
       const int ktn = kt_lo + 64 * (it - 1);
-      tile_load_async<false, 4>(kbase + (size_t)ktn * kstride, kstride, smem + (cur ^ 1) * 16384, w * 4, lane);
-      tile_load_async<true, 4>(vbase + (size_t)ktn * kstride, kstride, smem + 32768 + (cur ^ 1) * 16384, w * 4, lane);
+      tile_load_async<4>(kbase + (size_t)ktn * kstride, kstride, smem + (cur ^ 1) * 16384, w * 4, lane);
+      tile_load_async<4>(vbase + (size_t)ktn * kstride, kstride, smem + 32768 + (cur ^ 1) * 16384, w * 4, lane);
     }
     const unsigned char* kt = smem + cur * 16384;
     const unsigned char* vt = smem + 32768 + cur * 16384;
@@ -342,98 +293,6 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
   }
 }
 
-// ------------------------------------------------------------------------------------------------
-// State pre-pass, step 1 (Eq. 2, chunk-local part): U_c^T = V_c^T phi(K_c) for one chunk of 64 or
-// 128 tokens of one KV head, fp32 [128 (d)][128 (f)].  grid (nchunks, Hkv, B), 256 threads.
-// Chunk 0 is the 64-token head chunk when `base` = 64; the others are 128 tokens starting at
-// base + 128*(c - (base > 0)).
-__global__ __launch_bounds__(256) void rla_chunk_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-                                                        float* __restrict__ U, int T, int Hkv, int base) {
-  __shared__ __align__(16) unsigned char smem[65536];
-  unsigned char* Kt = smem;
-  unsigned char* Vt = smem + 32768;
-  const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z, nchunks = gridDim.x;
-  const int lane = lane_id(), w = wave_id(), tid = threadIdx.x;
-  const int r32 = lane & 31, h = lane >> 5;
-  const int hb = base > 0 ? 1 : 0;
-  const int lo = (hb && c == 0) ? 0 : base + 128 * (c - hb);
-  const int ntok = (hb && c == 0) ? 64 : 128;
-  const size_t kstride = (size_t)Hkv * 128;
-  const uint16_t* kb = k + ((size_t)(b * T + lo) * Hkv + g) * 128;
-  const uint16_t* vb = v + ((size_t)(b * T + lo) * Hkv + g) * 128;
-  tile_load_async<true, 4>(kb, kstride, Kt, w * 4, lane);
-  tile_load_async<true, 4>(vb, kstride, Vt, w * 4, lane);
-  if (ntok == 128) {
-    tile_load_async<true, 4>(kb, kstride, Kt, 16 + w * 4, lane);
-    tile_load_async<true, 4>(vb, kstride, Vt, 16 + w * 4, lane);
-  }
-  wait_vmem();
-  __syncthreads();
-  // phi(K) in place: two threads per token row, 64 features each
-  {
-    const int row = tid >> 1, half = tid & 1;
-    if (row < ntok) {
-      float x[64];
-      unsigned char* rp = Kt + row * ROW_BYTES;
-      const int sw = (row & 3) << 2;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) unpack_bf16x8(*reinterpret_cast<const bf16x8_t*>(rp + (((8 * half + j) ^ sw) << 4)), &x[8 * j]);
-      float m = x[0];
-#pragma unroll
-      for (int i = 1; i < 64; ++i) m = fmaxf(m, x[i]);
-      m = fmaxf(m, __shfl_xor(m, 1, 64));
-      float s = 0.f;
-#pragma unroll
-      for (int i = 0; i < 64; ++i) { x[i] = exp2f((x[i] - m) * LOG2E); s += x[i]; }
-      s += __shfl_xor(s, 1, 64);
-      const float inv = 1.f / s;
-#pragma unroll
-      for (int i = 0; i < 64; ++i) x[i] *= inv;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) *reinterpret_cast<bf16x8_t*>(rp + (((8 * half + j) ^ sw) << 4)) = pack_bf16x8(&x[8 * j]);
-    }
-  }
-  __syncthreads();
-  f32x16_t acc[4] = {{0}, {0}, {0}, {0}};
-  for (int ks = 0; ks < ntok / 16; ++ks) {
-    const int k0 = 16 * ks + 8 * h;
-    const bf16x8_t aop = lds_tr_pair(Vt, k0, k0 + 4, 32 * w, lane);
-#pragma unroll
-    for (int ft = 0; ft < 4; ++ft) acc[ft] = mfma32(aop, lds_tr_pair(Kt, k0, k0 + 4, 32 * ft, lane), acc[ft]);
-  }
-  float* out = U + ((size_t)(b * Hkv + g) * nchunks + c) * 16384;
-#pragma unroll
-  for (int ft = 0; ft < 4; ++ft)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int d = 32 * w + 8 * (i >> 2) + 4 * h + (i & 3);
-      out[(size_t)d * 128 + 32 * ft + r32] = acc[ft][i];
-    }
-}
-
-// State pre-pass, step 2 (Eq. 2, inter-chunk scan): states[i] = sum of the chunks before key position
-// base + 128*i, accumulated in fp32, stored as bf16 (the MFMA operand precision).  Every state
-// element scans independently.  grid (16, Hkv, B), 256 threads, 4 elements per thread.
-__global__ __launch_bounds__(256) void rla_scan_kernel(const float* __restrict__ U, uint16_t* __restrict__ states,
-                                                       int nchunks, int nstf, int base) {
-  const int g = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
-  const int e4 = (blockIdx.x * 256 + threadIdx.x) * 4;
-  const float* Ub = U + (size_t)(b * Hkv + g) * nchunks * 16384 + e4;
-  uint16_t* Sb = states + (size_t)(b * Hkv + g) * nstf * 16384 + e4;
-  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  int c = 0;
-  if (base > 0) { acc = *reinterpret_cast<const float4*>(Ub); c = 1; }
-  for (int i = 0; i < nstf; ++i) {
-    f32x4_t f = {acc.x, acc.y, acc.z, acc.w};
-    *reinterpret_cast<bf16x4_t*>(Sb + (size_t)i * 16384) = __builtin_convertvector(f, bf16x4_t);
-    if (i + 1 < nstf) {
-      const float4 u = *reinterpret_cast<const float4*>(Ub + (size_t)c * 16384);
-      acc.x += u.x; acc.y += u.y; acc.z += u.z; acc.w += u.w;
-      ++c;
-    }
-  }
-}
-
 }  // namespace
 
 bool fast_fwd_supported(const LayerDims& dm, int dtype) {
@@ -458,15 +317,7 @@ FastFwdPlan fast_fwd_plan(const LayerDims& dm) {
 void fast_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, const float* gs, const float* gr,
               void* o, const SavedPtrs& sv, float* U, void* states, hipStream_t st) {
   const FastFwdPlan pl = fast_fwd_plan(dm);
-  if (pl.nstf > 0) {
-    if (pl.nchunks > 0) {
-      ProfScope ps("rla_chunk_kernel", st);
-      rla_chunk_kernel<<<dim3(pl.nchunks, dm.Hkv, dm.B), 256, 0, st>>>((const uint16_t*)k, (const uint16_t*)v, U, dm.T,
-                                                                       dm.Hkv, pl.base);
-    }
-    ProfScope ps("rla_scan_kernel", st);
-    rla_scan_kernel<<<dim3(16, dm.Hkv, dm.B), 256, 0, st>>>(U, (uint16_t*)states, pl.nchunks, pl.nstf, pl.base);
-  }
+  if (pl.nstf > 0) rla_forward_states(dm, pl, k, v, U, states, st);
   FastFwdArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
   a.gs = gs; a.gr = gr;

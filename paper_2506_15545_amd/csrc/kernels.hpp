@@ -60,6 +60,33 @@ FastFwdPlan fast_fwd_plan(const LayerDims& dm);
 void fast_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, const float* gs, const float* gr,
               void* o, const SavedPtrs& sv, float* U, void* states, hipStream_t st);
 
+// linear-branch chunk states for the MFMA paths (bf16 [d][f] per state, fp32 scratch U per chunk)
+void rla_forward_states(const LayerDims& dm, const FastFwdPlan& pl, const void* k, const void* v, float* U,
+                        void* states, hipStream_t st);
+// reverse-time states R_i = sum over t' >= 128(i+1) and over the group's heads of phi(q_{t'+W})^T dxr_{t'+W},
+// i in [0, nk), nk = ceil((T-W)/128); stored transposed [d][f] bf16.  U needs (nk-1) chunks.
+void rla_reverse_states(const LayerDims& dm, int W, int nk, const void* q, const void* dxr, float* U,
+                        void* rstates, hipStream_t st);
+
+// MFMA backward path (same shape class as the MFMA forward)
+struct FastBwdPlan {
+  FastFwdPlan fwd;
+  int nk;  // key tiles that have a linear branch = number of reverse states
+  int RB;  // row blocks of the prep kernel (dgamma partials)
+  size_t u_bytes, rstate_bytes;
+};
+struct FastBwdWs {
+  void *dxs, *dxr;       // bf16 [B,T,Hq,128]
+  float* delta;          // [B,Hq,T]
+  float* U;              // chunk scratch
+  void *states, *rstates;
+  float* dgpart;         // [2,RB,Hq,128]
+};
+FastBwdPlan fast_bwd_plan(const LayerDims& dm);
+void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, const float* gs, const float* gr,
+              const SavedPtrs& sv, const void* dO, void* dq, void* dk, void* dv, float* dgs, float* dgr,
+              const FastBwdWs& ws, hipStream_t st);
+
 struct DecodeDims {
   int N, Hq, Hkv, D, W, G;
   float scale, eps;

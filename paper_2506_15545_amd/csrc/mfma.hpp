@@ -8,9 +8,11 @@
 //   lane i of the group receives M[k0+0..3][n0+i]: a 4(k) x 16(n) block of a row-major matrix is
 //   delivered k-contiguous per lane, which is what an MFMA operand wants when memory is n-contiguous.
 // Tiles in LDS are rows of 128 bf16 (256 bytes = 16 chunks of 16 bytes); the chunk index is XOR-swizzled
-// with the row so that both access patterns are bank-conflict free without padding:
-//   "row" swizzle  (operand rows read with ds_read_b128, 16 lanes on 16 consecutive rows): chunk ^ (row & 15)
-//   "tr" swizzle   (operand read with ds_read_b64_tr_b16, 4 consecutive rows x 64 bytes): chunk ^ ((row & 3) << 2)
+// with swz(row) = ((row & 3) << 2) | ((row >> 2) & 3) so that both access patterns are bank-conflict free
+// without padding:
+//   row reads (ds_read_b128, 16 lanes on 16 consecutive rows, same logical chunk): swz takes 16 values
+//   tr reads  (ds_read_b64_tr_b16, 4 consecutive rows x 64 bytes per half-wave): the upper two bits of
+//             swz differ between the 4 rows, so the four 64-byte pieces land in different bank groups
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -30,6 +32,8 @@ typedef float f32x2_t __attribute__((ext_vector_type(2)));
 
 constexpr int ROW_BYTES = 256;  // 128 bf16
 
+__device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+
 __device__ __forceinline__ f32x16_t mfma32(bf16x8_t a, bf16x8_t b, f32x16_t c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
@@ -40,7 +44,7 @@ __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70)
 // Asynchronously copy `NBLK` blocks of 4 rows x 256 bytes from global memory into an LDS tile, direct to
 // LDS (no VGPR staging).  Block index blk0 + i, lane l lands at tile + blk*1024 + l*16, i.e. row
 // 4*blk + l/16, physical chunk l%16; it fetches the logical chunk that the swizzle maps there.
-template <bool TR_SWZ, int NBLK>
+template <int NBLK>
 __device__ __forceinline__ void tile_load_async(const uint16_t* gbase, size_t row_stride, unsigned char* tile,
                                                 int blk0, int lane) {
 #pragma unroll
@@ -48,18 +52,18 @@ __device__ __forceinline__ void tile_load_async(const uint16_t* gbase, size_t ro
     const int blk = blk0 + i;
     const int r = blk * 4 + (lane >> 4);
     const int p = lane & 15;
-    const int c = TR_SWZ ? (p ^ ((r & 3) << 2)) : (p ^ (r & 15));
+    const int c = p ^ swz(r);
     const uint16_t* g = gbase + (size_t)r * row_stride + c * 8;
     __builtin_amdgcn_global_load_lds(g, RATTN_LDS(tile + blk * 1024), 16, 0, 0);
   }
 }
 
-// operand whose rows are tile rows ("row" swizzle): 8 consecutive elements at logical chunk c of row r
+// operand whose rows are tile rows: 8 consecutive elements at logical chunk c of row r
 __device__ __forceinline__ bf16x8_t lds_row_chunk(const unsigned char* tile, int r, int c) {
-  return *reinterpret_cast<const bf16x8_t*>(tile + r * ROW_BYTES + ((c ^ (r & 15)) << 4));
+  return *reinterpret_cast<const bf16x8_t*>(tile + r * ROW_BYTES + ((c ^ swz(r)) << 4));
 }
 
-// operand whose rows are tile COLUMNS ("tr" swizzle).  Lane (r = lane%32, h = lane/32) receives
+// operand whose rows are tile COLUMNS.  Lane (r = lane%32, h = lane/32) receives
 // tile[ka + 0..3][col0 + r] and tile[kb + 0..3][col0 + r]  (ka, kb multiples of 4, per-lane values allowed
 // as long as they are equal within each 16-lane group), col0 a multiple of 32.
 __device__ __forceinline__ bf16x8_t lds_tr_pair(const unsigned char* tile, int ka, int kb, int col0, int lane) {
@@ -68,8 +72,8 @@ __device__ __forceinline__ bf16x8_t lds_tr_pair(const unsigned char* tile, int k
   const int c = (col0 >> 3) + 2 * (gi & 1) + ((i & 3) >> 1);
   const int boff = (i & 1) << 3;
   const int ra = ka + j, rb = kb + j;
-  const unsigned char* pa = tile + ra * ROW_BYTES + ((c ^ ((ra & 3) << 2)) << 4) + boff;
-  const unsigned char* pb = tile + rb * ROW_BYTES + ((c ^ ((rb & 3) << 2)) << 4) + boff;
+  const unsigned char* pa = tile + ra * ROW_BYTES + ((c ^ swz(ra)) << 4) + boff;
+  const unsigned char* pb = tile + rb * ROW_BYTES + ((c ^ swz(rb)) << 4) + boff;
   s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(pa));
   s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(pb));
   union { struct { s16x4_t lo, hi; } s; bf16x8_t v; } u;
@@ -90,5 +94,84 @@ __device__ __forceinline__ void unpack_bf16x8(bf16x8_t v, float* x) {
 
 // value of the same register in lane ^ 32
 __device__ __forceinline__ float xhalf(float x) { return __shfl_xor(x, 32, 64); }
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+// phi = softmax over the 128 features of a row whose two halves sit in lanes l and l^32 (64 values
+// each, any fixed order); result packed as 8 MFMA operand registers in the same order
+__device__ __forceinline__ void phi_rows(float (&x)[64], bf16x8_t (&op)[8]) {
+  float m = x[0];
+#pragma unroll
+  for (int i = 1; i < 64; ++i) m = fmaxf(m, x[i]);
+  m = fmaxf(m, xhalf(m));
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 64; ++i) { x[i] = exp2f((x[i] - m) * LOG2E); s += x[i]; }
+  s += xhalf(s);
+  const float inv = 1.f / s;
+#pragma unroll
+  for (int i = 0; i < 64; ++i) x[i] *= inv;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) op[c] = pack_bf16x8(&x[8 * c]);
+}
+
+// phi applied in place to the first `nrows` (<= 128) rows of an LDS tile: two threads per row.
+// Call with all 256 threads; the caller synchronises before and after.
+__device__ __forceinline__ void phi_tile_inplace(unsigned char* tile, int nrows) {
+  const int row = threadIdx.x >> 1, half = threadIdx.x & 1;
+  if (row < nrows) {
+    float x[64];
+    unsigned char* rp = tile + row * ROW_BYTES;
+    const int sw = swz(row);
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      unpack_bf16x8(*reinterpret_cast<const bf16x8_t*>(rp + (((8 * half + j) ^ sw) << 4)), &x[8 * j]);
+    float m = x[0];
+#pragma unroll
+    for (int i = 1; i < 64; ++i) m = fmaxf(m, x[i]);
+    m = fmaxf(m, __shfl_xor(m, 1, 64));
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 64; ++i) { x[i] = exp2f((x[i] - m) * LOG2E); s += x[i]; }
+    s += __shfl_xor(s, 1, 64);
+    const float inv = 1.f / s;
+#pragma unroll
+    for (int i = 0; i < 64; ++i) x[i] *= inv;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      *reinterpret_cast<bf16x8_t*>(rp + (((8 * half + j) ^ sw) << 4)) = pack_bf16x8(&x[8 * j]);
+  }
+}
+
+// Write a [128 rows x 128] bf16 tile held transposed in accumulators (lane = tile row 32w + lane%32,
+// register (dt,i) = column 32dt + 8(i/4) + 4h + i%4) to global rows of stride `row_stride`, through
+// LDS so that the global stores are 16 bytes per lane and row-contiguous.  All 256 threads call it;
+// smem[0..32K) is used and is free again on return.
+__device__ __forceinline__ void store_tile_transposed(unsigned char* smem, const float (&vals)[4][16], uint16_t* dst,
+                                                      size_t row_stride, int w, int lane) {
+  const int r32 = lane & 31, h = lane >> 5;
+  const int row = 32 * w + r32;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      f32x4_t f = {vals[dt][4 * i4], vals[dt][4 * i4 + 1], vals[dt][4 * i4 + 2], vals[dt][4 * i4 + 3]};
+      bf16x4_t pk = __builtin_convertvector(f, bf16x4_t);
+      const int c = 4 * dt + i4;
+      *reinterpret_cast<bf16x4_t*>(smem + row * ROW_BYTES + ((c ^ swz(row)) << 4) + 8 * h) = pk;
+    }
+  __syncthreads();
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int id = tid + 256 * i;
+    const int r = id >> 4, p = id & 15;
+    const int c = p ^ swz(r);
+    const uint4 val = *reinterpret_cast<const uint4*>(smem + r * ROW_BYTES + (p << 4));
+    *reinterpret_cast<uint4*>(dst + (size_t)r * row_stride + c * 8) = val;
+  }
+  __syncthreads();
+}
 
 }  // namespace rattn

@@ -1,0 +1,133 @@
+// Chunk states of the linear branch for the MFMA paths (Eq. 2): chunk-local outer-product sums on the
+// matrix cores, then an element-wise scan over chunks in fp32, stored as bf16 MFMA operands.
+// States are kept transposed, [value feature d][phi feature f], because that is the row-major operand
+// the consumers need.
+#include "common.hpp"
+#include "kernels.hpp"
+#include "mfma.hpp"
+
+namespace rattn {
+
+namespace {
+
+struct ChunkArgs {
+  const uint16_t* a;   // rows that go through phi  (k, or q for the reverse states)
+  const uint16_t* b;   // rows multiplied in        (v, or dx_r)
+  float* U;            // [B,Hkv,nchunks,128,128] fp32, U^T = B^T phi(A)
+  int T, H, GA;        // heads in a/b, heads summed per kv head
+  int tok_off;         // token index = t' + tok_off
+  int first_lo, first_n, rest_lo, tok_end;  // chunk 0 = [first_lo, +first_n); chunk c>0 starts at rest_lo+128(c-1)
+};
+
+// grid (nchunks, Hkv, B), 256 threads.  Wave w owns rows d in [32w, 32w+32) of U^T.
+__global__ __launch_bounds__(256) void rla_chunk_kernel(ChunkArgs p) {
+  __shared__ __align__(16) unsigned char smem[65536];
+  unsigned char* At = smem;
+  unsigned char* Bt = smem + 32768;
+  const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z, nchunks = gridDim.x, Hkv = gridDim.y;
+  const int lane = lane_id(), w = wave_id();
+  const int r32 = lane & 31, h = lane >> 5;
+  const int lo = c == 0 ? p.first_lo : p.rest_lo + 128 * (c - 1);
+  const int ntok = min(c == 0 ? p.first_n : 128, p.tok_end - lo);  // 64 or 128
+  const size_t rstride = (size_t)p.H * 128;
+  f32x16_t acc[4] = {{0}, {0}, {0}, {0}};
+  for (int ga = 0; ga < p.GA; ++ga) {
+    const size_t off = ((size_t)(b * p.T + lo + p.tok_off) * p.H + g * p.GA + ga) * 128;
+    if (ga > 0) __syncthreads();
+    tile_load_async<4>(p.a + off, rstride, At, w * 4, lane);
+    tile_load_async<4>(p.b + off, rstride, Bt, w * 4, lane);
+    if (ntok == 128) {
+      tile_load_async<4>(p.a + off, rstride, At, 16 + w * 4, lane);
+      tile_load_async<4>(p.b + off, rstride, Bt, 16 + w * 4, lane);
+    }
+    wait_vmem();
+    __syncthreads();
+    phi_tile_inplace(At, ntok);
+    __syncthreads();
+    for (int ks = 0; ks < ntok / 16; ++ks) {
+      const int k0 = 16 * ks + 8 * h;
+      const bf16x8_t aop = lds_tr_pair(Bt, k0, k0 + 4, 32 * w, lane);
+#pragma unroll
+      for (int ft = 0; ft < 4; ++ft) acc[ft] = mfma32(aop, lds_tr_pair(At, k0, k0 + 4, 32 * ft, lane), acc[ft]);
+    }
+  }
+  float* out = p.U + ((size_t)(b * Hkv + g) * nchunks + c) * 16384;
+#pragma unroll
+  for (int ft = 0; ft < 4; ++ft)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int d = 32 * w + 8 * (i >> 2) + 4 * h + (i & 3);
+      out[(size_t)d * 128 + 32 * ft + r32] = acc[ft][i];
+    }
+}
+
+// Exclusive scan over chunks, every state element independently, fp32 accumulation, bf16 output.
+//   forward: state[0] = (head ? U[0] : 0); state[i+1] = state[i] + U[c++]
+//   reverse: state[n-1] = 0; state[i] = state[i+1] + U[i]
+// grid (16, Hkv, B), 256 threads, 4 elements per thread.
+template <bool REV>
+__global__ __launch_bounds__(256) void rla_scan_kernel(const float* __restrict__ U, uint16_t* __restrict__ states,
+                                                       int nchunks, int nst, int head) {
+  const int g = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
+  const int e4 = (blockIdx.x * 256 + threadIdx.x) * 4;
+  const float* Ub = U + (size_t)(b * Hkv + g) * nchunks * 16384 + e4;
+  uint16_t* Sb = states + (size_t)(b * Hkv + g) * nst * 16384 + e4;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  auto put = [&](int i) {
+    f32x4_t f = {acc.x, acc.y, acc.z, acc.w};
+    *reinterpret_cast<bf16x4_t*>(Sb + (size_t)i * 16384) = __builtin_convertvector(f, bf16x4_t);
+  };
+  auto add = [&](int c) {
+    const float4 u = *reinterpret_cast<const float4*>(Ub + (size_t)c * 16384);
+    acc.x += u.x; acc.y += u.y; acc.z += u.z; acc.w += u.w;
+  };
+  if (!REV) {
+    int c = 0;
+    if (head) { add(0); c = 1; }
+    for (int i = 0; i < nst; ++i) {
+      put(i);
+      if (i + 1 < nst) add(c++);
+    }
+  } else {
+    for (int i = nst - 1; i >= 0; --i) {
+      put(i);
+      if (i > 0) add(i - 1);
+    }
+  }
+}
+
+}  // namespace
+
+void rla_forward_states(const LayerDims& dm, const FastFwdPlan& pl, const void* k, const void* v, float* U,
+                        void* states, hipStream_t st) {
+  if (pl.nstf <= 0) return;
+  if (pl.nchunks > 0) {
+    ChunkArgs p;
+    p.a = (const uint16_t*)k; p.b = (const uint16_t*)v; p.U = U;
+    p.T = dm.T; p.H = dm.Hkv; p.GA = 1; p.tok_off = 0;
+    p.first_lo = 0; p.first_n = pl.base > 0 ? 64 : 128; p.rest_lo = pl.base > 0 ? 64 : 128; p.tok_end = 1 << 30;
+    ProfScope ps("rla_chunk_kernel", st);
+    rla_chunk_kernel<<<dim3(pl.nchunks, dm.Hkv, dm.B), 256, 0, st>>>(p);
+  }
+  ProfScope ps("rla_scan_kernel", st);
+  rla_scan_kernel<false><<<dim3(16, dm.Hkv, dm.B), 256, 0, st>>>(U, (uint16_t*)states, pl.nchunks, pl.nstf,
+                                                                  pl.base > 0 ? 1 : 0);
+}
+
+void rla_reverse_states(const LayerDims& dm, int W, int nk, const void* q, const void* dxr, float* U, void* rstates,
+                        hipStream_t st) {
+  if (nk <= 0) return;
+  const int Tp = dm.T - W;
+  if (nk > 1) {
+    ChunkArgs p;
+    p.a = (const uint16_t*)q; p.b = (const uint16_t*)dxr; p.U = U;
+    p.T = dm.T; p.H = dm.Hq; p.GA = dm.G; p.tok_off = W;
+    p.first_lo = 128; p.first_n = 128; p.rest_lo = 256; p.tok_end = Tp;
+    ProfScope ps("rla_chunk_kernel(rev)", st);
+    rla_chunk_kernel<<<dim3(nk - 1, dm.Hkv, dm.B), 256, 0, st>>>(p);
+  }
+  ProfScope ps("rla_scan_kernel(rev)", st);
+  rla_scan_kernel<true><<<dim3(16, dm.Hkv, dm.B), 256, 0, st>>>(U, (uint16_t*)rstates, nk - 1, nk, 0);
+}
+
+}  // namespace rattn
