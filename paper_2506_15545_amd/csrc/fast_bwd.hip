@@ -107,11 +107,11 @@ __device__ __forceinline__ void phi_row_clayout(const uint16_t* src, int h, floa
   float m = x[0];
 #pragma unroll
   for (int i = 1; i < 64; ++i) m = fmaxf(m, x[i]);
-  m = fmaxf(m, xhalf(m));
+  m = half_max(m);
   float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < 64; ++i) { x[i] = exp2f((x[i] - m) * LOG2E); s += x[i]; }
-  s += xhalf(s);
+  for (int i = 0; i < 64; ++i) { x[i] = fast_exp2((x[i] - m) * LOG2E); s += x[i]; }
+  s = half_sum(s);
   const float inv = 1.f / s;
 #pragma unroll
   for (int i = 0; i < 64; ++i) x[i] *= inv;
@@ -124,7 +124,7 @@ __device__ __forceinline__ void phi_jacobian(f32x16_t (&acc)[4], const float (&f
   for (int ft = 0; ft < 4; ++ft)
 #pragma unroll
     for (int i = 0; i < 16; ++i) inner += acc[ft][i] * f[ft * 16 + i];
-  inner += xhalf(inner);
+  inner = half_sum(inner);
 #pragma unroll
   for (int ft = 0; ft < 4; ++ft)
 #pragma unroll
@@ -141,17 +141,17 @@ template <bool MASKED>
 __device__ __forceinline__ void dq_subtile(const unsigned char* kt, const unsigned char* vt, int ks, int ka, int myq,
                                            int W, float scale, float scale_log2, float lse2, float dl,
                                            const bf16x8_t (&qop)[8], const bf16x8_t (&dxsop)[8], f32x16_t (&acc)[4],
-                                           int lane) {
+                                           int lane, const LaneOff& lo) {
   const int r32 = lane & 31, h = lane >> 5;
   f32x16_t s = {0}, dp = {0};
 #pragma unroll
-  for (int c = 0; c < 8; ++c) s = mfma32(lds_row_chunk(kt, 32 * ks + r32, 2 * c + h), qop[c], s);
+  for (int c = 0; c < 8; ++c) s = mfma32(lds_row(kt, lo, 32 * ks, c), qop[c], s);
 #pragma unroll
-  for (int c = 0; c < 8; ++c) dp = mfma32(lds_row_chunk(vt, 32 * ks + r32, 2 * c + h), dxsop[c], dp);
+  for (int c = 0; c < 8; ++c) dp = mfma32(lds_row(vt, lo, 32 * ks, c), dxsop[c], dp);
   float ds[16];
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
-    float p = exp2f(s[i] * scale_log2 - lse2);
+    float p = fast_exp2(s[i] * scale_log2 - lse2);
     if (MASKED) {
       const int key = ka + 8 * (i >> 2) + 4 * h + (i & 3);
       p = (key <= myq && key > myq - W) ? p : 0.f;
@@ -161,9 +161,8 @@ __device__ __forceinline__ void dq_subtile(const unsigned char* kt, const unsign
   bf16x8_t dsop[2] = {pack_bf16x8(&ds[0]), pack_bf16x8(&ds[8])};
 #pragma unroll
   for (int mf = 0; mf < 2; ++mf) {
-    const int k0 = 32 * ks + 16 * mf + 4 * h;
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) acc[dt] = mfma32(lds_tr_pair(kt, k0, k0 + 8, 32 * dt, lane), dsop[mf], acc[dt]);
+    for (int dt = 0; dt < 4; ++dt) acc[dt] = mfma32(lds_trp(kt, lo, 32 * ks + 16 * mf, dt), dsop[mf], acc[dt]);
   }
 }
 
@@ -172,6 +171,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
   __shared__ __align__(16) unsigned char smem[65536];
   const int lane = lane_id(), w = wave_id();
   const int r32 = lane & 31, h = lane >> 5;
+  const LaneOff lo = make_lane_off(lane);
+  const LaneOffN lon = make_lane_off_n(lane);
   const int T = a.T, W = a.W, Hq = a.Hq, Hkv = a.Hkv, G = a.G;
   const int total = gridDim.x, bid = blockIdx.x;
   int wid = (total % 8 == 0) ? (bid % 8) * (total / 8) + bid / 8 : bid;
@@ -210,9 +211,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
     if (has_state) {
 #pragma unroll
       for (int kd = 0; kd < 8; ++kd) {
-        const int k0 = 16 * kd + 8 * h;
 #pragma unroll
-        for (int ft = 0; ft < 4; ++ft) acc[ft] = mfma32(lds_tr_pair(smem, k0, k0 + 4, 32 * ft, lane), dxrop[kd], acc[ft]);
+        for (int ft = 0; ft < 4; ++ft) acc[ft] = mfma32(lds_trn(smem, lon, 16 * kd, ft), dxrop[kd], acc[ft]);
       }
     }
     __syncthreads();
@@ -229,7 +229,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
       const int ks = u & 1;
       f32x16_t c = {0};
 #pragma unroll
-      for (int kd = 0; kd < 8; ++kd) c = mfma32(lds_row_chunk(vt, 32 * ks + r32, 2 * kd + h), dxrop[kd], c);
+      for (int kd = 0; kd < 8; ++kd) c = mfma32(lds_row(vt, lo, 32 * ks, kd), dxrop[kd], c);
       float cv[16];
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
@@ -239,9 +239,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
       bf16x8_t cop[2] = {pack_bf16x8(&cv[0]), pack_bf16x8(&cv[8])};
 #pragma unroll
       for (int mf = 0; mf < 2; ++mf) {
-        const int k0 = 32 * ks + 16 * mf + 4 * h;
 #pragma unroll
-        for (int ft = 0; ft < 4; ++ft) acc[ft] = mfma32(lds_tr_pair(kt, k0, k0 + 8, 32 * ft, lane), cop[mf], acc[ft]);
+        for (int ft = 0; ft < 4; ++ft) acc[ft] = mfma32(lds_trp(kt, lo, 32 * ks + 16 * mf, ft), cop[mf], acc[ft]);
       }
     }
     __syncthreads();
@@ -282,8 +281,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
       const bool need = ka <= qb && ka + 31 >= qa - W + 1;
       if (need) {
         const bool full = ka + 31 <= qa && ka >= qb - W + 1;
-        if (full) dq_subtile<false>(kt, vt, ks, ka, myq, W, a.scale, a.scale_log2, lse2, dl, qop, dxsop, acc, lane);
-        else dq_subtile<true>(kt, vt, ks, ka, myq, W, a.scale, a.scale_log2, lse2, dl, qop, dxsop, acc, lane);
+        if (full) dq_subtile<false>(kt, vt, ks, ka, myq, W, a.scale, a.scale_log2, lse2, dl, qop, dxsop, acc, lane, lo);
+        else dq_subtile<true>(kt, vt, ks, ka, myq, W, a.scale, a.scale_log2, lse2, dl, qop, dxsop, acc, lane, lo);
       }
     }
     wait_vmem();
@@ -302,13 +301,13 @@ template <bool MASKED>
 __device__ __forceinline__ void dkv_subtile(const unsigned char* qt, const unsigned char* dxt, int qs, int qa, int mykey,
                                             int W, float scale, float scale_log2, const float* lse_row,
                                             const float* delta_row, const bf16x8_t (&kop)[8], const bf16x8_t (&vop)[8],
-                                            f32x16_t (&dk)[4], f32x16_t (&dv)[4], int lane) {
+                                            f32x16_t (&dk)[4], f32x16_t (&dv)[4], int lane, const LaneOff& lo) {
   const int r32 = lane & 31, h = lane >> 5;
   f32x16_t s = {0}, dp = {0};
 #pragma unroll
-  for (int c = 0; c < 8; ++c) s = mfma32(lds_row_chunk(qt, 32 * qs + r32, 2 * c + h), kop[c], s);
+  for (int c = 0; c < 8; ++c) s = mfma32(lds_row(qt, lo, 32 * qs, c), kop[c], s);
 #pragma unroll
-  for (int c = 0; c < 8; ++c) dp = mfma32(lds_row_chunk(dxt, 32 * qs + r32, 2 * c + h), vop[c], dp);
+  for (int c = 0; c < 8; ++c) dp = mfma32(lds_row(dxt, lo, 32 * qs, c), vop[c], dp);
   float pv[16], ds[16];
 #pragma unroll
   for (int i4 = 0; i4 < 4; ++i4) {
@@ -319,7 +318,7 @@ __device__ __forceinline__ void dkv_subtile(const unsigned char* qt, const unsig
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int i = 4 * i4 + e;
-      float p = exp2f(s[i] * scale_log2 - lsa[e] * LOG2E);
+      float p = fast_exp2(s[i] * scale_log2 - lsa[e] * LOG2E);
       if (MASKED) {
         const int query = qrow + e;
         p = (mykey <= query && query - mykey < W) ? p : 0.f;
@@ -332,20 +331,21 @@ __device__ __forceinline__ void dkv_subtile(const unsigned char* qt, const unsig
   bf16x8_t dsop[2] = {pack_bf16x8(&ds[0]), pack_bf16x8(&ds[8])};
 #pragma unroll
   for (int mf = 0; mf < 2; ++mf) {
-    const int k0 = 32 * qs + 16 * mf + 4 * h;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) {
-      dv[dt] = mfma32(lds_tr_pair(dxt, k0, k0 + 8, 32 * dt, lane), pop[mf], dv[dt]);
-      dk[dt] = mfma32(lds_tr_pair(qt, k0, k0 + 8, 32 * dt, lane), dsop[mf], dk[dt]);
+      dv[dt] = mfma32(lds_trp(dxt, lo, 32 * qs + 16 * mf, dt), pop[mf], dv[dt]);
+      dk[dt] = mfma32(lds_trp(qt, lo, 32 * qs + 16 * mf, dt), dsop[mf], dk[dt]);
     }
   }
 }
 
 // grid (ntile * Hkv * B), 256 threads: 128 keys of one KV head, wave w owns 32 (lane = key).
-__global__ __launch_bounds__(256, 2) void bwd_dkv_kernel(FastBwdArgs a) {
+__global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(FastBwdArgs a) {
   __shared__ __align__(16) unsigned char smem[65536];
   const int lane = lane_id(), w = wave_id();
   const int r32 = lane & 31, h = lane >> 5;
+  const LaneOff lo = make_lane_off(lane);
+  const LaneOffN lon = make_lane_off_n(lane);
   const int T = a.T, W = a.W, Hq = a.Hq, Hkv = a.Hkv, G = a.G;
   const int total = gridDim.x, bid = blockIdx.x;
   int wid = (total % 8 == 0) ? (bid % 8) * (total / 8) + bid / 8 : bid;
@@ -380,11 +380,10 @@ __global__ __launch_bounds__(256, 2) void bwd_dkv_kernel(FastBwdArgs a) {
     __syncthreads();
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
-      const int k0 = 16 * c + 8 * h;
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
-        dv[t] = mfma32(lds_row_chunk(smem, 32 * t + r32, 2 * c + h), kfop[c], dv[t]);
-        dk[t] = mfma32(lds_tr_pair(smem, k0, k0 + 4, 32 * t, lane), vop[c], dk[t]);
+        dv[t] = mfma32(lds_row(smem, lo, 32 * t, c), kfop[c], dv[t]);
+        dk[t] = mfma32(lds_trn(smem, lon, 16 * c, t), vop[c], dk[t]);
       }
     }
     for (int hh = 0; hh < G; ++hh) {
@@ -403,9 +402,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dkv_kernel(FastBwdArgs a) {
       for (int u = w; u < nq / 32; ++u) {
         f32x16_t c = {0}, dc = {0};
 #pragma unroll
-        for (int e = 0; e < 8; ++e) c = mfma32(lds_row_chunk(smem, 32 * u + r32, 2 * e + h), kfop[e], c);
+        for (int e = 0; e < 8; ++e) c = mfma32(lds_row(smem, lo, 32 * u, e), kfop[e], c);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) dc = mfma32(lds_row_chunk(smem + 32768, 32 * u + r32, 2 * e + h), vop[e], dc);
+        for (int e = 0; e < 8; ++e) dc = mfma32(lds_row(smem + 32768, lo, 32 * u, e), vop[e], dc);
         float cv[16], dcv[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -418,11 +417,10 @@ __global__ __launch_bounds__(256, 2) void bwd_dkv_kernel(FastBwdArgs a) {
         bf16x8_t dcop[2] = {pack_bf16x8(&dcv[0]), pack_bf16x8(&dcv[8])};
 #pragma unroll
         for (int mf = 0; mf < 2; ++mf) {
-          const int k0 = 32 * u + 16 * mf + 4 * h;
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
-            dv[t] = mfma32(lds_tr_pair(smem + 32768, k0, k0 + 8, 32 * t, lane), cop[mf], dv[t]);
-            dk[t] = mfma32(lds_tr_pair(smem, k0, k0 + 8, 32 * t, lane), dcop[mf], dk[t]);
+            dv[t] = mfma32(lds_trp(smem + 32768, lo, 32 * u + 16 * mf, t), cop[mf], dv[t]);
+            dk[t] = mfma32(lds_trp(smem, lo, 32 * u + 16 * mf, t), dcop[mf], dk[t]);
           }
         }
       }
@@ -461,8 +459,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dkv_kernel(FastBwdArgs a) {
       const bool need = qa + 31 >= ka && qa <= ka + 31 + W - 1;
       if (need) {
         const bool full = qa >= ka + 31 && qa + 31 <= ka + W - 1;
-        if (full) dkv_subtile<false>(qtile, dxt, qs, qa, mykey, W, a.scale, a.scale_log2, lse_row, delta_row, kop, vop, dk, dv, lane);
-        else dkv_subtile<true>(qtile, dxt, qs, qa, mykey, W, a.scale, a.scale_log2, lse_row, delta_row, kop, vop, dk, dv, lane);
+        if (full) dkv_subtile<false>(qtile, dxt, qs, qa, mykey, W, a.scale, a.scale_log2, lse_row, delta_row, kop, vop, dk, dv, lane, lo);
+        else dkv_subtile<true>(qtile, dxt, qs, qa, mykey, W, a.scale, a.scale_log2, lse_row, delta_row, kop, vop, dk, dv, lane, lo);
       }
     }
     wait_vmem();

@@ -32,11 +32,11 @@ struct FastFwdArgs {
 template <bool MASKED>
 __device__ __forceinline__ void swa_subtile(const unsigned char* kt, const unsigned char* vt, int ks, int ka, int myq,
                                             int W, float scale_log2, const bf16x8_t (&qop)[8], f32x16_t (&oacc)[4],
-                                            float& m, float& l, int lane) {
+                                            float& m, float& l, int lane, const LaneOff& lo) {
   const int r32 = lane & 31, h = lane >> 5;
   f32x16_t s = {0};
 #pragma unroll
-  for (int dk = 0; dk < 8; ++dk) s = mfma32(lds_row_chunk(kt, 32 * ks + r32, 2 * dk + h), qop[dk], s);
+  for (int dk = 0; dk < 8; ++dk) s = mfma32(lds_row(kt, lo, 32 * ks, dk), qop[dk], s);
   float x[16];
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
@@ -50,12 +50,12 @@ __device__ __forceinline__ void swa_subtile(const unsigned char* kt, const unsig
   float mx = x[0];
 #pragma unroll
   for (int i = 1; i < 16; ++i) mx = fmaxf(mx, x[i]);
-  mx = fmaxf(mx, xhalf(mx));
+  mx = half_max(mx);
   const float m_new = fmaxf(m, mx);
-  const float alpha = exp2f(m - m_new);
+  const float alpha = fast_exp2(m - m_new);
   float ps = 0.f;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) { x[i] = exp2f(x[i] - m_new); ps += x[i]; }
+  for (int i = 0; i < 16; ++i) { x[i] = fast_exp2(x[i] - m_new); ps += x[i]; }
   l = l * alpha + ps;
   m = m_new;
   if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
@@ -65,9 +65,8 @@ __device__ __forceinline__ void swa_subtile(const unsigned char* kt, const unsig
   bf16x8_t pop[2] = {pack_bf16x8(&x[0]), pack_bf16x8(&x[8])};
 #pragma unroll
   for (int mf = 0; mf < 2; ++mf) {
-    const int k0 = 32 * ks + 16 * mf + 4 * h;
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) oacc[dt] = mfma32(lds_tr_pair(vt, k0, k0 + 8, 32 * dt, lane), pop[mf], oacc[dt]);
+    for (int dt = 0; dt < 4; ++dt) oacc[dt] = mfma32(lds_trp(vt, lo, 32 * ks + 16 * mf, dt), pop[mf], oacc[dt]);
   }
 }
 
@@ -75,6 +74,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
   __shared__ __align__(16) unsigned char smem[65536];
   const int lane = lane_id(), w = wave_id();
   const int r32 = lane & 31, h = lane >> 5;
+  const LaneOff lo = make_lane_off(lane);
   const int T = a.T, W = a.W, Hq = a.Hq, Hkv = a.Hkv, G = a.G;
 
   // work id: consecutive ids share a KV head (its G query heads, then the next query tile); each XCD
@@ -131,27 +131,23 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
       for (int kf = 0; kf < 8; ++kf)
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
-          xr[dt] = mfma32(lds_row_chunk(smem, 32 * dt + r32, 2 * kf + h), qfop[kf], xr[dt]);
+          xr[dt] = mfma32(lds_row(smem, lo, 32 * dt, kf), qfop[kf], xr[dt]);
     }
     __syncthreads();
     if (has_state) tile_load_async<4>(kbase + (size_t)j0 * kstride, kstride, smem, w * 4, lane);
     tile_load_async<4>(kbase + (size_t)(j0 + 64) * kstride, kstride, smem + 16384, w * 4, lane);
     wait_vmem();
     __syncthreads();
+    if (has_state) phi_tile_inplace(smem, 128);
+    else phi_tile_inplace(smem + 16384, 64);
+    __syncthreads();
     for (int u = has_state ? 0 : 2; u <= w; ++u) {
       const unsigned char* kt = smem + (u >> 1) * 16384;
       const unsigned char* vt = smem + 32768 + (u >> 1) * 16384;
       const int ks = u & 1;
-      bf16x8_t kfop[8];
-      {
-        float x[64];
-#pragma unroll
-        for (int dk = 0; dk < 8; ++dk) unpack_bf16x8(lds_row_chunk(kt, 32 * ks + r32, 2 * dk + h), &x[8 * dk]);
-        phi_rows(x, kfop);
-      }
       f32x16_t c = {0};
 #pragma unroll
-      for (int dk = 0; dk < 8; ++dk) c = mfma32(kfop[dk], qfop[dk], c);
+      for (int dk = 0; dk < 8; ++dk) c = mfma32(lds_row(kt, lo, 32 * ks, dk), qfop[dk], c);
       float cv[16];
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
@@ -161,9 +157,8 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
       bf16x8_t cop[2] = {pack_bf16x8(&cv[0]), pack_bf16x8(&cv[8])};
 #pragma unroll
       for (int mf = 0; mf < 2; ++mf) {
-        const int k0 = 32 * ks + 16 * mf + 4 * h;
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) xr[dt] = mfma32(lds_tr_pair(vt, k0, k0 + 8, 32 * dt, lane), cop[mf], xr[dt]);
+    #pragma unroll
+        for (int dt = 0; dt < 4; ++dt) xr[dt] = mfma32(lds_trp(vt, lo, 32 * ks + 16 * mf, dt), cop[mf], xr[dt]);
       }
     }
     __syncthreads();
@@ -172,7 +167,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) ss += xr[dt][i] * xr[dt][i];
-    ss += xhalf(ss);
+    ss = half_sum(ss);
     rr_val = rsqrtf(ss * (1.f / 128.f) + a.eps);
     if (a.xr_out) {
       float vals[4][16];
@@ -238,8 +233,8 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
       const bool need = ka <= qb && ka + 31 >= qa - W + 1;
       if (need) {
         const bool full = ka + 31 <= qa && ka >= qb - W + 1;
-        if (full) swa_subtile<false>(kt, vt, ks, ka, myq, W, a.scale_log2, qop, oacc, m, l, lane);
-        else swa_subtile<true>(kt, vt, ks, ka, myq, W, a.scale_log2, qop, oacc, m, l, lane);
+        if (full) swa_subtile<false>(kt, vt, ks, ka, myq, W, a.scale_log2, qop, oacc, m, l, lane, lo);
+        else swa_subtile<true>(kt, vt, ks, ka, myq, W, a.scale_log2, qop, oacc, m, l, lane, lo);
       }
     }
     wait_vmem();
@@ -247,7 +242,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
   }
 
   // ------------------------------------------------------------------ combination
-  l += xhalf(l);
+  l = half_sum(l);
   const float inv_l = 1.f / l;
   float ss = 0.f;
 #pragma unroll
@@ -256,7 +251,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) ss += oacc[dt][i] * oacc[dt][i];
   }
-  ss += xhalf(ss);
+  ss = half_sum(ss);
   const float rs_val = rsqrtf(ss * (1.f / 128.f) + a.eps);
   if (a.xs_out) {
     float vals[4][16];

@@ -81,6 +81,62 @@ __device__ __forceinline__ bf16x8_t lds_tr_pair(const unsigned char* tile, int k
   return u.v;
 }
 
+// Per-lane LDS byte offsets, computed once per kernel so that the hot loops issue ds_read with a
+// register offset plus an immediate (the XOR swizzle is not affine, the compiler cannot fold it).
+struct LaneOff {
+  int row[8];     // row read: logical chunk 2*c2 + h of row (lane % 32)
+  int trp[4][2];  // transposed read, contraction slots in accumulator order: rows 4h + 8*ab + (0..3), columns 32*ct + lane%32
+};
+struct LaneOffN {
+  int trn[4][2];  // transposed read, natural contraction order: rows 8h + 4*ab + (0..3), columns 32*ct + lane%32
+};
+__device__ __forceinline__ int tr_lane_off(int rl, int ct, int lane) {
+  const int i = lane & 15, gi = lane >> 4;
+  const int r = rl + (i >> 2);
+  const int c = 4 * ct + 2 * (gi & 1) + ((i & 3) >> 1);
+  return r * ROW_BYTES + ((c ^ swz(r)) << 4) + ((i & 1) << 3);
+}
+__device__ __forceinline__ LaneOff make_lane_off(int lane) {
+  LaneOff lo;
+  const int r32 = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int c2 = 0; c2 < 8; ++c2) lo.row[c2] = r32 * ROW_BYTES + (((2 * c2 + h) ^ swz(r32)) << 4);
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+    for (int ab = 0; ab < 2; ++ab) lo.trp[ct][ab] = tr_lane_off(4 * h + 8 * ab, ct, lane);
+  return lo;
+}
+__device__ __forceinline__ LaneOffN make_lane_off_n(int lane) {
+  LaneOffN lo;
+  const int h = lane >> 5;
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+    for (int ab = 0; ab < 2; ++ab) lo.trn[ct][ab] = tr_lane_off(8 * h + 4 * ab, ct, lane);
+  return lo;
+}
+// A/B operand = rows R0 + lane%32 of the tile (R0 % 16 == 0), elements 16*c2 + 8h .. +7
+__device__ __forceinline__ bf16x8_t lds_row(const unsigned char* tile, const LaneOff& lo, int R0, int c2) {
+  return *reinterpret_cast<const bf16x8_t*>(tile + lo.row[c2] + R0 * ROW_BYTES);
+}
+__device__ __forceinline__ bf16x8_t lds_tr2(const unsigned char* pa, const unsigned char* pb) {
+  s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(pa));
+  s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(pb));
+  union { struct { s16x4_t lo, hi; } s; bf16x8_t v; } u;
+  u.s.lo = lo; u.s.hi = hi;
+  return u.v;
+}
+// operand = columns 32*ct + lane%32 of the tile; slot e of half h is tile row K0 + 8(e/4) + 4h + e%4
+// (the order in which a 32x32 accumulator holds its rows), K0 % 16 == 0
+__device__ __forceinline__ bf16x8_t lds_trp(const unsigned char* tile, const LaneOff& lo, int K0, int ct) {
+  return lds_tr2(tile + lo.trp[ct][0] + K0 * ROW_BYTES, tile + lo.trp[ct][1] + K0 * ROW_BYTES);
+}
+// same with natural order: slot e of half h is tile row K0 + 8h + e, K0 % 16 == 0
+__device__ __forceinline__ bf16x8_t lds_trn(const unsigned char* tile, const LaneOffN& lo, int K0, int ct) {
+  return lds_tr2(tile + lo.trn[ct][0] + K0 * ROW_BYTES, tile + lo.trn[ct][1] + K0 * ROW_BYTES);
+}
+
 __device__ __forceinline__ bf16x8_t pack_bf16x8(const float* x) {
   f32x8_t v = {x[0], x[1], x[2], x[3], x[4], x[5], x[6], x[7]};
   return __builtin_convertvector(v, bf16x8_t);
@@ -92,8 +148,17 @@ __device__ __forceinline__ void unpack_bf16x8(bf16x8_t v, float* x) {
   for (int i = 0; i < 8; ++i) x[i] = f[i];
 }
 
-// value of the same register in lane ^ 32
-__device__ __forceinline__ float xhalf(float x) { return __shfl_xor(x, 32, 64); }
+// combine a value with the one held by lane ^ 32 (v_permlane32_swap: one VALU op, no LDS traffic)
+__device__ __forceinline__ float half_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float half_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+// 2^x on the transcendental unit (v_exp_f32): 2^-inf = 0, no denormal fix-up code
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
@@ -104,11 +169,11 @@ __device__ __forceinline__ void phi_rows(float (&x)[64], bf16x8_t (&op)[8]) {
   float m = x[0];
 #pragma unroll
   for (int i = 1; i < 64; ++i) m = fmaxf(m, x[i]);
-  m = fmaxf(m, xhalf(m));
+  m = half_max(m);
   float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < 64; ++i) { x[i] = exp2f((x[i] - m) * LOG2E); s += x[i]; }
-  s += xhalf(s);
+  for (int i = 0; i < 64; ++i) { x[i] = fast_exp2((x[i] - m) * LOG2E); s += x[i]; }
+  s = half_sum(s);
   const float inv = 1.f / s;
 #pragma unroll
   for (int i = 0; i < 64; ++i) x[i] *= inv;
@@ -133,7 +198,7 @@ __device__ __forceinline__ void phi_tile_inplace(unsigned char* tile, int nrows)
     m = fmaxf(m, __shfl_xor(m, 1, 64));
     float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < 64; ++i) { x[i] = exp2f((x[i] - m) * LOG2E); s += x[i]; }
+    for (int i = 0; i < 64; ++i) { x[i] = fast_exp2((x[i] - m) * LOG2E); s += x[i]; }
     s += __shfl_xor(s, 1, 64);
     const float inv = 1.f / s;
 #pragma unroll
