@@ -29,39 +29,45 @@ struct FastFwdArgs {
   float scale_log2, eps;
 };
 
-template <bool MASKED>
+// One 32-key sub-tile of the softmax branch for this wave's 32 queries (lane = query):
+// S^T = K Q^T, running-max update, P^T = 2^(c S^T - m), O^T += V^T P^T.
+// `m` is the reference maximum in scaled log2 units.  It is only raised (and O, l rescaled) when some
+// row's maximum exceeds it by more than RESCALE_TH, so P stays below 2^RESCALE_TH and most sub-tiles skip
+// the 64-register rescale.  `masked` is wave-uniform: only the window-edge and diagonal sub-tiles pay
+// for the per-element mask.
+constexpr float RESCALE_TH = 8.f;
+
 __device__ __forceinline__ void swa_subtile(const unsigned char* kt, const unsigned char* vt, int ks, int ka, int myq,
-                                            int W, float scale_log2, const bf16x8_t (&qop)[8], f32x16_t (&oacc)[4],
-                                            float& m, float& l, int lane, const LaneOff& lo) {
-  const int r32 = lane & 31, h = lane >> 5;
+                                            int W, bool masked, float scale_log2, const bf16x8_t (&qop)[8],
+                                            f32x16_t (&oacc)[4], float& m, float& l, int lane, const LaneOff& lo) {
+  const int h = lane >> 5;
   f32x16_t s = {0};
 #pragma unroll
   for (int dk = 0; dk < 8; ++dk) s = mfma32(lds_row(kt, lo, 32 * ks, dk), qop[dk], s);
-  float x[16];
+  if (masked) {
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    x[i] = s[i] * scale_log2;
-    if (MASKED) {
+    for (int i = 0; i < 16; ++i) {
       const int key = ka + 8 * (i >> 2) + 4 * h + (i & 3);
       const bool ok = key <= myq && key > myq - W;
-      x[i] = ok ? x[i] : -INFINITY;
+      s[i] = ok ? s[i] : -INFINITY;
     }
   }
-  float mx = x[0];
+  float mx = fmaxf(s[0], s[1]);
 #pragma unroll
-  for (int i = 1; i < 16; ++i) mx = fmaxf(mx, x[i]);
-  mx = half_max(mx);
-  const float m_new = fmaxf(m, mx);
-  const float alpha = fast_exp2(m - m_new);
-  float ps = 0.f;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) { x[i] = fast_exp2(x[i] - m_new); ps += x[i]; }
-  l = l * alpha + ps;
-  m = m_new;
-  if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
+  for (int i = 2; i < 16; i += 2) mx = fmaxf(mx, fmaxf(s[i], s[i + 1]));
+  mx = half_max(mx) * scale_log2;
+  if (__builtin_amdgcn_ballot_w64(mx - m > RESCALE_TH) != 0) {
+    const float m_new = fmaxf(m, mx);
+    const float alpha = fast_exp2(m - m_new);
+    m = m_new;
+    l *= alpha;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) oacc[dt] *= alpha;
   }
+  float x[16], ps = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { x[i] = fast_exp2(__builtin_fmaf(s[i], scale_log2, -m)); ps += x[i]; }
+  l += ps;
   bf16x8_t pop[2] = {pack_bf16x8(&x[0]), pack_bf16x8(&x[8])};
 #pragma unroll
   for (int mf = 0; mf < 2; ++mf) {
@@ -233,8 +239,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
       const bool need = ka <= qb && ka + 31 >= qa - W + 1;
       if (need) {
         const bool full = ka + 31 <= qa && ka >= qb - W + 1;
-        if (full) swa_subtile<false>(kt, vt, ks, ka, myq, W, a.scale_log2, qop, oacc, m, l, lane, lo);
-        else swa_subtile<true>(kt, vt, ks, ka, myq, W, a.scale_log2, qop, oacc, m, l, lane, lo);
+        swa_subtile(kt, vt, ks, ka, myq, W, !full, a.scale_log2, qop, oacc, m, l, lane, lo);
       }
     }
     wait_vmem();
