@@ -137,9 +137,8 @@ __device__ __forceinline__ void load_bop(const uint16_t* rowp, int h, bf16x8_t (
 }
 
 // ------------------------------------------------------------------------------------------------
-template <bool MASKED>
 __device__ __forceinline__ void dq_subtile(const unsigned char* kt, const unsigned char* vt, int ks, int ka, int myq,
-                                           int W, float scale, float scale_log2, float lse2, float dl,
+                                           int W, bool masked, float scale, float scale_log2, float lse2, float dl,
                                            const bf16x8_t (&qop)[8], const bf16x8_t (&dxsop)[8], f32x16_t (&acc)[4],
                                            int lane, const LaneOff& lo) {
   const int r32 = lane & 31, h = lane >> 5;
@@ -148,14 +147,17 @@ __device__ __forceinline__ void dq_subtile(const unsigned char* kt, const unsign
   for (int c = 0; c < 8; ++c) s = mfma32(lds_row(kt, lo, 32 * ks, c), qop[c], s);
 #pragma unroll
   for (int c = 0; c < 8; ++c) dp = mfma32(lds_row(vt, lo, 32 * ks, c), dxsop[c], dp);
+  if (masked) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int key = ka + 8 * (i >> 2) + 4 * h + (i & 3);
+      s[i] = (key <= myq && key > myq - W) ? s[i] : -INFINITY;
+    }
+  }
   float ds[16];
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
-    float p = fast_exp2(s[i] * scale_log2 - lse2);
-    if (MASKED) {
-      const int key = ka + 8 * (i >> 2) + 4 * h + (i & 3);
-      p = (key <= myq && key > myq - W) ? p : 0.f;
-    }
+    const float p = fast_exp2(__builtin_fmaf(s[i], scale_log2, -lse2));
     ds[i] = p * (dp[i] - dl) * scale;
   }
   bf16x8_t dsop[2] = {pack_bf16x8(&ds[0]), pack_bf16x8(&ds[8])};
@@ -281,8 +283,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_kernel(FastBwdArgs a) {
       const bool need = ka <= qb && ka + 31 >= qa - W + 1;
       if (need) {
         const bool full = ka + 31 <= qa && ka >= qb - W + 1;
-        if (full) dq_subtile<false>(kt, vt, ks, ka, myq, W, a.scale, a.scale_log2, lse2, dl, qop, dxsop, acc, lane, lo);
-        else dq_subtile<true>(kt, vt, ks, ka, myq, W, a.scale, a.scale_log2, lse2, dl, qop, dxsop, acc, lane, lo);
+        dq_subtile(kt, vt, ks, ka, myq, W, !full, a.scale, a.scale_log2, lse2, dl, qop, dxsop, acc, lane, lo);
       }
     }
     wait_vmem();
@@ -297,9 +298,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_kernel(FastBwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-template <bool MASKED>
 __device__ __forceinline__ void dkv_subtile(const unsigned char* qt, const unsigned char* dxt, int qs, int qa, int mykey,
-                                            int W, float scale, float scale_log2, const float* lse_row,
+                                            int W, bool masked, float scale, float scale_log2, const float* lse_row,
                                             const float* delta_row, const bf16x8_t (&kop)[8], const bf16x8_t (&vop)[8],
                                             f32x16_t (&dk)[4], f32x16_t (&dv)[4], int lane, const LaneOff& lo) {
   const int r32 = lane & 31, h = lane >> 5;
@@ -308,6 +308,13 @@ __device__ __forceinline__ void dkv_subtile(const unsigned char* qt, const unsig
   for (int c = 0; c < 8; ++c) s = mfma32(lds_row(qt, lo, 32 * qs, c), kop[c], s);
 #pragma unroll
   for (int c = 0; c < 8; ++c) dp = mfma32(lds_row(dxt, lo, 32 * qs, c), vop[c], dp);
+  if (masked) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int query = qa + 8 * (i >> 2) + 4 * h + (i & 3);
+      s[i] = (mykey <= query && query - mykey < W) ? s[i] : -INFINITY;
+    }
+  }
   float pv[16], ds[16];
 #pragma unroll
   for (int i4 = 0; i4 < 4; ++i4) {
@@ -318,11 +325,7 @@ __device__ __forceinline__ void dkv_subtile(const unsigned char* qt, const unsig
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int i = 4 * i4 + e;
-      float p = fast_exp2(s[i] * scale_log2 - lsa[e] * LOG2E);
-      if (MASKED) {
-        const int query = qrow + e;
-        p = (mykey <= query && query - mykey < W) ? p : 0.f;
-      }
+      const float p = fast_exp2(__builtin_fmaf(s[i], scale_log2, -lsa[e] * LOG2E));
       pv[i] = p;
       ds[i] = p * (dp[i] - dla[e]) * scale;
     }
@@ -459,8 +462,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(FastBwdArgs a) {
       const bool need = qa + 31 >= ka && qa <= ka + 31 + W - 1;
       if (need) {
         const bool full = qa >= ka + 31 && qa + 31 <= ka + W - 1;
-        if (full) dkv_subtile<false>(qtile, dxt, qs, qa, mykey, W, a.scale, a.scale_log2, lse_row, delta_row, kop, vop, dk, dv, lane, lo);
-        else dkv_subtile<true>(qtile, dxt, qs, qa, mykey, W, a.scale, a.scale_log2, lse_row, delta_row, kop, vop, dk, dv, lane, lo);
+        dkv_subtile(qtile, dxt, qs, qa, mykey, W, !full, a.scale, a.scale_log2, lse_row, delta_row, kop, vop, dk, dv, lane, lo);
       }
     }
     wait_vmem();

@@ -32,18 +32,25 @@ struct FastFwdArgs {
 // One 32-key sub-tile of the softmax branch for this wave's 32 queries (lane = query):
 // S^T = K Q^T, running-max update, P^T = 2^(c S^T - m), O^T += V^T P^T.
 // `m` is the reference maximum in scaled log2 units.  It is only raised (and O, l rescaled) when some
-// row's maximum exceeds it by more than RESCALE_TH, so P stays below 2^RESCALE_TH and most sub-tiles skip
-// the 64-register rescale.  `masked` is wave-uniform: only the window-edge and diagonal sub-tiles pay
-// for the per-element mask.
+// row's maximum exceeds it by more than RESCALE_TH, so P stays below 2^RESCALE_TH and almost every
+// sub-tile takes the short path: 16 fma, 8 max3, 16 exp, 16 add, 8 cvt per lane.  The exponent
+// arguments x = c*s - m are formed first and the maximum is taken over them (they are already needed,
+// and being fma results they need no NaN quieting).  `masked` is wave-uniform: only the window-edge and
+// diagonal sub-tiles pay for the per-element mask.  CUR (LDS buffer) and KS (sub-tile) are compile-time
+// so every LDS address is a per-lane register plus an immediate.
 constexpr float RESCALE_TH = 8.f;
+constexpr float M_INIT = -1.0e30f;  // finite "minus infinity" for the running maximum
 
-__device__ __forceinline__ void swa_subtile(const unsigned char* kt, const unsigned char* vt, int ks, int ka, int myq,
-                                            int W, bool masked, float scale_log2, const bf16x8_t (&qop)[8],
-                                            f32x16_t (&oacc)[4], float& m, float& l, int lane, const LaneOff& lo) {
+template <int CUR, int KS>
+__device__ __forceinline__ void swa_subtile(unsigned char* smem, int ka, int myq, int W, bool masked, float scale_log2,
+                                            const bf16x8_t (&qop)[8], f32x16_t (&oacc)[4], float& m, float& l, int lane,
+                                            const LaneOff& lo) {
+  const unsigned char* kt = smem + CUR * 16384;
+  const unsigned char* vt = smem + 32768 + CUR * 16384;
   const int h = lane >> 5;
   f32x16_t s = {0};
 #pragma unroll
-  for (int dk = 0; dk < 8; ++dk) s = mfma32(lds_row(kt, lo, 32 * ks, dk), qop[dk], s);
+  for (int dk = 0; dk < 8; ++dk) s = mfma32(lds_row(kt, lo, 32 * KS, dk), qop[dk], s);
   if (masked) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -52,28 +59,69 @@ __device__ __forceinline__ void swa_subtile(const unsigned char* kt, const unsig
       s[i] = ok ? s[i] : -INFINITY;
     }
   }
-  float mx = fmaxf(s[0], s[1]);
+  float x[16];
 #pragma unroll
-  for (int i = 2; i < 16; i += 2) mx = fmaxf(mx, fmaxf(s[i], s[i + 1]));
-  mx = half_max(mx) * scale_log2;
-  if (__builtin_amdgcn_ballot_w64(mx - m > RESCALE_TH) != 0) {
-    const float m_new = fmaxf(m, mx);
+  for (int i = 0; i < 16; ++i) x[i] = __builtin_fmaf(s[i], scale_log2, -m);
+  float mx = fmaxf(fmaxf(x[0], x[1]), x[2]);
+#pragma unroll
+  for (int i = 3; i < 15; i += 2) mx = fmaxf(fmaxf(mx, x[i]), x[i + 1]);
+  mx = half_max(fmaxf(mx, x[15]));
+  if (__builtin_amdgcn_ballot_w64(mx > RESCALE_TH) != 0) {
+    // raise the reference: redo the exponent arguments from s against the new maximum
+    float sm = fmaxf(s[0], s[1]);
+#pragma unroll
+    for (int i = 2; i < 16; ++i) sm = fmaxf(sm, s[i]);
+    const float m_new = fmaxf(m, half_max(sm) * scale_log2);
     const float alpha = fast_exp2(m - m_new);
     m = m_new;
     l *= alpha;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) oacc[dt] *= alpha;
-  }
-  float x[16], ps = 0.f;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) { x[i] = fast_exp2(__builtin_fmaf(s[i], scale_log2, -m)); ps += x[i]; }
+    for (int i = 0; i < 16; ++i) x[i] = __builtin_fmaf(s[i], scale_log2, -m);
+  }
+  float ps = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { x[i] = fast_exp2(x[i]); ps += x[i]; }
   l += ps;
   bf16x8_t pop[2] = {pack_bf16x8(&x[0]), pack_bf16x8(&x[8])};
 #pragma unroll
   for (int mf = 0; mf < 2; ++mf) {
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) oacc[dt] = mfma32(lds_trp(vt, lo, 32 * ks + 16 * mf, dt), pop[mf], oacc[dt]);
+    for (int dt = 0; dt < 4; ++dt) oacc[dt] = mfma32(lds_trp(vt, lo, 32 * KS + 16 * mf, dt), pop[mf], oacc[dt]);
   }
+}
+
+// one key tile (two sub-tiles, upper keys first) out of LDS buffer CUR
+template <int CUR>
+__device__ __forceinline__ void swa_tile(unsigned char* smem, int kt0, int qa, int myq, int W, float scale_log2,
+                                         const bf16x8_t (&qop)[8], f32x16_t (&oacc)[4], float& m, float& l, int lane,
+                                         const LaneOff& lo) {
+  const int qb = qa + 31;
+  {
+    const int ka = kt0 + 32;
+    if (ka <= qb && ka + 31 >= qa - W + 1)
+      swa_subtile<CUR, 1>(smem, ka, myq, W, !(ka + 31 <= qa && ka >= qb - W + 1), scale_log2, qop, oacc, m, l, lane, lo);
+  }
+  {
+    const int ka = kt0;
+    if (ka <= qb && ka + 31 >= qa - W + 1)
+      swa_subtile<CUR, 0>(smem, ka, myq, W, !(ka + 31 <= qa && ka >= qb - W + 1), scale_log2, qop, oacc, m, l, lane, lo);
+  }
+}
+
+// 8-byte stores straight from accumulator layout (used where LDS still holds live tiles)
+__device__ __forceinline__ void store_tile_direct(const f32x16_t (&acc)[4], uint16_t* dst, size_t row_stride, int w,
+                                                  int lane) {
+  const int r32 = lane & 31, h = lane >> 5;
+  uint16_t* rowp = dst + (size_t)(32 * w + r32) * row_stride + 4 * h;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      f32x4_t f = {acc[dt][4 * i4], acc[dt][4 * i4 + 1], acc[dt][4 * i4 + 2], acc[dt][4 * i4 + 3]};
+      *reinterpret_cast<bf16x4_t*>(rowp + 32 * dt + 8 * i4) = __builtin_convertvector(f, bf16x4_t);
+    }
 }
 
 __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
@@ -101,21 +149,91 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
   const int myq = t0 + 32 * w + r32;
   const size_t stat_off = (size_t)(b * Hq + hq) * T + myq;
 
+  // ------------------------------------------------------------------ softmax branch
+  // key tiles of 64 from the diagonal down to kt_lo; the first one is in flight while q arrives
+  const int kt_lo = max(0, t0 - W);
+  const int ntiles = (t0 + 128 - kt_lo) / 64;
+  {
+    const int kt0 = kt_lo + 64 * (ntiles - 1);
+    tile_load_async<4>(kbase + (size_t)kt0 * kstride, kstride, smem, w * 4, lane);
+    tile_load_async<4>(vbase + (size_t)kt0 * kstride, kstride, smem + 32768, w * 4, lane);
+  }
   bf16x8_t qop[8];
   {
     const uint16_t* qp = a.q + qtile_off + (size_t)(32 * w + r32) * qstride + 8 * h;
 #pragma unroll
     for (int dk = 0; dk < 8; ++dk) qop[dk] = *reinterpret_cast<const bf16x8_t*>(qp + 16 * dk);
   }
+  wait_vmem();
+  __syncthreads();
+  f32x16_t oacc[4] = {{0}, {0}, {0}, {0}};
+  float m = M_INIT, l = 0.f;
+  const int qa = t0 + 32 * w;
+  auto prefetch = [&](int n) {  // tile of iteration n+1 into the buffer iteration n does not read
+    const int ktn = kt_lo + 64 * (ntiles - 2 - n);
+    const int nb = (n & 1) ^ 1;
+    tile_load_async<4>(kbase + (size_t)ktn * kstride, kstride, smem + nb * 16384, w * 4, lane);
+    tile_load_async<4>(vbase + (size_t)ktn * kstride, kstride, smem + 32768 + nb * 16384, w * 4, lane);
+  };
+  for (int n = 0; n < ntiles; n += 2) {
+    if (n + 1 < ntiles) prefetch(n);
+    swa_tile<0>(smem, kt_lo + 64 * (ntiles - 1 - n), qa, myq, W, a.scale_log2, qop, oacc, m, l, lane, lo);
+    wait_vmem();
+    __syncthreads();
+    if (n + 1 < ntiles) {
+      if (n + 2 < ntiles) prefetch(n + 1);
+      swa_tile<1>(smem, kt_lo + 64 * (ntiles - 2 - n), qa, myq, W, a.scale_log2, qop, oacc, m, l, lane, lo);
+      wait_vmem();
+      __syncthreads();
+    }
+  }
+  // the two lowest key tiles are still resident: tile `it` sits in buffer (ntiles-1-it) & 1
 
-  // ------------------------------------------------------------------ linear branch
-  bf16x2_t yr[4][8];  // x_r * r_r, packed
-  float rr_val = rsqrtf(a.eps);
+  l = half_sum(l);
+  const float inv_l = 1.f / l;
+  float ss = 0.f;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) {
+    oacc[dt] *= inv_l;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) ss += oacc[dt][i] * oacc[dt][i];
+  }
+  ss = half_sum(ss);
+  const float rs_val = rsqrtf(ss * (1.f / 128.f) + a.eps);
   // key tile of the intra-chunk part starts at j0 = t0 - W; when W % 128 == 64 the first query tile that
   // reaches past the window has j0 = -64: no state yet (S = 0) and only its upper 64 keys exist
   const int j0 = t0 - W;
-  if (j0 > -128) {
+  const bool has_lin = j0 > -128;
+  if (a.xs_out) {
+    if (has_lin) {
+      store_tile_direct(oacc, a.xs_out + qtile_off, qstride, w, lane);
+    } else {
+      float vals[4][16];
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) vals[dt][i] = oacc[dt][i];
+      store_tile_transposed(smem, vals, a.xs_out + qtile_off, qstride, w, lane);
+    }
+  }
+  bf16x2_t ys[4][8];  // x_s * r_s, packed
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      f32x2_t f = {oacc[dt][2 * i] * rs_val, oacc[dt][2 * i + 1] * rs_val};
+      ys[dt][i] = __builtin_convertvector(f, bf16x2_t);
+    }
+  const float lse_val = (m + log2f(l)) * LN2;
+
+  // ------------------------------------------------------------------ linear branch
+  // intra-chunk part on the resident tiles (phi applied to K in place), then the state product
+  f32x16_t xr[4] = {{0}, {0}, {0}, {0}};
+  float rr_val = rsqrtf(a.eps);
+  if (has_lin) {
     const bool has_state = j0 >= 0;
+    const int shift = has_state ? 0 : 1;                  // chunk tile ti is softmax tile ti - shift
+    const int buf0 = (ntiles - 1 + shift) & 1;            // buffer of chunk tile 0 (tile 1 is the other one)
     bf16x8_t qfop[8];
     {
       float x[64];
@@ -123,33 +241,12 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
       for (int dk = 0; dk < 8; ++dk) unpack_bf16x8(qop[dk], &x[8 * dk]);
       phi_rows(x, qfop);
     }
-    f32x16_t xr[4] = {{0}, {0}, {0}, {0}};
-    if (has_state) {
-      const uint16_t* sbase = a.states + ((size_t)(b * Hkv + g) * a.nstf + j0 / 128) * 16384;
-      tile_load_async<8>(sbase, 128, smem, w * 8, lane);
-      tile_load_async<4>(vbase + (size_t)j0 * kstride, kstride, smem + 32768, w * 4, lane);
-    }
-    tile_load_async<4>(vbase + (size_t)(j0 + 64) * kstride, kstride, smem + 49152, w * 4, lane);
-    wait_vmem();
-    __syncthreads();
-    if (has_state) {
-#pragma unroll
-      for (int kf = 0; kf < 8; ++kf)
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-          xr[dt] = mfma32(lds_row(smem, lo, 32 * dt, kf), qfop[kf], xr[dt]);
-    }
-    __syncthreads();
-    if (has_state) tile_load_async<4>(kbase + (size_t)j0 * kstride, kstride, smem, w * 4, lane);
-    tile_load_async<4>(kbase + (size_t)(j0 + 64) * kstride, kstride, smem + 16384, w * 4, lane);
-    wait_vmem();
-    __syncthreads();
-    if (has_state) phi_tile_inplace(smem, 128);
-    else phi_tile_inplace(smem + 16384, 64);
+    phi_tiles_inplace(has_state ? smem + buf0 * 16384 : nullptr, smem + (buf0 ^ 1) * 16384);
     __syncthreads();
     for (int u = has_state ? 0 : 2; u <= w; ++u) {
-      const unsigned char* kt = smem + (u >> 1) * 16384;
-      const unsigned char* vt = smem + 32768 + (u >> 1) * 16384;
+      const int bsel = buf0 ^ (u >> 1);
+      const unsigned char* kt = smem + bsel * 16384;
+      const unsigned char* vt = smem + 32768 + bsel * 16384;
       const int ks = u & 1;
       f32x16_t c = {0};
 #pragma unroll
@@ -163,114 +260,45 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
       bf16x8_t cop[2] = {pack_bf16x8(&cv[0]), pack_bf16x8(&cv[8])};
 #pragma unroll
       for (int mf = 0; mf < 2; ++mf) {
-    #pragma unroll
+#pragma unroll
         for (int dt = 0; dt < 4; ++dt) xr[dt] = mfma32(lds_trp(vt, lo, 32 * ks + 16 * mf, dt), cop[mf], xr[dt]);
       }
     }
     __syncthreads();
-    float ss = 0.f;
+    if (has_state) {
+      const uint16_t* sbase = a.states + ((size_t)(b * Hkv + g) * a.nstf + j0 / 128) * 16384;
+      tile_load_async<8>(sbase, 128, smem, w * 8, lane);
+      wait_vmem();
+      __syncthreads();
+#pragma unroll
+      for (int kf = 0; kf < 8; ++kf)
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) xr[dt] = mfma32(lds_row(smem, lo, 32 * dt, kf), qfop[kf], xr[dt]);
+      __syncthreads();
+    }
+    float sr = 0.f;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) ss += xr[dt][i] * xr[dt][i];
-    ss = half_sum(ss);
-    rr_val = rsqrtf(ss * (1.f / 128.f) + a.eps);
-    if (a.xr_out) {
-      float vals[4][16];
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) vals[dt][i] = xr[dt][i];
-      store_tile_transposed(smem, vals, a.xr_out + qtile_off, qstride, w, lane);
-    }
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        f32x2_t f = {xr[dt][2 * i] * rr_val, xr[dt][2 * i + 1] * rr_val};
-        yr[dt][i] = __builtin_convertvector(f, bf16x2_t);
-      }
-  } else {
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        f32x2_t f = {0.f, 0.f};
-        yr[dt][i] = __builtin_convertvector(f, bf16x2_t);
-      }
-    if (a.xr_out) {
-      const int tid = threadIdx.x;
-      const uint4 z = make_uint4(0, 0, 0, 0);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int id = tid + 256 * i;
-        *reinterpret_cast<uint4*>(a.xr_out + qtile_off + (size_t)(id >> 4) * qstride + (id & 15) * 8) = z;
-      }
-    }
+      for (int i = 0; i < 16; ++i) sr += xr[dt][i] * xr[dt][i];
+    sr = half_sum(sr);
+    rr_val = rsqrtf(sr * (1.f / 128.f) + a.eps);
   }
-
-  // ------------------------------------------------------------------ softmax branch
-  f32x16_t oacc[4] = {{0}, {0}, {0}, {0}};
-  float m = -INFINITY, l = 0.f;
-  const int kt_lo = max(0, t0 - W);
-  const int ntiles = (t0 + 128 - kt_lo) / 64;
-  {
-    const int kt0 = kt_lo + 64 * (ntiles - 1);
-    tile_load_async<4>(kbase + (size_t)kt0 * kstride, kstride, smem, w * 4, lane);
-    tile_load_async<4>(vbase + (size_t)kt0 * kstride, kstride, smem + 32768, w * 4, lane);
-    wait_vmem();
-    __syncthreads();
-  }
-  const int qa = t0 + 32 * w, qb = qa + 31;
-  for (int n = 0; n < ntiles; ++n) {
-    const int it = ntiles - 1 - n;
-    const int cur = n & 1;
-    if (n + 1 < ntiles) {
-      const int ktn = kt_lo + 64 * (it - 1);
-      tile_load_async<4>(kbase + (size_t)ktn * kstride, kstride, smem + (cur ^ 1) * 16384, w * 4, lane);
-      tile_load_async<4>(vbase + (size_t)ktn * kstride, kstride, smem + 32768 + (cur ^ 1) * 16384, w * 4, lane);
-    }
-    const unsigned char* kt = smem + cur * 16384;
-    const unsigned char* vt = smem + 32768 + cur * 16384;
-    const int kt0 = kt_lo + 64 * it;
-#pragma unroll
-    for (int ks = 1; ks >= 0; --ks) {
-      const int ka = kt0 + 32 * ks;
-      const bool need = ka <= qb && ka + 31 >= qa - W + 1;
-      if (need) {
-        const bool full = ka + 31 <= qa && ka >= qb - W + 1;
-        swa_subtile(kt, vt, ks, ka, myq, W, !full, a.scale_log2, qop, oacc, m, l, lane, lo);
-      }
-    }
-    wait_vmem();
-    __syncthreads();
-  }
-
-  // ------------------------------------------------------------------ combination
-  l = half_sum(l);
-  const float inv_l = 1.f / l;
-  float ss = 0.f;
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt) {
-    oacc[dt] *= inv_l;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) ss += oacc[dt][i] * oacc[dt][i];
-  }
-  ss = half_sum(ss);
-  const float rs_val = rsqrtf(ss * (1.f / 128.f) + a.eps);
   if (a.xs_out) {
     float vals[4][16];
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) vals[dt][i] = oacc[dt][i];
-    store_tile_transposed(smem, vals, a.xs_out + qtile_off, qstride, w, lane);
+      for (int i = 0; i < 16; ++i) vals[dt][i] = xr[dt][i];
+    store_tile_transposed(smem, vals, a.xr_out + qtile_off, qstride, w, lane);
     if (h == 0) {
-      a.lse_out[stat_off] = (m + log2f(l)) * LN2;
+      a.lse_out[stat_off] = lse_val;
       a.rs_out[stat_off] = rs_val;
       a.rr_out[stat_off] = rr_val;
     }
   }
+
+  // ------------------------------------------------------------------ combination
   {
     float vals[4][16];
 #pragma unroll
@@ -281,12 +309,11 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
         float4 g1 = make_float4(1.f, 1.f, 1.f, 1.f), g2 = g1;
         if (a.gs) g1 = *reinterpret_cast<const float4*>(a.gs + hq * 128 + d0);
         if (a.gr) g2 = *reinterpret_cast<const float4*>(a.gr + hq * 128 + d0);
-        const float ga[4] = {g1.x, g1.y, g1.z, g1.w}, gb[4] = {g2.x, g2.y, g2.z, g2.w};
+        const float ga[4] = {g1.x, g1.y, g1.z, g1.w}, gb[4] = {g2.x * rr_val, g2.y * rr_val, g2.z * rr_val, g2.w * rr_val};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int i = 4 * i4 + e;
-          const float y = (float)yr[dt][i >> 1][i & 1];
-          vals[dt][i] = ga[e] * oacc[dt][i] * rs_val + gb[e] * y;
+          vals[dt][i] = ga[e] * (float)ys[dt][i >> 1][i & 1] + gb[e] * xr[dt][i];
         }
       }
     store_tile_transposed(smem, vals, a.o + qtile_off, qstride, w, lane);

@@ -41,6 +41,14 @@ __device__ __forceinline__ f32x16_t mfma32(bf16x8_t a, bf16x8_t b, f32x16_t c) {
 // wait until every outstanding vector-memory operation of this wave (incl. direct-to-LDS loads) is done
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
+// 16 bytes per lane from global memory straight into LDS at lds_addr + 16*lane (lds_addr wave-uniform).
+// Issued through inline assembly on purpose: the compiler then does not put its own conservative
+// vmcnt waits in front of later LDS reads, so a tile prefetch really overlaps the math on the current
+// tile; completion is awaited explicitly with wait_vmem() before the barrier that publishes the tile.
+__device__ __forceinline__ void dma16(const void* g, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(__builtin_amdgcn_readfirstlane(lds_addr)) : "memory", "m0");
+}
+
 // Asynchronously copy `NBLK` blocks of 4 rows x 256 bytes from global memory into an LDS tile, direct to
 // LDS (no VGPR staging).  Block index blk0 + i, lane l lands at tile + blk*1024 + l*16, i.e. row
 // 4*blk + l/16, physical chunk l%16; it fetches the logical chunk that the swizzle maps there.
@@ -54,7 +62,7 @@ __device__ __forceinline__ void tile_load_async(const uint16_t* gbase, size_t ro
     const int p = lane & 15;
     const int c = p ^ swz(r);
     const uint16_t* g = gbase + (size_t)r * row_stride + c * 8;
-    __builtin_amdgcn_global_load_lds(g, RATTN_LDS(tile + blk * 1024), 16, 0, 0);
+    dma16(g, (unsigned)(size_t)RATTN_LDS(tile + blk * 1024));
   }
 }
 
@@ -181,11 +189,14 @@ __device__ __forceinline__ void phi_rows(float (&x)[64], bf16x8_t (&op)[8]) {
   for (int c = 0; c < 8; ++c) op[c] = pack_bf16x8(&x[8 * c]);
 }
 
-// phi applied in place to the first `nrows` (<= 128) rows of an LDS tile: two threads per row.
-// Call with all 256 threads; the caller synchronises before and after.
-__device__ __forceinline__ void phi_tile_inplace(unsigned char* tile, int nrows) {
-  const int row = threadIdx.x >> 1, half = threadIdx.x & 1;
-  if (row < nrows) {
+// phi applied in place to LDS tile rows, two threads per row: thread pair r works on row r of tile A
+// (r < 64) or row r-64 of tile B (r >= 64); a null tile pointer skips that half.  Tiles A and B
+// contiguous = one 128-row tile.  Call with all 256 threads; the caller synchronises before and after.
+__device__ __forceinline__ void phi_tiles_inplace(unsigned char* tileA, unsigned char* tileB) {
+  const int r = threadIdx.x >> 1, half = threadIdx.x & 1;
+  unsigned char* tile = r < 64 ? tileA : tileB;
+  const int row = r & 63;
+  if (tile) {
     float x[64];
     unsigned char* rp = tile + row * ROW_BYTES;
     const int sw = swz(row);
@@ -207,6 +218,10 @@ __device__ __forceinline__ void phi_tile_inplace(unsigned char* tile, int nrows)
     for (int j = 0; j < 8; ++j)
       *reinterpret_cast<bf16x8_t*>(rp + (((8 * half + j) ^ sw) << 4)) = pack_bf16x8(&x[8 * j]);
   }
+}
+// first `nrows` (64 or 128) rows of one contiguous tile
+__device__ __forceinline__ void phi_tile_inplace(unsigned char* tile, int nrows) {
+  phi_tiles_inplace(tile, nrows > 64 ? tile + 64 * ROW_BYTES : nullptr);
 }
 
 // Write a [128 rows x 128] bf16 tile held transposed in accumulators (lane = tile row 32w + lane%32,
