@@ -41,73 +41,120 @@ struct FastFwdArgs {
 constexpr float RESCALE_TH = 8.f;
 constexpr float M_INIT = -1.0e30f;  // finite "minus infinity" for the running maximum
 
-template <int CUR, int KS>
-__device__ __forceinline__ void swa_subtile(unsigned char* smem, int ka, int myq, int W, bool masked, float scale_log2,
-                                            const bf16x8_t (&qop)[8], f32x16_t (&oacc)[4], float& m, float& l, int lane,
-                                            const LaneOff& lo) {
-  const unsigned char* kt = smem + CUR * 16384;
-  const unsigned char* vt = smem + 32768 + CUR * 16384;
-  const int h = lane >> 5;
-  f32x16_t s = {0};
+// The sweep is software-pipelined per wave over its sequence of 32-key sub-tiles j (upper keys first):
+// step j issues, in one instruction stream, the S^T chain of sub-tile j+1 (matrix cores), the softmax of
+// sub-tile j (vector ALU) and the O^T update of sub-tile j-1 (matrix cores), so the two kinds of work
+// overlap inside every wave instead of relying on another wave being in the opposite phase.
+
+// A: S^T = K Q^T for sub-tile KS of the K tile in buffer KB
+template <int KB, int KS>
+__device__ __forceinline__ void qk_chain(const unsigned char* smem, const LaneOff& lo, const bf16x8_t (&qop)[8],
+                                         f32x16_t& s) {
+  const unsigned char* kt = smem + KB * 16384;
+  s = f32x16_t{0};
 #pragma unroll
   for (int dk = 0; dk < 8; ++dk) s = mfma32(lds_row(kt, lo, 32 * KS, dk), qop[dk], s);
-  if (masked) {
+}
+
+// C: O^T += V^T P^T for sub-tile KS of the V tile in buffer VB
+template <int VB, int KS>
+__device__ __forceinline__ void pv_chain(const unsigned char* smem, const LaneOff& lo, const bf16x8_t (&pop)[2],
+                                         f32x16_t (&oacc)[4]) {
+  const unsigned char* vt = smem + 32768 + VB * 16384;
+#pragma unroll
+  for (int mf = 0; mf < 2; ++mf)
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) oacc[dt] = mfma32(lds_trp(vt, lo, 32 * KS + 16 * mf, dt), pop[mf], oacc[dt]);
+}
+
+struct SweepGeom {
+  int kt_lo, ntiles, qa, W;
+  // first key of sub-tile j (tile j/2 counted from the diagonal, upper half first)
+  __device__ __forceinline__ int ka(int j) const { return kt_lo + 64 * (ntiles - 1 - (j >> 1)) + 32 * (1 - (j & 1)); }
+  // every (query, key) pair of the wave's 32 queries and the sub-tile's 32 keys is inside the window
+  __device__ __forceinline__ bool full(int j) const {
+    const int k = ka(j);
+    return k + 31 <= qa && k >= qa + 31 - W + 1;
+  }
+};
+
+// Step j with R = j % 4 (fixes which LDS buffers / halves sub-tiles j+1 and j-1 live in).  Every wave runs
+// every step of the work-group's key range: sub-tiles outside a wave's own window are fully masked (their
+// probabilities are exactly 0), which costs a few percent of the matrix work and keeps one straight
+// code path.  Two scheduling regions, each pairing a matrix-core chain with vector work:
+//   1. S^T(j+1) = K Q^T          ||  exponent arguments x = c*S^T(j) - m and their row maximum
+//   2. O^T += V^T P^T(j-1)       ||  P^T(j) = 2^x, row sums, bf16 packing
+// The reference maximum m is raised only when some row exceeds it by RESCALE_TH (rare); the rescale of
+// O is applied after region 2, i.e. after the update that was still expressed against the old m.
+template <int R, bool DO_C>
+__device__ __forceinline__ void sweep_step(const unsigned char* smem, const LaneOff& lo, const SweepGeom& gm, int j,
+                                           int myq, float scale_log2, const bf16x8_t (&qop)[8], f32x16_t (&oacc)[4],
+                                           float& m, float& l, f32x16_t& s_cur, bf16x8_t (&p_prev)[2], int lane) {
+  constexpr int KS = R & 1;                           // sub-tile half of both j+1 and j-1
+  constexpr int KB = (R == 1 || R == 2) ? 1 : 0;      // K buffer of sub-tile j+1
+  constexpr int VB = (R == 0 || R == 3) ? 1 : 0;      // V buffer of sub-tile j-1
+  const int h = lane >> 5;
+  if (!gm.full(j)) {  // wave-uniform: window edge, diagonal, or a sub-tile this wave does not see at all
+    const int ka = gm.ka(j);
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int key = ka + 8 * (i >> 2) + 4 * h + (i & 3);
-      const bool ok = key <= myq && key > myq - W;
-      s[i] = ok ? s[i] : -INFINITY;
+      const bool ok = key <= myq && key > myq - gm.W;
+      s_cur[i] = ok ? s_cur[i] : -INFINITY;
     }
   }
+  // ---- region 1
+  f32x16_t s_next;
+  qk_chain<KB, KS>(smem, lo, qop, s_next);
   float x[16];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) x[i] = __builtin_fmaf(s[i], scale_log2, -m);
+  for (int i = 0; i < 16; ++i) x[i] = __builtin_fmaf(s_cur[i], scale_log2, -m);
   float mx = fmaxf(fmaxf(x[0], x[1]), x[2]);
 #pragma unroll
   for (int i = 3; i < 15; i += 2) mx = fmaxf(fmaxf(mx, x[i]), x[i + 1]);
   mx = half_max(fmaxf(mx, x[15]));
-  if (__builtin_amdgcn_ballot_w64(mx > RESCALE_TH) != 0) {
-    // raise the reference: redo the exponent arguments from s against the new maximum
-    float sm = fmaxf(s[0], s[1]);
+  __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
 #pragma unroll
-    for (int i = 2; i < 16; ++i) sm = fmaxf(sm, s[i]);
+  for (int i = 0; i < 8; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
+    __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);  // 3 VALU
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 LDS read
+  }
+  const bool trig = __builtin_amdgcn_ballot_w64(mx > RESCALE_TH) != 0;
+  float alpha = 1.f;
+  if (trig) {
+    float sm = fmaxf(s_cur[0], s_cur[1]);
+#pragma unroll
+    for (int i = 2; i < 16; ++i) sm = fmaxf(sm, s_cur[i]);
     const float m_new = fmaxf(m, half_max(sm) * scale_log2);
-    const float alpha = fast_exp2(m - m_new);
+    alpha = fast_exp2(m - m_new);
     m = m_new;
     l *= alpha;
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) oacc[dt] *= alpha;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) x[i] = __builtin_fmaf(s[i], scale_log2, -m);
+    for (int i = 0; i < 16; ++i) x[i] = __builtin_fmaf(s_cur[i], scale_log2, -m);
   }
+  // ---- region 2
+  if (DO_C) pv_chain<VB, KS>(smem, lo, p_prev, oacc);
   float ps = 0.f;
 #pragma unroll
   for (int i = 0; i < 16; ++i) { x[i] = fast_exp2(x[i]); ps += x[i]; }
   l += ps;
-  bf16x8_t pop[2] = {pack_bf16x8(&x[0]), pack_bf16x8(&x[8])};
+  p_prev[0] = pack_bf16x8(&x[0]);
+  p_prev[1] = pack_bf16x8(&x[8]);
+  if (DO_C) {
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
-  for (int mf = 0; mf < 2; ++mf) {
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
+      __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);  // 6 VALU
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // 2 LDS reads
+    }
+  }
+  if (trig) {
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) oacc[dt] = mfma32(lds_trp(vt, lo, 32 * KS + 16 * mf, dt), pop[mf], oacc[dt]);
+    for (int dt = 0; dt < 4; ++dt) oacc[dt] *= alpha;
   }
-}
-
-// one key tile (two sub-tiles, upper keys first) out of LDS buffer CUR
-template <int CUR>
-__device__ __forceinline__ void swa_tile(unsigned char* smem, int kt0, int qa, int myq, int W, float scale_log2,
-                                         const bf16x8_t (&qop)[8], f32x16_t (&oacc)[4], float& m, float& l, int lane,
-                                         const LaneOff& lo) {
-  const int qb = qa + 31;
-  {
-    const int ka = kt0 + 32;
-    if (ka <= qb && ka + 31 >= qa - W + 1)
-      swa_subtile<CUR, 1>(smem, ka, myq, W, !(ka + 31 <= qa && ka >= qb - W + 1), scale_log2, qop, oacc, m, l, lane, lo);
-  }
-  {
-    const int ka = kt0;
-    if (ka <= qb && ka + 31 >= qa - W + 1)
-      swa_subtile<CUR, 0>(smem, ka, myq, W, !(ka + 31 <= qa && ka >= qb - W + 1), scale_log2, qop, oacc, m, l, lane, lo);
-  }
+  s_cur = s_next;
 }
 
 // 8-byte stores straight from accumulator layout (used where LDS still holds live tiles)
@@ -150,14 +197,19 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
   const size_t stat_off = (size_t)(b * Hq + hq) * T + myq;
 
   // ------------------------------------------------------------------ softmax branch
-  // key tiles of 64 from the diagonal down to kt_lo; the first one is in flight while q arrives
+  // key tiles of 64 from the diagonal (n = 0) down to kt_lo (n = ntiles-1); tile n uses LDS buffer n & 1.
+  // K runs one tile ahead of V through the buffers (the S^T chain of a sub-tile is issued one step early).
   const int kt_lo = max(0, t0 - W);
-  const int ntiles = (t0 + 128 - kt_lo) / 64;
-  {
-    const int kt0 = kt_lo + 64 * (ntiles - 1);
-    tile_load_async<4>(kbase + (size_t)kt0 * kstride, kstride, smem, w * 4, lane);
-    tile_load_async<4>(vbase + (size_t)kt0 * kstride, kstride, smem + 32768, w * 4, lane);
-  }
+  const int ntiles = (t0 + 128 - kt_lo) / 64;  // >= 2
+  auto load_k = [&](int n) {
+    tile_load_async<4>(kbase + (size_t)(kt_lo + 64 * (ntiles - 1 - n)) * kstride, kstride, smem + (n & 1) * 16384, w * 4, lane);
+  };
+  auto load_v = [&](int n) {
+    tile_load_async<4>(vbase + (size_t)(kt_lo + 64 * (ntiles - 1 - n)) * kstride, kstride, smem + 32768 + (n & 1) * 16384, w * 4, lane);
+  };
+  load_k(0);
+  load_v(0);
+  load_k(1);
   bf16x8_t qop[8];
   {
     const uint16_t* qp = a.q + qtile_off + (size_t)(32 * w + r32) * qstride + 8 * h;
@@ -168,25 +220,32 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
   __syncthreads();
   f32x16_t oacc[4] = {{0}, {0}, {0}, {0}};
   float m = M_INIT, l = 0.f;
-  const int qa = t0 + 32 * w;
-  auto prefetch = [&](int n) {  // tile of iteration n+1 into the buffer iteration n does not read
-    const int ktn = kt_lo + 64 * (ntiles - 2 - n);
-    const int nb = (n & 1) ^ 1;
-    tile_load_async<4>(kbase + (size_t)ktn * kstride, kstride, smem + nb * 16384, w * 4, lane);
-    tile_load_async<4>(vbase + (size_t)ktn * kstride, kstride, smem + 32768 + nb * 16384, w * 4, lane);
-  };
+  SweepGeom gm;
+  gm.kt_lo = kt_lo; gm.ntiles = ntiles; gm.qa = t0 + 32 * w; gm.W = W;
+  f32x16_t s_cur;
+  bf16x8_t p_prev[2];
+  qk_chain<0, 1>(smem, lo, qop, s_cur);
+  // step 0 has no earlier sub-tile to fold in; the step after the last one only folds
+  sweep_step<0, false>(smem, lo, gm, 0, myq, a.scale_log2, qop, oacc, m, l, s_cur, p_prev, lane);
   for (int n = 0; n < ntiles; n += 2) {
-    if (n + 1 < ntiles) prefetch(n);
-    swa_tile<0>(smem, kt_lo + 64 * (ntiles - 1 - n), qa, myq, W, a.scale_log2, qop, oacc, m, l, lane, lo);
+    if (n > 0) sweep_step<0, true>(smem, lo, gm, 2 * n, myq, a.scale_log2, qop, oacc, m, l, s_cur, p_prev, lane);
     wait_vmem();
     __syncthreads();
+    if (n + 2 < ntiles) load_k(n + 2);
+    if (n + 1 < ntiles) load_v(n + 1);
+    sweep_step<1, true>(smem, lo, gm, 2 * n + 1, myq, a.scale_log2, qop, oacc, m, l, s_cur, p_prev, lane);
     if (n + 1 < ntiles) {
-      if (n + 2 < ntiles) prefetch(n + 1);
-      swa_tile<1>(smem, kt_lo + 64 * (ntiles - 2 - n), qa, myq, W, a.scale_log2, qop, oacc, m, l, lane, lo);
+      sweep_step<2, true>(smem, lo, gm, 2 * n + 2, myq, a.scale_log2, qop, oacc, m, l, s_cur, p_prev, lane);
       wait_vmem();
       __syncthreads();
+      if (n + 3 < ntiles) load_k(n + 3);
+      if (n + 2 < ntiles) load_v(n + 2);
+      sweep_step<3, true>(smem, lo, gm, 2 * n + 3, myq, a.scale_log2, qop, oacc, m, l, s_cur, p_prev, lane);
     }
   }
+  if (ntiles & 1) pv_chain<0, 0>(smem, lo, p_prev, oacc);
+  else pv_chain<1, 0>(smem, lo, p_prev, oacc);
+  __syncthreads();
   // the two lowest key tiles are still resident: tile `it` sits in buffer (ntiles-1-it) & 1
 
   l = half_sum(l);
