@@ -131,7 +131,7 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
     off = 0;
     L->fb_dxs = off; off += align_up(nq * 2);
     L->fb_dxr = off; off += align_up(nq * 2);
-    L->fb_delta = off; off += align_up(nrow * 4);
+    L->fb_delta = off; off += align_up(nrow * 8);  // delta, then log-sum-exp in log2 units
     L->fb_u = off; off += align_up(bp.u_bytes);
     L->fb_states = off; off += align_up(bp.fwd.state_bytes);
     L->fb_rstates = off; off += align_up(bp.rstate_bytes);

@@ -184,3 +184,34 @@ def test_decode_step_random_positions(dtype):
     assert maxerr(o, o_ref) <= TOL[dtype]
     assert np.array_equal(np64(d["k_ring"]), kr_ref) and np.array_equal(np64(d["v_ring"]), vr_ref)
     assert float(np.max(np.abs(np64(d["state"]) - S_ref))) <= 1e-5 * max(1.0, float(np.abs(S_ref).max()))
+
+
+def _decode_vs_oracle(cfg, pos, tol):
+    x = synth.make_decode_inputs(cfg, pos=pos)
+    pos_l = [int(p) for p in x["pos"]]
+    o_ref, kr_ref, vr_ref, S_ref = orc.decode_step(np64(x["q"]), np64(x["k_new"]), np64(x["v_new"]), pos_l,
+                                                   np64(x["k_ring"]), np64(x["v_ring"]), np64(x["state"]), cfg.W,
+                                                   scale=cfg.scale)
+    d = {k_: v_.cuda() for k_, v_ in x.items()}
+    o = rb.rattn_decode_step(d["q"], d["k_new"], d["v_new"], d["pos"], d["k_ring"], d["v_ring"], d["state"],
+                             softmax_scale=cfg.scale)
+    err = np.abs(np64(o) - o_ref)
+    if cfg.dtype == "bf16":     # discount the rounding of the stored output itself
+        err = np.maximum(err - 2.0 ** -8 * np.abs(o_ref), 0.0)
+    assert float(err.max()) <= tol
+    assert np.array_equal(np64(d["k_ring"]), kr_ref) and np.array_equal(np64(d["v_ring"]), vr_ref)
+    assert float(np.max(np.abs(np64(d["state"]) - S_ref))) <= 1e-5 * max(1.0, float(np.abs(S_ref).max()))
+
+
+@pytest.mark.parametrize("W", [200, 512, 1000])
+def test_decode_bf16_long_rings(W):
+    """Rings spanning several 128-key steps, a ragged last step, and every fill level of the ring."""
+    cfg = synth.DecodeConfig("rings", 8, 8, 2, 128, W, "bf16", 13, 0, 4 * W, 1.0 / math.sqrt(128))
+    pos = [0, 31, 127, 128, W - 1, W, W + 1, 3 * W + 77]
+    _decode_vs_oracle(cfg, pos, TOL["bf16"])
+
+
+def test_decode_full_config_all_sequences():
+    """The decode workload the benchmark times (128 sequences, 32 query / 8 kv heads, W = 512), every output."""
+    cfg = synth.DECODE_CONFIGS["decode_b128_w512"]
+    _decode_vs_oracle(cfg, None, TOL["bf16"])
