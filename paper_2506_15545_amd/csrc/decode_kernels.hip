@@ -234,7 +234,7 @@ template <> struct raw8<bf16_t> {
 //           output feature d = 8*(l%16)+e and whose contraction slots are the lane group's eight keys; B is
 //           the matching run of eight probabilities of head l%16 (bf16, from LDS).
 template <typename IO, int D, bool MFMA>
-__global__ __launch_bounds__(256) void decode_kernel_2pass(const IO* __restrict__ q, const IO* __restrict__ k_new,
+__global__ __launch_bounds__(256, 4) void decode_kernel_2pass(const IO* __restrict__ q, const IO* __restrict__ k_new,
                                                            const IO* __restrict__ v_new, const int32_t* __restrict__ pos,
                                                            IO* __restrict__ k_ring, IO* __restrict__ v_ring,
                                                            float* __restrict__ state, const float* __restrict__ gs,
