@@ -5,7 +5,7 @@ A step = rattn_fwd (saving for backward) + rattn_bwd on the 3B-scale layer
 (B=4, Hq=24, Hkv=8, T=4096, D=128, W=512, bf16), inputs resident in HBM.  `value` is the
 algorithmic TFLOP/s of fwd+bwd: exact in-window (t,s) pairs plus the chunked linear-attention
 products at nominal chunk 64, no recomputation and no masked-tile waste counted.
-Prints ONE JSON line (see the design doc for the field definitions).
+Prints ONE JSON line.
 """
 import argparse
 import json
@@ -59,6 +59,18 @@ def kernel_algorithmic_flops(name, fl):
     return table.get(name)
 
 
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` from the committed counter summary (FETCH_SIZE + WRITE_SIZE, scaled by
+    what the same counters read for a plain copy of known size), or None when no summary covers it."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    try:
+        with open(path) as f:
+            rows = json.loads(f.read().split("---JSON---", 1)[1])
+        return rows.get(kernel, {}).get("hbm_bytes_per_launch")
+    except (OSError, IndexError, ValueError):
+        return None
+
+
 def decode_bytes(N, Hkv, Hq, D, W, esize, nvalid_sum=None):
     ring = 2 * N * Hkv * W * D * esize if nvalid_sum is None else 2 * nvalid_sum * Hkv * D * esize
     state = 2 * N * Hkv * D * D * 4
@@ -95,11 +107,14 @@ def cpu_baseline(cfg, heads):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
-    ap.add_argument("--cpu-heads", type=int, default=3)
+    ap.add_argument("--cpu-heads", type=int, default=24)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain out-of-place elementwise pass over 256 MiB (reads and writes 256 MiB): "
+                         "under a counter run its FETCH_SIZE / WRITE_SIZE readings give the counters' scale")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -122,30 +137,43 @@ def main():
     o = torch.empty_like(q)
     grads = (torch.empty_like(q), torch.empty_like(k), torch.empty_like(v))
 
-    def step():
+    def fwd_only():
         rb.rattn_fwd(q, k, v, cfg.W, softmax_scale=cfg.scale, save_for_bwd=True, out=o, saved=saved, workspace=ws)
+
+    def bwd_only():
         rb.rattn_bwd(q, k, v, saved, dO, cfg.W, softmax_scale=cfg.scale, want_dgamma=False, workspace=ws, out=grads)
+
+    def step():
+        fwd_only()
+        bwd_only()
+
+    def timed(fn, n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
 
     for _ in range(args.warmup):
         step()
-    torch.cuda.synchronize()
+    # the timed region: exactly `steps` steps, nothing else on the stream
+    ms_per_step = timed(step, args.steps)
+    # the same steps again with the library's per-kernel HIP events (recorded on the launch stream) switched
+    # on; they serialise neighbouring kernels, so they stay out of the region `value` is taken from
     rb.rattn_profile_enable(True)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(args.steps):
-        step()
-    e1.record()
-    torch.cuda.synchronize()
-    ms_per_step = e0.elapsed_time(e1) / args.steps
+    ms_per_step_profiled = timed(step, args.steps)
     recs = rb.rattn_profile_records()
     rb.rattn_profile_enable(False)
+    fwd_ms = timed(fwd_only, args.steps)
+    bwd_ms = timed(bwd_only, args.steps)
 
     fl = layer_flops(cfg.B, cfg.T, cfg.Hq, cfg.Hkv, cfg.D, cfg.W)
     total = fl["fwd"] + fl["bwd"]
     value = total / (ms_per_step * 1e-3) / 1e12
 
-    # per-kernel averages from the library's own HIP events (recorded on the launch stream)
     agg = {}
     for name, ms in recs:
         a = agg.setdefault(name, [0.0, 0])
@@ -157,11 +185,9 @@ def main():
     peak = PEAK_BF16_MFMA if mfma_path else PEAK_FP32_VALU
     achieved = (dom_fl or 0.0) / (kernels[dom]["avg_ms"] * 1e-3)
     roofline = {"bound": "mfma" if mfma_path else "alu", "kernel": dom, "achieved": achieved / 1e12,
-                "peak": peak / 1e12, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
-                "avg_ms": kernels[dom]["avg_ms"]}
-    fwd_ms = sum(kernels[n]["avg_ms"] * kernels[n]["launches_per_step"] for n in kernels
-                 if "bwd" not in n and n not in ("gen_scan_kernel(x2)",))
-    bwd_ms = sum(kernels[n]["avg_ms"] * kernels[n]["launches_per_step"] for n in kernels) - fwd_ms
+                "peak": peak / 1e12, "unit": "TFLOP/s", "frac": achieved / peak,
+                "traffic": measured_traffic(dom, cfg.name), "avg_ms": kernels[dom]["avg_ms"],
+                "algorithmic_flops": dom_fl}
 
     out = {
         "metric": "fused SWA+RLA fwd+bwd TFLOP/s & % MFMA peak @T=4096,w=512,d=128",
@@ -172,6 +198,7 @@ def main():
                    "W": cfg.W, "step": "rattn_fwd(save_for_bwd)+rattn_bwd"},
         "frac_mfma_peak": value * 1e12 / PEAK_BF16_MFMA,
         "tokens_per_s": cfg.B * cfg.T / (ms_per_step * 1e-3),
+        "ms_per_step_profiled": ms_per_step_profiled,
         "fwd": {"ms": fwd_ms, "tflops": fl["fwd"] / (fwd_ms * 1e-3) / 1e12,
                 "frac_mfma_peak": fl["fwd"] / (fwd_ms * 1e-3) / PEAK_BF16_MFMA},
         "bwd": {"ms": bwd_ms, "tflops": fl["bwd"] / (bwd_ms * 1e-3) / 1e12,
@@ -186,7 +213,7 @@ def main():
         od = torch.empty_like(d["q"])
         dstep = lambda: rb.rattn_decode_step(d["q"], d["k_new"], d["v_new"], d["pos"], d["k_ring"], d["v_ring"],
                                              d["state"], softmax_scale=dcfg.scale, out=od)
-        for _ in range(5):
+        for _ in range(20):
             dstep()
         torch.cuda.synchronize()
         rb.rattn_profile_enable(True)
@@ -198,9 +225,19 @@ def main():
         rb.rattn_profile_enable(False)
         us = sum(drecs) / len(drecs) * 1e3
         nbytes = decode_bytes(dcfg.N, dcfg.Hkv, dcfg.Hq, dcfg.D, dcfg.W, 2)
-        out["decode"] = {"workload": dcfg.name, "us_per_step": us, "algorithmic_bytes": nbytes,
-                         "achieved_GBps": nbytes / (us * 1e-6) / 1e9, "frac_hbm_peak": nbytes / (us * 1e-6) / PEAK_HBM,
-                         "tokens_per_s": dcfg.N / (us * 1e-6)}
+        out["decode"] = {"workload": dcfg.name, "us_per_step": us, "tokens_per_s": dcfg.N / (us * 1e-6),
+                         "roofline": {"bound": "hbm", "kernel": "decode_kernel", "achieved": nbytes / (us * 1e-6) / 1e9,
+                                      "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": nbytes / (us * 1e-6) / PEAK_HBM,
+                                      "traffic": measured_traffic("decode_kernel", dcfg.name),
+                                      "algorithmic_bytes": nbytes}}
+
+    if args.calibrate_copy:
+        src = torch.zeros(256 * 2 ** 20 // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        out["calibration"] = {"kernel": "elementwise add, out-of-place", "bytes_read": src.numel() * 4,
+                              "bytes_written": dst.numel() * 4}
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, list(range(args.cpu_heads)))
