@@ -10,7 +10,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "librattn.so")
 OBJDIR = os.path.join(PKG, "_build")
 
-# packed fp32 VALU forms are switched off on purpose (see DESIGN notes on gfx950 code generation)
+# packed fp32 VALU forms are switched off on purpose: some of them have produced wrong results on gfx950 boxes
 HIPFLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
             "-I", os.path.join(ROOT, "include"), "-I", CSRC]

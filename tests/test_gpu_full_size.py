@@ -1,0 +1,144 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration `bench.py` times: the whole tensor
+goes through the library once, and whole KV groups (all G query heads that share a K/V head, in different
+batch rows) are compared with the fp64 oracle, which is fed just that group's slices.  Heads and batch rows
+are independent in the method, so a group is a complete sub-problem.  Covers the 3B-shaped layer (forward
+and backward, every token), the 12B-shaped layer at T = 8192 (forward; dq, dk, dv for every token of one
+group, and for the tokens from the middle of the sequence on in another), and the window sweep at T = 8192
+including W = T, where the linear branch is empty and the layer is RMS-normed causal attention."""
+import math
+import numpy as np
+import pytest
+import torch
+
+from oracle import rattn_oracle as orc
+from paper_2506_15545_amd import binding as rb
+from paper_2506_15545_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+OUT_TOL = 2e-2          # max-abs on unit-scale outputs, after the bf16 storage rounding of the output
+GRAD_TOL_MAX = 3e-2     # worst element against RMS + |ref|
+GRAD_TOL_RMS = 5e-3     # RMS error against RMS(ref)
+
+
+def np64(t):
+    return t.detach().cpu().to(torch.float64).numpy()
+
+
+def out_err(got, ref):
+    e = np.abs(np64(got) - ref)
+    return float(np.max(np.maximum(e - np.abs(ref) / 256.0, 0.0)))
+
+
+def grad_err(got, ref):
+    rms = math.sqrt(float(np.mean(ref ** 2))) + 1e-30
+    e = np.abs(np64(got) - ref)
+    return float(np.max(e / (rms + np.abs(ref)))), math.sqrt(float(np.mean(e ** 2))) / rms
+
+
+def group(cfg, t, b, g):
+    """[1, T, G or 1, D] slice of tensor t for KV group g of batch row b."""
+    G = cfg.Hq // cfg.Hkv
+    if t.shape[2] == cfg.Hq:
+        return t[b:b + 1, :, g * G:(g + 1) * G]
+    return t[b:b + 1, :, g:g + 1]
+
+
+def run_fwd(cfg, q, k, v, save):
+    return rb.rattn_fwd(q.cuda(), k.cuda(), v.cuda(), cfg.W, softmax_scale=cfg.scale, save_for_bwd=save)
+
+
+def check_fwd_groups(cfg, q, k, v, o, groups):
+    for b, g in groups:
+        print(f"  oracle fwd {cfg.name} W={cfg.W} batch {b} kv-group {g}", flush=True)
+        ref = orc.fwd_dense(np64(group(cfg, q, b, g)), np64(group(cfg, k, b, g)), np64(group(cfg, v, b, g)),
+                            cfg.W, scale=cfg.scale)
+        assert out_err(group(cfg, o, b, g), ref["o"]) <= OUT_TOL, (b, g)
+        yield b, g, ref
+
+
+def test_layer3b_fwd_bwd_full_size():
+    cfg = synth.CONFIGS["layer3b_t4096_w512"]
+    q, k, v, dO = synth.make_layer_inputs(cfg, with_dO=True)
+    print("layer3b: forward + backward on the GPU", flush=True)
+    o, saved = run_fwd(cfg, q, k, v, True)
+    dq, dk, dv, _, _ = rb.rattn_bwd(q.cuda(), k.cuda(), v.cuda(), saved, dO.cuda(), cfg.W, softmax_scale=cfg.scale,
+                                    want_dgamma=False)
+    torch.cuda.synchronize()
+    groups = [(0, 0), (cfg.B - 1, cfg.Hkv - 1)]
+    for b, g, _ in check_fwd_groups(cfg, q, k, v, o, groups):
+        print(f"  oracle bwd batch {b} kv-group {g}", flush=True)
+        ref = orc.bwd_dense(np64(group(cfg, q, b, g)), np64(group(cfg, k, b, g)), np64(group(cfg, v, b, g)),
+                            np64(group(cfg, dO, b, g)), cfg.W, scale=cfg.scale)
+        for name, got in (("dq", dq), ("dk", dk), ("dv", dv)):
+            emax, erms = grad_err(group(cfg, got, b, g), ref[name])
+            assert emax <= GRAD_TOL_MAX and erms <= GRAD_TOL_RMS, (name, b, g, emax, erms)
+
+
+_cache = {}
+
+
+def layer12b_on_gpu():
+    """One library pass over the whole 12B-shaped tensor, shared by the tests below."""
+    if "12b" not in _cache:
+        cfg = synth.CONFIGS["layer12b_t8192_w512"]
+        q, k, v, dO = synth.make_layer_inputs(cfg, with_dO=True)
+        print("layer12b: forward + backward on the GPU", flush=True)
+        o, saved = run_fwd(cfg, q, k, v, True)
+        dq, dk, dv, _, _ = rb.rattn_bwd(q.cuda(), k.cuda(), v.cuda(), saved, dO.cuda(), cfg.W,
+                                        softmax_scale=cfg.scale, want_dgamma=False)
+        torch.cuda.synchronize()
+        _cache["12b"] = (cfg, q, k, v, dO, o.cpu(), dq.cpu(), dk.cpu(), dv.cpu())
+    return _cache["12b"]
+
+
+def test_layer12b_fwd_full_size():
+    cfg, q, k, v, dO, o, dq, dk, dv = layer12b_on_gpu()
+    list(check_fwd_groups(cfg, q, k, v, o, [(0, 0), (1, cfg.Hkv - 1)]))
+
+
+def test_layer12b_bwd_whole_group():
+    """Every query row of one group: dq everywhere (incl. t < W and the sequence end), dk/dv everywhere."""
+    cfg, q, k, v, dO, o, dq, dk, dv = layer12b_on_gpu()
+    b, g = 0, 0
+    print("  oracle bwd batch 0 kv-group 0, all rows", flush=True)
+    ref = orc.bwd_dense(np64(group(cfg, q, b, g)), np64(group(cfg, k, b, g)), np64(group(cfg, v, b, g)),
+                        np64(group(cfg, dO, b, g)), cfg.W, scale=cfg.scale)
+    for name, got in (("dq", dq), ("dk", dk), ("dv", dv)):
+        emax, erms = grad_err(group(cfg, got, b, g), ref[name])
+        assert emax <= GRAD_TOL_MAX and erms <= GRAD_TOL_RMS, (name, emax, erms)
+
+
+def test_layer12b_bwd_middle_slice():
+    """The 512-token slice in the middle of another batch row and group.  dq of rows [3840, 4352) needs only
+    those rows; dk/dv of keys [3840, 4352) need every later query (in-window ones t < s + W, residual ones
+    t >= s + W)."""
+    cfg, q, k, v, dO, o, dq, dk, dv = layer12b_on_gpu()
+    b, g = 1, cfg.Hkv - 1
+    lo, hi = 3840, 4352
+    print("  oracle bwd batch 1 last kv-group, rows 3840..T", flush=True)
+    ref = orc.bwd_dense(np64(group(cfg, q, b, g)), np64(group(cfg, k, b, g)), np64(group(cfg, v, b, g)),
+                        np64(group(cfg, dO, b, g)), cfg.W, scale=cfg.scale, rows=np.arange(lo, cfg.T))
+    for name, got in (("dq", dq), ("dk", dk), ("dv", dv)):
+        emax, erms = grad_err(group(cfg, got, b, g)[:, lo:hi], ref[name][:, lo:hi])
+        assert emax <= GRAD_TOL_MAX and erms <= GRAD_TOL_RMS, (name + " slice", emax, erms)
+
+
+@pytest.mark.parametrize("W", [128, 512, 1024, 4096, 8192])
+def test_window_sweep_fwd_full_size(W):
+    cfg = synth.sweep_config(W)
+    q, k, v = synth.make_layer_inputs(cfg)
+    print(f"sweep W={W}: forward on the GPU", flush=True)
+    o = run_fwd(cfg, q, k, v, False)
+    torch.cuda.synchronize()
+    for b, g, ref in check_fwd_groups(cfg, q, k, v, o, [(0, 0), (cfg.B - 1, cfg.Hkv - 1)]):
+        if W >= cfg.T:
+            # degenerate case: the linear branch is empty and the layer is RMS-normed causal attention
+            assert not np.any(ref["xr"])
+            qq, kk, vv = (torch.from_numpy(np64(group(cfg, t, b, g))).permute(0, 2, 1, 3) for t in (q, k, v))
+            G = cfg.Hq // cfg.Hkv
+            att = torch.nn.functional.scaled_dot_product_attention(qq, kk.expand(-1, G, -1, -1), vv.expand(-1, G, -1, -1),
+                                                                   is_causal=True, scale=cfg.scale)
+            att = att.permute(0, 2, 1, 3).numpy()
+            causal = att / np.sqrt(np.mean(att * att, axis=-1, keepdims=True) + 1e-6)
+            assert out_err(group(cfg, o, b, g), causal) <= OUT_TOL
