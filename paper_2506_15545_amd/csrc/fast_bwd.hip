@@ -169,7 +169,7 @@ __device__ __forceinline__ void dq_subtile(const unsigned char* kt, const unsign
 }
 
 // grid (ntile * Hq * B), 256 threads: 128 queries of one head, wave w owns 32.
-__global__ __launch_bounds__(256, 1) void bwd_dq_kernel(FastBwdArgs a) {
+__global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
   __shared__ __align__(16) unsigned char smem[65536];
   const int lane = lane_id(), w = wave_id();
   const int r32 = lane & 31, h = lane >> 5;
