@@ -298,57 +298,57 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ void dkv_subtile(const unsigned char* qt, const unsigned char* dxt, int qs, int qa, int mykey,
-                                            int W, bool masked, float scale, float scale_log2, const float* lse_row,
-                                            const float* delta_row, const bf16x8_t (&kop)[8], const bf16x8_t (&vop)[8],
-                                            f32x16_t (&dk)[4], f32x16_t (&dv)[4], int lane, const LaneOff& lo) {
-  const int r32 = lane & 31, h = lane >> 5;
-  f32x16_t s = {0}, dp = {0};
+// phi in place on the first `nrows` rows of an LDS tile with 512 threads: four threads per row, 32 elements each
+__device__ __forceinline__ void phi_tile_inplace_512(unsigned char* tile, int nrows) {
+  const int row = threadIdx.x >> 2, part = threadIdx.x & 3;
+  if (row < nrows) {
+    float x[32];
+    unsigned char* rp = tile + row * ROW_BYTES;
+    const int sw = swz(row);
 #pragma unroll
-  for (int c = 0; c < 8; ++c) s = mfma32(lds_row(qt, lo, 32 * qs, c), kop[c], s);
+    for (int j = 0; j < 4; ++j)
+      unpack_bf16x8(*reinterpret_cast<const bf16x8_t*>(rp + (((4 * part + j) ^ sw) << 4)), &x[8 * j]);
+    float m = x[0];
 #pragma unroll
-  for (int c = 0; c < 8; ++c) dp = mfma32(lds_row(dxt, lo, 32 * qs, c), vop[c], dp);
-  if (masked) {
+    for (int i = 1; i < 32; ++i) m = fmaxf(m, x[i]);
+    m = fmaxf(m, __shfl_xor(m, 1, 64));
+    m = fmaxf(m, __shfl_xor(m, 2, 64));
+    float sum = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int query = qa + 8 * (i >> 2) + 4 * h + (i & 3);
-      s[i] = (mykey <= query && query - mykey < W) ? s[i] : -INFINITY;
-    }
-  }
-  float pv[16], ds[16];
+    for (int i = 0; i < 32; ++i) { x[i] = fast_exp2((x[i] - m) * LOG2E); sum += x[i]; }
+    sum += __shfl_xor(sum, 1, 64);
+    sum += __shfl_xor(sum, 2, 64);
+    const float inv = 1.f / sum;
 #pragma unroll
-  for (int i4 = 0; i4 < 4; ++i4) {
-    const int qrow = qa + 8 * i4 + 4 * h;
-    const float4 ls = *reinterpret_cast<const float4*>(lse_row + qrow);
-    const float4 dl = *reinterpret_cast<const float4*>(delta_row + qrow);
-    const float lsa[4] = {ls.x, ls.y, ls.z, ls.w}, dla[4] = {dl.x, dl.y, dl.z, dl.w};
+    for (int i = 0; i < 32; ++i) x[i] *= inv;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int i = 4 * i4 + e;
-      const float p = fast_exp2(__builtin_fmaf(s[i], scale_log2, -lsa[e] * LOG2E));
-      pv[i] = p;
-      ds[i] = p * (dp[i] - dla[e]) * scale;
-    }
-  }
-  bf16x8_t pop[2] = {pack_bf16x8(&pv[0]), pack_bf16x8(&pv[8])};
-  bf16x8_t dsop[2] = {pack_bf16x8(&ds[0]), pack_bf16x8(&ds[8])};
-#pragma unroll
-  for (int mf = 0; mf < 2; ++mf) {
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt) {
-      dv[dt] = mfma32(lds_trp(dxt, lo, 32 * qs + 16 * mf, dt), pop[mf], dv[dt]);
-      dk[dt] = mfma32(lds_trp(qt, lo, 32 * qs + 16 * mf, dt), dsop[mf], dk[dt]);
-    }
+    for (int j = 0; j < 4; ++j)
+      *reinterpret_cast<bf16x8_t*>(rp + (((4 * part + j) ^ sw) << 4)) = pack_bf16x8(&x[8 * j]);
   }
 }
 
-// grid (ntile * Hkv * B), 256 threads: 128 keys of one KV head, wave w owns 32 (lane = key).
-__global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(FastBwdArgs a) {
-  __shared__ __align__(16) unsigned char smem[65536];
-  const int lane = lane_id(), w = wave_id();
+constexpr int DKV_TILE_BYTES = 65536;  // q / dx tiles (two buffers of 64 rows each, or one of 128 rows each)
+constexpr int DKV_PEX_BYTES = 32768;   // probabilities handed from the V-role to the K-role waves
+constexpr int DKV_LDS_BYTES = DKV_TILE_BYTES + DKV_PEX_BYTES;
+
+// grid (ntile * Hkv * B), 512 threads: 128 keys of one KV head.  Waves w and w+4 both work on key block w
+// (lane = key) and share a SIMD, with complementary roles, so each keeps only one 128 x 32 accumulator and one
+// set of operand rows and two waves fit on a SIMD:
+//   V-role (waves 0-3): S^T = Q K^T -> P (also written to LDS, fp32),  dV^T += dXs^T P;
+//                       linear branch: C = phi(Q) phi(K)^T (masked),   dV^T += dXr^T C + R-state rows * phi(K)
+//   K-role (waves 4-7): dP = dXs V^T, then dS = P .* (dP - delta) * scale with the P of its partner,
+//                       dK^T += Q^T dS;  linear branch: dC = dXr V^T (masked), dphi(K)^T += phi(Q)^T dC + R V^T,
+//                       softmax Jacobian of phi before the softmax-branch terms are added.
+// Per 32-query sub-tile: one work-group barrier hands P over (LDS buffer alternates with the sub-tile parity),
+// one more per 64-query tile publishes the next DMA'd tile.
+__global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char* pex = smem + DKV_TILE_BYTES;
+  const int lane = lane_id(), w8 = wave_id();
+  const int w = w8 & 3;
+  const bool krole = w8 >= 4;
   const int r32 = lane & 31, h = lane >> 5;
   const LaneOff lo = make_lane_off(lane);
-  const LaneOffN lon = make_lane_off_n(lane);
   const int T = a.T, W = a.W, Hq = a.Hq, Hkv = a.Hkv, G = a.G;
   const int total = gridDim.x, bid = blockIdx.x;
   int wid = (total % 8 == 0) ? (bid % 8) * (total / 8) + bid / 8 : bid;
@@ -362,76 +362,76 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(FastBwdArgs a) {
   const size_t myrow_off = ktile_off + (size_t)(32 * w + r32) * kstride;
   const int mykey = s0 + 32 * w + r32;
 
-  bf16x8_t kop[8], vop[8];
-  load_bop(a.k + myrow_off, h, kop);
-  load_bop(a.v + myrow_off, h, vop);
-  f32x16_t dk[4] = {{0}, {0}, {0}, {0}}, dv[4] = {{0}, {0}, {0}, {0}};
+  bf16x8_t xop[8];  // V-role: K rows (phi(K) rows during the linear branch); K-role: V rows
+  load_bop((krole ? a.v : a.k) + myrow_off, h, xop);
+  f32x16_t acc[4] = {{0}, {0}, {0}, {0}};  // V-role: dV^T; K-role: dK^T
 
-  // ---- linear branch (dk accumulates d phi(k) here, turned into dk by the Jacobian at the end)
+  // ---- linear branch
   if (s0 < Tp) {
     const int nq = min(128, Tp - s0);  // query rows t = s0 + W + [0, nq) pair with this key tile
-    bf16x8_t kfop[8];
-    {
+    if (!krole) {
       float x[64];
 #pragma unroll
-      for (int c = 0; c < 8; ++c) unpack_bf16x8(kop[c], &x[8 * c]);
-      phi_rows(x, kfop);
+      for (int c = 0; c < 8; ++c) unpack_bf16x8(xop[c], &x[8 * c]);
+      phi_rows(x, xop);
     }
     const uint16_t* rbase = a.rstates + ((size_t)(b * Hkv + g) * a.nk + kti) * 16384;
-    tile_load_async<8>(rbase, 128, smem, w * 8, lane);
+    tile_load_async<4>(rbase, 128, smem, w8 * 4, lane);
     wait_vmem();
     __syncthreads();
+    if (!krole) {
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {
+      for (int c = 0; c < 8; ++c)
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        dv[t] = mfma32(lds_row(smem, lo, 32 * t, c), kfop[c], dv[t]);
-        dk[t] = mfma32(lds_trn(smem, lon, 16 * c, t), vop[c], dk[t]);
-      }
+        for (int t = 0; t < 4; ++t) acc[t] = mfma32(lds_row(smem, lo, 32 * t, c), xop[c], acc[t]);
+    } else {
+      const LaneOffN lon = make_lane_off_n(lane);
+#pragma unroll
+      for (int c = 0; c < 8; ++c)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[t] = mfma32(lds_trn(smem, lon, 16 * c, t), xop[c], acc[t]);
     }
     for (int hh = 0; hh < G; ++hh) {
       const size_t qoff = ((size_t)(b * T + s0 + W) * Hq + g * G + hh) * 128;
       __syncthreads();
-      tile_load_async<4>(a.q + qoff, qstride, smem, w * 4, lane);
-      tile_load_async<4>(a.dxr + qoff, qstride, smem + 32768, w * 4, lane);
+      tile_load_async<2>(a.q + qoff, qstride, smem, w8 * 2, lane);
+      tile_load_async<2>(a.dxr + qoff, qstride, smem + 32768, w8 * 2, lane);
       if (nq == 128) {
-        tile_load_async<4>(a.q + qoff, qstride, smem, 16 + w * 4, lane);
-        tile_load_async<4>(a.dxr + qoff, qstride, smem + 32768, 16 + w * 4, lane);
+        tile_load_async<2>(a.q + qoff, qstride, smem, 16 + w8 * 2, lane);
+        tile_load_async<2>(a.dxr + qoff, qstride, smem + 32768, 16 + w8 * 2, lane);
       }
       wait_vmem();
       __syncthreads();
-      phi_tile_inplace(smem, nq);
+      phi_tile_inplace_512(smem, nq);
       __syncthreads();
+      const unsigned char* mine = krole ? smem + 32768 : smem;    // rows contracted with xop
+      const unsigned char* other = krole ? smem : smem + 32768;   // rows accumulated into acc
       for (int u = w; u < nq / 32; ++u) {
-        f32x16_t c = {0}, dc = {0};
+        f32x16_t c = {0};
 #pragma unroll
-        for (int e = 0; e < 8; ++e) c = mfma32(lds_row(smem, lo, 32 * u, e), kfop[e], c);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) dc = mfma32(lds_row(smem + 32768, lo, 32 * u, e), vop[e], dc);
-        float cv[16], dcv[16];
+        for (int e = 0; e < 8; ++e) c = mfma32(lds_row(mine, lo, 32 * u, e), xop[e], c);
+        float cv[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int q_local = 32 * u + 8 * (i >> 2) + 4 * h + (i & 3);
           const bool keep = !(u == w && 32 * w + r32 > q_local);
           cv[i] = keep ? c[i] : 0.f;
-          dcv[i] = keep ? dc[i] : 0.f;
         }
-        bf16x8_t cop[2] = {pack_bf16x8(&cv[0]), pack_bf16x8(&cv[8])};
-        bf16x8_t dcop[2] = {pack_bf16x8(&dcv[0]), pack_bf16x8(&dcv[8])};
+        const bf16x8_t cop[2] = {pack_bf16x8(&cv[0]), pack_bf16x8(&cv[8])};
 #pragma unroll
-        for (int mf = 0; mf < 2; ++mf) {
+        for (int mf = 0; mf < 2; ++mf)
 #pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            dv[t] = mfma32(lds_trp(smem + 32768, lo, 32 * u + 16 * mf, t), cop[mf], dv[t]);
-            dk[t] = mfma32(lds_trp(smem, lo, 32 * u + 16 * mf, t), dcop[mf], dk[t]);
-          }
-        }
+          for (int t = 0; t < 4; ++t) acc[t] = mfma32(lds_trp(other, lo, 32 * u + 16 * mf, t), cop[mf], acc[t]);
       }
     }
     __syncthreads();
-    float kf[64];
-    phi_row_clayout(a.k + myrow_off, h, kf);
-    phi_jacobian(dk, kf);
+    if (krole) {
+      float kf[64];
+      phi_row_clayout(a.k + myrow_off, h, kf);
+      phi_jacobian(acc, kf);
+    } else {
+      load_bop(a.k + myrow_off, h, xop);
+    }
   }
 
   // ---- softmax branch: query tiles of 64 rows from s0 up to the last row that still sees these keys
@@ -441,8 +441,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(FastBwdArgs a) {
   auto issue = [&](int step, int buf) {
     const int hh = step / n_qt, n = step % n_qt;
     const size_t qoff = ((size_t)(b * T + s0 + 64 * n) * Hq + g * G + hh) * 128;
-    tile_load_async<4>(a.q + qoff, qstride, smem + buf * 16384, w * 4, lane);
-    tile_load_async<4>(a.dxs + qoff, qstride, smem + 32768 + buf * 16384, w * 4, lane);
+    tile_load_async<2>(a.q + qoff, qstride, smem + buf * 16384, w8 * 2, lane);
+    tile_load_async<2>(a.dxs + qoff, qstride, smem + 32768 + buf * 16384, w8 * 2, lane);
   };
   issue(0, 0);
   wait_vmem();
@@ -452,33 +452,90 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(FastBwdArgs a) {
     if (step + 1 < nsteps) issue(step + 1, cur ^ 1);
     const int hh = step / n_qt, n = step % n_qt;
     const int hq = g * G + hh;
-    const float* lse_row = a.lse + (size_t)(b * Hq + hq) * T;
-    const float* delta_row = a.delta + (size_t)(b * Hq + hq) * T;
+    const float* stat_row = (krole ? a.delta : a.lse) + (size_t)(b * Hq + hq) * T;
     const unsigned char* qtile = smem + cur * 16384;
     const unsigned char* dxt = smem + 32768 + cur * 16384;
 #pragma unroll
     for (int qs = 0; qs < 2; ++qs) {
       const int qa = s0 + 64 * n + 32 * qs;
       const bool need = qa + 31 >= ka && qa <= ka + 31 + W - 1;
+      const bool full = qa >= ka + 31 && qa + 31 <= ka + W - 1;
+      f32x4_t* px = reinterpret_cast<f32x4_t*>(pex + (w * 2 + qs) * 4096 + lane * 16);  // [i4][lane] x 16 bytes
+      f32x16_t s = {0};
+      float stat[16];
       if (need) {
-        const bool full = qa >= ka + 31 && qa + 31 <= ka + W - 1;
-        dkv_subtile(qtile, dxt, qs, qa, mykey, W, !full, a.scale, a.scale_log2, lse_row, delta_row, kop, vop, dk, dv, lane, lo);
+        const unsigned char* rows = krole ? dxt : qtile;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) s = mfma32(lds_row(rows, lo, 32 * qs, c), xop[c], s);
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const float4 f = *reinterpret_cast<const float4*>(stat_row + qa + 8 * i4 + 4 * h);
+          stat[4 * i4] = f.x; stat[4 * i4 + 1] = f.y; stat[4 * i4 + 2] = f.z; stat[4 * i4 + 3] = f.w;
+        }
+        if (!krole) {
+          if (!full) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int query = qa + 8 * (i >> 2) + 4 * h + (i & 3);
+              s[i] = (mykey <= query && query - mykey < W) ? s[i] : -INFINITY;
+            }
+          }
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s[i] = fast_exp2(__builtin_fmaf(s[i], a.scale_log2, -stat[i] * LOG2E));
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) px[i4 * 64] = f32x4_t{s[4 * i4], s[4 * i4 + 1], s[4 * i4 + 2], s[4 * i4 + 3]};
+        }
+      }
+      __syncthreads();  // P of this sub-tile is in LDS
+      if (need) {
+        float x[16];
+        if (!krole) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) x[i] = s[i];
+        } else {
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) {
+            const f32x4_t pv = px[i4 * 64];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[4 * i4 + e] = pv[e] * (s[4 * i4 + e] - stat[4 * i4 + e]) * a.scale;
+          }
+        }
+        const bf16x8_t xo[2] = {pack_bf16x8(&x[0]), pack_bf16x8(&x[8])};
+        const unsigned char* cols = krole ? qtile : dxt;
+#pragma unroll
+        for (int mf = 0; mf < 2; ++mf)
+#pragma unroll
+          for (int dt = 0; dt < 4; ++dt) acc[dt] = mfma32(lds_trp(cols, lo, 32 * qs + 16 * mf, dt), xo[mf], acc[dt]);
       }
     }
     wait_vmem();
     __syncthreads();
   }
-  float vals[4][16];
+  // ---- dV^T (V-role) and dK^T (K-role) leave through LDS as two row-major tiles
+  {
+    unsigned char* tile = smem + (krole ? 32768 : 0);
+    const int row = 32 * w + r32;
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
+    for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) vals[dt][i] = dk[dt][i];
-  store_tile_transposed(smem, vals, a.dk + ktile_off, kstride, w, lane);
+      for (int i4 = 0; i4 < 4; ++i4) {
+        f32x4_t f = {acc[dt][4 * i4], acc[dt][4 * i4 + 1], acc[dt][4 * i4 + 2], acc[dt][4 * i4 + 3]};
+        const int c = 4 * dt + i4;
+        *reinterpret_cast<bf16x4_t*>(tile + row * ROW_BYTES + ((c ^ swz(row)) << 4) + 8 * h) =
+            __builtin_convertvector(f, bf16x4_t);
+      }
+    __syncthreads();
+    const int tid = threadIdx.x;
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) vals[dt][i] = dv[dt][i];
-  store_tile_transposed(smem, vals, a.dv + ktile_off, kstride, w, lane);
+    for (int i = 0; i < 8; ++i) {
+      const int id = tid + 512 * i;
+      const int which = id >> 11, r = (id >> 4) & 127, pch = id & 15;
+      const int c = pch ^ swz(r);
+      const uint4 val = *reinterpret_cast<const uint4*>(smem + which * 32768 + r * ROW_BYTES + (pch << 4));
+      uint16_t* dst = (which ? a.dk : a.dv) + ktile_off;
+      *reinterpret_cast<uint4*>(dst + (size_t)r * kstride + c * 8) = val;
+    }
+  }
 }
 
 }  // namespace
@@ -524,8 +581,11 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
     ProfScope ps("bwd_dq_kernel", st);
     bwd_dq_kernel<<<dim3(a.ntile * dm.Hq * dm.B), 256, 0, st>>>(a);
   }
+  static const hipError_t lds_attr = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(bwd_dkv_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS_BYTES);
+  (void)lds_attr;
   ProfScope ps("bwd_dkv_kernel", st);
-  bwd_dkv_kernel<<<dim3(a.ntile * dm.Hkv * dm.B), 256, 0, st>>>(a);
+  bwd_dkv_kernel<<<dim3(a.ntile * dm.Hkv * dm.B), 512, DKV_LDS_BYTES, st>>>(a);
 }
 
 }  // namespace rattn
