@@ -68,7 +68,8 @@ rattn_status rattn_workspace_bytes(const rattn_params* p, size_t* fwd_bytes, siz
  *   q [B,T,Hq,D]; k,v [B,T,Hkv,D]; o [B,T,Hq,D]
  *   gamma_swa, gamma_rla: fp32 [Hq,D] RMS gains of the two branches, NULL = all ones
  *   saved: opaque, saved_bytes large, written iff p->save_for_bwd (else may be NULL);
- *          holds the pre-norm branch outputs and the softmax / RMS row statistics
+ *          holds the pre-norm branch outputs, the softmax / RMS row statistics and, on the
+ *          matrix-core path, the linear-branch chunk states
  *   workspace: fwd_bytes of scratch (16-byte aligned), contents undefined on return */
 rattn_status rattn_fwd(const rattn_params* p, const void* q, const void* k, const void* v,
                        const float* gamma_swa, const float* gamma_rla, void* o, void* saved,
@@ -76,8 +77,9 @@ rattn_status rattn_fwd(const rattn_params* p, const void* q, const void* k, cons
 
 /* Backward of the layer: gradients of sum(o * dO) w.r.t. q, k, v and the gains.
  * Derived from Sec. 2.1, Eq. 4 and Sec. 3.2 (the linear-branch state gradients are the
- * reverse-time counterpart of Eqs. 2-3; chunk states are recomputed, not saved).
- *   saved: as written by rattn_fwd with the same params and inputs
+ * reverse-time counterpart of Eqs. 2-3).
+ *   saved: as written by rattn_fwd with the same params and inputs, in the same process
+ *          environment (the RATTN_FORCE_GENERIC debugging switch changes what `saved` holds)
  *   dq [B,T,Hq,D]; dk,dv [B,T,Hkv,D] (summed over the query heads of each group)
  *   dgamma_swa, dgamma_rla: fp32 [Hq,D], each may be NULL (then not computed) */
 rattn_status rattn_bwd(const rattn_params* p, const void* q, const void* k, const void* v,

@@ -48,7 +48,7 @@ struct Layout {
   rattn::LayerDims dm;
   size_t esize;
   // saved
-  size_t sv_xs, sv_xr, sv_lse, sv_rs, sv_rr, saved_bytes;
+  size_t sv_xs, sv_xr, sv_lse, sv_rs, sv_rr, sv_states, saved_bytes;
   // generic forward / backward workspace
   size_t gf_states, gen_fwd_bytes;
   size_t gb_states, gb_rstates, gb_dxs, gb_dxr, gb_delta, gb_dgpart, gen_bwd_bytes;
@@ -100,6 +100,9 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
   L->sv_lse = off; off += align_up(nrow * 4);
   L->sv_rs = off; off += align_up(nrow * 4);
   L->sv_rr = off; off += align_up(nrow * 4);
+  L->fast_fwd = rattn::fast_fwd_supported(dm, p->dtype);
+  L->sv_states = off;
+  if (L->fast_fwd) off += align_up(rattn::fast_fwd_plan(dm).state_bytes);
   L->saved_bytes = off;
 
   const size_t nstate = (size_t)dm.B * dm.Hkv * dm.nst * dm.D * dm.D;
@@ -117,7 +120,6 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
   L->gb_dgpart = off; off += align_up((size_t)2 * L->RB * dm.Hq * dm.D * 4);
   L->gen_bwd_bytes = off;
 
-  L->fast_fwd = rattn::fast_fwd_supported(dm, p->dtype);
   L->ff_u = L->ff_states = L->fast_fwd_bytes = 0;
   if (L->fast_fwd) {
     const rattn::FastFwdPlan pl = rattn::fast_fwd_plan(dm);
@@ -145,11 +147,12 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
 }
 
 rattn::SavedPtrs saved_views(const Layout& L, void* saved) {
-  rattn::SavedPtrs sv = {nullptr, nullptr, nullptr, nullptr, nullptr};
+  rattn::SavedPtrs sv = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   if (saved) {
     char* s = (char*)saved;
     sv.xs = s + L.sv_xs; sv.xr = s + L.sv_xr;
     sv.lse = (float*)(s + L.sv_lse); sv.rs = (float*)(s + L.sv_rs); sv.rr = (float*)(s + L.sv_rr);
+    if (L.fast_fwd) sv.states = s + L.sv_states;
   }
   return sv;
 }
@@ -224,7 +227,7 @@ rattn_status rattn_fwd(const rattn_params* p, const void* q, const void* k, cons
   rattn::SavedPtrs sv = saved_views(L, p->save_for_bwd ? saved : nullptr);
   if (L.fast_fwd && !force_generic())
     rattn::fast_fwd(L.dm, q, k, v, gamma_swa, gamma_rla, o, sv, (float*)((char*)workspace + L.ff_u),
-                    (char*)workspace + L.ff_states, st);
+                    sv.states ? sv.states : (void*)((char*)workspace + L.ff_states), st);
   else
     rattn::generic_fwd(L.dm, p->dtype, q, k, v, gamma_swa, gamma_rla, o, sv, (float*)((char*)workspace + L.gf_states), st);
   return check_launch("rattn_fwd");

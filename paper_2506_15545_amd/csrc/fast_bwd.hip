@@ -5,7 +5,7 @@
 //
 //   prep : through the two RMS norms (Sec. 3.2): dx_s, dx_r (bf16 MFMA operands), delta = <dx_s, x_s>,
 //          dgamma partials
-//   states: S_[j] (Eq. 2, recomputed) and the reverse-time states R_[j] = sum_{later chunks} phi(q)^T dx_r
+//   states: S_[j] (Eq. 2, kept by the forward pass) and the reverse-time states R_[j] = sum_{later chunks} phi(q)^T dx_r
 //   dq   : transposed, lane = query:  dQ^T = scale * K^T dS^T,  dS = P .* (dP - delta),  dP^T = V dXs^T
 //          linear branch: dphi(Q)^T = S dXr^T + Kf^T (M^T .* (V dXr^T)), then the softmax Jacobian of phi
 //   dkv  : transposed, lane = key:   dV^T = dXs^T P + dXr^T C + R^T Kf^T,
@@ -566,13 +566,12 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
     const int HD = dm.Hq * 128;
     dgamma_reduce_kernel<<<(HD + 255) / 256, 256, 0, st>>>(ws.dgpart, dgs, dgr, pl.RB, HD);
   }
-  rla_forward_states(dm, pl.fwd, k, v, ws.U, ws.states, st);
   rla_reverse_states(dm, pl.fwd.W, pl.nk, q, ws.dxr, ws.U, ws.rstates, st);
   FastBwdArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
   a.dxs = (const uint16_t*)ws.dxs; a.dxr = (const uint16_t*)ws.dxr;
   a.lse = sv.lse; a.delta = ws.delta;
-  a.states = (const uint16_t*)ws.states; a.rstates = (const uint16_t*)ws.rstates;
+  a.states = (const uint16_t*)sv.states; a.rstates = (const uint16_t*)ws.rstates;
   a.dq = (uint16_t*)dq; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv;
   a.B = dm.B; a.T = dm.T; a.Hq = dm.Hq; a.Hkv = dm.Hkv; a.G = dm.G; a.W = pl.fwd.W;
   a.nstf = pl.fwd.nstf; a.nk = pl.nk; a.ntile = dm.T / 128;

@@ -22,13 +22,15 @@ struct LayerDims {
 };
 
 // views into the opaque `saved` buffer: pre-norm branch outputs (I/O dtype, [B,T,Hq,D]) and the
-// row statistics (fp32, [B,Hq,T]): log-sum-exp of the softmax branch and the two RMS reciprocals
+// row statistics (fp32, [B,Hq,T]): log-sum-exp of the softmax branch and the two RMS reciprocals; on the MFMA
+// path also the linear-branch chunk states (bf16, transposed), so that backward does not rebuild them
 struct SavedPtrs {
   void* xs;
   void* xr;
   float* lse;
   float* rs;
   float* rr;
+  void* states;  // null on the general path
 };
 
 struct GenericBwdWs {
