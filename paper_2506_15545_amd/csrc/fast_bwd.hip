@@ -327,9 +327,15 @@ __device__ __forceinline__ void phi_tile_inplace_512(unsigned char* tile, int nr
   }
 }
 
-constexpr int DKV_TILE_BYTES = 65536;  // q / dx tiles (two buffers of 64 rows each, or one of 128 rows each)
-constexpr int DKV_PEX_BYTES = 32768;   // probabilities handed from the V-role to the K-role waves
-constexpr int DKV_LDS_BYTES = DKV_TILE_BYTES + DKV_PEX_BYTES;
+// LDS map of the dk/dv kernel: three 64-row q tiles, three 64-row dx tiles (the linear branch uses the first
+// 64 KB as one 128-row q tile and one 128-row dx tile), the probabilities handed from the V-role to the K-role
+// waves, and per tile the 64 log-sum-exp and 64 delta values of its rows.
+constexpr int DKV_Q_OFF = 0, DKV_DX_OFF = 49152, DKV_PEX_OFF = 98304, DKV_STAT_OFF = 131072;
+constexpr int DKV_LDS_BYTES = DKV_STAT_OFF + 3 * 2048;
+
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
 
 // grid (ntile * Hkv * B), 512 threads: 128 keys of one KV head.  Waves w and w+4 both work on key block w
 // (lane = key) and share a SIMD, with complementary roles, so each keeps only one 128 x 32 accumulator and one
@@ -339,11 +345,14 @@ constexpr int DKV_LDS_BYTES = DKV_TILE_BYTES + DKV_PEX_BYTES;
 //   K-role (waves 4-7): dP = dXs V^T, then dS = P .* (dP - delta) * scale with the P of its partner,
 //                       dK^T += Q^T dS;  linear branch: dC = dXr V^T (masked), dphi(K)^T += phi(Q)^T dC + R V^T,
 //                       softmax Jacobian of phi before the softmax-branch terms are added.
-// Per 32-query sub-tile: one work-group barrier hands P over (LDS buffer alternates with the sub-tile parity),
-// one more per 64-query tile publishes the next DMA'd tile.
+// Per 32-query sub-tile one work-group barrier hands P over (LDS buffer alternates with the sub-tile parity).
+// Query tiles run through three LDS buffers: tile s+2 is requested right after the first barrier of step s
+// (every wave has then left tile s-1, whose buffer it takes) and each wave waits for its share of tile s+1
+// before the second barrier of step s, so no further barrier is needed.  The loop has no other vector-memory
+// operation (row statistics arrive with the tiles), which is what makes the explicit counter waits exact.
 __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  unsigned char* pex = smem + DKV_TILE_BYTES;
+  unsigned char* pex = smem + DKV_PEX_OFF;
   const int lane = lane_id(), w8 = wave_id();
   const int w = w8 & 3;
   const bool krole = w8 >= 4;
@@ -438,23 +447,27 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
   const int n_qt = (min(s0 + 128 + W, T) - s0) / 64;
   const int nsteps = G * n_qt;
   const int ka = s0 + 32 * w;
-  auto issue = [&](int step, int buf) {
+  auto issue = [&](int step) {
+    const int buf = step % 3;
     const int hh = step / n_qt, n = step % n_qt;
     const size_t qoff = ((size_t)(b * T + s0 + 64 * n) * Hq + g * G + hh) * 128;
-    tile_load_async<2>(a.q + qoff, qstride, smem + buf * 16384, w8 * 2, lane);
-    tile_load_async<2>(a.dxs + qoff, qstride, smem + 32768 + buf * 16384, w8 * 2, lane);
+    tile_load_async<2>(a.q + qoff, qstride, smem + DKV_Q_OFF + buf * 16384, w8 * 2, lane);
+    tile_load_async<2>(a.dxs + qoff, qstride, smem + DKV_DX_OFF + buf * 16384, w8 * 2, lane);
+    if (w == 0) {  // waves 0 and 4: the row statistics their role consumes (lanes 16.. fetch duplicates)
+      const float* row = (krole ? a.delta : a.lse) + (size_t)(b * Hq + g * G + hh) * T + s0 + 64 * n;
+      dma16(row + 4 * (lane & 15), (unsigned)(size_t)RATTN_LDS(smem + DKV_STAT_OFF + buf * 2048 + (krole ? 1024 : 0)));
+    }
   };
-  issue(0, 0);
+  issue(0);
+  if (nsteps > 1) issue(1);
   wait_vmem();
   __syncthreads();
   for (int step = 0; step < nsteps; ++step) {
-    const int cur = step & 1;
-    if (step + 1 < nsteps) issue(step + 1, cur ^ 1);
-    const int hh = step / n_qt, n = step % n_qt;
-    const int hq = g * G + hh;
-    const float* stat_row = (krole ? a.delta : a.lse) + (size_t)(b * Hq + hq) * T;
-    const unsigned char* qtile = smem + cur * 16384;
-    const unsigned char* dxt = smem + 32768 + cur * 16384;
+    const int buf = step % 3;
+    const int n = step % n_qt;
+    const unsigned char* qtile = smem + DKV_Q_OFF + buf * 16384;
+    const unsigned char* dxt = smem + DKV_DX_OFF + buf * 16384;
+    const float* stat_lds = reinterpret_cast<const float*>(smem + DKV_STAT_OFF + buf * 2048 + (krole ? 1024 : 0));
 #pragma unroll
     for (int qs = 0; qs < 2; ++qs) {
       const int qa = s0 + 64 * n + 32 * qs;
@@ -469,8 +482,8 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
         for (int c = 0; c < 8; ++c) s = mfma32(lds_row(rows, lo, 32 * qs, c), xop[c], s);
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
-          const float4 f = *reinterpret_cast<const float4*>(stat_row + qa + 8 * i4 + 4 * h);
-          stat[4 * i4] = f.x; stat[4 * i4 + 1] = f.y; stat[4 * i4 + 2] = f.z; stat[4 * i4 + 3] = f.w;
+          const f32x4_t f = *reinterpret_cast<const f32x4_t*>(stat_lds + 32 * qs + 8 * i4 + 4 * h);
+          stat[4 * i4] = f[0]; stat[4 * i4 + 1] = f[1]; stat[4 * i4 + 2] = f[2]; stat[4 * i4 + 3] = f[3];
         }
         if (!krole) {
           if (!full) {
@@ -486,7 +499,16 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
           for (int i4 = 0; i4 < 4; ++i4) px[i4 * 64] = f32x4_t{s[4 * i4], s[4 * i4 + 1], s[4 * i4 + 2], s[4 * i4 + 3]};
         }
       }
+      if (qs == 1) {  // this wave's share of tile step+1 has landed (tile step+2 may still be in flight)
+        if (step + 2 < nsteps) {
+          if (w == 0) wait_vmcnt<5>();
+          else wait_vmcnt<4>();
+        } else {
+          wait_vmcnt<0>();
+        }
+      }
       __syncthreads();  // P of this sub-tile is in LDS
+      if (qs == 0 && step + 2 < nsteps) issue(step + 2);
       if (need) {
         float x[16];
         if (!krole) {
@@ -508,9 +530,8 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
           for (int dt = 0; dt < 4; ++dt) acc[dt] = mfma32(lds_trp(cols, lo, 32 * qs + 16 * mf, dt), xo[mf], acc[dt]);
       }
     }
-    wait_vmem();
-    __syncthreads();
   }
+  __syncthreads();
   // ---- dV^T (V-role) and dK^T (K-role) leave through LDS as two row-major tiles
   {
     unsigned char* tile = smem + (krole ? 32768 : 0);
