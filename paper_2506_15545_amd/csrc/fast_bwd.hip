@@ -447,24 +447,33 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
   const int n_qt = (min(s0 + 128 + W, T) - s0) / 64;
   const int nsteps = G * n_qt;
   const int ka = s0 + 32 * w;
-  auto issue = [&](int step) {
-    const int buf = step % 3;
-    const int hh = step / n_qt, n = step % n_qt;
-    const size_t qoff = ((size_t)(b * T + s0 + 64 * n) * Hq + g * G + hh) * 128;
-    tile_load_async<2>(a.q + qoff, qstride, smem + DKV_Q_OFF + buf * 16384, w8 * 2, lane);
-    tile_load_async<2>(a.dxs + qoff, qstride, smem + DKV_DX_OFF + buf * 16384, w8 * 2, lane);
-    if (w == 0) {  // waves 0 and 4: the row statistics their role consumes (lanes 16.. fetch duplicates)
-      const float* row = (krole ? a.delta : a.lse) + (size_t)(b * Hq + g * G + hh) * T + s0 + 64 * n;
-      dma16(row + 4 * (lane & 15), (unsigned)(size_t)RATTN_LDS(smem + DKV_STAT_OFF + buf * 2048 + (krole ? 1024 : 0)));
-    }
+  // per-lane part of the tile addresses (swizzled 16-byte chunk of rows 8*w8 + lane/16 and +4), computed once
+  const int ir0 = 8 * w8 + (lane >> 4), ir1 = ir0 + 4, ip = lane & 15;
+  const size_t lane_g0 = (size_t)ir0 * qstride + ((ip ^ swz(ir0)) << 3);
+  const size_t lane_g1 = (size_t)ir1 * qstride + ((ip ^ swz(ir1)) << 3);
+  const unsigned lds_q = (unsigned)(size_t)RATTN_LDS(smem + DKV_Q_OFF) + w8 * 2048;
+  const unsigned lds_dx = (unsigned)(size_t)RATTN_LDS(smem + DKV_DX_OFF) + w8 * 2048;
+  const unsigned lds_st = (unsigned)(size_t)RATTN_LDS(smem + DKV_STAT_OFF) + (krole ? 1024 : 0);
+  const float* stat_g = (krole ? a.delta : a.lse) + (size_t)(b * Hq + g * G) * T + s0 + 4 * ip;
+  const size_t tile_g = ((size_t)(b * T + s0) * Hq + g * G) * 128;
+  int is_h = 0, is_n = 0, is_buf = 0;  // head, tile and buffer of the next tile to request
+  auto issue = [&]() {
+    const size_t qoff = tile_g + (size_t)is_n * 64 * qstride + (size_t)is_h * 128;
+    dma16(a.q + qoff + lane_g0, lds_q + is_buf * 16384);
+    dma16(a.q + qoff + lane_g1, lds_q + is_buf * 16384 + 1024);
+    dma16(a.dxs + qoff + lane_g0, lds_dx + is_buf * 16384);
+    dma16(a.dxs + qoff + lane_g1, lds_dx + is_buf * 16384 + 1024);
+    if (w == 0)  // waves 0 and 4: the row statistics their role consumes (lanes 16.. fetch duplicates)
+      dma16(stat_g + (size_t)is_h * T + 64 * is_n, lds_st + is_buf * 2048);
+    if (++is_n == n_qt) { is_n = 0; ++is_h; }
+    if (++is_buf == 3) is_buf = 0;
   };
-  issue(0);
-  if (nsteps > 1) issue(1);
+  issue();
+  if (nsteps > 1) issue();
   wait_vmem();
   __syncthreads();
-  for (int step = 0; step < nsteps; ++step) {
-    const int buf = step % 3;
-    const int n = step % n_qt;
+  int buf = 0, n = 0;
+  for (int step = 0; step < nsteps; ++step, buf = buf == 2 ? 0 : buf + 1, n = n + 1 == n_qt ? 0 : n + 1) {
     const unsigned char* qtile = smem + DKV_Q_OFF + buf * 16384;
     const unsigned char* dxt = smem + DKV_DX_OFF + buf * 16384;
     const float* stat_lds = reinterpret_cast<const float*>(smem + DKV_STAT_OFF + buf * 2048 + (krole ? 1024 : 0));
@@ -508,7 +517,7 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
         }
       }
       __syncthreads();  // P of this sub-tile is in LDS
-      if (qs == 0 && step + 2 < nsteps) issue(step + 2);
+      if (qs == 0 && step + 2 < nsteps) issue();
       if (need) {
         float x[16];
         if (!krole) {
