@@ -147,6 +147,15 @@ __device__ __forceinline__ void dq_subtile(const unsigned char* kt, const unsign
   for (int c = 0; c < 8; ++c) s = mfma32(lds_row(kt, lo, 32 * ks, c), qop[c], s);
 #pragma unroll
   for (int c = 0; c < 8; ++c) dp = mfma32(lds_row(vt, lo, 32 * ks, c), dxsop[c], dp);
+  // keep four operand reads in flight ahead of the matrix chain (the default schedule issues them one ahead,
+  // which exposes the LDS latency once per MFMA)
+  __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+  for (int i = 0; i < 12; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+  }
+  __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
   if (masked) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -489,6 +498,13 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
         const unsigned char* rows = krole ? dxt : qtile;
 #pragma unroll
         for (int c = 0; c < 8; ++c) s = mfma32(lds_row(rows, lo, 32 * qs, c), xop[c], s);
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);  // operand reads run four ahead of the chain
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
           const f32x4_t f = *reinterpret_cast<const f32x4_t*>(stat_lds + 32 * qs + 8 * i4 + 4 * h);
