@@ -336,10 +336,11 @@ __device__ __forceinline__ void phi_tile_inplace_512(unsigned char* tile, int nr
   }
 }
 
-// LDS map of the dk/dv kernel: three 64-row q tiles, three 64-row dx tiles (the linear branch uses the first
-// 64 KB as one 128-row q tile and one 128-row dx tile), the probabilities handed from the V-role to the K-role
-// waves, and per tile the 64 log-sum-exp and 64 delta values of its rows.
-constexpr int DKV_Q_OFF = 0, DKV_DX_OFF = 49152, DKV_PEX_OFF = 98304, DKV_STAT_OFF = 131072;
+// LDS map of the dk/dv kernel: three 32 KB slots, each a 64-row q tile followed by a 64-row dx tile; 32 KB for the
+// probabilities handed from the V-role to the K-role waves; per slot the 64 log-sum-exp and 64 delta values of
+// its rows.  The linear branch uses the same space as two buffers of one 128-row q tile and one 128-row dx tile
+// each: A = slots 0-1, B = slot 2 + the hand-over area (which first receives the reverse-state tile).
+constexpr int DKV_SLOT = 32768, DKV_PEX_OFF = 98304, DKV_STAT_OFF = 131072;
 constexpr int DKV_LDS_BYTES = DKV_STAT_OFF + 3 * 2048;
 
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
@@ -384,6 +385,33 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
   load_bop((krole ? a.v : a.k) + myrow_off, h, xop);
   f32x16_t acc[4] = {{0}, {0}, {0}, {0}};  // V-role: dV^T; K-role: dK^T
 
+  // ---- request machinery of the softmax branch (query tiles of 64 rows from s0 up to the last row that still
+  // sees these keys); defined first because the linear branch already requests the first tiles
+  const int n_qt = (min(s0 + 128 + W, T) - s0) / 64;
+  const int nsteps = G * n_qt;
+  const int ka = s0 + 32 * w;
+  // per-lane part of the tile addresses (swizzled 16-byte chunk of rows 8*w8 + lane/16 and +4), computed once
+  const int ir0 = 8 * w8 + (lane >> 4), ir1 = ir0 + 4, ip = lane & 15;
+  const size_t lane_g0 = (size_t)ir0 * qstride + ((ip ^ swz(ir0)) << 3);
+  const size_t lane_g1 = (size_t)ir1 * qstride + ((ip ^ swz(ir1)) << 3);
+  const unsigned lds_q = (unsigned)(size_t)RATTN_LDS(smem) + w8 * 2048;
+  const unsigned lds_st = (unsigned)(size_t)RATTN_LDS(smem + DKV_STAT_OFF) + (krole ? 1024 : 0);
+  const float* stat_g = (krole ? a.delta : a.lse) + (size_t)(b * Hq + g * G) * T + s0 + 4 * ip;
+  const size_t tile_g = ((size_t)(b * T + s0) * Hq + g * G) * 128;
+  int is_h = 0, is_n = 0, is_buf = 0;  // head, tile and slot of the next tile to request
+  auto issue = [&]() {
+    const size_t qoff = tile_g + (size_t)is_n * 64 * qstride + (size_t)is_h * 128;
+    dma16(a.q + qoff + lane_g0, lds_q + is_buf * DKV_SLOT);
+    dma16(a.q + qoff + lane_g1, lds_q + is_buf * DKV_SLOT + 1024);
+    dma16(a.dxs + qoff + lane_g0, lds_q + is_buf * DKV_SLOT + 16384);
+    dma16(a.dxs + qoff + lane_g1, lds_q + is_buf * DKV_SLOT + 16384 + 1024);
+    if (w == 0)  // waves 0 and 4: the row statistics their role consumes (lanes 16.. fetch duplicates)
+      dma16(stat_g + (size_t)is_h * T + 64 * is_n, lds_st + is_buf * 2048);
+    if (++is_n == n_qt) { is_n = 0; ++is_h; }
+    if (++is_buf == 3) is_buf = 0;
+  };
+  int buf = 0, issued = 0;  // slot of the first softmax-branch tile, tiles requested so far
+
   // ---- linear branch
   if (s0 < Tp) {
     const int nq = min(128, Tp - s0);  // query rows t = s0 + W + [0, nq) pair with this key tile
@@ -393,37 +421,58 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
       for (int c = 0; c < 8; ++c) unpack_bf16x8(xop[c], &x[8 * c]);
       phi_rows(x, xop);
     }
+    unsigned char* const qA = smem;
+    unsigned char* const dA = smem + 32768;
+    unsigned char* const qB = smem + 65536;
+    unsigned char* const dB = smem + DKV_PEX_OFF;
+    auto issue_head = [&](int hh, unsigned char* qb, unsigned char* db) {
+      const size_t qoff = ((size_t)(b * T + s0 + W) * Hq + g * G + hh) * 128;
+      tile_load_async<2>(a.q + qoff, qstride, qb, w8 * 2, lane);
+      tile_load_async<2>(a.dxr + qoff, qstride, db, w8 * 2, lane);
+      if (nq == 128) {
+        tile_load_async<2>(a.q + qoff, qstride, qb, 16 + w8 * 2, lane);
+        tile_load_async<2>(a.dxr + qoff, qstride, db, 16 + w8 * 2, lane);
+      }
+    };
     const uint16_t* rbase = a.rstates + ((size_t)(b * Hkv + g) * a.nk + kti) * 16384;
-    tile_load_async<4>(rbase, 128, smem, w8 * 4, lane);
+    tile_load_async<4>(rbase, 128, dB, w8 * 4, lane);
+    issue_head(0, qA, dA);
     wait_vmem();
     __syncthreads();
     if (!krole) {
 #pragma unroll
       for (int c = 0; c < 8; ++c)
 #pragma unroll
-        for (int t = 0; t < 4; ++t) acc[t] = mfma32(lds_row(smem, lo, 32 * t, c), xop[c], acc[t]);
+        for (int t = 0; t < 4; ++t) acc[t] = mfma32(lds_row(dB, lo, 32 * t, c), xop[c], acc[t]);
     } else {
       const LaneOffN lon = make_lane_off_n(lane);
 #pragma unroll
       for (int c = 0; c < 8; ++c)
 #pragma unroll
-        for (int t = 0; t < 4; ++t) acc[t] = mfma32(lds_trn(smem, lon, 16 * c, t), xop[c], acc[t]);
+        for (int t = 0; t < 4; ++t) acc[t] = mfma32(lds_trn(dB, lon, 16 * c, t), xop[c], acc[t]);
     }
+    __syncthreads();  // buffer B is free again
     for (int hh = 0; hh < G; ++hh) {
-      const size_t qoff = ((size_t)(b * T + s0 + W) * Hq + g * G + hh) * 128;
-      __syncthreads();
-      tile_load_async<2>(a.q + qoff, qstride, smem, w8 * 2, lane);
-      tile_load_async<2>(a.dxr + qoff, qstride, smem + 32768, w8 * 2, lane);
-      if (nq == 128) {
-        tile_load_async<2>(a.q + qoff, qstride, smem, 16 + w8 * 2, lane);
-        tile_load_async<2>(a.dxr + qoff, qstride, smem + 32768, 16 + w8 * 2, lane);
+      const bool in_a = !(hh & 1);
+      unsigned char* const qb = in_a ? qA : qB;
+      unsigned char* const db = in_a ? dA : dB;
+      // while this head is worked on, the other buffer receives the next head, or after the last head the
+      // first query tiles of the softmax branch (slot 2 if buffer B is the free one, else slots 0 and 1)
+      if (hh + 1 < G) {
+        issue_head(hh + 1, in_a ? qB : qA, in_a ? dB : dA);
+      } else if (in_a) {
+        is_buf = buf = 2;
+        issue();
+        issued = 1;
+      } else {
+        issue();
+        issued = 1;
+        if (nsteps > 1) { issue(); issued = 2; }
       }
-      wait_vmem();
+      phi_tile_inplace_512(qb, nq);
       __syncthreads();
-      phi_tile_inplace_512(smem, nq);
-      __syncthreads();
-      const unsigned char* mine = krole ? smem + 32768 : smem;    // rows contracted with xop
-      const unsigned char* other = krole ? smem : smem + 32768;   // rows accumulated into acc
+      const unsigned char* mine = krole ? db : qb;    // rows contracted with xop
+      const unsigned char* other = krole ? qb : db;   // rows accumulated into acc
       for (int u = w; u < nq / 32; ++u) {
         f32x16_t c = {0};
 #pragma unroll
@@ -441,8 +490,9 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
 #pragma unroll
           for (int t = 0; t < 4; ++t) acc[t] = mfma32(lds_trp(other, lo, 32 * u + 16 * mf, t), cop[mf], acc[t]);
       }
+      wait_vmem();
+      __syncthreads();  // what was requested above has landed, and everyone is done with this buffer
     }
-    __syncthreads();
     if (krole) {
       float kf[64];
       phi_row_clayout(a.k + myrow_off, h, kf);
@@ -452,39 +502,19 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
     }
   }
 
-  // ---- softmax branch: query tiles of 64 rows from s0 up to the last row that still sees these keys
-  const int n_qt = (min(s0 + 128 + W, T) - s0) / 64;
-  const int nsteps = G * n_qt;
-  const int ka = s0 + 32 * w;
-  // per-lane part of the tile addresses (swizzled 16-byte chunk of rows 8*w8 + lane/16 and +4), computed once
-  const int ir0 = 8 * w8 + (lane >> 4), ir1 = ir0 + 4, ip = lane & 15;
-  const size_t lane_g0 = (size_t)ir0 * qstride + ((ip ^ swz(ir0)) << 3);
-  const size_t lane_g1 = (size_t)ir1 * qstride + ((ip ^ swz(ir1)) << 3);
-  const unsigned lds_q = (unsigned)(size_t)RATTN_LDS(smem + DKV_Q_OFF) + w8 * 2048;
-  const unsigned lds_dx = (unsigned)(size_t)RATTN_LDS(smem + DKV_DX_OFF) + w8 * 2048;
-  const unsigned lds_st = (unsigned)(size_t)RATTN_LDS(smem + DKV_STAT_OFF) + (krole ? 1024 : 0);
-  const float* stat_g = (krole ? a.delta : a.lse) + (size_t)(b * Hq + g * G) * T + s0 + 4 * ip;
-  const size_t tile_g = ((size_t)(b * T + s0) * Hq + g * G) * 128;
-  int is_h = 0, is_n = 0, is_buf = 0;  // head, tile and buffer of the next tile to request
-  auto issue = [&]() {
-    const size_t qoff = tile_g + (size_t)is_n * 64 * qstride + (size_t)is_h * 128;
-    dma16(a.q + qoff + lane_g0, lds_q + is_buf * 16384);
-    dma16(a.q + qoff + lane_g1, lds_q + is_buf * 16384 + 1024);
-    dma16(a.dxs + qoff + lane_g0, lds_dx + is_buf * 16384);
-    dma16(a.dxs + qoff + lane_g1, lds_dx + is_buf * 16384 + 1024);
-    if (w == 0)  // waves 0 and 4: the row statistics their role consumes (lanes 16.. fetch duplicates)
-      dma16(stat_g + (size_t)is_h * T + 64 * is_n, lds_st + is_buf * 2048);
-    if (++is_n == n_qt) { is_n = 0; ++is_h; }
-    if (++is_buf == 3) is_buf = 0;
-  };
-  issue();
-  if (nsteps > 1) issue();
-  wait_vmem();
-  __syncthreads();
-  int buf = 0, n = 0;
+  // ---- softmax branch
+  if (issued == 0) {
+    issue();
+    if (nsteps > 1) issue();
+    wait_vmem();
+    __syncthreads();
+  } else if (issued == 1 && nsteps > 1) {
+    issue();  // tile 0 is already visible; tile 1 has all of step 0 to arrive
+  }
+  int n = 0;
   for (int step = 0; step < nsteps; ++step, buf = buf == 2 ? 0 : buf + 1, n = n + 1 == n_qt ? 0 : n + 1) {
-    const unsigned char* qtile = smem + DKV_Q_OFF + buf * 16384;
-    const unsigned char* dxt = smem + DKV_DX_OFF + buf * 16384;
+    const unsigned char* qtile = smem + buf * DKV_SLOT;
+    const unsigned char* dxt = qtile + 16384;
     const float* stat_lds = reinterpret_cast<const float*>(smem + DKV_STAT_OFF + buf * 2048 + (krole ? 1024 : 0));
 #pragma unroll
     for (int qs = 0; qs < 2; ++qs) {
