@@ -147,28 +147,40 @@ __device__ __forceinline__ void dq_subtile(const unsigned char* kt, const unsign
   for (int c = 0; c < 8; ++c) s = mfma32(lds_row(kt, lo, 32 * ks, c), qop[c], s);
 #pragma unroll
   for (int c = 0; c < 8; ++c) dp = mfma32(lds_row(vt, lo, 32 * ks, c), dxsop[c], dp);
-  // keep four operand reads in flight ahead of the matrix chain (the default schedule issues them one ahead,
-  // which exposes the LDS latency once per MFMA)
+  // probabilities of the unmasked case; they depend on the first chain only, so they are scheduled into the
+  // second chain (masked entries are zeroed afterwards, which equals masking the logits)
+  float p[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) p[i] = fast_exp2(__builtin_fmaf(s[i], scale_log2, -lse2));
+  // operand reads run four ahead of the matrix chains (the default schedule issues them one ahead, which
+  // exposes the LDS latency once per MFMA); the exponentials go between the MFMAs of the dP chain
   __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
-  for (int i = 0; i < 12; ++i) {
+  for (int i = 0; i < 8; ++i) {
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
   }
-  __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+  }
   if (masked) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int key = ka + 8 * (i >> 2) + 4 * h + (i & 3);
-      s[i] = (key <= myq && key > myq - W) ? s[i] : -INFINITY;
+      p[i] = (key <= myq && key > myq - W) ? p[i] : 0.f;
     }
   }
   float ds[16];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const float p = fast_exp2(__builtin_fmaf(s[i], scale_log2, -lse2));
-    ds[i] = p * (dp[i] - dl) * scale;
-  }
+  for (int i = 0; i < 16; ++i) ds[i] = p[i] * (dp[i] - dl) * scale;
   bf16x8_t dsop[2] = {pack_bf16x8(&ds[0]), pack_bf16x8(&ds[8])};
 #pragma unroll
   for (int mf = 0; mf < 2; ++mf) {
