@@ -360,21 +360,28 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
   // ------------------------------------------------------------------ combination
   {
     float vals[4][16];
+    if (!a.gs && !a.gr) {  // no gains: one multiply-add per element, no loads
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+      for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        const int d0 = 32 * dt + 8 * i4 + 4 * h;
-        float4 g1 = make_float4(1.f, 1.f, 1.f, 1.f), g2 = g1;
-        if (a.gs) g1 = *reinterpret_cast<const float4*>(a.gs + hq * 128 + d0);
-        if (a.gr) g2 = *reinterpret_cast<const float4*>(a.gr + hq * 128 + d0);
-        const float ga[4] = {g1.x, g1.y, g1.z, g1.w}, gb[4] = {g2.x * rr_val, g2.y * rr_val, g2.z * rr_val, g2.w * rr_val};
+        for (int i = 0; i < 16; ++i) vals[dt][i] = __builtin_fmaf(rr_val, xr[dt][i], (float)ys[dt][i >> 1][i & 1]);
+    } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int i = 4 * i4 + e;
-          vals[dt][i] = ga[e] * (float)ys[dt][i >> 1][i & 1] + gb[e] * xr[dt][i];
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const int d0 = 32 * dt + 8 * i4 + 4 * h;
+          float4 g1 = make_float4(1.f, 1.f, 1.f, 1.f), g2 = g1;
+          if (a.gs) g1 = *reinterpret_cast<const float4*>(a.gs + hq * 128 + d0);
+          if (a.gr) g2 = *reinterpret_cast<const float4*>(a.gr + hq * 128 + d0);
+          const float ga[4] = {g1.x, g1.y, g1.z, g1.w}, gb[4] = {g2.x * rr_val, g2.y * rr_val, g2.z * rr_val, g2.w * rr_val};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int i = 4 * i4 + e;
+            vals[dt][i] = ga[e] * (float)ys[dt][i >> 1][i & 1] + gb[e] * xr[dt][i];
+          }
         }
-      }
+    }
     store_tile_transposed(smem, vals, a.o + qtile_off, qstride, w, lane);
   }
 }
