@@ -317,6 +317,25 @@ def decode_step(q, k_new, v_new, pos, k_ring, v_ring, state, W, scale=1.0, eps=1
     return o, k_ring, v_ring, state
 
 
+def prefill_export(k, v, W):
+    """What a decode step at pos = T expects after a prompt of T tokens (the hand-over the paper's
+    inference discussion implies, Sec. 2.1 / 2.2 / 4.4): rings with key/value s in slot s % W for the last
+    min(T, W) tokens (other slots zero), and the state sum_{s < T-W} phi(k_s)^T v_s (rows = feature,
+    columns = value), i.e. the S_{t-W} that Eq. 4 lets query t = T read.
+    k, v [B,T,Hkv,D]; returns (k_ring [B,Hkv,W,D], v_ring, state [B,Hkv,D,D])."""
+    k = np.asarray(k, np.float64); v = np.asarray(v, np.float64)
+    B, T, Hkv, D = k.shape
+    k_ring = np.zeros((B, Hkv, W, D)); v_ring = np.zeros((B, Hkv, W, D))
+    state = np.zeros((B, Hkv, D, D))
+    for b in range(B):
+        for g in range(Hkv):
+            for s in range(max(0, T - W), T):
+                k_ring[b, g, s % W] = k[b, s, g]; v_ring[b, g, s % W] = v[b, s, g]
+            for s in range(0, T - W):
+                state[b, g] += np.outer(phi(k[b, s, g]), v[b, s, g])
+    return k_ring, v_ring, state
+
+
 # ----------------------------------------------------------------------------- closed forms in the text
 def kv_cache_saving(layers, global_every, ctx, w_from, w_to):
     """Fraction of KV cache saved when local layers shrink their window (Sec. 1 example):

@@ -319,3 +319,31 @@ def test_text_closed_forms():
     assert abs(orc.kv_cache_saving(40, 4, 4096, 4096, 1024) - 0.5625) < 1e-12
     # Sec. 2.2 footnote: a 128 x 128 state costs as much as a 64-token window
     assert orc.state_equivalent_window(128, 128) == 64
+
+
+# ------------------------------------------------------------------------------ prefill -> decode hand-over
+@pytest.mark.parametrize("T,W", [(3, 8), (8, 8), (9, 8), (21, 4), (16, 1)])
+def test_prefill_export_equals_decode_chain(T, W):
+    """The exported rings/state are what T decode steps from empty rings and a zero state leave behind, and a
+    decode step on top of them reproduces row T of the full forward pass over T+1 tokens."""
+    rng = np.random.default_rng(70 + T + W)
+    B, Hq, Hkv, D = 2, 4, 2, 4
+    q = rng.standard_normal((B, T + 1, Hq, D)); k = rng.standard_normal((B, T + 1, Hkv, D))
+    v = rng.standard_normal((B, T + 1, Hkv, D))
+    kr = np.zeros((B, Hkv, W, D)); vr = np.zeros((B, Hkv, W, D)); S = np.zeros((B, Hkv, D, D))
+    for t in range(T):
+        _, kr, vr, S = orc.decode_step(q[:, t], k[:, t], v[:, t], [t] * B, kr, vr, S, W, scale=0.5)
+    kr2, vr2, S2 = orc.prefill_export(k[:, :T], v[:, :T], W)
+    assert np.array_equal(kr, kr2) and np.array_equal(vr, vr2)
+    assert np.allclose(S, S2, rtol=1e-12, atol=1e-12)
+    o, _, _, _ = orc.decode_step(q[:, T], k[:, T], v[:, T], [T] * B, kr2, vr2, S2, W, scale=0.5)
+    ref = orc.fwd_dense(q, k, v, W, scale=0.5)["o"][:, T]
+    assert np.allclose(o, ref, rtol=1e-9, atol=1e-9)
+
+
+def test_prefill_export_state_is_cumulative_outer_products():
+    rng = np.random.default_rng(5)
+    k = rng.standard_normal((1, 12, 1, 3)); v = rng.standard_normal((1, 12, 1, 3))
+    _, _, S = orc.prefill_export(k, v, 5)
+    f = np.exp(k[0, :7, 0]); f /= f.sum(axis=1, keepdims=True)      # softmax rows of the 7 out-of-window keys
+    assert np.allclose(S[0, 0], f.T @ v[0, :7, 0], rtol=1e-12, atol=1e-12)
