@@ -231,6 +231,23 @@ def main():
                                       "traffic": measured_traffic("decode_kernel", dcfg.name),
                                       "algorithmic_bytes": nbytes}}
 
+    if not args.no_decode:
+        # prefill -> decode hand-over on the layer's K/V (one-off per prompt; reported, not part of `value`)
+        for _ in range(3):
+            rb.rattn_prefill_export(k, v, cfg.W)
+        torch.cuda.synchronize()
+        rb.rattn_profile_enable(True)
+        for _ in range(10):
+            rb.rattn_prefill_export(k, v, cfg.W)
+        torch.cuda.synchronize()
+        per = {}
+        for name, ms in rb.rattn_profile_records():
+            if name.startswith("export_"):
+                per.setdefault(name, []).append(ms)
+        rb.rattn_profile_enable(False)
+        out["prefill_export"] = {"workload": cfg.name, "us": {n_: sum(v_) / len(v_) * 1e3 for n_, v_ in per.items()},
+                                 "us_total": sum(sum(v_) / len(v_) for v_ in per.values()) * 1e3}
+
     if args.calibrate_copy:
         src = torch.zeros(256 * 2 ** 20 // 4, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)

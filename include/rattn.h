@@ -112,6 +112,19 @@ rattn_status rattn_decode_step(const rattn_decode_params* p, const void* q, cons
                                float* state, const float* gamma_swa, const float* gamma_rla,
                                void* o, void* stream);
 
+/* Prefill -> decode hand-over (Sec. 2.1: the window cache; Sec. 2.2 and Eq. 4: the lagged state).  From the keys
+ * and values of a prompt of T tokens (k, v [B,T,Hkv,D] as in rattn_fwd; Hq, chunk, softmax_scale, rms_eps,
+ * save_for_bwd of *p are not used but must be valid) it fills what rattn_decode_step with pos = T expects for
+ * the N = B sequences:
+ *   k_ring, v_ring [B,Hkv,W,D]: token s in slot s % W for s in [max(0, T-W), T); other slots are left untouched;
+ *   state fp32 [B,Hkv,D,D] = sum over s < T-W of phi(k_s)^T v_s (row = feature, column = value), zero if T <= W,
+ *   summed in a fixed order (deterministic).
+ * workspace: rattn_prefill_export_workspace_bytes() bytes of scratch (may be 0 => NULL allowed). */
+rattn_status rattn_prefill_export_workspace_bytes(const rattn_params* p, size_t* bytes);
+rattn_status rattn_prefill_export(const rattn_params* p, const void* k, const void* v, void* k_ring,
+                                  void* v_ring, float* state, void* workspace, size_t workspace_bytes,
+                                  void* stream);
+
 /* Per-kernel timing (tracing aid; off by default).  While enabled, every kernel the library
  * launches is bracketed by a pair of HIP events recorded on the launch stream.  Records pile up
  * until rattn_profile_reset().  rattn_profile_get waits for record `idx` to finish and returns

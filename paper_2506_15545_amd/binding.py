@@ -15,6 +15,7 @@ RATTN_F32, RATTN_BF16 = 0, 1
 _DTYPES = {torch.float32: RATTN_F32, torch.bfloat16: RATTN_BF16}
 
 EXPORTS = ["rattn_workspace_bytes", "rattn_fwd", "rattn_bwd", "rattn_decode_step",
+           "rattn_prefill_export_workspace_bytes", "rattn_prefill_export",
            "rattn_status_string", "rattn_last_error", "rattn_version",
            "rattn_profile_enable", "rattn_profile_reset", "rattn_profile_count", "rattn_profile_get"]
 
@@ -59,6 +60,10 @@ def lib():
     L.rattn_bwd.argtypes = [ctypes.POINTER(RattnParams)] + [vp] * 13 + [sz, vp]
     L.rattn_decode_step.restype = ctypes.c_int
     L.rattn_decode_step.argtypes = [ctypes.POINTER(RattnDecodeParams)] + [vp] * 11
+    L.rattn_prefill_export_workspace_bytes.restype = ctypes.c_int
+    L.rattn_prefill_export_workspace_bytes.argtypes = [ctypes.POINTER(RattnParams), ctypes.POINTER(sz)]
+    L.rattn_prefill_export.restype = ctypes.c_int
+    L.rattn_prefill_export.argtypes = [ctypes.POINTER(RattnParams)] + [vp] * 6 + [sz, vp]
     L.rattn_status_string.restype = ctypes.c_char_p
     L.rattn_status_string.argtypes = [ctypes.c_int]
     L.rattn_last_error.restype = ctypes.c_char_p
@@ -193,6 +198,31 @@ def rattn_decode_step(q, k_new, v_new, pos, k_ring, v_ring, state, gamma_swa=Non
     _check(lib().rattn_decode_step(ctypes.byref(p), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(pos), _ptr(k_ring),
                                    _ptr(v_ring), _ptr(state), _ptr(gs), _ptr(gr), _ptr(o), _stream()))
     return o
+
+
+def rattn_prefill_export(k, v, window, k_ring=None, v_ring=None, state=None):
+    """Rings and lagged state a decode step at pos = T expects after the prompt k, v [B,T,Hkv,D].
+    Returns (k_ring [B,Hkv,W,D], v_ring, state [B,Hkv,D,D] fp32); ring slots the prompt does not reach are zero
+    when the rings are allocated here."""
+    B, T, Hkv, D = k.shape
+    for name, t in (("k", k), ("v", v)):
+        if not (t.is_cuda and t.is_contiguous()):
+            raise ValueError(f"{name} must be a contiguous device tensor")
+    if v.shape != k.shape or v.dtype != k.dtype or k.dtype not in _DTYPES:
+        raise ValueError("k and v must share shape and dtype float32 or bfloat16")
+    p = RattnParams(B, T, Hkv, Hkv, D, window, 0, _DTYPES[k.dtype], 1.0, 1e-6, 0)
+    if k_ring is None:
+        k_ring = torch.zeros(B, Hkv, window, D, dtype=k.dtype, device=k.device)
+    if v_ring is None:
+        v_ring = torch.zeros(B, Hkv, window, D, dtype=k.dtype, device=k.device)
+    if state is None:
+        state = torch.empty(B, Hkv, D, D, dtype=torch.float32, device=k.device)
+    nbytes = ctypes.c_size_t()
+    _check(lib().rattn_prefill_export_workspace_bytes(ctypes.byref(p), ctypes.byref(nbytes)))
+    ws = torch.empty(max(nbytes.value, 16), dtype=torch.uint8, device=k.device)
+    _check(lib().rattn_prefill_export(ctypes.byref(p), _ptr(k), _ptr(v), _ptr(k_ring), _ptr(v_ring), _ptr(state),
+                                      _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()))
+    return k_ring, v_ring, state
 
 
 def rattn_profile_enable(on):

@@ -295,4 +295,28 @@ rattn_status rattn_decode_step(const rattn_decode_params* p, const void* q, cons
   return check_launch("rattn_decode_step");
 }
 
+rattn_status rattn_prefill_export_workspace_bytes(const rattn_params* p, size_t* bytes) {
+  Layout L;
+  rattn_status s = make_layout(p, &L);
+  if (s != RATTN_OK) return s;
+  if (bytes) *bytes = align_up(rattn::export_plan(L.dm).partial_bytes);
+  return RATTN_OK;
+}
+
+rattn_status rattn_prefill_export(const rattn_params* p, const void* k, const void* v, void* k_ring, void* v_ring,
+                                  float* state, void* workspace, size_t workspace_bytes, void* stream) {
+  Layout L;
+  rattn_status s = make_layout(p, &L);
+  if (s != RATTN_OK) return s;
+  if (!k || !v || !k_ring || !v_ring || !state) return fail(RATTN_ERR_INVALID_ARG, "k, v, k_ring, v_ring, state must be non-NULL");
+  if (!aligned16(k) || !aligned16(v) || !aligned16(k_ring) || !aligned16(v_ring) || !aligned16(state) ||
+      !aligned16(workspace))
+    return fail(RATTN_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+  const size_t need = align_up(rattn::export_plan(L.dm).partial_bytes);
+  if (need > 0 && (!workspace || workspace_bytes < need))
+    return fail(RATTN_ERR_WORKSPACE, "prefill export needs %zu workspace bytes, got %zu", need, workspace_bytes);
+  rattn::prefill_export(L.dm, p->dtype, k, v, k_ring, v_ring, state, (float*)workspace, (hipStream_t)stream);
+  return check_launch("rattn_prefill_export");
+}
+
 }  // extern "C"

@@ -89,6 +89,17 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
               const SavedPtrs& sv, const void* dO, void* dq, void* dk, void* dv, float* dgs, float* dgr,
               const FastBwdWs& ws, hipStream_t st);
 
+// prefill -> decode hand-over: rings of the last min(T, W) tokens and the state of all keys before them
+struct ExportPlan {
+  int Tp;        // keys folded into the state (T - W, or 0)
+  int nseg;      // key segments with their own partial state
+  int seg_len;   // keys per segment (multiple of the staging batch)
+  size_t partial_bytes;
+};
+ExportPlan export_plan(const LayerDims& dm);
+void prefill_export(const LayerDims& dm, int dtype, const void* k, const void* v, void* k_ring, void* v_ring,
+                    float* state, float* partial, hipStream_t st);
+
 struct DecodeDims {
   int N, Hq, Hkv, D, W, G;
   float scale, eps;

@@ -78,3 +78,21 @@ def test_small_workspace_rejected():
     assert st == -3 and b"workspace" in L.rattn_last_error()
     st = L.rattn_fwd(ctypes.byref(p), ctypes.c_void_p(4097), fake, fake, None, None, fake, None, fake, 1 << 40, None)
     assert st == -1 and b"aligned" in L.rattn_last_error()
+
+
+def test_prefill_export_host_checks():
+    L = rb.lib()
+    p = params()
+    n = ctypes.c_size_t()
+    assert L.rattn_prefill_export_workspace_bytes(ctypes.byref(p), ctypes.byref(n)) == 0
+    # one fp32 D x D partial state per (batch row, kv head, key segment)
+    assert n.value > 0 and n.value % (p.B * p.Hkv * p.D * p.D * 4) == 0
+    fake = ctypes.c_void_p(4096)  # never dereferenced: the checks below fail first
+    assert L.rattn_prefill_export(ctypes.byref(p), None, None, None, None, None, None, 0, None) == -1
+    st = L.rattn_prefill_export(ctypes.byref(p), fake, fake, fake, fake, fake, fake, 16, None)
+    assert st == -3 and b"workspace" in L.rattn_last_error()
+    st = L.rattn_prefill_export(ctypes.byref(p), ctypes.c_void_p(4100), fake, fake, fake, fake, fake, 1 << 40, None)
+    assert st == -1 and b"aligned" in L.rattn_last_error()
+    # a prompt shorter than the window has no state to build: no scratch needed
+    q = params(window=1000)
+    assert L.rattn_prefill_export_workspace_bytes(ctypes.byref(q), ctypes.byref(n)) == 0 and n.value == 0

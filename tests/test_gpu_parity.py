@@ -215,3 +215,36 @@ def test_decode_full_config_all_sequences():
     """The decode workload the benchmark times (128 sequences, 32 query / 8 kv heads, W = 512), every output."""
     cfg = synth.DECODE_CONFIGS["decode_b128_w512"]
     _decode_vs_oracle(cfg, None, TOL["bf16"])
+
+
+# ------------------------------------------------------------------------------ prefill -> decode hand-over
+@pytest.mark.parametrize("dtype,B,T,Hkv,D,W", [("f32", 2, 5, 2, 64, 8), ("f32", 1, 8, 1, 64, 8), ("f32", 2, 77, 2, 128, 10),
+                                                 ("bf16", 2, 384, 2, 128, 128), ("bf16", 1, 1000, 3, 64, 200),
+                                                 ("bf16", 2, 2048, 2, 128, 512)])
+def test_prefill_export_matches_oracle(dtype, B, T, Hkv, D, W):
+    x = synth.make_random_layer(B, T, Hkv, Hkv, D, dtype, 800 + T)
+    kr_ref, vr_ref, S_ref = orc.prefill_export(np64(x["k"]), np64(x["v"]), W)
+    kr, vr, S = rb.rattn_prefill_export(dev(x["k"]), dev(x["v"]), W)
+    assert np.array_equal(np64(kr), kr_ref) and np.array_equal(np64(vr), vr_ref)
+    # fp32 sums of up to T-W exact products of a softmax row (fp32 exp) with a value
+    assert float(np.max(np.abs(np64(S) - S_ref))) <= 2e-5 * max(1.0, float(np.abs(S_ref).max()))
+    kr2, vr2, S2 = rb.rattn_prefill_export(dev(x["k"]), dev(x["v"]), W)
+    assert torch.equal(S, S2)       # fixed summation order
+
+
+@pytest.mark.parametrize("dtype,T,W", [("f32", 40, 16), ("bf16", 256, 64), ("bf16", 300, 512)])
+def test_prefill_then_decode_reproduces_forward_row(dtype, T, W):
+    """fwd over T+1 tokens, last row  ==  export(first T tokens) followed by one decode step at pos = T."""
+    B, Hq, Hkv, D = 2, 4, 2, 128
+    x = synth.make_random_layer(B, T + 1, Hq, Hkv, D, dtype, 850 + T, with_gains=True)
+    scale = 1.0 / math.sqrt(D)
+    gs, gr = x["gamma_swa"], x["gamma_rla"]
+    ref = orc.fwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), W, scale=scale, gamma_swa=np64(gs),
+                        gamma_rla=np64(gr), rows=np.array([T]))["o"][:, T]
+    q, k, v = dev(x["q"]), dev(x["k"]), dev(x["v"])
+    kr, vr, S = rb.rattn_prefill_export(k[:, :T].contiguous(), v[:, :T].contiguous(), W)
+    pos = torch.full((B,), T, dtype=torch.int32, device="cuda")
+    o = rb.rattn_decode_step(q[:, T].contiguous(), k[:, T].contiguous(), v[:, T].contiguous(), pos, kr, vr, S,
+                             dev(gs), dev(gr), softmax_scale=scale)
+    gmax = max(float(gs.abs().max()), float(gr.abs().max()), 1.0)
+    assert maxerr(o, ref) <= TOL[dtype] * gmax
