@@ -112,6 +112,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=24)
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the reported-only timings of the 12B-shaped layer and the window sweep")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain out-of-place elementwise pass over 256 MiB (reads and writes 256 MiB): "
                          "under a counter run its FETCH_SIZE / WRITE_SIZE readings give the counters' scale")
@@ -247,6 +249,45 @@ def main():
         rb.rattn_profile_enable(False)
         out["prefill_export"] = {"workload": cfg.name, "us": {n_: sum(v_) / len(v_) * 1e3 for n_, v_ in per.items()},
                                  "us_total": sum(sum(v_) / len(v_) for v_ in per.values()) * 1e3}
+
+    if not args.no_other_workloads:
+        # reported next to the headline (never part of `value`): the 12B-shaped layer fwd+bwd and the forward
+        # window sweep at T = 8192, same timing method, 10 iterations after 3 warm-up ones
+        del q, k, v, dO, o, grads, saved, ws
+        torch.cuda.empty_cache()
+        other = {}
+
+        def run_layer(c, with_bwd):
+            t = [x_.cuda() for x_ in synth.make_layer_inputs(c, with_dO=with_bwd)]
+            pp = rb.make_params(t[0], t[1], c.W, 0, c.scale, 1e-6, with_bwd)
+            fb, bb, sb = rb.rattn_workspace_bytes(pp)
+            w_ = torch.empty(max(fb, bb, 16), dtype=torch.uint8, device="cuda")
+            sv_ = torch.empty(max(sb, 16), dtype=torch.uint8, device="cuda") if with_bwd else None
+            o_ = torch.empty_like(t[0])
+            g_ = (torch.empty_like(t[0]), torch.empty_like(t[1]), torch.empty_like(t[2])) if with_bwd else None
+            f_ = lambda: rb.rattn_fwd(t[0], t[1], t[2], c.W, softmax_scale=c.scale, save_for_bwd=with_bwd, out=o_,
+                                      saved=sv_, workspace=w_)
+            b_ = lambda: rb.rattn_bwd(t[0], t[1], t[2], sv_, t[3], c.W, softmax_scale=c.scale, want_dgamma=False,
+                                      workspace=w_, out=g_)
+            for _ in range(3):
+                f_()
+                if with_bwd:
+                    b_()
+            fl_ = layer_flops(c.B, c.T, c.Hq, c.Hkv, c.D, c.W)
+            r = {"fwd_ms": timed(f_, 10)}
+            r["fwd_tflops"] = fl_["fwd"] / (r["fwd_ms"] * 1e-3) / 1e12
+            if with_bwd:
+                r["bwd_ms"] = timed(b_, 10)
+                r["bwd_tflops"] = fl_["bwd"] / (r["bwd_ms"] * 1e-3) / 1e12
+                r["fwd_bwd_tflops"] = (fl_["fwd"] + fl_["bwd"]) / ((r["fwd_ms"] + r["bwd_ms"]) * 1e-3) / 1e12
+            r["tokens_per_s"] = c.B * c.T / ((r["fwd_ms"] + r.get("bwd_ms", 0.0)) * 1e-3)
+            return r
+
+        other["layer12b_t8192_w512"] = run_layer(synth.CONFIGS["layer12b_t8192_w512"], True)
+        for W_ in (128, 512, 1024, 4096, 8192):
+            c_ = synth.sweep_config(W_)
+            other[c_.name] = run_layer(c_, False)
+        out["other_workloads"] = other
 
     if args.calibrate_copy:
         src = torch.zeros(256 * 2 ** 20 // 4, dtype=torch.float32, device="cuda")
