@@ -228,6 +228,9 @@ def main():
         us = sum(drecs) / len(drecs) * 1e3
         nbytes = decode_bytes(dcfg.N, dcfg.Hkv, dcfg.Hq, dcfg.D, dcfg.W, 2)
         out["decode"] = {"workload": dcfg.name, "us_per_step": us, "tokens_per_s": dcfg.N / (us * 1e-6),
+                         # attention term of the generation step-time model (batch * cache bytes per sequence /
+                         # memory bandwidth) at the MI355X peak, for this layer alone
+                         "step_time_model_us": nbytes / PEAK_HBM * 1e6,
                          "roofline": {"bound": "hbm", "kernel": "decode_kernel", "achieved": nbytes / (us * 1e-6) / 1e9,
                                       "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": nbytes / (us * 1e-6) / PEAK_HBM,
                                       "traffic": measured_traffic("decode_kernel", dcfg.name),
