@@ -292,6 +292,29 @@ def main():
             other[c_.name] = run_layer(c_, False)
         out["other_workloads"] = other
 
+    if not args.no_other_workloads:
+        # what this device sustains on nothing but matrix-core instructions, and on a plain copy: context for the
+        # fractions of the published peaks above
+        sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+        rb.rattn_probe_mfma(sink, 200, 2048)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        probe_flops = rb.rattn_probe_mfma(sink, 2000, 2048)
+        e1.record()
+        torch.cuda.synchronize()
+        mfma_tflops = probe_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        src = torch.zeros(512 * 2 ** 20 // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)
+        copy_ms = timed(lambda: torch.add(src, 1.0, out=dst), 10)
+        copy_gbps = 2 * src.numel() * 4 / (copy_ms * 1e-3) / 1e9
+        del src, dst
+        out["machine"] = {"mfma_loop_tflops": mfma_tflops, "copy_GBps": copy_gbps,
+                          "value_over_mfma_loop": value / mfma_tflops,
+                          "roofline_achieved_over_mfma_loop": roofline["achieved"] / mfma_tflops}
+
     if args.calibrate_copy:
         src = torch.zeros(256 * 2 ** 20 // 4, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)

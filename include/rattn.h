@@ -135,6 +135,12 @@ void rattn_profile_reset(void);
 int rattn_profile_count(void);
 rattn_status rattn_profile_get(int idx, const char** name, float* ms);
 
+/* Machine probe for benchmarks: enqueues a kernel of `blocks` work-groups (256 threads) in which every wave issues
+ * 16 * iters bf16 matrix-core instructions (v_mfma_f32_32x32x16_bf16) and nothing else; *flops (HOST, may be NULL)
+ * receives the floating-point operations issued.  The caller times the stream.  sink: >= 16 bytes of device
+ * memory (never written in practice).  Context for the MFMA roofline (Sec. 3.2 argues from matrix-unit rates). */
+rattn_status rattn_probe_mfma(void* sink, int iters, int blocks, double* flops, void* stream);
+
 /* Static description of a status code. */
 const char* rattn_status_string(rattn_status s);
 /* Detail of the last failure on the calling thread ("" if none). HOST string, library-owned. */

@@ -15,7 +15,7 @@ RATTN_F32, RATTN_BF16 = 0, 1
 _DTYPES = {torch.float32: RATTN_F32, torch.bfloat16: RATTN_BF16}
 
 EXPORTS = ["rattn_workspace_bytes", "rattn_fwd", "rattn_bwd", "rattn_decode_step",
-           "rattn_prefill_export_workspace_bytes", "rattn_prefill_export",
+           "rattn_prefill_export_workspace_bytes", "rattn_prefill_export", "rattn_probe_mfma",
            "rattn_status_string", "rattn_last_error", "rattn_version",
            "rattn_profile_enable", "rattn_profile_reset", "rattn_profile_count", "rattn_profile_get"]
 
@@ -64,6 +64,8 @@ def lib():
     L.rattn_prefill_export_workspace_bytes.argtypes = [ctypes.POINTER(RattnParams), ctypes.POINTER(sz)]
     L.rattn_prefill_export.restype = ctypes.c_int
     L.rattn_prefill_export.argtypes = [ctypes.POINTER(RattnParams)] + [vp] * 6 + [sz, vp]
+    L.rattn_probe_mfma.restype = ctypes.c_int
+    L.rattn_probe_mfma.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double), vp]
     L.rattn_status_string.restype = ctypes.c_char_p
     L.rattn_status_string.argtypes = [ctypes.c_int]
     L.rattn_last_error.restype = ctypes.c_char_p
@@ -223,6 +225,13 @@ def rattn_prefill_export(k, v, window, k_ring=None, v_ring=None, state=None):
     _check(lib().rattn_prefill_export(ctypes.byref(p), _ptr(k), _ptr(v), _ptr(k_ring), _ptr(v_ring), _ptr(state),
                                       _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()))
     return k_ring, v_ring, state
+
+
+def rattn_probe_mfma(sink, iters, blocks):
+    """Enqueue the matrix-core probe loop on the current stream; returns the FLOPs it issues."""
+    flops = ctypes.c_double()
+    _check(lib().rattn_probe_mfma(_ptr(sink), iters, blocks, ctypes.byref(flops), _stream()))
+    return flops.value
 
 
 def rattn_profile_enable(on):

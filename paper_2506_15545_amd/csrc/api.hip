@@ -319,4 +319,13 @@ rattn_status rattn_prefill_export(const rattn_params* p, const void* k, const vo
   return check_launch("rattn_prefill_export");
 }
 
+rattn_status rattn_probe_mfma(void* sink, int iters, int blocks, double* flops, void* stream) {
+  if (!sink || !aligned16(sink)) return fail(RATTN_ERR_INVALID_ARG, "sink must be a 16-byte aligned device pointer");
+  if (iters < 1 || iters > (1 << 24) || blocks < 1 || blocks > (1 << 20))
+    return fail(RATTN_ERR_INVALID_ARG, "iters must be in [1, 2^24] and blocks in [1, 2^20] (got %d, %d)", iters, blocks);
+  const double f = rattn::probe_mfma((float*)sink, iters, blocks, (hipStream_t)stream);
+  if (flops) *flops = f;
+  return check_launch("rattn_probe_mfma");
+}
+
 }  // extern "C"

@@ -100,6 +100,9 @@ ExportPlan export_plan(const LayerDims& dm);
 void prefill_export(const LayerDims& dm, int dtype, const void* k, const void* v, void* k_ring, void* v_ring,
                     float* state, float* partial, hipStream_t st);
 
+// launches the matrix-core probe loop; returns the FLOPs it issues
+double probe_mfma(float* sink, int iters, int blocks, hipStream_t st);
+
 struct DecodeDims {
   int N, Hq, Hkv, D, W, G;
   float scale, eps;
