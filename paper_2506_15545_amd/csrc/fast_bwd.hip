@@ -172,11 +172,10 @@ __device__ __forceinline__ void dq_subtile(const unsigned char* kt, const unsign
     __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
   }
   if (masked) {
+    // in the window <=> 0 <= query - key < W: one unsigned compare per element against a per-lane base
+    const unsigned dist0 = (unsigned)(myq - ka - 4 * h);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int key = ka + 8 * (i >> 2) + 4 * h + (i & 3);
-      p[i] = (key <= myq && key > myq - W) ? p[i] : 0.f;
-    }
+    for (int i = 0; i < 16; ++i) p[i] = (dist0 - (unsigned)(8 * (i >> 2) + (i & 3)) < (unsigned)W) ? p[i] : 0.f;
   }
   float ds[16];
 #pragma unroll
@@ -554,11 +553,10 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
         }
         if (!krole) {
           if (!full) {
+            const unsigned dist0 = (unsigned)(qa + 4 * h - mykey);  // 0 <= query - key < W, one compare per element
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const int query = qa + 8 * (i >> 2) + 4 * h + (i & 3);
-              s[i] = (mykey <= query && query - mykey < W) ? s[i] : -INFINITY;
-            }
+            for (int i = 0; i < 16; ++i)
+              s[i] = (dist0 + (unsigned)(8 * (i >> 2) + (i & 3)) < (unsigned)W) ? s[i] : -INFINITY;
           }
 #pragma unroll
           for (int i = 0; i < 16; ++i) s[i] = fast_exp2(__builtin_fmaf(s[i], a.scale_log2, -stat[i] * LOG2E));

@@ -96,12 +96,11 @@ __device__ __forceinline__ void sweep_step(const unsigned char* smem, const Lane
   const int h = lane >> 5;
   if (!gm.full(j)) {  // wave-uniform: window edge, diagonal, or a sub-tile this wave does not see at all
     const int ka = gm.ka(j);
+    // in the window <=> 0 <= query - key < W: one unsigned compare per element against a per-lane base
+    const unsigned dist0 = (unsigned)(myq - ka - 4 * h);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int key = ka + 8 * (i >> 2) + 4 * h + (i & 3);
-      const bool ok = key <= myq && key > myq - gm.W;
-      s_cur[i] = ok ? s_cur[i] : -INFINITY;
-    }
+    for (int i = 0; i < 16; ++i)
+      s_cur[i] = (dist0 - (unsigned)(8 * (i >> 2) + (i & 3)) < (unsigned)gm.W) ? s_cur[i] : -INFINITY;
   }
   // ---- region 1
   f32x16_t s_next;
