@@ -25,6 +25,10 @@ struct FastBwdArgs {
   uint16_t *dq, *dk, *dv;
   int B, T, Hq, Hkv, G, W, nstf, nk, ntile;
   float scale, scale_log2;
+  // inputs of the RMS-norm backward when the dq kernel does it itself (unit gains); dxs, dxr and delta
+  // above then name the buffers it fills
+  const uint16_t *dO, *xs, *xr;
+  const float *rs, *rr;
 };
 
 // ------------------------------------------------------------------------------------------------
@@ -189,6 +193,62 @@ __device__ __forceinline__ void dq_subtile(const unsigned char* kt, const unsign
 }
 
 // grid (ntile * Hq * B), 256 threads: 128 queries of one head, wave w owns 32.
+// sum over the 16 lanes of a DPP row (quad butterflies, then the two mirror steps)
+template <int CTRL>
+__device__ __forceinline__ float dpp_get(float x) {
+  return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float sum16(float x) {
+  x += dpp_get<0xB1>(x);   // quad_perm [1,0,3,2]
+  x += dpp_get<0x4E>(x);   // quad_perm [2,3,0,1]
+  x += dpp_get<0x141>(x);  // row_half_mirror
+  x += dpp_get<0x140>(x);  // row_mirror
+  return x;
+}
+
+// Backward of the two RMS norms (unit gains) for 32 consecutive query rows of one head, by one wave: 16 lanes
+// per row, 8 features each, four rows per pass (row-contiguous 16-byte accesses).  Same arithmetic as
+// bwd_prep_kernel.  Stores d xs, d xr (bf16) and delta = rowsum(d xs * xs) to global memory for the later
+// kernels, and, if `stage` is given, d xr also into rows 0..31 of that LDS tile (swizzled row layout), from
+// where the wave takes it as an MFMA operand without waiting for the global stores.
+__device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, size_t row0_off, size_t qstride, size_t stat0,
+                                             unsigned char* stage, int lane) {
+  const int sub = lane >> 4, c = lane & 15;
+  uint16_t* dxs_w = const_cast<uint16_t*>(a.dxs);
+  uint16_t* dxr_w = const_cast<uint16_t*>(a.dxr);
+  float* delta_w = const_cast<float*>(a.delta);
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int r = 4 * it + sub;
+    const size_t off = row0_off + (size_t)r * qstride + 8 * c;
+    float dy[8], xs[8], xr[8];
+    unpack_bf16x8(*reinterpret_cast<const bf16x8_t*>(a.dO + off), dy);
+    unpack_bf16x8(*reinterpret_cast<const bf16x8_t*>(a.xs + off), xs);
+    unpack_bf16x8(*reinterpret_cast<const bf16x8_t*>(a.xr + off), xr);
+    const float r_s = a.rs[stat0 + r], r_r = a.rr[stat0 + r];
+    float m1 = 0.f, m2 = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { m1 = fmaf(dy[e], xs[e], m1); m2 = fmaf(dy[e], xr[e], m2); }
+    m1 = sum16(m1) * (1.f / 128.f);
+    m2 = sum16(m2) * (1.f / 128.f);
+    const float b_s = r_s * r_s * r_s * m1, b_r = r_r * r_r * r_r * m2;
+    float av[8], cv[8], dl = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      av[e] = r_s * dy[e] - xs[e] * b_s;
+      cv[e] = r_r * dy[e] - xr[e] * b_r;
+      dl = fmaf(av[e], xs[e], dl);
+    }
+    const bf16x8_t cpk = pack_bf16x8(cv);
+    *reinterpret_cast<bf16x8_t*>(dxs_w + off) = pack_bf16x8(av);
+    *reinterpret_cast<bf16x8_t*>(dxr_w + off) = cpk;
+    if (stage) *reinterpret_cast<bf16x8_t*>(stage + r * ROW_BYTES + ((c ^ swz(r)) << 4)) = cpk;
+    dl = sum16(dl);
+    if (c == 0) delta_w[stat0 + r] = dl;
+  }
+}
+
+template <bool FUSED_PREP>
 __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
   __shared__ __align__(16) unsigned char smem[65536];
   const int lane = lane_id(), w = wave_id();
@@ -212,16 +272,27 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
   const int myq = t0 + 32 * w + r32;
   const size_t stat_off = (size_t)(b * Hq + hq) * T + myq;
 
+  const int j0 = t0 - W;
+  if (FUSED_PREP)
+    rms_bwd_rows(a, qtile_off + (size_t)(32 * w) * qstride, qstride, stat_off - r32,
+                 j0 > -128 ? smem + 32 * w * ROW_BYTES : nullptr, lane);
   bf16x8_t qop[8];
   load_bop(a.q + myrow_off, h, qop);
   f32x16_t acc[4] = {{0}, {0}, {0}, {0}};
 
   // ---- linear branch: d phi(q)
-  const int j0 = t0 - W;
   if (j0 > -128) {
     const bool has_state = j0 >= 0;
     bf16x8_t dxrop[8];
-    load_bop(a.dxr + myrow_off, h, dxrop);
+    if (FUSED_PREP) {
+      // own rows, staged by this wave: LDS executes a wave's accesses in order, and the reads are complete
+      // before the tile loads below may overwrite the rows
+#pragma unroll
+      for (int c = 0; c < 8; ++c) dxrop[c] = lds_row(smem, lo, 32 * w, c);
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    } else {
+      load_bop(a.dxr + myrow_off, h, dxrop);
+    }
     if (has_state) {
       const uint16_t* sbase = a.states + ((size_t)(b * Hkv + g) * a.nstf + j0 / 128) * 16384;
       tile_load_async<8>(sbase, 128, smem, w * 8, lane);
@@ -272,6 +343,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
   }
 
   // ---- softmax branch
+  // With the fused RMS backward the wave reads back d xs and delta of its own rows: its stores are complete
+  // after a full vector-memory wait (the linear branch has had several), and the vector cache is the wave's own.
+  if (FUSED_PREP && j0 <= -128) wait_vmem();
   bf16x8_t dxsop[8];
   load_bop(a.dxs + myrow_off, h, dxsop);
   const float lse2 = a.lse[stat_off] * LOG2E;
@@ -642,17 +716,21 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
               const SavedPtrs& sv, const void* dO, void* dq, void* dk, void* dv, float* dgs, float* dgr,
               const FastBwdWs& ws, hipStream_t st) {
   const FastBwdPlan pl = fast_bwd_plan(dm);
-  {
-    ProfScope ps("bwd_prep_kernel", st);
-    bwd_prep_kernel<<<dim3(pl.RB, dm.Hq), 256, 0, st>>>((const uint16_t*)dO, (const uint16_t*)sv.xs, (const uint16_t*)sv.xr,
-                                                        sv.rs, sv.rr, gs, gr, (uint16_t*)ws.dxs, (uint16_t*)ws.dxr,
-                                                        ws.delta, ws.dgpart, dm.B, dm.T, dm.Hq);
+  // With unit gains and no gain gradients asked for, the RMS-norm backward runs inside the dq kernel (each wave
+  // on its own rows) and the separate pass over dO, xs and xr is dropped.
+  const bool fused_prep = !gs && !gr && !dgs && !dgr;
+  if (!fused_prep) {
+    {
+      ProfScope ps("bwd_prep_kernel", st);
+      bwd_prep_kernel<<<dim3(pl.RB, dm.Hq), 256, 0, st>>>((const uint16_t*)dO, (const uint16_t*)sv.xs,
+                                                          (const uint16_t*)sv.xr, sv.rs, sv.rr, gs, gr, (uint16_t*)ws.dxs,
+                                                          (uint16_t*)ws.dxr, ws.delta, ws.dgpart, dm.B, dm.T, dm.Hq);
+    }
+    if (dgs || dgr) {
+      const int HD = dm.Hq * 128;
+      dgamma_reduce_kernel<<<(HD + 255) / 256, 256, 0, st>>>(ws.dgpart, dgs, dgr, pl.RB, HD);
+    }
   }
-  if (dgs || dgr) {
-    const int HD = dm.Hq * 128;
-    dgamma_reduce_kernel<<<(HD + 255) / 256, 256, 0, st>>>(ws.dgpart, dgs, dgr, pl.RB, HD);
-  }
-  rla_reverse_states(dm, pl.fwd.W, pl.nk, q, ws.dxr, ws.U, ws.rstates, st);
   FastBwdArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
   a.dxs = (const uint16_t*)ws.dxs; a.dxr = (const uint16_t*)ws.dxr;
@@ -662,10 +740,14 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
   a.B = dm.B; a.T = dm.T; a.Hq = dm.Hq; a.Hkv = dm.Hkv; a.G = dm.G; a.W = pl.fwd.W;
   a.nstf = pl.fwd.nstf; a.nk = pl.nk; a.ntile = dm.T / 128;
   a.scale = dm.scale; a.scale_log2 = dm.scale * LOG2E;
+  a.dO = (const uint16_t*)dO; a.xs = (const uint16_t*)sv.xs; a.xr = (const uint16_t*)sv.xr;
+  a.rs = sv.rs; a.rr = sv.rr;
   {
     ProfScope ps("bwd_dq_kernel", st);
-    bwd_dq_kernel<<<dim3(a.ntile * dm.Hq * dm.B), 256, 0, st>>>(a);
+    if (fused_prep) bwd_dq_kernel<true><<<dim3(a.ntile * dm.Hq * dm.B), 256, 0, st>>>(a);
+    else bwd_dq_kernel<false><<<dim3(a.ntile * dm.Hq * dm.B), 256, 0, st>>>(a);
   }
+  rla_reverse_states(dm, pl.fwd.W, pl.nk, q, ws.dxr, ws.U, ws.rstates, st);
   static const hipError_t lds_attr = hipFuncSetAttribute(
       reinterpret_cast<const void*>(bwd_dkv_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS_BYTES);
   (void)lds_attr;

@@ -153,6 +153,35 @@ def test_fast_bwd_matches_oracle(B, T, Hq, Hkv, W):
             assert float(np.max(np.abs(np64(g_) - ref[n]))) / rms <= 2e-2, n
 
 
+@pytest.mark.parametrize("B,T,Hq,Hkv,W", BWD_CASES)
+def test_fast_bwd_unit_gains_no_dgamma(B, T, Hq, Hkv, W):
+    """Without gains and without gain gradients the library folds the RMS-norm backward into the dq kernel
+    (no separate preparation pass): same bar as above, and that pass must not have run."""
+    D = 128
+    x = synth.make_random_layer(B, T, Hq, Hkv, D, "bf16", 1700 + T + W, with_dO=True)
+    scale = 1.0 / math.sqrt(D)
+    print(f"fast bwd (unit gains) case B={B} T={T} Hq={Hq} Hkv={Hkv} W={W}", flush=True)
+    q, k, v, dO = x["q"].cuda(), x["k"].cuda(), x["v"].cuda(), x["dO"].cuda()
+    o, saved = rb.rattn_fwd(q, k, v, W, softmax_scale=scale, save_for_bwd=True)
+    rb.rattn_profile_enable(True)
+    dq, dk, dv, dgs, dgr = rb.rattn_bwd(q, k, v, saved, dO, W, softmax_scale=scale, want_dgamma=False)
+    torch.cuda.synchronize()
+    names = [n for n, _ in rb.rattn_profile_records()]
+    rb.rattn_profile_enable(False)
+    assert "bwd_dkv_kernel" in names and "bwd_prep_kernel" not in names
+    assert dgs is None and dgr is None
+    ref = orc.bwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), np64(x["dO"]), W, scale=scale)
+    errs = {n: grad_err(g_, ref[n]) for n, g_ in (("dq", dq), ("dk", dk), ("dv", dv))}
+    print(errs, flush=True)
+    for n, (emax, erms) in errs.items():
+        assert emax <= 3e-2 and erms <= 5e-3, f"{n}: max {emax} rms {erms}"
+    # asking for the gain gradients takes the separate pass; dq, dk, dv agree to rounding of the row sums
+    dq2, dk2, dv2, dgs2, dgr2 = rb.rattn_bwd(q, k, v, saved, dO, W, softmax_scale=scale, want_dgamma=True)
+    for n, g1, g2 in (("dq", dq, dq2), ("dk", dk, dk2), ("dv", dv, dv2)):
+        emax, erms = grad_err(g1, np64(g2))
+        assert emax <= 1e-2 and erms <= 2e-3, f"{n} fused vs separate: max {emax} rms {erms}"
+
+
 def test_fast_bwd_is_deterministic():
     x = synth.make_random_layer(1, 512, 4, 2, 128, "bf16", 6, with_dO=True)
     q, k, v, dO = x["q"].cuda(), x["k"].cuda(), x["v"].cuda(), x["dO"].cuda()
