@@ -432,9 +432,9 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
 }
 
-// grid (ntile * Hkv * B), 512 threads: 128 keys of one KV head.  Waves w and w+4 both work on key block w
-// (lane = key) and share a SIMD, with complementary roles, so each keeps only one 128 x 32 accumulator and one
-// set of operand rows and two waves fit on a SIMD:
+// grid (ntile * Hkv * B), 512 threads: 128 keys of one KV head.  Waves w and 7-w both work on key block w
+// (lane = key) with complementary roles, so each keeps only one 128 x 32 accumulator and one set of operand
+// rows and two waves (w and w+4, one of each role) fit on a SIMD:
 //   V-role (waves 0-3): S^T = Q K^T -> P (also written to LDS, fp32),  dV^T += dXs^T P;
 //                       linear branch: C = phi(Q) phi(K)^T (masked),   dV^T += dXr^T C + R-state rows * phi(K)
 //   K-role (waves 4-7): dP = dXs V^T, then dS = P .* (dP - delta) * scale with the P of its partner,
@@ -449,8 +449,10 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* pex = smem + DKV_PEX_OFF;
   const int lane = lane_id(), w8 = wave_id();
-  const int w = w8 & 3;
   const bool krole = w8 >= 4;
+  // key block of the wave: the K-role takes them in reverse, so that in the linear branch, where block j pairs with
+  // 4 - j query sub-tiles, the two waves of every SIMD (w8 and w8 + 4) carry five sub-tiles between them
+  const int w = krole ? 7 - w8 : w8;
   const int r32 = lane & 31, h = lane >> 5;
   const LaneOff lo = make_lane_off(lane);
   const int T = a.T, W = a.W, Hq = a.Hq, Hkv = a.Hkv, G = a.G;
