@@ -254,8 +254,8 @@ def main():
                                  "us_total": sum(sum(v_) / len(v_) for v_ in per.values()) * 1e3}
 
     if not args.no_other_workloads:
-        # reported next to the headline (never part of `value`): the 12B-shaped layer fwd+bwd and the forward
-        # window sweep at T = 8192, same timing method, 10 iterations after 3 warm-up ones
+        # reported next to the headline (never part of `value`): the 12B-shaped layer and the window
+        # sweep at T = 8192 (fwd and bwd), same timing method, 10 iterations after 3 warm-up ones
         del q, k, v, dO, o, grads, saved, ws
         torch.cuda.empty_cache()
         other = {}
@@ -289,7 +289,7 @@ def main():
         other["layer12b_t8192_w512"] = run_layer(synth.CONFIGS["layer12b_t8192_w512"], True)
         for W_ in (128, 512, 1024, 4096, 8192):
             c_ = synth.sweep_config(W_)
-            other[c_.name] = run_layer(c_, False)
+            other[c_.name] = run_layer(c_, True)
         out["other_workloads"] = other
 
     if not args.no_other_workloads:
