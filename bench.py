@@ -8,6 +8,7 @@ products at nominal chunk 64, no recomputation and no masked-tile waste counted.
 Prints ONE JSON line.
 """
 import argparse
+import dataclasses
 import json
 import math
 import os
@@ -255,7 +256,7 @@ def main():
 
     if not args.no_other_workloads:
         # reported next to the headline (never part of `value`): the 12B-shaped layer and the window
-        # sweep at T = 8192 (fwd and bwd), same timing method, 10 iterations after 3 warm-up ones
+        # sweep at T = 8192 (fwd and bwd), same timing method, 20 iterations after 5 warm-up ones
         del q, k, v, dO, o, grads, saved, ws
         torch.cuda.empty_cache()
         other = {}
@@ -272,21 +273,23 @@ def main():
                                       saved=sv_, workspace=w_)
             b_ = lambda: rb.rattn_bwd(t[0], t[1], t[2], sv_, t[3], c.W, softmax_scale=c.scale, want_dgamma=False,
                                       workspace=w_, out=g_)
-            for _ in range(3):
+            for _ in range(5):
                 f_()
                 if with_bwd:
                     b_()
             fl_ = layer_flops(c.B, c.T, c.Hq, c.Hkv, c.D, c.W)
-            r = {"fwd_ms": timed(f_, 10)}
+            r = {"fwd_ms": timed(f_, 20)}
             r["fwd_tflops"] = fl_["fwd"] / (r["fwd_ms"] * 1e-3) / 1e12
             if with_bwd:
-                r["bwd_ms"] = timed(b_, 10)
+                r["bwd_ms"] = timed(b_, 20)
                 r["bwd_tflops"] = fl_["bwd"] / (r["bwd_ms"] * 1e-3) / 1e12
                 r["fwd_bwd_tflops"] = (fl_["fwd"] + fl_["bwd"]) / ((r["fwd_ms"] + r["bwd_ms"]) * 1e-3) / 1e12
             r["tokens_per_s"] = c.B * c.T / ((r["fwd_ms"] + r.get("bwd_ms", 0.0)) * 1e-3)
             return r
 
         other["layer12b_t8192_w512"] = run_layer(synth.CONFIGS["layer12b_t8192_w512"], True)
+        # the headline shape with the window read as 512 earlier tokens + the current one (not a tile multiple)
+        other["layer3b_t4096_w513"] = run_layer(dataclasses.replace(cfg, name="layer3b_t4096_w513", W=513), True)
         for W_ in (128, 512, 1024, 4096, 8192):
             c_ = synth.sweep_config(W_)
             other[c_.name] = run_layer(c_, True)

@@ -1,7 +1,8 @@
 // MFMA backward of the RAttention layer (same shape class as the MFMA forward: bf16, D = 128,
-// T % 128 == 0, W % 64 == 0 or W >= T).  No floating-point atomics: dq is produced by a kernel that
-// owns query tiles, dk/dv by a kernel that owns key tiles (and visits the G query heads of its KV
-// head in turn); both recompute the attention probabilities from the saved log-sum-exp.
+// T % 128 == 0, any W >= 8; tiles and states are laid out for W rounded up to 64, see fast_fwd.hip).
+// No floating-point atomics: dq is produced by a kernel that owns query tiles, dk/dv by a kernel that
+// owns key tiles (and visits the G query heads of its KV head in turn); both recompute the attention
+// probabilities from the saved log-sum-exp.
 //
 //   prep : through the two RMS norms (Sec. 3.2): dx_s, dx_r (bf16 MFMA operands), delta = <dx_s, x_s>,
 //          dgamma partials
@@ -23,7 +24,7 @@ struct FastBwdArgs {
   const float *lse, *delta;
   const uint16_t *states, *rstates;
   uint16_t *dq, *dk, *dv;
-  int B, T, Hq, Hkv, G, W, nstf, nk, ntile;
+  int B, T, Hq, Hkv, G, W, gap, nstf, nk, ntile;  // W: window rounded up to 64; true window = W - gap
   float scale, scale_log2;
   // inputs of the RMS-norm backward when the dq kernel does it itself (unit gains); dxs, dxr and delta
   // above then name the buffers it fills
@@ -272,17 +273,23 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
   const int myq = t0 + 32 * w + r32;
   const size_t stat_off = (size_t)(b * Hq + hq) * T + myq;
 
-  const int j0 = t0 - W;
+  const int j0 = t0 - W, gap = a.gap;
+  const bool has_lin = j0 > -128 || (gap > 0 && j0 == -128);
   if (FUSED_PREP)
     rms_bwd_rows(a, qtile_off + (size_t)(32 * w) * qstride, qstride, stat_off - r32,
-                 j0 > -128 ? smem + 32 * w * ROW_BYTES : nullptr, lane);
+                 has_lin ? smem + 32 * w * ROW_BYTES : nullptr, lane);
   bf16x8_t qop[8];
   load_bop(a.q + myrow_off, h, qop);
   f32x16_t acc[4] = {{0}, {0}, {0}, {0}};
 
   // ---- linear branch: d phi(q)
-  if (j0 > -128) {
-    const bool has_state = j0 >= 0;
+  // Tiles and states are laid out for the window rounded up to 64 (W); with gap = W - true window > 0 a query
+  // sees key_local <= q_local + gap of the chunk that starts at j0 = t0 - W, i.e. up to 64 keys past the two
+  // 64-key tiles of the aligned layout (a third tile, handled after them), and the query tile at j0 = -128
+  // reaches keys only through that third tile.
+  if (has_lin) {
+    const bool has_state = j0 >= 0, has_res = j0 > -128;
+    const int u_hi = w + ((31 + gap) >> 5);
     bf16x8_t dxrop[8];
     if (FUSED_PREP) {
       // own rows, staged by this wave: LDS executes a wave's accesses in order, and the reads are complete
@@ -293,41 +300,21 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
     } else {
       load_bop(a.dxr + myrow_off, h, dxrop);
     }
-    if (has_state) {
-      const uint16_t* sbase = a.states + ((size_t)(b * Hkv + g) * a.nstf + j0 / 128) * 16384;
-      tile_load_async<8>(sbase, 128, smem, w * 8, lane);
-      tile_load_async<4>(vbase + (size_t)j0 * kstride, kstride, smem + 32768, w * 4, lane);
-    }
-    tile_load_async<4>(vbase + (size_t)(j0 + 64) * kstride, kstride, smem + 49152, w * 4, lane);
-    wait_vmem();
-    __syncthreads();
-    if (has_state) {
-#pragma unroll
-      for (int kd = 0; kd < 8; ++kd) {
-#pragma unroll
-        for (int ft = 0; ft < 4; ++ft) acc[ft] = mfma32(lds_trn(smem, lon, 16 * kd, ft), dxrop[kd], acc[ft]);
-      }
-    }
-    __syncthreads();
-    if (has_state) tile_load_async<4>(kbase + (size_t)j0 * kstride, kstride, smem, w * 4, lane);
-    tile_load_async<4>(kbase + (size_t)(j0 + 64) * kstride, kstride, smem + 16384, w * 4, lane);
-    wait_vmem();
-    __syncthreads();
-    if (has_state) phi_tile_inplace(smem, 128);
-    else phi_tile_inplace(smem + 16384, 64);
-    __syncthreads();
-    for (int u = has_state ? 0 : 2; u <= w; ++u) {
-      const unsigned char* kt = smem + (u >> 1) * 16384;
-      const unsigned char* vt = smem + 32768 + (u >> 1) * 16384;
-      const int ks = u & 1;
+    // key sub-tile u (keys j0 + 32u .. +31): dC = V dXr^T, masked, then d phi(q)^T += phi(K)^T dC
+    auto intra_unit = [&](const unsigned char* kt, const unsigned char* vt, int ks, int u) {
       f32x16_t c = {0};
 #pragma unroll
       for (int kd = 0; kd < 8; ++kd) c = mfma32(lds_row(vt, lo, 32 * ks, kd), dxrop[kd], c);
       float cv[16];
+      if (32 * u + 31 > 32 * w + gap) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key_local = 32 * u + 8 * (i >> 2) + 4 * h + (i & 3);
-        cv[i] = (u == w && key_local > 32 * w + r32) ? 0.f : c[i];
+        for (int i = 0; i < 16; ++i) {
+          const int key_local = 32 * u + 8 * (i >> 2) + 4 * h + (i & 3);
+          cv[i] = key_local > 32 * w + r32 + gap ? 0.f : c[i];
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) cv[i] = c[i];
       }
       bf16x8_t cop[2] = {pack_bf16x8(&cv[0]), pack_bf16x8(&cv[8])};
 #pragma unroll
@@ -335,8 +322,45 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
 #pragma unroll
         for (int ft = 0; ft < 4; ++ft) acc[ft] = mfma32(lds_trp(kt, lo, 32 * ks + 16 * mf, ft), cop[mf], acc[ft]);
       }
+    };
+    if (has_res) {
+      if (has_state) {
+        const uint16_t* sbase = a.states + ((size_t)(b * Hkv + g) * a.nstf + j0 / 128) * 16384;
+        tile_load_async<8>(sbase, 128, smem, w * 8, lane);
+        tile_load_async<4>(vbase + (size_t)j0 * kstride, kstride, smem + 32768, w * 4, lane);
+      }
+      tile_load_async<4>(vbase + (size_t)(j0 + 64) * kstride, kstride, smem + 49152, w * 4, lane);
+      wait_vmem();
+      __syncthreads();
+      if (has_state) {
+#pragma unroll
+        for (int kd = 0; kd < 8; ++kd) {
+#pragma unroll
+          for (int ft = 0; ft < 4; ++ft) acc[ft] = mfma32(lds_trn(smem, lon, 16 * kd, ft), dxrop[kd], acc[ft]);
+        }
+      }
+      __syncthreads();
+      if (has_state) tile_load_async<4>(kbase + (size_t)j0 * kstride, kstride, smem, w * 4, lane);
+      tile_load_async<4>(kbase + (size_t)(j0 + 64) * kstride, kstride, smem + 16384, w * 4, lane);
+      wait_vmem();
+      __syncthreads();
+      if (has_state) phi_tile_inplace(smem, 128);
+      else phi_tile_inplace(smem + 16384, 64);
+      __syncthreads();
+      for (int u = has_state ? 0 : 2; u <= min(3, u_hi); ++u)
+        intra_unit(smem + (u >> 1) * 16384, smem + 32768 + (u >> 1) * 16384, u & 1, u);
     }
     __syncthreads();
+    if (gap > 0) {
+      tile_load_async<4>(kbase + (size_t)(j0 + 128) * kstride, kstride, smem, w * 4, lane);
+      tile_load_async<4>(vbase + (size_t)(j0 + 128) * kstride, kstride, smem + 32768, w * 4, lane);
+      wait_vmem();
+      __syncthreads();
+      phi_tile_inplace(smem, 64);
+      __syncthreads();
+      for (int u = 4; u <= min(5, u_hi); ++u) intra_unit(smem, smem + 32768, u & 1, u);
+      __syncthreads();
+    }
     float qf[64];
     phi_row_clayout(a.q + myrow_off, h, qf);
     phi_jacobian(acc, qf);
@@ -345,7 +369,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
   // ---- softmax branch
   // With the fused RMS backward the wave reads back d xs and delta of its own rows: its stores are complete
   // after a full vector-memory wait (the linear branch has had several), and the vector cache is the wave's own.
-  if (FUSED_PREP && j0 <= -128) wait_vmem();
+  if (FUSED_PREP && !has_lin) wait_vmem();
   bf16x8_t dxsop[8];
   load_bop(a.dxs + myrow_off, h, dxsop);
   const float lse2 = a.lse[stat_off] * LOG2E;
@@ -360,6 +384,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
     __syncthreads();
   }
   const int qa = t0 + 32 * w, qb = qa + 31;
+  const int Wm = W - gap;  // the true window: element masks and sub-tile skipping
   for (int n = 0; n < ntiles; ++n) {
     const int it = ntiles - 1 - n;
     const int cur = n & 1;
@@ -374,10 +399,10 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
 #pragma unroll
     for (int ks = 1; ks >= 0; --ks) {
       const int ka = kt0 + 32 * ks;
-      const bool need = ka <= qb && ka + 31 >= qa - W + 1;
+      const bool need = ka <= qb && ka + 31 >= qa - Wm + 1;
       if (need) {
-        const bool full = ka + 31 <= qa && ka >= qb - W + 1;
-        dq_subtile(kt, vt, ks, ka, myq, W, !full, a.scale, a.scale_log2, lse2, dl, qop, dxsop, acc, lane, lo);
+        const bool full = ka + 31 <= qa && ka >= qb - Wm + 1;
+        dq_subtile(kt, vt, ks, ka, myq, Wm, !full, a.scale, a.scale_log2, lse2, dl, qop, dxsop, acc, lane, lo);
       }
     }
     wait_vmem();
@@ -500,8 +525,17 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
   int buf = 0, issued = 0;  // slot of the first softmax-branch tile, tiles requested so far
 
   // ---- linear branch
-  if (s0 < Tp) {
-    const int nq = min(128, Tp - s0);  // query rows t = s0 + W + [0, nq) pair with this key tile
+  // Key s pairs with the queries t >= s + (true window).  In the aligned layout (W) those of this key tile are
+  // the "head" rows t = s0 + W + [0, nq) of every query head, masked to q_local >= key_local, plus everything
+  // later through the reverse state.  With gap = W - true window > 0 a key also pairs with up to `gap` earlier
+  // queries, q_local >= key_local - gap: they lie in the 64 rows before the head rows, which are run as a
+  // second (first) pass per head.  A pass = 64 or 128 query rows of one head, q_local of its first row = qb0.
+  const int gap = a.gap;
+  const bool has_main = s0 < Tp;
+  const bool has_pre = gap > 0 && s0 <= Tp;
+  if (has_main || has_pre) {
+    const int nq = has_main ? min(128, Tp - s0) : 0;  // head rows
+    const int np = (has_pre ? 1 : 0) + (has_main ? 1 : 0), NV = G * np;
     if (!krole) {
       float x[64];
 #pragma unroll
@@ -512,41 +546,48 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
     unsigned char* const dA = smem + 32768;
     unsigned char* const qB = smem + 65536;
     unsigned char* const dB = smem + DKV_PEX_OFF;
-    auto issue_head = [&](int hh, unsigned char* qb, unsigned char* db) {
-      const size_t qoff = ((size_t)(b * T + s0 + W) * Hq + g * G + hh) * 128;
+    auto pass_is_pre = [&](int vh) { return has_pre && (vh % np) == 0; };
+    auto issue_pass = [&](int vh, unsigned char* qb, unsigned char* db) {
+      const bool pre = pass_is_pre(vh);
+      const int row0 = s0 + W - (pre ? 64 : 0), nrow = pre ? 64 : nq;
+      const size_t qoff = ((size_t)(b * T + row0) * Hq + g * G + vh / np) * 128;
       tile_load_async<2>(a.q + qoff, qstride, qb, w8 * 2, lane);
       tile_load_async<2>(a.dxr + qoff, qstride, db, w8 * 2, lane);
-      if (nq == 128) {
+      if (nrow == 128) {
         tile_load_async<2>(a.q + qoff, qstride, qb, 16 + w8 * 2, lane);
         tile_load_async<2>(a.dxr + qoff, qstride, db, 16 + w8 * 2, lane);
       }
     };
-    const uint16_t* rbase = a.rstates + ((size_t)(b * Hkv + g) * a.nk + kti) * 16384;
-    tile_load_async<4>(rbase, 128, dB, w8 * 4, lane);
-    issue_head(0, qA, dA);
+    if (has_main) {
+      const uint16_t* rbase = a.rstates + ((size_t)(b * Hkv + g) * a.nk + kti) * 16384;
+      tile_load_async<4>(rbase, 128, dB, w8 * 4, lane);
+    }
+    issue_pass(0, qA, dA);
     wait_vmem();
     __syncthreads();
-    if (!krole) {
+    if (has_main) {
+      if (!krole) {
 #pragma unroll
-      for (int c = 0; c < 8; ++c)
+        for (int c = 0; c < 8; ++c)
 #pragma unroll
-        for (int t = 0; t < 4; ++t) acc[t] = mfma32(lds_row(dB, lo, 32 * t, c), xop[c], acc[t]);
-    } else {
-      const LaneOffN lon = make_lane_off_n(lane);
+          for (int t = 0; t < 4; ++t) acc[t] = mfma32(lds_row(dB, lo, 32 * t, c), xop[c], acc[t]);
+      } else {
+        const LaneOffN lon = make_lane_off_n(lane);
 #pragma unroll
-      for (int c = 0; c < 8; ++c)
+        for (int c = 0; c < 8; ++c)
 #pragma unroll
-        for (int t = 0; t < 4; ++t) acc[t] = mfma32(lds_trn(dB, lon, 16 * c, t), xop[c], acc[t]);
+          for (int t = 0; t < 4; ++t) acc[t] = mfma32(lds_trn(dB, lon, 16 * c, t), xop[c], acc[t]);
+      }
     }
     __syncthreads();  // buffer B is free again
-    for (int hh = 0; hh < G; ++hh) {
-      const bool in_a = !(hh & 1);
+    for (int vh = 0; vh < NV; ++vh) {
+      const bool in_a = !(vh & 1);
       unsigned char* const qb = in_a ? qA : qB;
       unsigned char* const db = in_a ? dA : dB;
-      // while this head is worked on, the other buffer receives the next head, or after the last head the
+      // while this pass is worked on, the other buffer receives the next one, or after the last pass the
       // first query tiles of the softmax branch (slot 2 if buffer B is the free one, else slots 0 and 1)
-      if (hh + 1 < G) {
-        issue_head(hh + 1, in_a ? qB : qA, in_a ? dB : dA);
+      if (vh + 1 < NV) {
+        issue_pass(vh + 1, in_a ? qB : qA, in_a ? dB : dA);
       } else if (in_a) {
         is_buf = buf = 2;
         issue();
@@ -556,20 +597,28 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
         issued = 1;
         if (nsteps > 1) { issue(); issued = 2; }
       }
-      phi_tile_inplace_512(qb, nq);
+      const bool pre = pass_is_pre(vh);
+      const int nrow = pre ? 64 : nq, qb0 = pre ? -64 : 0;
+      phi_tile_inplace_512(qb, nrow);
       __syncthreads();
       const unsigned char* mine = krole ? db : qb;    // rows contracted with xop
       const unsigned char* other = krole ? qb : db;   // rows accumulated into acc
-      for (int u = w; u < nq / 32; ++u) {
+      for (int u = 0; u < nrow / 32; ++u) {
+        const int ql0 = qb0 + 32 * u;                  // q_local of the sub-tile's first row
+        if (32 * w > ql0 + 31 + gap) continue;         // no pair of this key block and sub-tile
         f32x16_t c = {0};
 #pragma unroll
         for (int e = 0; e < 8; ++e) c = mfma32(lds_row(mine, lo, 32 * u, e), xop[e], c);
         float cv[16];
+        if (32 * w + 31 > ql0 + gap) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int q_local = 32 * u + 8 * (i >> 2) + 4 * h + (i & 3);
-          const bool keep = !(u == w && 32 * w + r32 > q_local);
-          cv[i] = keep ? c[i] : 0.f;
+          for (int i = 0; i < 16; ++i) {
+            const int q_local = ql0 + 8 * (i >> 2) + 4 * h + (i & 3);
+            cv[i] = 32 * w + r32 > q_local + gap ? 0.f : c[i];
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) cv[i] = c[i];
         }
         const bf16x8_t cop[2] = {pack_bf16x8(&cv[0]), pack_bf16x8(&cv[8])};
 #pragma unroll
@@ -590,6 +639,7 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
   }
 
   // ---- softmax branch
+  const int Wm = W - gap;  // the true window: element masks and sub-tile skipping
   if (issued == 0) {
     issue();
     if (nsteps > 1) issue();
@@ -606,8 +656,8 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
 #pragma unroll
     for (int qs = 0; qs < 2; ++qs) {
       const int qa = s0 + 64 * n + 32 * qs;
-      const bool need = qa + 31 >= ka && qa <= ka + 31 + W - 1;
-      const bool full = qa >= ka + 31 && qa + 31 <= ka + W - 1;
+      const bool need = qa + 31 >= ka && qa <= ka + 31 + Wm - 1;
+      const bool full = qa >= ka + 31 && qa + 31 <= ka + Wm - 1;
       f32x4_t* px = reinterpret_cast<f32x4_t*>(pex + (w * 2 + qs) * 4096 + lane * 16);  // [i4][lane] x 16 bytes
       f32x16_t s = {0};
       float stat[16];
@@ -632,7 +682,7 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
             const unsigned dist0 = (unsigned)(qa + 4 * h - mykey);  // 0 <= query - key < W, one compare per element
 #pragma unroll
             for (int i = 0; i < 16; ++i)
-              s[i] = (dist0 + (unsigned)(8 * (i >> 2) + (i & 3)) < (unsigned)W) ? s[i] : -INFINITY;
+              s[i] = (dist0 + (unsigned)(8 * (i >> 2) + (i & 3)) < (unsigned)Wm) ? s[i] : -INFINITY;
           }
 #pragma unroll
           for (int i = 0; i < 16; ++i) s[i] = fast_exp2(__builtin_fmaf(s[i], a.scale_log2, -stat[i] * LOG2E));
@@ -739,7 +789,7 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
   a.lse = sv.lse; a.delta = ws.delta;
   a.states = (const uint16_t*)sv.states; a.rstates = (const uint16_t*)ws.rstates;
   a.dq = (uint16_t*)dq; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv;
-  a.B = dm.B; a.T = dm.T; a.Hq = dm.Hq; a.Hkv = dm.Hkv; a.G = dm.G; a.W = pl.fwd.W;
+  a.B = dm.B; a.T = dm.T; a.Hq = dm.Hq; a.Hkv = dm.Hkv; a.G = dm.G; a.W = pl.fwd.W; a.gap = pl.fwd.gap;
   a.nstf = pl.fwd.nstf; a.nk = pl.nk; a.ntile = dm.T / 128;
   a.scale = dm.scale; a.scale_log2 = dm.scale * LOG2E;
   a.dO = (const uint16_t*)dO; a.xs = (const uint16_t*)sv.xs; a.xr = (const uint16_t*)sv.xr;

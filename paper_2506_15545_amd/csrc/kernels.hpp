@@ -49,9 +49,10 @@ void generic_bwd(const LayerDims& dm, int dtype, const void* q, const void* k, c
                  const float* gr, const SavedPtrs& sv, const void* dO, void* dq, void* dk, void* dv, float* dgs,
                  float* dgr, const GenericBwdWs& ws, hipStream_t st);
 
-// MFMA forward path (bf16, D = 128, T % 128 == 0, W % 64 == 0 or W >= T)
+// MFMA forward path (bf16, D = 128, T % 128 == 0, any W >= 8)
 struct FastFwdPlan {
-  int W;        // effective window (min(W, T))
+  int W;        // window the tiles and states are laid out for: min(W, T) rounded up to a multiple of 64
+  int gap;      // that minus the true window (0..63): masks and the reach of the intra-chunk part
   int base;     // key position of state 0 (0 or 64); state i sits at base + 128*i
   int nstf;     // number of states per (batch, kv head) = query tiles that have a linear branch
   int nchunks;  // chunk-local products needed to build them

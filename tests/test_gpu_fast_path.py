@@ -1,4 +1,4 @@
-"""GPU parity of the MFMA kernels (bf16, D=128, T % 128 == 0, W % 64 == 0 or W >= T) against the
+"""GPU parity of the MFMA kernels (bf16, D=128, T % 128 == 0, any W) against the
 fp64 oracle, on shapes that span several query tiles, both state alignments (W % 128 == 0 and 64),
 the causal degenerate case and GQA; plus agreement with the general-shape kernels."""
 import math
@@ -33,7 +33,14 @@ CASES = [
     (1, 768, 2, 1, 512),
     (1, 384, 2, 2, 384),     # W == T: causal attention, no linear branch
     (1, 256, 2, 1, 4096),    # W > T
-    (1, 640, 6, 2, 64),      # smallest window
+    (1, 640, 6, 2, 64),      # smallest aligned window
+    (1, 1024, 2, 1, 513),    # window not a multiple of 64: 512 earlier tokens + the current one
+    (1, 384, 3, 1, 100),
+    (2, 256, 2, 2, 8),       # the smallest window the matrix-core path takes
+    (1, 640, 2, 1, 65),
+    (1, 512, 4, 2, 191),
+    (1, 256, 2, 1, 250),     # rounds up to T: linear branch only through the last keys' gap
+    (1, 384, 2, 1, 130),
 ]
 
 
@@ -57,7 +64,8 @@ def test_fast_fwd_matches_oracle(B, T, Hq, Hkv, W):
     xr = saved[off:off + 2 * n].view(torch.bfloat16).view(B, T, Hq, D)
     s_rms = math.sqrt(float(np.mean(ref["xs"] ** 2)))
     assert bf16_err(xs, ref["xs"]) <= 2e-2 * s_rms
-    r_rms = math.sqrt(float(np.mean(ref["xr"] ** 2)))
+    lin_rows = np.any(ref["xr"] != 0, axis=-1)       # rows before the window is full have no linear branch
+    r_rms = math.sqrt(float(np.mean(ref["xr"][lin_rows] ** 2))) if lin_rows.any() else 0.0
     if r_rms > 0:
         assert bf16_err(xr, ref["xr"]) <= 2e-2 * r_rms
     else:
@@ -121,6 +129,13 @@ BWD_CASES = [
     (1, 384, 2, 2, 384),
     (1, 640, 6, 2, 64),
     (1, 896, 2, 1, 320),     # T - W = 576: last key tile of the linear branch is half full
+    (1, 1024, 2, 1, 513),    # windows that are not multiples of 64
+    (1, 384, 3, 1, 100),
+    (2, 256, 2, 2, 10),
+    (1, 640, 2, 1, 65),
+    (1, 512, 4, 2, 191),
+    (1, 256, 2, 1, 250),
+    (1, 384, 2, 1, 130),
 ]
 
 

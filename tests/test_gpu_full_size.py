@@ -75,6 +75,31 @@ def test_layer3b_fwd_bwd_full_size():
             assert emax <= GRAD_TOL_MAX and erms <= GRAD_TOL_RMS, (name, b, g, emax, erms)
 
 
+def test_layer3b_literal_window_513():
+    """The window read literally as 512 earlier tokens plus the current one (W = 513, not a multiple of the
+    64-key tiles): forward and backward of the 3B-shaped layer on the matrix-core kernels, one group checked."""
+    import dataclasses
+    cfg = dataclasses.replace(synth.CONFIGS["layer3b_t4096_w512"], name="layer3b_t4096_w513", W=513)
+    q, k, v, dO = synth.make_layer_inputs(cfg, with_dO=True)
+    print("layer3b, W = 513: forward + backward on the GPU", flush=True)
+    o, saved = run_fwd(cfg, q, k, v, True)
+    rb.rattn_profile_enable(True)
+    dq, dk, dv, _, _ = rb.rattn_bwd(q.cuda(), k.cuda(), v.cuda(), saved, dO.cuda(), cfg.W, softmax_scale=cfg.scale,
+                                    want_dgamma=False)
+    torch.cuda.synchronize()
+    names = [n for n, _ in rb.rattn_profile_records()]
+    rb.rattn_profile_enable(False)
+    assert "bwd_dkv_kernel" in names
+    b, g = 1, 3
+    for _, _, _ in check_fwd_groups(cfg, q, k, v, o, [(b, g)]):
+        print(f"  oracle bwd batch {b} kv-group {g}", flush=True)
+        ref = orc.bwd_dense(np64(group(cfg, q, b, g)), np64(group(cfg, k, b, g)), np64(group(cfg, v, b, g)),
+                            np64(group(cfg, dO, b, g)), cfg.W, scale=cfg.scale)
+        for name, got in (("dq", dq), ("dk", dk), ("dv", dv)):
+            emax, erms = grad_err(group(cfg, got, b, g), ref[name])
+            assert emax <= GRAD_TOL_MAX and erms <= GRAD_TOL_RMS, (name, b, g, emax, erms)
+
+
 _cache = {}
 
 
