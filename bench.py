@@ -8,6 +8,7 @@ products at nominal chunk 64, no recomputation and no masked-tile waste counted.
 Prints ONE JSON line.
 """
 import argparse
+import ctypes
 import dataclasses
 import json
 import math
@@ -253,6 +254,35 @@ def main():
         rb.rattn_profile_enable(False)
         out["prefill_export"] = {"workload": cfg.name, "us": {n_: sum(v_) / len(v_) * 1e3 for n_, v_ in per.items()},
                                  "us_total": sum(sum(v_) / len(v_) for v_ in per.values()) * 1e3}
+
+        # chunked prefill: the second half of the layer's tokens given rings and state after the first half
+        # (reported, not part of `value`); per-kernel averages and the whole call
+        half = cfg.T // 2
+        kr_, vr_, S_ = rb.rattn_prefill_export(k[:, :half].contiguous(), v[:, :half].contiguous(), cfg.W)
+        qh, kh, vh = (t_[:, half:].contiguous() for t_ in (q, k, v))
+        oh = torch.empty_like(qh)
+        pc = rb.make_params(qh, kh, cfg.W, 0, cfg.scale, 1e-6, False)
+        nb_ = ctypes.c_size_t()
+        rb.lib().rattn_prefill_chunk_workspace_bytes(ctypes.byref(pc), half, ctypes.byref(nb_))
+        wsc = torch.empty(nb_.value, dtype=torch.uint8, device="cuda")
+        # every call advances rings and state by `half` tokens in place; the timing does not depend on their values
+        chunk_call = lambda: rb.rattn_prefill_chunk(qh, kh, vh, cfg.W, half, kr_, vr_, S_, softmax_scale=cfg.scale,
+                                                    workspace=wsc, out=oh)
+        for _ in range(3):
+            chunk_call()
+        ms_chunk = timed(chunk_call, 10)
+        rb.rattn_profile_enable(True)
+        for _ in range(5):
+            chunk_call()
+        torch.cuda.synchronize()
+        per = {}
+        for name, ms in rb.rattn_profile_records():
+            per.setdefault(name, []).append(ms)
+        rb.rattn_profile_enable(False)
+        out["prefill_chunk"] = {"workload": f"{cfg.name}: tokens {half}..{cfg.T - 1} after {half}",
+                                "ms": ms_chunk, "tokens_per_s": cfg.B * half / (ms_chunk * 1e-3),
+                                "us": {n_: sum(v_) / len(v_) * 1e3 for n_, v_ in per.items()}}
+        del kr_, vr_, S_, qh, kh, vh, oh, wsc
 
     if not args.no_other_workloads:
         # reported next to the headline (never part of `value`): the 12B-shaped layer and the window

@@ -125,6 +125,25 @@ rattn_status rattn_prefill_export(const rattn_params* p, const void* k, const vo
                                   void* v_ring, float* state, void* workspace, size_t workspace_bytes,
                                   void* stream);
 
+/* Chunked prefill (Sec. 2.1: the window cache; Sec. 2.2 and Eq. 4: the state carried between chunks).  The layer's
+ * forward for tokens pos0 .. pos0 + T - 1 of B sequences whose first pos0 tokens (pos0 >= 0, HOST value, the same
+ * for every sequence) are present only as rings and state, i.e. as rattn_prefill_export / rattn_prefill_chunk /
+ * rattn_decode_step leave them at position pos0.  The result equals rows pos0 .. pos0 + T - 1 of rattn_fwd over the
+ * whole sequence.
+ *   p: B, T (= tokens in this chunk), Hq, Hkv, D, window, chunk, dtype, softmax_scale, rms_eps as for rattn_fwd;
+ *      save_for_bwd is ignored
+ *   q [B,T,Hq,D]; k,v [B,T,Hkv,D]: the chunk; o [B,T,Hq,D]
+ *   k_ring, v_ring [B,Hkv,W,D], state fp32 [B,Hkv,D,D]: read (rings: the last min(pos0, W) tokens; state: only if
+ *      pos0 > W, before that it is zero by definition and the buffer's contents are ignored) and updated in place
+ *      to position pos0 + T (slots of tokens that stay in the window are left as they are)
+ *   workspace: rattn_prefill_chunk_workspace_bytes(p, pos0) bytes of scratch, 16-byte aligned.
+ * The matrix-core kernels are used when dtype = bf16, D = 128, window >= 8 and min(pos0, W) + T is a multiple of
+ * 128; any other shape runs on the general kernels. */
+rattn_status rattn_prefill_chunk_workspace_bytes(const rattn_params* p, int32_t pos0, size_t* bytes);
+rattn_status rattn_prefill_chunk(const rattn_params* p, int32_t pos0, const void* q, const void* k, const void* v,
+                                 const float* gamma_swa, const float* gamma_rla, void* k_ring, void* v_ring,
+                                 float* state, void* o, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Per-kernel timing (tracing aid; off by default).  While enabled, every kernel the library
  * launches is bracketed by a pair of HIP events recorded on the launch stream.  Records pile up
  * until rattn_profile_reset().  rattn_profile_get waits for record `idx` to finish and returns

@@ -15,7 +15,8 @@ RATTN_F32, RATTN_BF16 = 0, 1
 _DTYPES = {torch.float32: RATTN_F32, torch.bfloat16: RATTN_BF16}
 
 EXPORTS = ["rattn_workspace_bytes", "rattn_fwd", "rattn_bwd", "rattn_decode_step",
-           "rattn_prefill_export_workspace_bytes", "rattn_prefill_export", "rattn_probe_mfma",
+           "rattn_prefill_export_workspace_bytes", "rattn_prefill_export",
+           "rattn_prefill_chunk_workspace_bytes", "rattn_prefill_chunk", "rattn_probe_mfma",
            "rattn_status_string", "rattn_last_error", "rattn_version",
            "rattn_profile_enable", "rattn_profile_reset", "rattn_profile_count", "rattn_profile_get"]
 
@@ -64,6 +65,10 @@ def lib():
     L.rattn_prefill_export_workspace_bytes.argtypes = [ctypes.POINTER(RattnParams), ctypes.POINTER(sz)]
     L.rattn_prefill_export.restype = ctypes.c_int
     L.rattn_prefill_export.argtypes = [ctypes.POINTER(RattnParams)] + [vp] * 6 + [sz, vp]
+    L.rattn_prefill_chunk_workspace_bytes.restype = ctypes.c_int
+    L.rattn_prefill_chunk_workspace_bytes.argtypes = [ctypes.POINTER(RattnParams), ctypes.c_int32, ctypes.POINTER(sz)]
+    L.rattn_prefill_chunk.restype = ctypes.c_int
+    L.rattn_prefill_chunk.argtypes = [ctypes.POINTER(RattnParams), ctypes.c_int32] + [vp] * 10 + [sz, vp]
     L.rattn_probe_mfma.restype = ctypes.c_int
     L.rattn_probe_mfma.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double), vp]
     L.rattn_status_string.restype = ctypes.c_char_p
@@ -225,6 +230,34 @@ def rattn_prefill_export(k, v, window, k_ring=None, v_ring=None, state=None):
     _check(lib().rattn_prefill_export(ctypes.byref(p), _ptr(k), _ptr(v), _ptr(k_ring), _ptr(v_ring), _ptr(state),
                                       _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()))
     return k_ring, v_ring, state
+
+
+def rattn_prefill_chunk(q, k, v, window, pos0, k_ring, v_ring, state, gamma_swa=None, gamma_rla=None, chunk=0,
+                        softmax_scale=1.0, rms_eps=1e-6, workspace=None, out=None):
+    """Layer output for tokens pos0 .. pos0+T-1 (q [B,T,Hq,D], k, v [B,T,Hkv,D]) of sequences whose first pos0
+    tokens live in k_ring, v_ring [B,Hkv,W,D] and state [B,Hkv,D,D] fp32; those three are updated in place to
+    position pos0 + T.  Returns o [B,T,Hq,D]."""
+    _check_layer(q, k, v)
+    for name, t in (("k_ring", k_ring), ("v_ring", v_ring), ("state", state)):
+        if not (t.is_cuda and t.is_contiguous()):
+            raise ValueError(f"{name} must be a contiguous device tensor")
+    B, T, Hq, D = q.shape
+    Hkv = k.shape[2]
+    if tuple(k_ring.shape) != (B, Hkv, window, D) or v_ring.shape != k_ring.shape or k_ring.dtype != q.dtype or \
+            v_ring.dtype != q.dtype:
+        raise ValueError("k_ring, v_ring must be [B,Hkv,window,D] in the dtype of q")
+    if tuple(state.shape) != (B, Hkv, D, D) or state.dtype != torch.float32:
+        raise ValueError("state must be fp32 [B,Hkv,D,D]")
+    p = make_params(q, k, window, chunk, softmax_scale, rms_eps, False)
+    nbytes = ctypes.c_size_t()
+    _check(lib().rattn_prefill_chunk_workspace_bytes(ctypes.byref(p), int(pos0), ctypes.byref(nbytes)))
+    if workspace is None:
+        workspace = torch.empty(max(nbytes.value, 16), dtype=torch.uint8, device=q.device)
+    o = torch.empty_like(q) if out is None else out
+    _check(lib().rattn_prefill_chunk(ctypes.byref(p), int(pos0), _ptr(q), _ptr(k), _ptr(v), _ptr(gamma_swa),
+                                     _ptr(gamma_rla), _ptr(k_ring), _ptr(v_ring), _ptr(state), _ptr(o), _ptr(workspace),
+                                     ctypes.c_size_t(workspace.numel()), _stream()))
+    return o
 
 
 def rattn_probe_mfma(sink, iters, blocks):

@@ -157,6 +157,40 @@ rattn::SavedPtrs saved_views(const Layout& L, void* saved) {
   return sv;
 }
 
+// chunked prefill: the forward runs over R ring rows + the chunk's T rows
+struct ChunkLayout {
+  rattn_params p2;
+  Layout L2;
+  int R;
+  size_t kc, vc, qc, oc, saved, fwdws, partial, bytes;
+};
+
+rattn_status make_chunk_layout(const rattn_params* p, int32_t pos0, ChunkLayout* C) {
+  Layout L;
+  rattn_status s = make_layout(p, &L);
+  if (s != RATTN_OK) return s;
+  if (pos0 < 0) return fail(RATTN_ERR_INVALID_ARG, "pos0 must be >= 0 (got %d)", pos0);
+  if ((long long)pos0 + p->T >= (1ll << 31)) return fail(RATTN_ERR_UNSUPPORTED, "pos0 + T must stay below 2^31");
+  C->R = pos0 < p->window ? pos0 : p->window;
+  C->p2 = *p;
+  C->p2.T = C->R + p->T;
+  C->p2.save_for_bwd = 1;
+  s = make_layout(&C->p2, &C->L2);
+  if (s != RATTN_OK) return s;
+  const rattn::LayerDims& dm = C->L2.dm;
+  const size_t nkv = (size_t)dm.B * dm.T * dm.Hkv * dm.D * C->L2.esize, nq = (size_t)dm.B * dm.T * dm.Hq * dm.D * C->L2.esize;
+  size_t off = 0;
+  C->kc = off; off += align_up(nkv);
+  C->vc = off; off += align_up(nkv);
+  C->qc = off; off += align_up(nq);
+  C->oc = off; off += align_up(nq);
+  C->saved = off; off += align_up(C->L2.saved_bytes);
+  C->fwdws = off; off += align_up(C->L2.fwd_bytes);
+  C->partial = off; off += align_up(rattn::export_plan(dm).partial_bytes);
+  C->bytes = off;
+  return RATTN_OK;
+}
+
 rattn_status check_launch(const char* what) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(RATTN_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
@@ -317,6 +351,48 @@ rattn_status rattn_prefill_export(const rattn_params* p, const void* k, const vo
     return fail(RATTN_ERR_WORKSPACE, "prefill export needs %zu workspace bytes, got %zu", need, workspace_bytes);
   rattn::prefill_export(L.dm, p->dtype, k, v, k_ring, v_ring, state, (float*)workspace, (hipStream_t)stream);
   return check_launch("rattn_prefill_export");
+}
+
+rattn_status rattn_prefill_chunk_workspace_bytes(const rattn_params* p, int32_t pos0, size_t* bytes) {
+  ChunkLayout C;
+  rattn_status s = make_chunk_layout(p, pos0, &C);
+  if (s != RATTN_OK) return s;
+  if (bytes) *bytes = C.bytes;
+  return RATTN_OK;
+}
+
+rattn_status rattn_prefill_chunk(const rattn_params* p, int32_t pos0, const void* q, const void* k, const void* v,
+                                 const float* gamma_swa, const float* gamma_rla, void* k_ring, void* v_ring,
+                                 float* state, void* o, void* workspace, size_t workspace_bytes, void* stream) {
+  ChunkLayout C;
+  rattn_status s = make_chunk_layout(p, pos0, &C);
+  if (s != RATTN_OK) return s;
+  if (!q || !k || !v || !o || !k_ring || !v_ring || !state)
+    return fail(RATTN_ERR_INVALID_ARG, "q, k, v, o, k_ring, v_ring, state must be non-NULL");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(k_ring) || !aligned16(v_ring) ||
+      !aligned16(state) || !aligned16(workspace))
+    return fail(RATTN_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+  if (!workspace || workspace_bytes < C.bytes)
+    return fail(RATTN_ERR_WORKSPACE, "chunked prefill needs %zu workspace bytes, got %zu", C.bytes, workspace_bytes);
+  hipStream_t st = (hipStream_t)stream;
+  char* w = (char*)workspace;
+  const rattn::LayerDims& dm = C.L2.dm;
+  rattn::chunk_concat(dm, p->dtype, p->T, C.R, pos0, q, k, v, k_ring, v_ring, w + C.qc, w + C.kc, w + C.vc, st);
+  s = check_launch("rattn_prefill_chunk (gather)");
+  if (s != RATTN_OK) return s;
+  s = rattn_fwd(&C.p2, w + C.qc, w + C.kc, w + C.vc, gamma_swa, gamma_rla, w + C.oc, w + C.saved, w + C.fwdws,
+                C.L2.fwd_bytes, stream);
+  if (s != RATTN_OK) return s;
+  // keys before the ring exist only once more than `window` tokens have been seen; until then the state is zero
+  // by definition and what the caller's buffer holds is not read
+  const bool carried = pos0 > p->window;
+  if (carried)
+    rattn::chunk_fixup(dm, p->dtype, p->T, C.R, w + C.qc, saved_views(C.L2, w + C.saved), state, gamma_swa, gamma_rla, o, st);
+  else
+    rattn::chunk_copy_out(dm, p->dtype, p->T, C.R, w + C.oc, o, st);
+  rattn::prefill_export(dm, p->dtype, w + C.kc, w + C.vc, k_ring, v_ring, state, (float*)(w + C.partial), st,
+                        pos0 - C.R, carried);
+  return check_launch("rattn_prefill_chunk");
 }
 
 rattn_status rattn_probe_mfma(void* sink, int iters, int blocks, double* flops, void* stream) {

@@ -9,10 +9,11 @@ namespace rattn {
 
 namespace {
 
-// ring slot s % W <- row s of k / v for the last min(T, W) tokens.  One thread per 16 bytes.
+// ring slot (tok0 + s) % W <- row s of k / v for the last min(T, W) rows (row s is token tok0 + s of its sequence).
+// One thread per 16 bytes.
 __global__ __launch_bounds__(256) void export_ring_kernel(const uint4* __restrict__ k, const uint4* __restrict__ v,
                                                           uint4* __restrict__ k_ring, uint4* __restrict__ v_ring,
-                                                          int B, int T, int Hkv, int W, int row_vecs) {
+                                                          int B, int T, int Hkv, int W, int row_vecs, int tok0) {
   const int first = max(0, T - W), ntok = T - first;
   const long long total = (long long)B * ntok * Hkv * row_vecs;
   for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
@@ -22,7 +23,7 @@ __global__ __launch_bounds__(256) void export_ring_kernel(const uint4* __restric
     const int s = first + (int)(r % ntok);
     const int b = (int)(r / ntok);
     const size_t src = ((size_t)(b * T + s) * Hkv + g) * row_vecs + c;
-    const size_t dst = (((size_t)b * Hkv + g) * W + s % W) * row_vecs + c;
+    const size_t dst = (((size_t)b * Hkv + g) * W + (tok0 + s) % W) * row_vecs + c;
     k_ring[dst] = k[src];
     v_ring[dst] = v[src];
   }
@@ -86,14 +87,13 @@ __global__ __launch_bounds__(256) void export_state_partial_kernel(const IO* __r
   for (int j = 0; j < NR; ++j) out[(size_t)(rg + RG * j) * CG + cg] = acc[j];
 }
 
-// state[b,g] = sum over segments, in segment order.  One thread per float4.
-__global__ __launch_bounds__(256) void export_state_reduce_kernel(const float4* __restrict__ partial,
-                                                                  float4* __restrict__ state, int nseg, int vecs,
-                                                                  long long total) {
+// state[b,g] = (accumulate ? state[b,g] : 0) + sum over segments, in segment order.  One thread per float4.
+__global__ __launch_bounds__(256) void export_state_reduce_kernel(const float4* __restrict__ partial, float4* state,
+                                                                  int nseg, int vecs, long long total, int accumulate) {
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
   if (i >= total) return;
   const long long bg = i / vecs, e = i % vecs;
-  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 s = accumulate ? state[i] : make_float4(0.f, 0.f, 0.f, 0.f);
   for (int c = 0; c < nseg; ++c) {
     const float4 p = partial[(bg * nseg + c) * vecs + e];
     s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
@@ -116,7 +116,7 @@ ExportPlan export_plan(const LayerDims& dm) {
 }
 
 void prefill_export(const LayerDims& dm, int dtype, const void* k, const void* v, void* k_ring, void* v_ring,
-                    float* state, float* partial, hipStream_t st) {
+                    float* state, float* partial, hipStream_t st, int tok0, bool accumulate) {
   const ExportPlan pl = export_plan(dm);
   const int esize = dtype == 0 ? 4 : 2;
   const int row_vecs = dm.D * esize / 16;
@@ -125,7 +125,7 @@ void prefill_export(const LayerDims& dm, int dtype, const void* k, const void* v
     const int blocks = (int)((total + 255) / 256 < 8192 ? (total + 255) / 256 : 8192);
     ProfScope ps("export_ring_kernel", st);
     export_ring_kernel<<<blocks, 256, 0, st>>>((const uint4*)k, (const uint4*)v, (uint4*)k_ring, (uint4*)v_ring, dm.B,
-                                               dm.T, dm.Hkv, dm.W, row_vecs);
+                                               dm.T, dm.Hkv, dm.W, row_vecs, tok0);
   }
   if (pl.nseg > 0) {
     const dim3 grid(pl.nseg, dm.Hkv, dm.B);
@@ -144,7 +144,7 @@ void prefill_export(const LayerDims& dm, int dtype, const void* k, const void* v
   const long long total = (long long)dm.B * dm.Hkv * vecs;
   ProfScope ps("export_state_reduce_kernel", st);
   export_state_reduce_kernel<<<(int)((total + 255) / 256), 256, 0, st>>>((const float4*)partial, (float4*)state,
-                                                                         pl.nseg, vecs, total);
+                                                                         pl.nseg, vecs, total, accumulate ? 1 : 0);
 }
 
 }  // namespace rattn

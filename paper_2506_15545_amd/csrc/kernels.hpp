@@ -98,8 +98,17 @@ struct ExportPlan {
   size_t partial_bytes;
 };
 ExportPlan export_plan(const LayerDims& dm);
+// Row s of k / v is token tok0 + s of its sequence (ring slots); with `accumulate` the keys that fall out of the
+// window are added to what `state` already holds.
 void prefill_export(const LayerDims& dm, int dtype, const void* k, const void* v, void* k_ring, void* v_ring,
-                    float* state, float* partial, hipStream_t st);
+                    float* state, float* partial, hipStream_t st, int tok0 = 0, bool accumulate = false);
+
+// chunked prefill (see chunk_kernels.hip): dmc describes the concatenated sequence of R ring rows + Tc new rows
+void chunk_concat(const LayerDims& dmc, int dtype, int Tc, int R, int pos0, const void* q, const void* k, const void* v,
+                  const void* k_ring, const void* v_ring, void* qc, void* kc, void* vc, hipStream_t st);
+void chunk_copy_out(const LayerDims& dmc, int dtype, int Tc, int R, const void* oc, void* o, hipStream_t st);
+void chunk_fixup(const LayerDims& dmc, int dtype, int Tc, int R, const void* qc, const SavedPtrs& sv, const float* state,
+                 const float* gs, const float* gr, void* o, hipStream_t st);
 
 // launches the matrix-core probe loop; returns the FLOPs it issues
 double probe_mfma(float* sink, int iters, int blocks, hipStream_t st);

@@ -96,3 +96,24 @@ def test_prefill_export_host_checks():
     # a prompt shorter than the window has no state to build: no scratch needed
     q = params(window=1000)
     assert L.rattn_prefill_export_workspace_bytes(ctypes.byref(q), ctypes.byref(n)) == 0 and n.value == 0
+
+
+def test_prefill_chunk_host_checks():
+    L = rb.lib()
+    p = params()
+    n0, n1 = ctypes.c_size_t(), ctypes.c_size_t()
+    assert L.rattn_prefill_chunk_workspace_bytes(ctypes.byref(p), 0, ctypes.byref(n0)) == 0
+    assert L.rattn_prefill_chunk_workspace_bytes(ctypes.byref(p), 10 * p.window, ctypes.byref(n1)) == 0
+    # with a history the forward also runs over the ring rows: more scratch, and no more than for a full ring
+    assert n1.value > n0.value > 0
+    n2 = ctypes.c_size_t()
+    assert L.rattn_prefill_chunk_workspace_bytes(ctypes.byref(p), p.window, ctypes.byref(n2)) == 0 and n2.value == n1.value
+    assert L.rattn_prefill_chunk_workspace_bytes(ctypes.byref(p), -1, ctypes.byref(n0)) == -1
+    fake = ctypes.c_void_p(4096)  # never dereferenced: the checks below fail first
+    args = [fake] * 3 + [None, None] + [fake] * 4
+    assert L.rattn_prefill_chunk(ctypes.byref(p), 0, *([None] * 9), None, 0, None) == -1
+    st = L.rattn_prefill_chunk(ctypes.byref(p), 0, *args, fake, 16, None)
+    assert st == -3 and b"workspace" in L.rattn_last_error()
+    bad = [ctypes.c_void_p(4100)] + args[1:]
+    st = L.rattn_prefill_chunk(ctypes.byref(p), 0, *bad, fake, 1 << 40, None)
+    assert st == -1 and b"aligned" in L.rattn_last_error()

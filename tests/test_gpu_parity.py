@@ -248,3 +248,57 @@ def test_prefill_then_decode_reproduces_forward_row(dtype, T, W):
                              dev(gs), dev(gr), softmax_scale=scale)
     gmax = max(float(gs.abs().max()), float(gr.abs().max()), 1.0)
     assert maxerr(o, ref) <= TOL[dtype] * gmax
+
+
+@pytest.mark.parametrize("dtype,D,Hq,Hkv,W,chunks", [
+    ("f32", 64, 4, 2, 8, [5, 3, 9, 1, 12]),          # history shorter than, equal to and longer than the window
+    ("f32", 128, 2, 1, 16, [16, 16, 7]),
+    ("f32", 64, 2, 2, 4, [1, 1, 1, 1, 1, 1, 3]),     # single-token chunks = decode steps
+    ("bf16", 128, 4, 2, 128, [128, 256, 128]),       # ring + chunk a multiple of 128: matrix-core kernels
+    ("bf16", 128, 2, 1, 513, [640, 255, 383]),       # the same with a window that is no tile multiple
+    ("bf16", 64, 3, 1, 50, [70, 130]),
+])
+def test_chunked_prefill_reproduces_forward(dtype, D, Hq, Hkv, W, chunks):
+    """A prompt fed in chunks through rattn_prefill_chunk gives the rows of the forward over the whole prompt
+    (oracle, fp64), and leaves the rings and the state the oracle's export gives for the whole prompt."""
+    B, T = 2, sum(chunks)
+    x = synth.make_random_layer(B, T, Hq, Hkv, D, dtype, 4100 + T + W, with_gains=True)
+    scale = 1.0 / math.sqrt(D)
+    gs, gr = x["gamma_swa"], x["gamma_rla"]
+    ref = orc.fwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), W, scale=scale, gamma_swa=np64(gs),
+                        gamma_rla=np64(gr))["o"]
+    kr_ref, vr_ref, S_ref = orc.prefill_export(np64(x["k"]), np64(x["v"]), W)
+    q, k, v = dev(x["q"]), dev(x["k"]), dev(x["v"])
+    kr = torch.zeros(B, Hkv, W, D, dtype=q.dtype, device="cuda")
+    vr = torch.zeros_like(kr)
+    S = torch.full((B, Hkv, D, D), float("nan"), dtype=torch.float32, device="cuda")  # not read before pos0 > W
+    gmax = max(float(gs.abs().max()), float(gr.abs().max()), 1.0)
+    pos0 = 0
+    for n in chunks:
+        print(f"chunked prefill {dtype} D={D} W={W}: tokens {pos0}..{pos0 + n - 1}", flush=True)
+        sl = slice(pos0, pos0 + n)
+        o = rb.rattn_prefill_chunk(q[:, sl].contiguous(), k[:, sl].contiguous(), v[:, sl].contiguous(), W, pos0, kr, vr,
+                                   S, dev(gs), dev(gr), softmax_scale=scale)
+        torch.cuda.synchronize()
+        r = ref[:, sl]
+        e = np.abs(np64(o) - r)
+        if dtype == "bf16":
+            e = np.maximum(e - np.abs(r) / 256.0, 0.0)   # storage rounding of the output
+        assert float(e.max()) <= TOL[dtype] * gmax, (pos0, float(e.max()))
+        pos0 += n
+    assert np.array_equal(np64(kr), kr_ref) and np.array_equal(np64(vr), vr_ref)
+    assert float(np.max(np.abs(np64(S) - S_ref))) <= 2e-5 * max(1.0, float(np.abs(S_ref).max()))
+
+
+def test_chunked_prefill_uses_matrix_core_kernels():
+    B, Hq, Hkv, D, W = 1, 2, 1, 128, 128
+    x = synth.make_random_layer(B, 384, Hq, Hkv, D, "bf16", 4200)
+    q, k, v = dev(x["q"]), dev(x["k"]), dev(x["v"])
+    kr, vr, S = rb.rattn_prefill_export(k[:, :256].contiguous(), v[:, :256].contiguous(), W)
+    rb.rattn_profile_enable(True)
+    rb.rattn_prefill_chunk(q[:, 256:].contiguous(), k[:, 256:].contiguous(), v[:, 256:].contiguous(), W, 256, kr, vr, S,
+                           softmax_scale=0.09)
+    torch.cuda.synchronize()
+    names = [n for n, _ in rb.rattn_profile_records()]
+    rb.rattn_profile_enable(False)
+    assert "fwd_fused_kernel" in names and "chunk_fixup_kernel" in names and "gen_fwd_kernel" not in names
