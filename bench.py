@@ -239,6 +239,22 @@ def main():
                                       "algorithmic_bytes": nbytes}}
 
     if not args.no_decode:
+        # generation step-time model of the paper's inference analysis with MI355X figures (8 TB/s, 2.5 PFLOP/s
+        # bf16), local:global 3:1 stacks, window 512 + state against sliding-window 4096; the measured decode
+        # kernel turns the model's cache term for the local layers into a measured one
+        def stack(layers, hkv, pcount, batch, ctx):
+            swa = rb.rattn_cache_bytes(layers, 4, ctx, 4096, False, hkv, 128, 2)
+            ratt = rb.rattn_cache_bytes(layers, 4, ctx, 512, True, hkv, 128, 2)
+            t0 = rb.rattn_step_time_model(batch, swa, pcount, 2 * pcount, PEAK_HBM, PEAK_BF16_MFMA)
+            t1 = rb.rattn_step_time_model(batch, ratt, pcount, 2 * pcount, PEAK_HBM, PEAK_BF16_MFMA)
+            return {"batch": batch, "ctx": ctx, "swa4096_ms": t0 * 1e3, "rattn512_ms": t1 * 1e3, "gain": 1.0 - t1 / t0}
+        out["step_time_model"] = {
+            "hardware": {"bandwidth_GBps": PEAK_HBM / 1e9, "tflops": PEAK_BF16_MFMA / 1e12},
+            "3B_56layers_4kv": [stack(56, 4, 3e9, b_, c_) for b_ in (1, 128) for c_ in (4096, 32768)],
+            "12B_40layers_8kv": [stack(40, 8, 12e9, b_, c_) for b_ in (1, 128) for c_ in (4096, 32768)],
+            "local_layer_cache_term_us": {"model_at_peak": out["decode"]["step_time_model_us"],
+                                          "measured_kernel": out["decode"]["us_per_step"]}}
+
         # prefill -> decode hand-over on the layer's K/V (one-off per prompt; reported, not part of `value`)
         for _ in range(3):
             rb.rattn_prefill_export(k, v, cfg.W)

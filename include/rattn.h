@@ -144,6 +144,22 @@ rattn_status rattn_prefill_chunk(const rattn_params* p, int32_t pos0, const void
                                  const float* gamma_swa, const float* gamma_rla, void* k_ring, void* v_ring,
                                  float* state, void* o, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Closed forms of the paper's inference analysis (Sec. 4.4), evaluated on the HOST: nothing is launched, every
+ * argument is a host value and the result is written to *out (HOST).
+ *
+ * rattn_cache_bytes: bytes of decode cache one sequence holds in a stack of `layers` token-mixing layers of which
+ * every `global_every`-th is global attention (0 = none) and the others are local with `window` keys: a global
+ * layer keeps ctx tokens, a local one min(ctx, window) tokens, each token 2 * Hkv * D * elem_bytes (key and value),
+ * and a local layer with `with_state` != 0 also one fp32 D x D state per KV head (Sec. 2.2).
+ *
+ * rattn_step_time_model: T_step = batch * cache_bytes / bandwidth + max(2 * batch * param_count / flops,
+ * param_bytes / bandwidth), in seconds (bandwidth in bytes/s, flops in FLOP/s).
+ * Both return RATTN_ERR_INVALID_ARG for NULL out, negative sizes or non-positive rates. */
+rattn_status rattn_cache_bytes(int32_t layers, int32_t global_every, int64_t ctx, int64_t window, int32_t with_state,
+                               int32_t Hkv, int32_t D, int32_t elem_bytes, double* out);
+rattn_status rattn_step_time_model(double batch, double cache_bytes, double param_count, double param_bytes,
+                                   double bandwidth, double flops, double* out);
+
 /* Per-kernel timing (tracing aid; off by default).  While enabled, every kernel the library
  * launches is bracketed by a pair of HIP events recorded on the launch stream.  Records pile up
  * until rattn_profile_reset().  rattn_profile_get waits for record `idx` to finish and returns

@@ -17,6 +17,7 @@ _DTYPES = {torch.float32: RATTN_F32, torch.bfloat16: RATTN_BF16}
 EXPORTS = ["rattn_workspace_bytes", "rattn_fwd", "rattn_bwd", "rattn_decode_step",
            "rattn_prefill_export_workspace_bytes", "rattn_prefill_export",
            "rattn_prefill_chunk_workspace_bytes", "rattn_prefill_chunk", "rattn_probe_mfma",
+           "rattn_cache_bytes", "rattn_step_time_model",
            "rattn_status_string", "rattn_last_error", "rattn_version",
            "rattn_profile_enable", "rattn_profile_reset", "rattn_profile_count", "rattn_profile_get"]
 
@@ -69,6 +70,11 @@ def lib():
     L.rattn_prefill_chunk_workspace_bytes.argtypes = [ctypes.POINTER(RattnParams), ctypes.c_int32, ctypes.POINTER(sz)]
     L.rattn_prefill_chunk.restype = ctypes.c_int
     L.rattn_prefill_chunk.argtypes = [ctypes.POINTER(RattnParams), ctypes.c_int32] + [vp] * 10 + [sz, vp]
+    L.rattn_cache_bytes.restype = ctypes.c_int
+    L.rattn_cache_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                                    ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_double)]
+    L.rattn_step_time_model.restype = ctypes.c_int
+    L.rattn_step_time_model.argtypes = [ctypes.c_double] * 6 + [ctypes.POINTER(ctypes.c_double)]
     L.rattn_probe_mfma.restype = ctypes.c_int
     L.rattn_probe_mfma.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double), vp]
     L.rattn_status_string.restype = ctypes.c_char_p
@@ -258,6 +264,21 @@ def rattn_prefill_chunk(q, k, v, window, pos0, k_ring, v_ring, state, gamma_swa=
                                      _ptr(gamma_rla), _ptr(k_ring), _ptr(v_ring), _ptr(state), _ptr(o), _ptr(workspace),
                                      ctypes.c_size_t(workspace.numel()), _stream()))
     return o
+
+
+def rattn_cache_bytes(layers, global_every, ctx, window, with_state, Hkv, D, elem_bytes):
+    """Decode-cache bytes of one sequence in a local-global stack (host arithmetic, nothing is launched)."""
+    out = ctypes.c_double()
+    _check(lib().rattn_cache_bytes(layers, global_every, ctx, window, 1 if with_state else 0, Hkv, D, elem_bytes,
+                                   ctypes.byref(out)))
+    return out.value
+
+
+def rattn_step_time_model(batch, cache_bytes, param_count, param_bytes, bandwidth, flops):
+    """Theoretical generation step time in seconds (host arithmetic, nothing is launched)."""
+    out = ctypes.c_double()
+    _check(lib().rattn_step_time_model(batch, cache_bytes, param_count, param_bytes, bandwidth, flops, ctypes.byref(out)))
+    return out.value
 
 
 def rattn_probe_mfma(sink, iters, blocks):

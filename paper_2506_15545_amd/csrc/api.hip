@@ -395,6 +395,31 @@ rattn_status rattn_prefill_chunk(const rattn_params* p, int32_t pos0, const void
   return check_launch("rattn_prefill_chunk");
 }
 
+rattn_status rattn_cache_bytes(int32_t layers, int32_t global_every, int64_t ctx, int64_t window, int32_t with_state,
+                               int32_t Hkv, int32_t D, int32_t elem_bytes, double* out) {
+  if (!out) return fail(RATTN_ERR_INVALID_ARG, "out is NULL");
+  if (layers < 0 || global_every < 0 || ctx < 0 || window < 0 || Hkv < 1 || D < 1 || elem_bytes < 1)
+    return fail(RATTN_ERR_INVALID_ARG, "sizes must be non-negative (Hkv, D, elem_bytes positive)");
+  const int n_glob = global_every > 0 ? layers / global_every : 0;
+  const int n_loc = layers - n_glob;
+  const double tok = 2.0 * Hkv * D * elem_bytes;
+  const double loc_tokens = (double)(ctx < window ? ctx : window);
+  const double st = with_state ? (double)Hkv * D * D * 4.0 : 0.0;
+  *out = n_glob * (double)ctx * tok + n_loc * (loc_tokens * tok + st);
+  return RATTN_OK;
+}
+
+rattn_status rattn_step_time_model(double batch, double cache_bytes, double param_count, double param_bytes,
+                                   double bandwidth, double flops, double* out) {
+  if (!out) return fail(RATTN_ERR_INVALID_ARG, "out is NULL");
+  if (!(batch >= 0.0) || !(cache_bytes >= 0.0) || !(param_count >= 0.0) || !(param_bytes >= 0.0))
+    return fail(RATTN_ERR_INVALID_ARG, "batch, cache_bytes, param_count, param_bytes must be >= 0");
+  if (!(bandwidth > 0.0) || !(flops > 0.0)) return fail(RATTN_ERR_INVALID_ARG, "bandwidth and flops must be > 0");
+  const double compute = 2.0 * batch * param_count / flops, weights = param_bytes / bandwidth;
+  *out = batch * cache_bytes / bandwidth + (compute > weights ? compute : weights);
+  return RATTN_OK;
+}
+
 rattn_status rattn_probe_mfma(void* sink, int iters, int blocks, double* flops, void* stream) {
   if (!sink || !aligned16(sink)) return fail(RATTN_ERR_INVALID_ARG, "sink must be a 16-byte aligned device pointer");
   if (iters < 1 || iters > (1 << 24) || blocks < 1 || blocks > (1 << 20))

@@ -117,3 +117,58 @@ def test_prefill_chunk_host_checks():
     bad = [ctypes.c_void_p(4100)] + args[1:]
     st = L.rattn_prefill_chunk(ctypes.byref(p), 0, *bad, fake, 1 << 40, None)
     assert st == -1 and b"aligned" in L.rattn_last_error()
+
+
+def test_inference_closed_forms_match_the_oracle_and_the_text():
+    """rattn_cache_bytes / rattn_step_time_model (host arithmetic) against the oracle's closed forms, and against
+    what the text says: ~56 % cache saving for the 12B stack at 4K context when the local window shrinks from 4K
+    to 1K (Sec. 1), and a step-time gain that grows with the batch towards roughly 60 % and depends on the cache
+    ratio alone, not on the model size, once the cache dominates (Sec. 4.4: window 512 against sliding-window 4K, H100 figures, bf16)."""
+    import random
+    from oracle import rattn_oracle as orc
+    # cache of a local-global stack without state = the oracle's token count times the bytes of a token
+    big = rb.rattn_cache_bytes(40, 4, 4096, 4096, False, 8, 128, 2)
+    small = rb.rattn_cache_bytes(40, 4, 4096, 1024, False, 8, 128, 2)
+    assert abs((1.0 - small / big) - orc.kv_cache_saving(40, 4, 4096, 4096, 1024)) < 1e-12
+    assert abs((1.0 - small / big) - 0.5625) < 1e-12
+    assert big == 40 * 4096 * 2 * 8 * 128 * 2
+    # the fp32 D x D state of a local layer = twice the bf16 window-equivalent of the text's footnote (64 tokens)
+    with_state = rb.rattn_cache_bytes(40, 4, 4096, 1024, True, 8, 128, 2)
+    per_state = (with_state - small) / (30 * 8)
+    assert per_state == 2 * orc.state_equivalent_window(128, 128) * 2 * 128 * 2
+    # a context shorter than the window caps the local layers; no global layers when global_every = 0
+    assert rb.rattn_cache_bytes(8, 0, 100, 512, False, 2, 64, 4) == 8 * 100 * 2 * 2 * 64 * 4
+    rng = random.Random(5)
+    for _ in range(50):
+        a = [rng.uniform(0, 1e3), rng.uniform(0, 1e9), rng.uniform(0, 1e11), rng.uniform(0, 1e11), rng.uniform(1e9, 1e13),
+             rng.uniform(1e12, 1e16)]
+        assert abs(rb.rattn_step_time_model(*a) - orc.decode_step_time(*a)) <= 1e-12 * orc.decode_step_time(*a)
+    # Sec. 4.4 case study: H100 (3.35 TB/s, 989 TFLOP/s dense bf16), 3:1 local:global stacks
+    bw, fl = 3.35e12, 989e12
+    models = {"3B": (56, 4, 3e9), "12B": (40, 8, 12e9)}
+
+    def gain(name, batch, ctx):
+        layers, hkv, pc = models[name]
+        swa = rb.rattn_cache_bytes(layers, 4, ctx, 4096, False, hkv, 128, 2)
+        ratt = rb.rattn_cache_bytes(layers, 4, ctx, 512, True, hkv, 128, 2)
+        t0 = rb.rattn_step_time_model(batch, swa, pc, 2 * pc, bw, fl)
+        t1 = rb.rattn_step_time_model(batch, ratt, pc, 2 * pc, bw, fl)
+        return 1.0 - t1 / t0
+
+    for name in models:
+        g = [gain(name, b, 4096) for b in (1, 8, 64, 512, 4096)]
+        assert all(x <= y for x, y in zip(g, g[1:])) and g[0] < 0.1 < g[2]   # grows with the batch, then saturates
+        assert 0.55 < g[-1] < 0.66                                           # "up to approximately 60 %"
+    # where the cache is all that matters (no parameter terms) the gain is the cache ratio alone, whatever the model
+    lim = {}
+    for name, (layers, hkv, pc) in models.items():
+        swa = rb.rattn_cache_bytes(layers, 4, 4096, 4096, False, hkv, 128, 2)
+        ratt = rb.rattn_cache_bytes(layers, 4, 4096, 512, True, hkv, 128, 2)
+        lim[name] = 1.0 - rb.rattn_step_time_model(1e6, ratt, 0.0, 0.0, bw, fl) / rb.rattn_step_time_model(1e6, swa, 0.0, 0.0, bw, fl)
+        assert gain(name, 4096, 4096) < lim[name]
+    assert abs(lim["3B"] - lim["12B"]) < 1e-12 and abs(lim["3B"] - (1.0 - (3 * 640 + 4096) / (4 * 4096))) < 1e-12
+    assert gain("12B", 4096, 131072) < gain("12B", 4096, 4096)                  # global layers dominate long contexts
+    out = ctypes.c_double()
+    assert rb.lib().rattn_step_time_model(1.0, 1.0, 1.0, 1.0, 0.0, 1.0, ctypes.byref(out)) == -1
+    assert rb.lib().rattn_cache_bytes(4, 4, -1, 8, 0, 1, 64, 2, ctypes.byref(out)) == -1
+    assert rb.lib().rattn_cache_bytes(4, 4, 1, 8, 0, 1, 64, 2, None) == -1
