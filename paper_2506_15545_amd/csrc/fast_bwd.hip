@@ -4,8 +4,8 @@
 // owns key tiles (and visits the G query heads of its KV head in turn); both recompute the attention
 // probabilities from the saved log-sum-exp.
 //
-//   prep : through the two RMS norms (Sec. 3.2): dx_s, dx_r (bf16 MFMA operands), delta = <dx_s, x_s>,
-//          dgamma partials
+//   RMS  : through the two RMS norms (Sec. 3.2), as the prologue of the dq kernel: dx_s, dx_r (bf16 MFMA
+//          operands, also written out for the kernels that follow), delta = <dx_s, x_s>, dgamma partials
 //   states: S_[j] (Eq. 2, kept by the forward pass) and the reverse-time states R_[j] = sum_{later chunks} phi(q)^T dx_r
 //   dq   : transposed, lane = query:  dQ^T = scale * K^T dS^T,  dS = P .* (dP - delta),  dP^T = V dXs^T
 //          linear branch: dphi(Q)^T = S dXr^T + Kf^T (M^T .* (V dXr^T)), then the softmax Jacobian of phi
@@ -26,75 +26,39 @@ struct FastBwdArgs {
   uint16_t *dq, *dk, *dv;
   int B, T, Hq, Hkv, G, W, gap, nstf, nk, ntile;  // W: window rounded up to 64; true window = W - gap
   float scale, scale_log2;
-  // inputs of the RMS-norm backward when the dq kernel does it itself (unit gains); dxs, dxr and delta
-  // above then name the buffers it fills
+  // inputs of the RMS-norm backward in the dq kernel's prologue, which fills dxs, dxr and delta above
   const uint16_t *dO, *xs, *xr;
-  const float *rs, *rr;
+  const float *rs, *rr, *gs, *gr;  // gains: NULL = ones
+  float* dgpart;                   // gain-gradient partials [2][4 * ntile * B][Hq][128], NULL = not wanted
 };
 
 // ------------------------------------------------------------------------------------------------
-// grid (RB, Hq), 256 threads; a wave takes one (b,t) row of head h at a time, lane owns features
-// 2*lane, 2*lane+1.
-__global__ __launch_bounds__(256) void bwd_prep_kernel(const uint16_t* __restrict__ dO, const uint16_t* __restrict__ xs_in,
-                                                       const uint16_t* __restrict__ xr_in, const float* __restrict__ rs_in,
-                                                       const float* __restrict__ rr_in, const float* __restrict__ gs,
-                                                       const float* __restrict__ gr, uint16_t* __restrict__ dxs,
-                                                       uint16_t* __restrict__ dxr, float* __restrict__ delta,
-                                                       float* __restrict__ dgpart, int B, int T, int Hq) {
-  __shared__ float red[2][4][128];
-  const int h = blockIdx.y, RB = gridDim.x, lane = lane_id(), w = wave_id();
-  const int rows = B * T;
-  float g1[2] = {1.f, 1.f}, g2[2] = {1.f, 1.f}, dg1[2] = {0.f, 0.f}, dg2[2] = {0.f, 0.f};
-  if (gs) { g1[0] = gs[h * 128 + 2 * lane]; g1[1] = gs[h * 128 + 2 * lane + 1]; }
-  if (gr) { g2[0] = gr[h * 128 + 2 * lane]; g2[1] = gr[h * 128 + 2 * lane + 1]; }
-  for (int r = blockIdx.x * 4 + w; r < rows; r += RB * 4) {
-    const int b = r / T, t = r % T;
-    const size_t off = ((size_t)r * Hq + h) * 128 + 2 * lane;
-    const size_t so = (size_t)(b * Hq + h) * T + t;
-    const uint32_t udy = *reinterpret_cast<const uint32_t*>(dO + off);
-    const uint32_t uxs = *reinterpret_cast<const uint32_t*>(xs_in + off);
-    const uint32_t uxr = *reinterpret_cast<const uint32_t*>(xr_in + off);
-    const float dy[2] = {__uint_as_float(udy << 16), __uint_as_float(udy & 0xffff0000u)};
-    const float xs[2] = {__uint_as_float(uxs << 16), __uint_as_float(uxs & 0xffff0000u)};
-    const float xr[2] = {__uint_as_float(uxr << 16), __uint_as_float(uxr & 0xffff0000u)};
-    const float r_s = rs_in[so], r_r = rr_in[so];
-    float m1 = 0.f, m2 = 0.f;
-#pragma unroll
-    for (int e = 0; e < 2; ++e) { m1 += g1[e] * dy[e] * xs[e]; m2 += g2[e] * dy[e] * xr[e]; }
-    m1 = wave_sum(m1) * (1.f / 128.f); m2 = wave_sum(m2) * (1.f / 128.f);
-    float a[2], c[2], dl = 0.f;
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-      a[e] = r_s * g1[e] * dy[e] - xs[e] * r_s * r_s * r_s * m1;
-      c[e] = r_r * g2[e] * dy[e] - xr[e] * r_r * r_r * r_r * m2;
-      dl += a[e] * xs[e];
-      dg1[e] += dy[e] * xs[e] * r_s;
-      dg2[e] += dy[e] * xr[e] * r_r;
-    }
-    f32x2_t fa = {a[0], a[1]}, fc = {c[0], c[1]};
-    *reinterpret_cast<bf16x2_t*>(dxs + off) = __builtin_convertvector(fa, bf16x2_t);
-    *reinterpret_cast<bf16x2_t*>(dxr + off) = __builtin_convertvector(fc, bf16x2_t);
-    dl = wave_sum(dl);
-    if (lane == 0) delta[so] = dl;
+// Sums the per-wave gain-gradient partials of the dq kernel's prologue, in a fixed order.  grid (HD / 32, 2),
+// 256 threads: the work-group owns 32 consecutive (head, feature) entries of one of the two gains; thread
+// (rg = tid / 8, c = tid % 8) adds every 32nd partial starting at rg for entries 4c .. 4c+3 (independent 16-byte
+// loads), then the 32 sums are added in order.
+__global__ __launch_bounds__(256) void dgamma_reduce_kernel(const float* __restrict__ dgpart, float* __restrict__ dgs,
+                                                            float* __restrict__ dgr, int RB, int HD) {
+  __shared__ float4 part[32][8];
+  const int which = blockIdx.y, rg = threadIdx.x >> 3, c = threadIdx.x & 7;
+  float* out = which ? dgr : dgs;
+  if (!out) return;
+  const int i = blockIdx.x * 32 + 4 * c;
+  const float* src = dgpart + (size_t)which * RB * HD + i;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 8
+  for (int r = rg; r < RB; r += 32) {
+    const float4 x = *reinterpret_cast<const float4*>(src + (size_t)r * HD);
+    s.x += x.x; s.y += x.y; s.z += x.z; s.w += x.w;
   }
-#pragma unroll
-  for (int e = 0; e < 2; ++e) { red[0][w][2 * lane + e] = dg1[e]; red[1][w][2 * lane + e] = dg2[e]; }
+  part[rg][c] = s;
   __syncthreads();
-  {
-    const int which = threadIdx.x >> 7, d = threadIdx.x & 127;
-    const float s = red[which][0][d] + red[which][1][d] + red[which][2][d] + red[which][3][d];
-    dgpart[((size_t)(which * RB + blockIdx.x) * Hq + h) * 128 + d] = s;
+  if (rg == 0) {
+    float4 t = part[0][c];
+#pragma unroll
+    for (int j = 1; j < 32; ++j) { const float4 x = part[j][c]; t.x += x.x; t.y += x.y; t.z += x.z; t.w += x.w; }
+    *reinterpret_cast<float4*>(out + i) = t;
   }
-}
-
-__global__ void dgamma_reduce_kernel(const float* __restrict__ dgpart, float* __restrict__ dgs, float* __restrict__ dgr,
-                                     int RB, int HD) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= HD) return;
-  float s1 = 0.f, s2 = 0.f;
-  for (int r = 0; r < RB; ++r) { s1 += dgpart[(size_t)r * HD + i]; s2 += dgpart[(size_t)(RB + r) * HD + i]; }
-  if (dgs) dgs[i] = s1;
-  if (dgr) dgr[i] = s2;
 }
 
 // row `src` (128 bf16) re-read in accumulator layout: lane keeps features 32ft + 8*i4 + 4h + e -> x[ft*16 + 4*i4 + e];
@@ -207,17 +171,27 @@ __device__ __forceinline__ float sum16(float x) {
   return x;
 }
 
-// Backward of the two RMS norms (unit gains) for 32 consecutive query rows of one head, by one wave: 16 lanes
-// per row, 8 features each, four rows per pass (row-contiguous 16-byte accesses).  Same arithmetic as
-// bwd_prep_kernel.  Stores d xs, d xr (bf16) and delta = rowsum(d xs * xs) to global memory for the later
-// kernels, and, if `stage` is given, d xr also into rows 0..31 of that LDS tile (swizzled row layout), from
-// where the wave takes it as an MFMA operand without waiting for the global stores.
-__device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, size_t row0_off, size_t qstride, size_t stat0,
-                                             unsigned char* stage, int lane) {
+// Backward of the two RMS norms (Sec. 3.2) for 32 consecutive query rows of one head, by one wave: 16 lanes per row,
+// 8 features each, four rows per pass (row-contiguous 16-byte accesses).  With y = g * x * r, r = rsqrt(mean x^2 +
+// eps):  dx = r g dy - x r^3 mean(g dy x),  dg += dy x r.  Stores d xs, d xr (bf16) and delta = rowsum(d xs * xs)
+// to global memory for the later kernels and, if `stage` is given, d xr also into rows 0..31 of that LDS tile
+// (swizzled row layout), from where the wave takes it as an MFMA operand without waiting for the global stores.
+// GAINS: gains other than one and/or gain gradients; the wave's gradient partials (sums over its 32 rows) go to
+// dgp_s / dgp_r (128 floats each) when those are given.
+template <bool GAINS>
+__device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, int hq, size_t row0_off, size_t qstride, size_t stat0,
+                                             unsigned char* stage, float* dgp_s, float* dgp_r, int lane) {
   const int sub = lane >> 4, c = lane & 15;
   uint16_t* dxs_w = const_cast<uint16_t*>(a.dxs);
   uint16_t* dxr_w = const_cast<uint16_t*>(a.dxr);
   float* delta_w = const_cast<float*>(a.delta);
+  float g1[8], g2[8], dg1[8], dg2[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    g1[e] = (GAINS && a.gs) ? a.gs[hq * 128 + 8 * c + e] : 1.f;
+    g2[e] = (GAINS && a.gr) ? a.gr[hq * 128 + 8 * c + e] : 1.f;
+    dg1[e] = dg2[e] = 0.f;
+  }
 #pragma unroll
   for (int it = 0; it < 8; ++it) {
     const int r = 4 * it + sub;
@@ -229,15 +203,22 @@ __device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, size_t row0_o
     const float r_s = a.rs[stat0 + r], r_r = a.rr[stat0 + r];
     float m1 = 0.f, m2 = 0.f;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { m1 = fmaf(dy[e], xs[e], m1); m2 = fmaf(dy[e], xr[e], m2); }
+    for (int e = 0; e < 8; ++e) {
+      if (GAINS) {
+        dg1[e] = fmaf(dy[e] * xs[e], r_s, dg1[e]);
+        dg2[e] = fmaf(dy[e] * xr[e], r_r, dg2[e]);
+      }
+      m1 = fmaf(g1[e] * dy[e], xs[e], m1);
+      m2 = fmaf(g2[e] * dy[e], xr[e], m2);
+    }
     m1 = sum16(m1) * (1.f / 128.f);
     m2 = sum16(m2) * (1.f / 128.f);
     const float b_s = r_s * r_s * r_s * m1, b_r = r_r * r_r * r_r * m2;
     float av[8], cv[8], dl = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      av[e] = r_s * dy[e] - xs[e] * b_s;
-      cv[e] = r_r * dy[e] - xr[e] * b_r;
+      av[e] = r_s * g1[e] * dy[e] - xs[e] * b_s;
+      cv[e] = r_r * g2[e] * dy[e] - xr[e] * b_r;
       dl = fmaf(av[e], xs[e], dl);
     }
     const bf16x8_t cpk = pack_bf16x8(cv);
@@ -247,9 +228,21 @@ __device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, size_t row0_o
     dl = sum16(dl);
     if (c == 0) delta_w[stat0 + r] = dl;
   }
+  if (GAINS && dgp_s) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      dg1[e] += __shfl_xor(dg1[e], 16, 64); dg1[e] += __shfl_xor(dg1[e], 32, 64);
+      dg2[e] += __shfl_xor(dg2[e], 16, 64); dg2[e] += __shfl_xor(dg2[e], 32, 64);
+    }
+    if (sub == 0) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { dgp_s[8 * c + e] = dg1[e]; dgp_r[8 * c + e] = dg2[e]; }
+    }
+  }
 }
 
-template <bool FUSED_PREP>
+// GAINS: RMS gains other than one and/or gain gradients (see rms_bwd_rows)
+template <bool GAINS>
 __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
   __shared__ __align__(16) unsigned char smem[65536];
   const int lane = lane_id(), w = wave_id();
@@ -275,9 +268,18 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
 
   const int j0 = t0 - W, gap = a.gap;
   const bool has_lin = j0 > -128 || (gap > 0 && j0 == -128);
-  if (FUSED_PREP)
-    rms_bwd_rows(a, qtile_off + (size_t)(32 * w) * qstride, qstride, stat_off - r32,
-                 has_lin ? smem + 32 * w * ROW_BYTES : nullptr, lane);
+  {
+    // RMS-norm backward of this wave's 32 rows first: everything below starts from d xs, d xr and delta
+    float* dgp_s = nullptr;
+    float* dgp_r = nullptr;
+    if (GAINS && a.dgpart) {
+      const int rb = ((b * a.ntile + qt) << 2) + w;  // one partial per wave: [2][4 * ntile * B][Hq][128]
+      dgp_s = a.dgpart + ((size_t)rb * Hq + hq) * 128;
+      dgp_r = dgp_s + (size_t)4 * a.ntile * a.B * Hq * 128;
+    }
+    rms_bwd_rows<GAINS>(a, hq, qtile_off + (size_t)(32 * w) * qstride, qstride, stat_off - r32,
+                        has_lin ? smem + 32 * w * ROW_BYTES : nullptr, dgp_s, dgp_r, lane);
+  }
   bf16x8_t qop[8];
   load_bop(a.q + myrow_off, h, qop);
   f32x16_t acc[4] = {{0}, {0}, {0}, {0}};
@@ -291,15 +293,11 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
     const bool has_state = j0 >= 0, has_res = j0 > -128;
     const int u_hi = w + ((31 + gap) >> 5);
     bf16x8_t dxrop[8];
-    if (FUSED_PREP) {
-      // own rows, staged by this wave: LDS executes a wave's accesses in order, and the reads are complete
-      // before the tile loads below may overwrite the rows
+    // own rows, staged by this wave in the prologue: LDS executes a wave's accesses in order, and the reads are
+    // complete before the tile loads below may overwrite the rows
 #pragma unroll
-      for (int c = 0; c < 8; ++c) dxrop[c] = lds_row(smem, lo, 32 * w, c);
-      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
-    } else {
-      load_bop(a.dxr + myrow_off, h, dxrop);
-    }
+    for (int c = 0; c < 8; ++c) dxrop[c] = lds_row(smem, lo, 32 * w, c);
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
     // key sub-tile u (keys j0 + 32u .. +31): dC = V dXr^T, masked, then d phi(q)^T += phi(K)^T dC
     auto intra_unit = [&](const unsigned char* kt, const unsigned char* vt, int ks, int u) {
       f32x16_t c = {0};
@@ -367,9 +365,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
   }
 
   // ---- softmax branch
-  // With the fused RMS backward the wave reads back d xs and delta of its own rows: its stores are complete
-  // after a full vector-memory wait (the linear branch has had several), and the vector cache is the wave's own.
-  if (FUSED_PREP && !has_lin) wait_vmem();
+  // The wave reads back d xs and delta of its own rows: its stores are complete after a full vector-memory wait
+  // (the linear branch has had several), and the vector cache is the wave's own.
+  if (!has_lin) wait_vmem();
   bf16x8_t dxsop[8];
   load_bop(a.dxs + myrow_off, h, dxsop);
   const float lse2 = a.lse[stat_off] * LOG2E;
@@ -760,7 +758,7 @@ FastBwdPlan fast_bwd_plan(const LayerDims& dm) {
   const int nch = p.fwd.nchunks > p.nk - 1 ? p.fwd.nchunks : p.nk - 1;
   p.u_bytes = (size_t)dm.B * dm.Hkv * (nch > 0 ? nch : 0) * 16384 * 4;
   p.rstate_bytes = (size_t)dm.B * dm.Hkv * p.nk * 16384 * 2;
-  p.RB = 512;
+  p.RB = 4 * (dm.T / 128) * dm.B;  // one gain-gradient partial per wave of the dq kernel
   return p;
 }
 
@@ -768,21 +766,9 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
               const SavedPtrs& sv, const void* dO, void* dq, void* dk, void* dv, float* dgs, float* dgr,
               const FastBwdWs& ws, hipStream_t st) {
   const FastBwdPlan pl = fast_bwd_plan(dm);
-  // With unit gains and no gain gradients asked for, the RMS-norm backward runs inside the dq kernel (each wave
-  // on its own rows) and the separate pass over dO, xs and xr is dropped.
-  const bool fused_prep = !gs && !gr && !dgs && !dgr;
-  if (!fused_prep) {
-    {
-      ProfScope ps("bwd_prep_kernel", st);
-      bwd_prep_kernel<<<dim3(pl.RB, dm.Hq), 256, 0, st>>>((const uint16_t*)dO, (const uint16_t*)sv.xs,
-                                                          (const uint16_t*)sv.xr, sv.rs, sv.rr, gs, gr, (uint16_t*)ws.dxs,
-                                                          (uint16_t*)ws.dxr, ws.delta, ws.dgpart, dm.B, dm.T, dm.Hq);
-    }
-    if (dgs || dgr) {
-      const int HD = dm.Hq * 128;
-      dgamma_reduce_kernel<<<(HD + 255) / 256, 256, 0, st>>>(ws.dgpart, dgs, dgr, pl.RB, HD);
-    }
-  }
+  // The RMS-norm backward runs as the prologue of the dq kernel (each wave on its own rows); the variant with
+  // gains also leaves per-wave partials of the gain gradients, summed afterwards in a fixed order.
+  const bool gains = gs || gr || dgs || dgr;
   FastBwdArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
   a.dxs = (const uint16_t*)ws.dxs; a.dxr = (const uint16_t*)ws.dxr;
@@ -793,11 +779,17 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
   a.nstf = pl.fwd.nstf; a.nk = pl.nk; a.ntile = dm.T / 128;
   a.scale = dm.scale; a.scale_log2 = dm.scale * LOG2E;
   a.dO = (const uint16_t*)dO; a.xs = (const uint16_t*)sv.xs; a.xr = (const uint16_t*)sv.xr;
-  a.rs = sv.rs; a.rr = sv.rr;
+  a.rs = sv.rs; a.rr = sv.rr; a.gs = gs; a.gr = gr;
+  a.dgpart = (dgs || dgr) ? ws.dgpart : nullptr;
   {
     ProfScope ps("bwd_dq_kernel", st);
-    if (fused_prep) bwd_dq_kernel<true><<<dim3(a.ntile * dm.Hq * dm.B), 256, 0, st>>>(a);
+    if (gains) bwd_dq_kernel<true><<<dim3(a.ntile * dm.Hq * dm.B), 256, 0, st>>>(a);
     else bwd_dq_kernel<false><<<dim3(a.ntile * dm.Hq * dm.B), 256, 0, st>>>(a);
+  }
+  if (dgs || dgr) {
+    const int HD = dm.Hq * 128;
+    ProfScope ps("dgamma_reduce_kernel", st);
+    dgamma_reduce_kernel<<<dim3(HD / 32, 2), 256, 0, st>>>(ws.dgpart, dgs, dgr, pl.RB, HD);
   }
   rla_reverse_states(dm, pl.fwd.W, pl.nk, q, ws.dxr, ws.U, ws.rstates, st);
   static const hipError_t lds_attr = hipFuncSetAttribute(

@@ -392,14 +392,20 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) vals[dt][i] = __builtin_fmaf(rr_val, xr[dt][i], (float)ys[dt][i >> 1][i & 1]);
     } else {
+      // the head's two gain rows go through LDS (free since the last barrier; the store below uses [0, 32K))
+      float* gl = reinterpret_cast<float*>(smem + 32768);
+      if (threadIdx.x < 128) {
+        gl[threadIdx.x] = a.gs ? a.gs[hq * 128 + threadIdx.x] : 1.f;
+        gl[128 + threadIdx.x] = a.gr ? a.gr[hq * 128 + threadIdx.x] : 1.f;
+      }
+      __syncthreads();
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
           const int d0 = 32 * dt + 8 * i4 + 4 * h;
-          float4 g1 = make_float4(1.f, 1.f, 1.f, 1.f), g2 = g1;
-          if (a.gs) g1 = *reinterpret_cast<const float4*>(a.gs + hq * 128 + d0);
-          if (a.gr) g2 = *reinterpret_cast<const float4*>(a.gr + hq * 128 + d0);
+          const float4 g1 = *reinterpret_cast<const float4*>(gl + d0);
+          const float4 g2 = *reinterpret_cast<const float4*>(gl + 128 + d0);
           const float ga[4] = {g1.x, g1.y, g1.z, g1.w}, gb[4] = {g2.x * rr_val, g2.y * rr_val, g2.z * rr_val, g2.w * rr_val};
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
