@@ -138,7 +138,7 @@ rattn_status rattn_prefill_export(const rattn_params* p, const void* k, const vo
  *      to position pos0 + T (slots of tokens that stay in the window are left as they are)
  *   workspace: rattn_prefill_chunk_workspace_bytes(p, pos0) bytes of scratch, 16-byte aligned.
  * The matrix-core kernels are used when dtype = bf16, D = 128, window >= 8 and min(pos0, W) + T is a multiple of
- * 128; any other shape runs on the general kernels. */
+ * 128 or at least 1024; any other shape runs on the general kernels. */
 rattn_status rattn_prefill_chunk_workspace_bytes(const rattn_params* p, int32_t pos0, size_t* bytes);
 rattn_status rattn_prefill_chunk(const rattn_params* p, int32_t pos0, const void* q, const void* k, const void* v,
                                  const float* gamma_swa, const float* gamma_rla, void* k_ring, void* v_ring,

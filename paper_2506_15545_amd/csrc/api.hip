@@ -44,8 +44,16 @@ rattn_status fail(rattn_status s, const char* fmt, ...) {
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
+// Sequence lengths from this size on that are not a multiple of 128 run on the matrix-core kernels through
+// zero-padded copies (bf16, D = 128); shorter ones stay on the general kernels, where the copies would not pay.
+constexpr int PAD_MIN_T = 1024;
+
 struct Layout {
   rattn::LayerDims dm;
+  rattn::LayerDims dmf;  // what the matrix-core kernels see: dm with T rounded up to 128 when `pad`
+  bool pad;
+  size_t pf_q, pf_k, pf_v, pf_o;                          // padded copies, forward workspace
+  size_t pb_q, pb_k, pb_v, pb_dO, pb_dq, pb_dk, pb_dv;    // padded copies, backward workspace
   size_t esize;
   // saved
   size_t sv_xs, sv_xr, sv_lse, sv_rs, sv_rr, sv_states, saved_bytes;
@@ -92,17 +100,25 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
   dm.scale = p->softmax_scale; dm.eps = p->rms_eps;
   L->esize = p->dtype == RATTN_F32 ? 4 : 2;
 
+  L->dmf = dm;
+  L->pad = p->dtype == RATTN_BF16 && dm.D == 128 && dm.T % 128 != 0 && dm.T >= PAD_MIN_T;
+  if (L->pad) L->dmf.T = (dm.T + 127) / 128 * 128;
+  const rattn::LayerDims& dmf = L->dmf;
+  L->fast_fwd = rattn::fast_fwd_supported(dmf, p->dtype);
+  if (!L->fast_fwd) { L->pad = false; L->dmf = dm; }
+  // `saved` is sized for the padded length (the general kernels, if forced, use the front of each part)
   const size_t nq = (size_t)dm.B * dm.T * dm.Hq * dm.D;
   const size_t nrow = (size_t)dm.B * dm.Hq * dm.T;
+  const size_t nq_f = (size_t)dmf.B * dmf.T * dmf.Hq * dmf.D, nkv_f = (size_t)dmf.B * dmf.T * dmf.Hkv * dmf.D;
+  const size_t nrow_f = (size_t)dmf.B * dmf.Hq * dmf.T;
   size_t off = 0;
-  L->sv_xs = off; off += align_up(nq * L->esize);
-  L->sv_xr = off; off += align_up(nq * L->esize);
-  L->sv_lse = off; off += align_up(nrow * 4);
-  L->sv_rs = off; off += align_up(nrow * 4);
-  L->sv_rr = off; off += align_up(nrow * 4);
-  L->fast_fwd = rattn::fast_fwd_supported(dm, p->dtype);
+  L->sv_xs = off; off += align_up(nq_f * L->esize);
+  L->sv_xr = off; off += align_up(nq_f * L->esize);
+  L->sv_lse = off; off += align_up(nrow_f * 4);
+  L->sv_rs = off; off += align_up(nrow_f * 4);
+  L->sv_rr = off; off += align_up(nrow_f * 4);
   L->sv_states = off;
-  if (L->fast_fwd) off += align_up(rattn::fast_fwd_plan(dm).state_bytes);
+  if (L->fast_fwd) off += align_up(rattn::fast_fwd_plan(dmf).state_bytes);
   L->saved_bytes = off;
 
   const size_t nstate = (size_t)dm.B * dm.Hkv * dm.nst * dm.D * dm.D;
@@ -122,22 +138,38 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
 
   L->ff_u = L->ff_states = L->fast_fwd_bytes = 0;
   if (L->fast_fwd) {
-    const rattn::FastFwdPlan pl = rattn::fast_fwd_plan(dm);
-    L->ff_u = 0;
-    L->ff_states = align_up(pl.u_bytes);
-    L->fast_fwd_bytes = L->ff_states + align_up(pl.state_bytes);
+    const rattn::FastFwdPlan pl = rattn::fast_fwd_plan(dmf);
+    off = 0;
+    L->ff_u = off; off += align_up(pl.u_bytes);
+    L->ff_states = off; off += align_up(pl.state_bytes);
+    if (L->pad) {
+      L->pf_q = off; off += align_up(nq_f * 2);
+      L->pf_k = off; off += align_up(nkv_f * 2);
+      L->pf_v = off; off += align_up(nkv_f * 2);
+      L->pf_o = off; off += align_up(nq_f * 2);
+    }
+    L->fast_fwd_bytes = off;
   }
   L->fast_bwd_bytes = 0;
   if (L->fast_fwd) {
-    const rattn::FastBwdPlan bp = rattn::fast_bwd_plan(dm);
+    const rattn::FastBwdPlan bp = rattn::fast_bwd_plan(dmf);
     off = 0;
-    L->fb_dxs = off; off += align_up(nq * 2);
-    L->fb_dxr = off; off += align_up(nq * 2);
-    L->fb_delta = off; off += align_up(nrow * 8);  // delta, then log-sum-exp in log2 units
+    L->fb_dxs = off; off += align_up(nq_f * 2);
+    L->fb_dxr = off; off += align_up(nq_f * 2);
+    L->fb_delta = off; off += align_up(nrow_f * 8);  // delta, then log-sum-exp in log2 units
     L->fb_u = off; off += align_up(bp.u_bytes);
     L->fb_states = off; off += align_up(bp.fwd.state_bytes);
     L->fb_rstates = off; off += align_up(bp.rstate_bytes);
-    L->fb_dgpart = off; off += align_up((size_t)2 * bp.RB * dm.Hq * dm.D * 4);
+    L->fb_dgpart = off; off += align_up((size_t)2 * bp.RB * dmf.Hq * dmf.D * 4);
+    if (L->pad) {
+      L->pb_q = off; off += align_up(nq_f * 2);
+      L->pb_k = off; off += align_up(nkv_f * 2);
+      L->pb_v = off; off += align_up(nkv_f * 2);
+      L->pb_dO = off; off += align_up(nq_f * 2);
+      L->pb_dq = off; off += align_up(nq_f * 2);
+      L->pb_dk = off; off += align_up(nkv_f * 2);
+      L->pb_dv = off; off += align_up(nkv_f * 2);
+    }
     L->fast_bwd_bytes = off;
   }
   // the general-shape kernels stay selectable (RATTN_FORCE_GENERIC=1), so size for both
@@ -259,10 +291,21 @@ rattn_status rattn_fwd(const rattn_params* p, const void* q, const void* k, cons
     return fail(RATTN_ERR_WORKSPACE, "forward needs %zu workspace bytes, got %zu", L.fwd_bytes, workspace_bytes);
   hipStream_t st = (hipStream_t)stream;
   rattn::SavedPtrs sv = saved_views(L, p->save_for_bwd ? saved : nullptr);
-  if (L.fast_fwd && !force_generic())
-    rattn::fast_fwd(L.dm, q, k, v, gamma_swa, gamma_rla, o, sv, (float*)((char*)workspace + L.ff_u),
-                    sv.states ? sv.states : (void*)((char*)workspace + L.ff_states), st);
-  else
+  if (L.fast_fwd && !force_generic()) {
+    char* w = (char*)workspace;
+    const void *qf = q, *kf = k, *vf = v;
+    void* of = o;
+    const size_t qrow = (size_t)L.dm.Hq * L.dm.D * 2, kvrow = (size_t)L.dm.Hkv * L.dm.D * 2;
+    if (L.pad) {
+      rattn::pad_rows(q, w + L.pf_q, L.dm.B, L.dm.T, L.dmf.T, qrow, st);
+      rattn::pad_rows(k, w + L.pf_k, L.dm.B, L.dm.T, L.dmf.T, kvrow, st);
+      rattn::pad_rows(v, w + L.pf_v, L.dm.B, L.dm.T, L.dmf.T, kvrow, st);
+      qf = w + L.pf_q; kf = w + L.pf_k; vf = w + L.pf_v; of = w + L.pf_o;
+    }
+    rattn::fast_fwd(L.dmf, qf, kf, vf, gamma_swa, gamma_rla, of, sv, (float*)(w + L.ff_u),
+                    sv.states ? sv.states : (void*)(w + L.ff_states), st);
+    if (L.pad) rattn::unpad_rows(of, o, L.dm.B, L.dm.T, L.dmf.T, qrow, st);
+  } else
     rattn::generic_fwd(L.dm, p->dtype, q, k, v, gamma_swa, gamma_rla, o, sv, (float*)((char*)workspace + L.gf_states), st);
   return check_launch("rattn_fwd");
 }
@@ -287,7 +330,20 @@ rattn_status rattn_bwd(const rattn_params* p, const void* q, const void* k, cons
     rattn::FastBwdWs fw;
     fw.dxs = w + L.fb_dxs; fw.dxr = w + L.fb_dxr; fw.delta = (float*)(w + L.fb_delta); fw.U = (float*)(w + L.fb_u);
     fw.states = w + L.fb_states; fw.rstates = w + L.fb_rstates; fw.dgpart = (float*)(w + L.fb_dgpart);
-    rattn::fast_bwd(L.dm, q, k, v, gamma_swa, gamma_rla, sv, dO, dq, dk, dv, dgamma_swa, dgamma_rla, fw, st);
+    const size_t qrow = (size_t)L.dm.Hq * L.dm.D * 2, kvrow = (size_t)L.dm.Hkv * L.dm.D * 2;
+    if (L.pad) {
+      rattn::pad_rows(q, w + L.pb_q, L.dm.B, L.dm.T, L.dmf.T, qrow, st);
+      rattn::pad_rows(k, w + L.pb_k, L.dm.B, L.dm.T, L.dmf.T, kvrow, st);
+      rattn::pad_rows(v, w + L.pb_v, L.dm.B, L.dm.T, L.dmf.T, kvrow, st);
+      rattn::pad_rows(dO, w + L.pb_dO, L.dm.B, L.dm.T, L.dmf.T, qrow, st);
+      rattn::fast_bwd(L.dmf, w + L.pb_q, w + L.pb_k, w + L.pb_v, gamma_swa, gamma_rla, sv, w + L.pb_dO, w + L.pb_dq,
+                      w + L.pb_dk, w + L.pb_dv, dgamma_swa, dgamma_rla, fw, st);
+      rattn::unpad_rows(w + L.pb_dq, dq, L.dm.B, L.dm.T, L.dmf.T, qrow, st);
+      rattn::unpad_rows(w + L.pb_dk, dk, L.dm.B, L.dm.T, L.dmf.T, kvrow, st);
+      rattn::unpad_rows(w + L.pb_dv, dv, L.dm.B, L.dm.T, L.dmf.T, kvrow, st);
+    } else {
+      rattn::fast_bwd(L.dm, q, k, v, gamma_swa, gamma_rla, sv, dO, dq, dk, dv, dgamma_swa, dgamma_rla, fw, st);
+    }
     return check_launch("rattn_bwd");
   }
   rattn::GenericBwdWs ws;
@@ -387,7 +443,8 @@ rattn_status rattn_prefill_chunk(const rattn_params* p, int32_t pos0, const void
   // by definition and what the caller's buffer holds is not read
   const bool carried = pos0 > p->window;
   if (carried)
-    rattn::chunk_fixup(dm, p->dtype, p->T, C.R, w + C.qc, saved_views(C.L2, w + C.saved), state, gamma_swa, gamma_rla, o, st);
+    rattn::chunk_fixup(dm, p->dtype, p->T, C.R, (C.L2.fast_fwd && !force_generic()) ? C.L2.dmf.T : dm.T, w + C.qc,
+                       saved_views(C.L2, w + C.saved), state, gamma_swa, gamma_rla, o, st);
   else
     rattn::chunk_copy_out(dm, p->dtype, p->T, C.R, w + C.oc, o, st);
   rattn::prefill_export(dm, p->dtype, w + C.kc, w + C.vc, k_ring, v_ring, state, (float*)(w + C.partial), st,

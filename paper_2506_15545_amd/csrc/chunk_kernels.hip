@@ -68,13 +68,14 @@ __global__ __launch_bounds__(256) void chunk_copy_out_kernel(const uint4* __rest
 // New rows with the carried state added to the linear branch.  grid (ceil(Tc / 64), Hq, B), 256 threads: the
 // work-group stages S0[b, g] (fp32 [feature][value]) in LDS, every wave takes 16 rows, a lane owns value columns
 // lane and lane + 64.  Per row: phi(q) (softmax over the D features), x_r = x_r(saved) + phi(q) S0, second RMS
-// recomputed, o = gs * x_s * r_s + gr * x_r * r_r (Sec. 3.2) with x_s, r_s as the forward saved them.
+// recomputed, o = gs * x_s * r_s + gr * x_r * r_r (Sec. 3.2) with x_s, r_s as the forward saved them (in tensors of
+// Ls >= R + Tc rows per sequence: the forward may have run on a zero-padded copy).
 template <typename IO, int D>
 __global__ __launch_bounds__(256) void chunk_fixup_kernel(const IO* __restrict__ qc, const IO* __restrict__ xs,
                                                           const IO* __restrict__ xr, const float* __restrict__ rs,
                                                           const float* __restrict__ state, const float* __restrict__ gs,
                                                           const float* __restrict__ gr, IO* __restrict__ o, int Tc, int R,
-                                                          int Hq, int Hkv, float eps) {
+                                                          int Ls, int Hq, int Hkv, float eps) {
   constexpr int NE = D / 64;  // elements per lane
   extern __shared__ __align__(16) float s0[];  // [D][D]
   const int hq = blockIdx.y, b = blockIdx.z, G = Hq / Hkv, g = hq / G;
@@ -95,7 +96,8 @@ __global__ __launch_bounds__(256) void chunk_fixup_kernel(const IO* __restrict__
   for (int i = 0; i < 16; ++i) {
     const int t = blockIdx.x * 64 + w * 16 + i;
     if (t >= Tc) break;
-    const size_t roff = ((size_t)(b * L + R + t) * Hq + hq) * D;
+    const size_t roff = ((size_t)(b * L + R + t) * Hq + hq) * D;    // row of the concatenated queries
+    const size_t soff = ((size_t)(b * Ls + R + t) * Hq + hq) * D;   // the same row in the saved tensors
     float x[NE];
 #pragma unroll
     for (int e = 0; e < NE; ++e) x[e] = io_traits<IO>::ld(qc + roff + lane + 64 * e);
@@ -111,7 +113,7 @@ __global__ __launch_bounds__(256) void chunk_fixup_kernel(const IO* __restrict__
     for (int e = 0; e < NE; ++e) x[e] *= inv;
     float acc[NE];
 #pragma unroll
-    for (int e = 0; e < NE; ++e) acc[e] = io_traits<IO>::ld(xr + roff + lane + 64 * e);
+    for (int e = 0; e < NE; ++e) acc[e] = io_traits<IO>::ld(xr + soff + lane + 64 * e);
 #pragma unroll
     for (int fe = 0; fe < NE; ++fe) {
       for (int fl = 0; fl < 64; ++fl) {
@@ -125,11 +127,11 @@ __global__ __launch_bounds__(256) void chunk_fixup_kernel(const IO* __restrict__
 #pragma unroll
     for (int e = 0; e < NE; ++e) ss += acc[e] * acc[e];
     const float r_r = rsqrtf(wave_sum(ss) * (1.f / D) + eps);
-    const float r_s = rs[((size_t)b * Hq + hq) * L + R + t];
+    const float r_s = rs[((size_t)b * Hq + hq) * Ls + R + t];
     const size_t ooff = ((size_t)(b * Tc + t) * Hq + hq) * D;
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
-      const float a = io_traits<IO>::ld(xs + roff + lane + 64 * e);
+      const float a = io_traits<IO>::ld(xs + soff + lane + 64 * e);
       io_traits<IO>::st(o + ooff + lane + 64 * e, g1[e] * a * r_s + g2[e] * acc[e] * r_r);
     }
   }
@@ -246,10 +248,10 @@ void chunk_copy_out(const LayerDims& dmc, int dtype, int Tc, int R, const void* 
   chunk_copy_out_kernel<<<blocks, 256, 0, st>>>((const uint4*)oc, (uint4*)o, dmc.B, Tc, R, rv);
 }
 
-void chunk_fixup(const LayerDims& dmc, int dtype, int Tc, int R, const void* qc, const SavedPtrs& sv, const float* state,
-                 const float* gs, const float* gr, void* o, hipStream_t st) {
+void chunk_fixup(const LayerDims& dmc, int dtype, int Tc, int R, int Ls, const void* qc, const SavedPtrs& sv,
+                 const float* state, const float* gs, const float* gr, void* o, hipStream_t st) {
   ProfScope ps("chunk_fixup_kernel", st);
-  if (dtype == 1 && dmc.D == 128 && dmc.T % 128 == 0) {
+  if (dtype == 1 && dmc.D == 128 && dmc.T % 128 == 0 && Ls == dmc.T) {
     const dim3 tiles(dmc.T / 128 - R / 128, dmc.Hq, dmc.B);
     chunk_fixup_mfma_kernel<<<tiles, 256, 0, st>>>((const uint16_t*)qc, (const uint16_t*)sv.xs, (const uint16_t*)sv.xr, sv.rs,
                                                    state, gs, gr, (uint16_t*)o, Tc, R, dmc.Hq, dmc.Hkv, dmc.eps);
@@ -259,7 +261,7 @@ void chunk_fixup(const LayerDims& dmc, int dtype, int Tc, int R, const void* qc,
   const size_t lds = (size_t)dmc.D * dmc.D * sizeof(float);
 #define RATTN_FIXUP(IO, DD)                                                                                          \
   chunk_fixup_kernel<IO, DD><<<grid, 256, lds, st>>>((const IO*)qc, (const IO*)sv.xs, (const IO*)sv.xr, sv.rs, state, gs, \
-                                                     gr, (IO*)o, Tc, R, dmc.Hq, dmc.Hkv, dmc.eps)
+                                                     gr, (IO*)o, Tc, R, Ls, dmc.Hq, dmc.Hkv, dmc.eps)
   if (dtype == 0) {
     if (dmc.D == 64) RATTN_FIXUP(float, 64); else RATTN_FIXUP(float, 128);
   } else {

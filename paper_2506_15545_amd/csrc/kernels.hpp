@@ -107,8 +107,13 @@ void prefill_export(const LayerDims& dm, int dtype, const void* k, const void* v
 void chunk_concat(const LayerDims& dmc, int dtype, int Tc, int R, int pos0, const void* q, const void* k, const void* v,
                   const void* k_ring, const void* v_ring, void* qc, void* kc, void* vc, hipStream_t st);
 void chunk_copy_out(const LayerDims& dmc, int dtype, int Tc, int R, const void* oc, void* o, hipStream_t st);
-void chunk_fixup(const LayerDims& dmc, int dtype, int Tc, int R, const void* qc, const SavedPtrs& sv, const float* state,
-                 const float* gs, const float* gr, void* o, hipStream_t st);
+// Ls: rows per sequence of the saved tensors (> R + Tc when the forward ran on a zero-padded copy)
+void chunk_fixup(const LayerDims& dmc, int dtype, int Tc, int R, int Ls, const void* qc, const SavedPtrs& sv,
+                 const float* state, const float* gs, const float* gr, void* o, hipStream_t st);
+
+// [B,T,row] <-> [B,Tp,row] with zero rows t >= T (row_bytes a multiple of 16)
+void pad_rows(const void* src, void* dst, int B, int T, int Tp, size_t row_bytes, hipStream_t st);
+void unpad_rows(const void* src, void* dst, int B, int T, int Tp, size_t row_bytes, hipStream_t st);
 
 // launches the matrix-core probe loop; returns the FLOPs it issues
 double probe_mfma(float* sink, int iters, int blocks, hipStream_t st);

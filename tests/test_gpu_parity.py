@@ -257,6 +257,7 @@ def test_prefill_then_decode_reproduces_forward_row(dtype, T, W):
     ("bf16", 128, 4, 2, 128, [128, 256, 128]),       # ring + chunk a multiple of 128: matrix-core kernels
     ("bf16", 128, 2, 1, 513, [640, 255, 383]),       # the same with a window that is no tile multiple
     ("bf16", 64, 3, 1, 50, [70, 130]),
+    ("bf16", 128, 2, 1, 100, [1100, 500]),           # ring + chunk >= 1024, not a multiple of 128: padded copies
 ])
 def test_chunked_prefill_reproduces_forward(dtype, D, Hq, Hkv, W, chunks):
     """A prompt fed in chunks through rattn_prefill_chunk gives the rows of the forward over the whole prompt
