@@ -433,15 +433,27 @@ rattn_status rattn_prefill_chunk(const rattn_params* p, int32_t pos0, const void
   hipStream_t st = (hipStream_t)stream;
   char* w = (char*)workspace;
   const rattn::LayerDims& dm = C.L2.dm;
+  // keys before the ring exist only once more than `window` tokens have been seen; until then the state is zero
+  // by definition and what the caller's buffer holds is not read
+  const bool carried = pos0 > p->window;
+  // Direct route on the matrix-core kernels: ring and chunk are whole 128-row tiles, so the forward computes the
+  // chunk's query tiles only, straight from q into o, and (window a multiple of 128: every such tile reads a chunk
+  // state) the carried state enters as the initial value of the state scan.  Only K and V are gathered.
+  if (C.L2.fast_fwd && !C.L2.pad && !force_generic() && C.R % 128 == 0 && (!carried || p->window % 128 == 0)) {
+    rattn::chunk_concat(dm, p->dtype, p->T, C.R, pos0, nullptr, k, v, k_ring, v_ring, nullptr, w + C.kc, w + C.vc, st);
+    rattn::SavedPtrs none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    rattn::fast_fwd(dm, q, w + C.kc, w + C.vc, gamma_swa, gamma_rla, o, none, (float*)(w + C.fwdws + C.L2.ff_u),
+                    w + C.fwdws + C.L2.ff_states, st, C.R / 128, carried ? state : nullptr);
+    rattn::prefill_export(dm, p->dtype, w + C.kc, w + C.vc, k_ring, v_ring, state, (float*)(w + C.partial), st,
+                          pos0 - C.R, carried);
+    return check_launch("rattn_prefill_chunk");
+  }
   rattn::chunk_concat(dm, p->dtype, p->T, C.R, pos0, q, k, v, k_ring, v_ring, w + C.qc, w + C.kc, w + C.vc, st);
   s = check_launch("rattn_prefill_chunk (gather)");
   if (s != RATTN_OK) return s;
   s = rattn_fwd(&C.p2, w + C.qc, w + C.kc, w + C.vc, gamma_swa, gamma_rla, w + C.oc, w + C.saved, w + C.fwdws,
                 C.L2.fwd_bytes, stream);
   if (s != RATTN_OK) return s;
-  // keys before the ring exist only once more than `window` tokens have been seen; until then the state is zero
-  // by definition and what the caller's buffer holds is not read
-  const bool carried = pos0 > p->window;
   if (carried)
     rattn::chunk_fixup(dm, p->dtype, p->T, C.R, (C.L2.fast_fwd && !force_generic()) ? C.L2.dmf.T : dm.T, w + C.qc,
                        saved_views(C.L2, w + C.saved), state, gamma_swa, gamma_rla, o, st);

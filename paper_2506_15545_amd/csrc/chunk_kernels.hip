@@ -16,7 +16,8 @@ namespace rattn {
 namespace {
 
 // Rows j < R of the concatenated tensors come from the rings (token pos0 - R + j sits in slot (pos0 - R + j) % W),
-// rows j >= R from the chunk; the query rows in front of the chunk are zero (their outputs are not used).
+// rows j >= R from the chunk; the query rows in front of the chunk are zero (their outputs are not used).  With
+// q = NULL only K and V are gathered.
 // One thread per 16 bytes; `row_vecs` = 16-byte pieces per row of one head.
 __global__ __launch_bounds__(256) void chunk_concat_kernel(const uint4* __restrict__ q, const uint4* __restrict__ k,
                                                            const uint4* __restrict__ v, const uint4* __restrict__ k_ring,
@@ -24,7 +25,7 @@ __global__ __launch_bounds__(256) void chunk_concat_kernel(const uint4* __restri
                                                            uint4* __restrict__ kc, uint4* __restrict__ vc, int B, int Tc,
                                                            int R, int Hq, int Hkv, int W, int pos0, int row_vecs) {
   const int L = R + Tc;
-  const long long nkv = (long long)B * L * Hkv * row_vecs, nq = (long long)B * L * Hq * row_vecs;
+  const long long nkv = (long long)B * L * Hkv * row_vecs, nq = q ? (long long)B * L * Hq * row_vecs : 0;
   for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < nkv + nq; i += (long long)gridDim.x * 256) {
     if (i < nkv) {
       const int c = (int)(i % row_vecs);
@@ -231,7 +232,7 @@ void chunk_concat(const LayerDims& dmc, int dtype, int Tc, int R, int pos0, cons
                   const void* k_ring, const void* v_ring, void* qc, void* kc, void* vc, hipStream_t st) {
   const int esize = dtype == 0 ? 4 : 2;
   const int row_vecs = dmc.D * esize / 16;
-  const long long total = (long long)dmc.B * (R + Tc) * (dmc.Hkv + dmc.Hq) * row_vecs;
+  const long long total = (long long)dmc.B * (R + Tc) * (dmc.Hkv + (q ? dmc.Hq : 0)) * row_vecs;
   const int blocks = (int)((total + 255) / 256 < 16384 ? (total + 255) / 256 : 16384);
   ProfScope ps("chunk_concat_kernel", st);
   chunk_concat_kernel<<<blocks, 256, 0, st>>>((const uint4*)q, (const uint4*)k, (const uint4*)v, (const uint4*)k_ring,

@@ -29,6 +29,7 @@ struct FastFwdArgs {
   float *lse_out, *rs_out, *rr_out;
   const uint16_t* states;  // [B,Hkv,nstf,128 (value d),128 (feature f)] bf16: S^T at key position base+128*i
   int B, T, Hq, Hkv, G, W, gap, nstf, ntile;  // W: window rounded up to 64; true window = W - gap
+  int qt0;  // first query tile that is computed; q, o and the saved tensors hold rows 128 qt0 .. T-1 only
   float scale_log2, eps;
 };
 
@@ -188,17 +189,18 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
   const int bid = blockIdx.x;
   int wid = (total % 8 == 0) ? (bid % 8) * (total / 8) + bid / 8 : bid;
   const int hh = wid % G; wid /= G;
-  const int qt = wid % a.ntile; wid /= a.ntile;
+  const int ntq = a.ntile - a.qt0, Tq = 128 * ntq;  // query tiles and query rows per sequence
+  const int qt = wid % ntq + a.qt0; wid /= ntq;
   const int g = wid % Hkv;
   const int b = wid / Hkv;
   const int hq = g * G + hh;
   const int t0 = qt * 128;
   const size_t qstride = (size_t)Hq * 128, kstride = (size_t)Hkv * 128;
-  const size_t qtile_off = ((size_t)(b * T + t0) * Hq + hq) * 128;
+  const size_t qtile_off = ((size_t)(b * Tq + t0 - 128 * a.qt0) * Hq + hq) * 128;
   const uint16_t* kbase = a.k + ((size_t)b * T * Hkv + g) * 128;
   const uint16_t* vbase = a.v + ((size_t)b * T * Hkv + g) * 128;
   const int myq = t0 + 32 * w + r32;
-  const size_t stat_off = (size_t)(b * Hq + hq) * T + myq;
+  const size_t stat_off = (size_t)(b * Hq + hq) * Tq + myq - 128 * a.qt0;
 
   // ------------------------------------------------------------------ softmax branch
   // key tiles of 64 from the diagonal (n = 0) down to kt_lo (n = ntiles-1); tile n uses LDS buffer n & 1.
@@ -445,9 +447,9 @@ FastFwdPlan fast_fwd_plan(const LayerDims& dm) {
 }
 
 void fast_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, const float* gs, const float* gr,
-              void* o, const SavedPtrs& sv, float* U, void* states, hipStream_t st) {
+              void* o, const SavedPtrs& sv, float* U, void* states, hipStream_t st, int qt0, const float* state0) {
   const FastFwdPlan pl = fast_fwd_plan(dm);
-  if (pl.nstf > 0) rla_forward_states(dm, pl, k, v, U, states, st);
+  if (pl.nstf > 0) rla_forward_states(dm, pl, k, v, U, states, st, state0);
   FastFwdArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
   a.gs = gs; a.gr = gr;
@@ -455,11 +457,12 @@ void fast_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
   a.lse_out = sv.lse; a.rs_out = sv.rs; a.rr_out = sv.rr;
   a.states = (const uint16_t*)states;
   a.B = dm.B; a.T = dm.T; a.Hq = dm.Hq; a.Hkv = dm.Hkv; a.G = dm.G; a.W = pl.W; a.gap = pl.gap; a.nstf = pl.nstf;
-  a.ntile = dm.T / 128;
+  a.ntile = dm.T / 128; a.qt0 = qt0;
   a.scale_log2 = dm.scale * LOG2E; a.eps = dm.eps;
   ProfScope ps("fwd_fused_kernel", st);
-  if (a.gap > 0) fwd_fused_kernel<true><<<dim3(a.ntile * dm.Hq * dm.B), 256, 0, st>>>(a);
-  else fwd_fused_kernel<false><<<dim3(a.ntile * dm.Hq * dm.B), 256, 0, st>>>(a);
+  const dim3 grid((a.ntile - qt0) * dm.Hq * dm.B);
+  if (a.gap > 0) fwd_fused_kernel<true><<<grid, 256, 0, st>>>(a);
+  else fwd_fused_kernel<false><<<grid, 256, 0, st>>>(a);
 }
 
 }  // namespace rattn

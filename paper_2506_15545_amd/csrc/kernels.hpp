@@ -60,12 +60,17 @@ struct FastFwdPlan {
 };
 bool fast_fwd_supported(const LayerDims& dm, int dtype);
 FastFwdPlan fast_fwd_plan(const LayerDims& dm);
+// qt0 > 0: only query tiles qt0 .. T/128-1 are computed, and q, o and the saved tensors hold just those rows
+// ([B, T - 128 qt0, Hq, D]); k, v always hold all T rows.  state0 (fp32 [B,Hkv,D(feature),D(value)], may be NULL): a
+// linear-branch state that precedes key 0 and is added to every chunk state; tiles whose chunk starts before key 0
+// do not see it, so the caller uses it only when no computed tile is of that kind.
 void fast_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, const float* gs, const float* gr,
-              void* o, const SavedPtrs& sv, float* U, void* states, hipStream_t st);
+              void* o, const SavedPtrs& sv, float* U, void* states, hipStream_t st, int qt0 = 0,
+              const float* state0 = nullptr);
 
 // linear-branch chunk states for the MFMA paths (bf16 [d][f] per state, fp32 scratch U per chunk)
 void rla_forward_states(const LayerDims& dm, const FastFwdPlan& pl, const void* k, const void* v, float* U,
-                        void* states, hipStream_t st);
+                        void* states, hipStream_t st, const float* state0 = nullptr);
 // reverse-time states R_i = sum over t' >= 128(i+1) and over the group's heads of phi(q_{t'+W})^T dxr_{t'+W},
 // i in [0, nk), nk = ceil((T-W)/128); stored transposed [d][f] bf16.  U needs (nk-1) chunks.
 void rla_reverse_states(const LayerDims& dm, int W, int nk, const void* q, const void* dxr, float* U,

@@ -65,14 +65,20 @@ __global__ __launch_bounds__(256) void rla_chunk_kernel(ChunkArgs p) {
 //   forward: state[0] = (head ? U[0] : 0); state[i+1] = state[i] + U[c++]
 //   reverse: state[n-1] = 0; state[i] = state[i+1] + U[i]
 // grid (16, Hkv, B), 256 threads, 4 elements per thread.
+// init (forward only, may be NULL): a state that precedes chunk 0, fp32 [B,Hkv,f,d] (not transposed).
 template <bool REV>
 __global__ __launch_bounds__(256) void rla_scan_kernel(const float* __restrict__ U, uint16_t* __restrict__ states,
-                                                       int nchunks, int nst, int head) {
+                                                       int nchunks, int nst, int head, const float* __restrict__ init) {
   const int g = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
   const int e4 = (blockIdx.x * 256 + threadIdx.x) * 4;
   const float* Ub = U + (size_t)(b * Hkv + g) * nchunks * 16384 + e4;
   uint16_t* Sb = states + (size_t)(b * Hkv + g) * nst * 16384 + e4;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (!REV && init) {  // element (d, f .. f+3) of the transposed state = init[f .. f+3][d]
+    const float* ib = init + (size_t)(b * Hkv + g) * 16384 + (e4 >> 7);
+    const int f = e4 & 127;
+    acc = make_float4(ib[(size_t)f * 128], ib[(size_t)(f + 1) * 128], ib[(size_t)(f + 2) * 128], ib[(size_t)(f + 3) * 128]);
+  }
   auto put = [&](int i) {
     f32x4_t f = {acc.x, acc.y, acc.z, acc.w};
     *reinterpret_cast<bf16x4_t*>(Sb + (size_t)i * 16384) = __builtin_convertvector(f, bf16x4_t);
@@ -99,7 +105,7 @@ __global__ __launch_bounds__(256) void rla_scan_kernel(const float* __restrict__
 }  // namespace
 
 void rla_forward_states(const LayerDims& dm, const FastFwdPlan& pl, const void* k, const void* v, float* U,
-                        void* states, hipStream_t st) {
+                        void* states, hipStream_t st, const float* state0) {
   if (pl.nstf <= 0) return;
   if (pl.nchunks > 0) {
     ChunkArgs p;
@@ -111,7 +117,7 @@ void rla_forward_states(const LayerDims& dm, const FastFwdPlan& pl, const void* 
   }
   ProfScope ps("rla_scan_kernel", st);
   rla_scan_kernel<false><<<dim3(16, dm.Hkv, dm.B), 256, 0, st>>>(U, (uint16_t*)states, pl.nchunks, pl.nstf,
-                                                                  pl.base > 0 ? 1 : 0);
+                                                                  pl.base > 0 ? 1 : 0, state0);
 }
 
 void rla_reverse_states(const LayerDims& dm, int W, int nk, const void* q, const void* dxr, float* U, void* rstates,
@@ -127,7 +133,7 @@ void rla_reverse_states(const LayerDims& dm, int W, int nk, const void* q, const
     rla_chunk_kernel<<<dim3(nk - 1, dm.Hkv, dm.B), 256, 0, st>>>(p);
   }
   ProfScope ps("rla_scan_kernel(rev)", st);
-  rla_scan_kernel<true><<<dim3(16, dm.Hkv, dm.B), 256, 0, st>>>(U, (uint16_t*)rstates, nk - 1, nk, 0);
+  rla_scan_kernel<true><<<dim3(16, dm.Hkv, dm.B), 256, 0, st>>>(U, (uint16_t*)rstates, nk - 1, nk, 0, nullptr);
 }
 
 }  // namespace rattn

@@ -255,6 +255,8 @@ def test_prefill_then_decode_reproduces_forward_row(dtype, T, W):
     ("f32", 128, 2, 1, 16, [16, 16, 7]),
     ("f32", 64, 2, 2, 4, [1, 1, 1, 1, 1, 1, 3]),     # single-token chunks = decode steps
     ("bf16", 128, 4, 2, 128, [128, 256, 128]),       # ring + chunk a multiple of 128: matrix-core kernels
+    ("bf16", 128, 2, 2, 256, [128, 384, 256, 128]),  # history shorter than the window in whole tiles, then longer
+    ("bf16", 128, 2, 1, 192, [192, 192, 256]),       # window no multiple of 128: gather + fix-up route
     ("bf16", 128, 2, 1, 513, [640, 255, 383]),       # the same with a window that is no tile multiple
     ("bf16", 64, 3, 1, 50, [70, 130]),
     ("bf16", 128, 2, 1, 100, [1100, 500]),           # ring + chunk >= 1024, not a multiple of 128: padded copies
@@ -302,4 +304,18 @@ def test_chunked_prefill_uses_matrix_core_kernels():
     torch.cuda.synchronize()
     names = [n for n, _ in rb.rattn_profile_records()]
     rb.rattn_profile_enable(False)
-    assert "fwd_fused_kernel" in names and "chunk_fixup_kernel" in names and "gen_fwd_kernel" not in names
+    # whole tiles of ring and chunk, window a multiple of 128: the forward runs on the chunk's query tiles only and
+    # takes the carried state as the start of its state scan; nothing is fixed up or copied afterwards
+    assert "fwd_fused_kernel" in names and "gen_fwd_kernel" not in names
+    assert "chunk_fixup_kernel" not in names and "chunk_copy_out_kernel" not in names
+    # a window that is no multiple of 128 leaves a first tile without a chunk state: gather + fix-up route
+    x = synth.make_random_layer(B, 704, Hq, Hkv, D, "bf16", 4201)      # ring 192 + chunk 320 = 512 rows
+    q, k, v = dev(x["q"]), dev(x["k"]), dev(x["v"])
+    kr, vr, S = rb.rattn_prefill_export(k[:, :384].contiguous(), v[:, :384].contiguous(), 192)
+    rb.rattn_profile_enable(True)
+    rb.rattn_prefill_chunk(q[:, 384:].contiguous(), k[:, 384:].contiguous(), v[:, 384:].contiguous(), 192, 384, kr, vr, S,
+                           softmax_scale=0.09)
+    torch.cuda.synchronize()
+    names = [n for n, _ in rb.rattn_profile_records()]
+    rb.rattn_profile_enable(False)
+    assert "fwd_fused_kernel" in names and "chunk_fixup_kernel" in names
