@@ -167,3 +167,27 @@ def test_window_sweep_fwd_full_size(W):
             att = att.permute(0, 2, 1, 3).numpy()
             causal = att / np.sqrt(np.mean(att * att, axis=-1, keepdims=True) + 1e-6)
             assert out_err(group(cfg, o, b, g), causal) <= OUT_TOL
+
+
+def test_long_sequence_sampled_rows():
+    """T = 32768 (256 chunk states per KV head, summed in fp32 and stored in bf16; decode's position range): the
+    forward on the matrix-core kernels against the oracle on sampled query rows (the oracle computes a row from
+    its definition, whatever the others are)."""
+    B, T, Hq, Hkv, D, W = 1, 32768, 2, 1, 128, 512
+    x = synth.make_random_layer(B, T, Hq, Hkv, D, "bf16", 5150)
+    scale = 1.0 / math.sqrt(D)
+    print("long sequence: forward on the GPU", flush=True)
+    rb.rattn_profile_enable(True)
+    o = rb.rattn_fwd(x["q"].cuda(), x["k"].cuda(), x["v"].cuda(), W, softmax_scale=scale)
+    torch.cuda.synchronize()
+    names = [n for n, _ in rb.rattn_profile_records()]
+    rb.rattn_profile_enable(False)
+    assert "fwd_fused_kernel" in names
+    rng = np.random.default_rng(7)
+    rows = np.unique(np.concatenate([np.arange(0, 130), np.arange(W - 2, W + 130), np.arange(T - 130, T),
+                                     rng.integers(0, T, 300)]))
+    print(f"  oracle on {len(rows)} rows", flush=True)
+    ref = orc.fwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), W, scale=scale, rows=rows)["o"]
+    e = np.abs(np64(o)[:, rows] - ref[:, rows])
+    e = np.maximum(e - np.abs(ref[:, rows]) / 256.0, 0.0)
+    assert float(e.max()) <= OUT_TOL, float(e.max())
