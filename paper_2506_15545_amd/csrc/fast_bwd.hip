@@ -382,14 +382,15 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
     __syncthreads();
   }
   const int qa = t0 + 32 * w, qb = qa + 31;
+  const DmaLane dma_lane = make_dma_lane(lane, kstride);
   const int Wm = W - gap;  // the true window: element masks and sub-tile skipping
   for (int n = 0; n < ntiles; ++n) {
     const int it = ntiles - 1 - n;
     const int cur = n & 1;
     if (n + 1 < ntiles) {
       const int ktn = kt_lo + 64 * (it - 1);
-      tile_load_async<4>(kbase + (size_t)ktn * kstride, kstride, smem + (cur ^ 1) * 16384, w * 4, lane);
-      tile_load_async<4>(vbase + (size_t)ktn * kstride, kstride, smem + 32768 + (cur ^ 1) * 16384, w * 4, lane);
+      tile_load_async_s<4>(kbase + (size_t)ktn * kstride, kstride, smem + (cur ^ 1) * 16384, w * 4, dma_lane);
+      tile_load_async_s<4>(vbase + (size_t)ktn * kstride, kstride, smem + 32768 + (cur ^ 1) * 16384, w * 4, dma_lane);
     }
     const unsigned char* kt = smem + cur * 16384;
     const unsigned char* vt = smem + 32768 + cur * 16384;
@@ -502,21 +503,21 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
   const int ka = s0 + 32 * w;
   // per-lane part of the tile addresses (swizzled 16-byte chunk of rows 8*w8 + lane/16 and +4), computed once
   const int ir0 = 8 * w8 + (lane >> 4), ir1 = ir0 + 4, ip = lane & 15;
-  const size_t lane_g0 = (size_t)ir0 * qstride + ((ip ^ swz(ir0)) << 3);
-  const size_t lane_g1 = (size_t)ir1 * qstride + ((ip ^ swz(ir1)) << 3);
+  const unsigned lane_g0 = (unsigned)(((size_t)ir0 * qstride + ((ip ^ swz(ir0)) << 3)) * 2);  // bytes
+  const unsigned lane_g1 = (unsigned)(((size_t)ir1 * qstride + ((ip ^ swz(ir1)) << 3)) * 2);
   const unsigned lds_q = (unsigned)(size_t)RATTN_LDS(smem) + w8 * 2048;
   const unsigned lds_st = (unsigned)(size_t)RATTN_LDS(smem + DKV_STAT_OFF) + (krole ? 1024 : 0);
-  const float* stat_g = (krole ? a.delta : a.lse) + (size_t)(b * Hq + g * G) * T + s0 + 4 * ip;
+  const float* stat_base = (krole ? a.delta : a.lse) + (size_t)(b * Hq + g * G) * T + s0;  // lane adds 16 * ip bytes
   const size_t tile_g = ((size_t)(b * T + s0) * Hq + g * G) * 128;
   int is_h = 0, is_n = 0, is_buf = 0;  // head, tile and slot of the next tile to request
   auto issue = [&]() {
     const size_t qoff = tile_g + (size_t)is_n * 64 * qstride + (size_t)is_h * 128;
-    dma16(a.q + qoff + lane_g0, lds_q + is_buf * DKV_SLOT);
-    dma16(a.q + qoff + lane_g1, lds_q + is_buf * DKV_SLOT + 1024);
-    dma16(a.dxs + qoff + lane_g0, lds_q + is_buf * DKV_SLOT + 16384);
-    dma16(a.dxs + qoff + lane_g1, lds_q + is_buf * DKV_SLOT + 16384 + 1024);
-    if (w == 0)  // waves 0 and 4: the row statistics their role consumes (lanes 16.. fetch duplicates)
-      dma16(stat_g + (size_t)is_h * T + 64 * is_n, lds_st + is_buf * 2048);
+    dma16s(a.q + qoff, lane_g0, lds_q + is_buf * DKV_SLOT);
+    dma16s(a.q + qoff, lane_g1, lds_q + is_buf * DKV_SLOT + 1024);
+    dma16s(a.dxs + qoff, lane_g0, lds_q + is_buf * DKV_SLOT + 16384);
+    dma16s(a.dxs + qoff, lane_g1, lds_q + is_buf * DKV_SLOT + 16384 + 1024);
+    if (w == 0)  // one wave of each role: the row statistics that role consumes (lanes 16.. fetch duplicates)
+      dma16s(stat_base + (size_t)is_h * T + 64 * is_n, 16 * ip, lds_st + is_buf * 2048);
     if (++is_n == n_qt) { is_n = 0; ++is_h; }
     if (++is_buf == 3) is_buf = 0;
   };

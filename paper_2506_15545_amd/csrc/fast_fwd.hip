@@ -93,11 +93,17 @@ struct SweepGeom {
 template <int R, bool DO_C>
 __device__ __forceinline__ void sweep_step(const unsigned char* smem, const LaneOff& lo, const SweepGeom& gm, int j,
                                            int myq, float scale_log2, const bf16x8_t (&qop)[8], f32x16_t (&oacc)[4],
-                                           float& m, float& l, f32x16_t& s_cur, bf16x8_t (&p_prev)[2], int lane) {
+                                           float& m, float& l, f32x16_t& s_cur, bf16x8_t (&p_prev)[2], bool& pend,
+                                           float& alpha_pend, int lane) {
   constexpr int KS = R & 1;                           // sub-tile half of both j+1 and j-1
   constexpr int KB = (R == 1 || R == 2) ? 1 : 0;      // K buffer of sub-tile j+1
   constexpr int VB = (R == 0 || R == 3) ? 1 : 0;      // V buffer of sub-tile j-1
   const int h = lane >> 5;
+  if (pend) {  // the rescale of O the previous step left behind (rare; wave-uniform)
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) oacc[dt] *= alpha_pend;
+    pend = false;
+  }
   if (!gm.full(j)) {  // wave-uniform: window edge, diagonal, or a sub-tile this wave does not see at all
     const int ka = gm.ka(j);
     // in the window <=> 0 <= query - key < W: one unsigned compare per element against a per-lane base
@@ -124,15 +130,19 @@ __device__ __forceinline__ void sweep_step(const unsigned char* smem, const Lane
     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 LDS read
   }
   const bool trig = __builtin_amdgcn_ballot_w64(mx > RESCALE_TH) != 0;
-  float alpha = 1.f;
   if (trig) {
     float sm = fmaxf(s_cur[0], s_cur[1]);
 #pragma unroll
     for (int i = 2; i < 16; ++i) sm = fmaxf(sm, s_cur[i]);
     const float m_new = fmaxf(m, half_max(sm) * scale_log2);
-    alpha = fast_exp2(m - m_new);
+    const float alpha = fast_exp2(m - m_new);
     m = m_new;
     l *= alpha;
+    // O is rescaled at the start of the next step: this step's O update below is still expressed against the
+    // old m, and keeping the rescale out of this place leaves the update and the exponentials in one block
+    // of straight-line code, where they overlap
+    pend = true;
+    alpha_pend = alpha;
 #pragma unroll
     for (int i = 0; i < 16; ++i) x[i] = __builtin_fmaf(s_cur[i], scale_log2, -m);
   }
@@ -152,10 +162,6 @@ __device__ __forceinline__ void sweep_step(const unsigned char* smem, const Lane
       __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);  // 6 VALU
       __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // 2 LDS reads
     }
-  }
-  if (trig) {
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt) oacc[dt] *= alpha;
   }
   s_cur = s_next;
 }
@@ -207,11 +213,12 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
   // K runs one tile ahead of V through the buffers (the S^T chain of a sub-tile is issued one step early).
   const int kt_lo = max(0, t0 - W);
   const int ntiles = (t0 + 128 - kt_lo) / 64;  // >= 2
+  const DmaLane dl = make_dma_lane(lane, kstride);
   auto load_k = [&](int n) {
-    tile_load_async<4>(kbase + (size_t)(kt_lo + 64 * (ntiles - 1 - n)) * kstride, kstride, smem + (n & 1) * 16384, w * 4, lane);
+    tile_load_async_s<4>(kbase + (size_t)(kt_lo + 64 * (ntiles - 1 - n)) * kstride, kstride, smem + (n & 1) * 16384, w * 4, dl);
   };
   auto load_v = [&](int n) {
-    tile_load_async<4>(vbase + (size_t)(kt_lo + 64 * (ntiles - 1 - n)) * kstride, kstride, smem + 32768 + (n & 1) * 16384, w * 4, lane);
+    tile_load_async_s<4>(vbase + (size_t)(kt_lo + 64 * (ntiles - 1 - n)) * kstride, kstride, smem + 32768 + (n & 1) * 16384, w * 4, dl);
   };
   load_k(0);
   load_v(0);
@@ -230,24 +237,30 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
   gm.kt_lo = kt_lo; gm.ntiles = ntiles; gm.qa = t0 + 32 * w; gm.W = W - (GAP ? a.gap : 0);
   f32x16_t s_cur;
   bf16x8_t p_prev[2];
+  bool pend = false;
+  float alpha_pend = 1.f;
   qk_chain<0, 1>(smem, lo, qop, s_cur);
   // step 0 has no earlier sub-tile to fold in; the step after the last one only folds
-  sweep_step<0, false>(smem, lo, gm, 0, myq, a.scale_log2, qop, oacc, m, l, s_cur, p_prev, lane);
+  sweep_step<0, false>(smem, lo, gm, 0, myq, a.scale_log2, qop, oacc, m, l, s_cur, p_prev, pend, alpha_pend, lane);
   for (int n = 0; n < ntiles; n += 2) {
-    if (n > 0) sweep_step<0, true>(smem, lo, gm, 2 * n, myq, a.scale_log2, qop, oacc, m, l, s_cur, p_prev, lane);
+    if (n > 0) sweep_step<0, true>(smem, lo, gm, 2 * n, myq, a.scale_log2, qop, oacc, m, l, s_cur, p_prev, pend, alpha_pend, lane);
     wait_vmem();
     __syncthreads();
     if (n + 2 < ntiles) load_k(n + 2);
     if (n + 1 < ntiles) load_v(n + 1);
-    sweep_step<1, true>(smem, lo, gm, 2 * n + 1, myq, a.scale_log2, qop, oacc, m, l, s_cur, p_prev, lane);
+    sweep_step<1, true>(smem, lo, gm, 2 * n + 1, myq, a.scale_log2, qop, oacc, m, l, s_cur, p_prev, pend, alpha_pend, lane);
     if (n + 1 < ntiles) {
-      sweep_step<2, true>(smem, lo, gm, 2 * n + 2, myq, a.scale_log2, qop, oacc, m, l, s_cur, p_prev, lane);
+      sweep_step<2, true>(smem, lo, gm, 2 * n + 2, myq, a.scale_log2, qop, oacc, m, l, s_cur, p_prev, pend, alpha_pend, lane);
       wait_vmem();
       __syncthreads();
       if (n + 3 < ntiles) load_k(n + 3);
       if (n + 2 < ntiles) load_v(n + 2);
-      sweep_step<3, true>(smem, lo, gm, 2 * n + 3, myq, a.scale_log2, qop, oacc, m, l, s_cur, p_prev, lane);
+      sweep_step<3, true>(smem, lo, gm, 2 * n + 3, myq, a.scale_log2, qop, oacc, m, l, s_cur, p_prev, pend, alpha_pend, lane);
     }
+  }
+  if (pend) {
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) oacc[dt] *= alpha_pend;
   }
   if (ntiles & 1) pv_chain<0, 0>(smem, lo, p_prev, oacc);
   else pv_chain<1, 0>(smem, lo, p_prev, oacc);

@@ -66,6 +66,32 @@ __device__ __forceinline__ void tile_load_async(const uint16_t* gbase, size_t ro
   }
 }
 
+// The same load with a wave-uniform base in scalar registers and a 32-bit per-lane byte offset: no per-lane 64-bit
+// address arithmetic per load.
+__device__ __forceinline__ void dma16s(const void* sbase, unsigned voff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(__builtin_amdgcn_readfirstlane(lds_addr)) : "memory", "m0");
+}
+// Per-lane byte offsets of tile_load_async's access pattern inside a 4-row block, one per value of (block & 3)
+// (the swizzle of row 4*blk + lane/16 depends on the block only through blk & 3); computed once per kernel.
+struct DmaLane { unsigned off[4]; };
+__device__ __forceinline__ DmaLane make_dma_lane(int lane, size_t row_stride_elems) {
+  DmaLane d;
+  const int l4 = lane >> 4, p = lane & 15;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) d.off[i] = (unsigned)(l4 * row_stride_elems * 2) + (unsigned)((p ^ ((l4 << 2) | i)) << 4);
+  return d;
+}
+// tile_load_async for NBLK consecutive blocks starting at blk0 (a multiple of 4, wave-uniform), NBLK <= 4... 8
+template <int NBLK>
+__device__ __forceinline__ void tile_load_async_s(const uint16_t* gbase, size_t row_stride, unsigned char* tile, int blk0,
+                                                  const DmaLane& dl) {
+#pragma unroll
+  for (int i = 0; i < NBLK; ++i) {
+    const int blk = blk0 + i;
+    dma16s(gbase + (size_t)blk * 4 * row_stride, dl.off[i & 3], (unsigned)(size_t)RATTN_LDS(tile + blk * 1024));
+  }
+}
+
 // operand whose rows are tile rows: 8 consecutive elements at logical chunk c of row r
 __device__ __forceinline__ bf16x8_t lds_row_chunk(const unsigned char* tile, int r, int c) {
   return *reinterpret_cast<const bf16x8_t*>(tile + r * ROW_BYTES + ((c ^ swz(r)) << 4));
