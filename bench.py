@@ -112,6 +112,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true",
+                    help="skip the reported-only prefill hand-over and chunked-prefill timings (profiling runs: keeps "
+                         "every forward launch in the trace on the headline workload)")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=24)
     ap.add_argument("--no-other-workloads", action="store_true",
@@ -255,6 +258,7 @@ def main():
             "local_layer_cache_term_us": {"model_at_peak": out["decode"]["step_time_model_us"],
                                           "measured_kernel": out["decode"]["us_per_step"]}}
 
+    if not args.no_decode and not args.no_prefill:
         # prefill -> decode hand-over on the layer's K/V (one-off per prompt; reported, not part of `value`)
         for _ in range(3):
             rb.rattn_prefill_export(k, v, cfg.W)
