@@ -349,6 +349,17 @@ def main():
         for W_ in (128, 512, 1024, 4096, 8192):
             c_ = synth.sweep_config(W_)
             other[c_.name] = run_layer(c_, True)
+        # chunk-size enumeration of the linear branch (Sec. 3.2's search over C) on the general kernels, which take the
+        # chunk as a parameter (the matrix-core path fixes one state per 128 keys): D = 64 forces that path
+        xg = synth.make_random_layer(1, 4096, 8, 2, 64, "bf16", 11)
+        qg, kg, vg = xg["q"].cuda(), xg["k"].cuda(), xg["v"].cuda()
+        sweep_c = {}
+        for c_ in (16, 32, 64, 128, 256, 512):
+            fg = lambda: rb.rattn_fwd(qg, kg, vg, 512, chunk=c_, softmax_scale=0.125)
+            for _ in range(3):
+                fg()
+            sweep_c[str(c_)] = timed(fg, 10)
+        other["general_path_chunk_sweep_t4096_d64_fwd_ms"] = sweep_c
         out["other_workloads"] = other
 
     if not args.no_other_workloads:
