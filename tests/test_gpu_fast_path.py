@@ -238,3 +238,22 @@ def test_ragged_length_runs_on_padded_copies(B, T, Hq, Hkv, W):
         else:
             rms = math.sqrt(float(np.mean(refb[n] ** 2)))
             assert float(np.max(np.abs(np64(g_) - refb[n]))) / rms <= 2e-2, n
+
+
+def test_side_stream_matches_default_stream():
+    """All work is enqueued on the stream the caller passes (default priority): a non-default stream gives the
+    same bits as the default one."""
+    x = synth.make_random_layer(1, 512, 4, 2, 128, "bf16", 9, with_dO=True)
+    q, k, v, dO = x["q"].cuda(), x["k"].cuda(), x["v"].cuda(), x["dO"].cuda()
+    o0, saved0 = rb.rattn_fwd(q, k, v, 128, softmax_scale=0.09, save_for_bwd=True)
+    g0 = rb.rattn_bwd(q, k, v, saved0, dO, 128, softmax_scale=0.09, want_dgamma=False)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        o1, saved1 = rb.rattn_fwd(q, k, v, 128, softmax_scale=0.09, save_for_bwd=True)
+        g1 = rb.rattn_bwd(q, k, v, saved1, dO, 128, softmax_scale=0.09, want_dgamma=False)
+    side.synchronize()
+    assert torch.equal(o0, o1)
+    for a, b in zip(g0[:3], g1[:3]):
+        assert torch.equal(a, b)
