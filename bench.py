@@ -168,6 +168,28 @@ def main():
         step()
     # the timed region: exactly `steps` steps, nothing else on the stream
     ms_per_step = timed(step, args.steps)
+    # the same step replayed as one HIP graph (reported only: launch gaps removed; `value` stays the eager figure)
+    graph_ms = None
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.synchronize()
+        for _ in range(5):
+            graph.replay()
+        # alternate with the eager step so that clock drift over the run hits both alike
+        te = tg = 0.0
+        for _ in range(3):
+            te += timed(step, 20) / 3
+            tg += timed(graph.replay, 20) / 3
+        graph_ms = {"graph": tg, "eager_interleaved": te}
+        del graph
+    except Exception as e:  # reported field only
+        print(f"bench: graph replay skipped: {e}", file=sys.stderr)
     # the same steps again with the library's per-kernel HIP events (recorded on the launch stream) switched
     # on; they serialise neighbouring kernels, so they stay out of the region `value` is taken from
     rb.rattn_profile_enable(True)
@@ -206,6 +228,7 @@ def main():
         "frac_mfma_peak": value * 1e12 / PEAK_BF16_MFMA,
         "tokens_per_s": cfg.B * cfg.T / (ms_per_step * 1e-3),
         "ms_per_step_profiled": ms_per_step_profiled,
+        "ms_per_step_graph": graph_ms,
         "fwd": {"ms": fwd_ms, "tflops": fl["fwd"] / (fwd_ms * 1e-3) / 1e12,
                 "frac_mfma_peak": fl["fwd"] / (fwd_ms * 1e-3) / PEAK_BF16_MFMA},
         "bwd": {"ms": bwd_ms, "tflops": fl["bwd"] / (bwd_ms * 1e-3) / 1e12,
