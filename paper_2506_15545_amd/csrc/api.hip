@@ -20,12 +20,12 @@ void prof_begin(const char* name, hipStream_t st) {
   ProfRec r;
   r.name = name;
   if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
-  hipEventRecord(r.a, st);
+  (void)hipEventRecord(r.a, st);  // tracing aid: a failed record shows up as a failed rattn_profile_get
   g_prof.push_back(r);
 }
 void prof_end(hipStream_t st) {
   if (!g_prof_on || g_prof.empty()) return;
-  hipEventRecord(g_prof.back().b, st);
+  (void)hipEventRecord(g_prof.back().b, st);
 }
 }  // namespace rattn
 
@@ -247,7 +247,7 @@ const char* rattn_status_string(rattn_status s) {
 const char* rattn_last_error(void) { return g_err; }
 
 void rattn_profile_reset(void) {
-  for (auto& r : rattn::g_prof) { hipEventDestroy(r.a); hipEventDestroy(r.b); }
+  for (auto& r : rattn::g_prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
   rattn::g_prof.clear();
 }
 void rattn_profile_enable(int on) {

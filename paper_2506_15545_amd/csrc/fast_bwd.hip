@@ -110,7 +110,7 @@ __device__ __forceinline__ void dq_subtile(const unsigned char* kt, const unsign
                                            int W, bool masked, float scale, float scale_log2, float lse2, float dl,
                                            const bf16x8_t (&qop)[8], const bf16x8_t (&dxsop)[8], f32x16_t (&acc)[4],
                                            int lane, const LaneOff& lo) {
-  const int r32 = lane & 31, h = lane >> 5;
+  const int h = lane >> 5;
   f32x16_t s = {0}, dp = {0};
 #pragma unroll
   for (int c = 0; c < 8; ++c) s = mfma32(lds_row(kt, lo, 32 * ks, c), qop[c], s);
