@@ -253,7 +253,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
   const int total = gridDim.x, bid = blockIdx.x;
   int wid = (total % 8 == 0) ? (bid % 8) * (total / 8) + bid / 8 : bid;
   const int hh = wid % G; wid /= G;
-  const int qt = wid % a.ntile; wid /= a.ntile;
+  const int qt = a.ntile - 1 - wid % a.ntile; wid /= a.ntile;  // late tiles first: they see the most keys
   const int g = wid % Hkv;
   const int b = wid / Hkv;
   const int hq = g * G + hh;

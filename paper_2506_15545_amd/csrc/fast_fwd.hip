@@ -196,7 +196,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
   int wid = (total % 8 == 0) ? (bid % 8) * (total / 8) + bid / 8 : bid;
   const int hh = wid % G; wid /= G;
   const int ntq = a.ntile - a.qt0, Tq = 128 * ntq;  // query tiles and query rows per sequence
-  const int qt = wid % ntq + a.qt0; wid /= ntq;
+  const int qt = a.ntile - 1 - wid % ntq; wid /= ntq;  // late tiles first: they see the most keys (causal / start-up tiles)
   const int g = wid % Hkv;
   const int b = wid / Hkv;
   const int hq = g * G + hh;
