@@ -219,10 +219,15 @@ __device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, int hq, size_
     for (int e = 0; e < 8; ++e) {
       av[e] = r_s * g1[e] * dy[e] - xs[e] * b_s;
       cv[e] = r_r * g2[e] * dy[e] - xr[e] * b_r;
-      dl = fmaf(av[e], xs[e], dl);
     }
+    const bf16x8_t apk = pack_bf16x8(av);
     const bf16x8_t cpk = pack_bf16x8(cv);
-    *reinterpret_cast<bf16x8_t*>(dxs_w + off) = pack_bf16x8(av);
+    // delta from d xs as the matrix cores will see it (rounded to bf16): dS = P (dP - delta) is a near-cancellation
+    // for peaked rows, and dP is formed from the rounded values
+    unpack_bf16x8(apk, av);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dl = fmaf(av[e], xs[e], dl);
+    *reinterpret_cast<bf16x8_t*>(dxs_w + off) = apk;
     *reinterpret_cast<bf16x8_t*>(dxr_w + off) = cpk;
     if (stage) *reinterpret_cast<bf16x8_t*>(stage + r * ROW_BYTES + ((c ^ swz(r)) << 4)) = cpk;
     dl = sum16(dl);
