@@ -345,12 +345,12 @@ __global__ void gen_dgamma_reduce_kernel(const float* __restrict__ dgpart, float
 // ------------------------------------------------------------------------------------------------
 // Backward, dq: one wave per query row (layout as the forward).
 //   softmax branch: p = exp(scale q.k - lse), dp = <dx_s, v_s>, da = p(dp - delta), dq += scale*da*k_s
+//                   (delta recomputed from p and dp, and written back, when the window fits one pass: W <= 64)
 //   linear branch : dphi(q) = S_[j] dx_r + sum_{intra} <dx_r, v_s> phi(k_s);  dq += phi(q)*(dphi - <dphi,phi(q)>)
 template <typename IO, int D>
 __global__ __launch_bounds__(256) void gen_bwd_dq_kernel(const IO* __restrict__ q, const IO* __restrict__ k,
                                                          const IO* __restrict__ v, const float* __restrict__ dxs,
-                                                         const float* __restrict__ dxr,
-                                                         const float* __restrict__ delta,
+                                                         const float* __restrict__ dxr, float* delta,
                                                          const float* __restrict__ lse,
                                                          const float* __restrict__ states, IO* __restrict__ dq,
                                                          LayerDims dm) {
@@ -367,7 +367,8 @@ __global__ __launch_bounds__(256) void gen_bwd_dq_kernel(const IO* __restrict__ 
     qv.load(q + qoff);
     Row<float, D> gxs, gxr;
     gxs.load(dxs + qoff); gxr.load(dxr + qoff);
-    const float dl = delta[so], ls = lse[so];
+    float dl = delta[so];
+    const float ls = lse[so];
     float acc[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
@@ -380,6 +381,13 @@ __global__ __launch_bounds__(256) void gen_bwd_dq_kernel(const IO* __restrict__ 
       const float a = dm.scale * lane_dot(qv, k + ko);
       const float p = valid ? expf(a - ls) : 0.f;
       const float dp = lane_dot(gxs, v + ko);
+      if (W <= 64) {
+        // The window fits one pass of the wave: delta = sum_j p_j dp_j from the very p and dp that form da, instead
+        // of <dx_s, x_s> with the stored x_s.  For windows of a few keys p is nearly one-hot and p (dp - delta)
+        // cancels; the rounding of a bf16-stored x_s would be what is left.  The dk/dv kernel reads it back.
+        dl = wave_sum(p * dp);
+        if (lane == 0) delta[so] = dl;
+      }
       const float da = p * (dp - dl);
       const int n = min(64, t - base + 1);
       for (int j = 0; j < n; ++j) {

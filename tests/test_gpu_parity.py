@@ -142,7 +142,9 @@ def test_bwd_config1_tiny_f32():
         assert rel_rms_err(got, ref[name]) <= 1e-4, name
 
 
-@pytest.mark.parametrize("B,T,Hq,Hkv,D,W", [(1, 200, 4, 2, 128, 48), (2, 140, 2, 1, 64, 20)])
+@pytest.mark.parametrize("B,T,Hq,Hkv,D,W", [(1, 200, 4, 2, 128, 48), (2, 140, 2, 1, 64, 20),
+                                              # windows of a few keys: near-one-hot softmax rows
+                                              (2, 143, 3, 3, 128, 5), (2, 70, 6, 3, 128, 2), (1, 100, 2, 1, 64, 3)])
 def test_bwd_bf16_shapes(B, T, Hq, Hkv, D, W):
     run_bwd_case(B, T, Hq, Hkv, D, W, "bf16", seed=400 + T)
 
