@@ -14,6 +14,8 @@ Conventions
 * Query head h uses KV head h // (Hq // Hkv)  (Sec. 3.1, group-query variant).
 * phi = softmax over the feature axis (Sec. 3.1 "Parameterization", Sec. 4.5 ablation);
   the paper prints no formula for phi, so this reading is "parity unpinned" by the paper.
+  The ablation's two alternatives are selectable with feature_map="relu" (max(x, 0) per
+  feature) and feature_map="identity" (phi(x) = x); every function takes the argument.
 * RMS epsilon and gains [H, D] per branch (Sec. 3.2) are arguments; the paper gives no
   defaults ("parity unpinned" for eps / gain shape).
 
@@ -34,12 +36,34 @@ def residual_set_1based(t, W):
 
 
 # ----------------------------------------------------------------------------- pieces
-def phi(x):
-    """Feature map: softmax over the last (feature) axis.  Sec. 3.1, Sec. 4.5."""
+FEATURE_MAPS = ("softmax", "relu", "identity")
+
+
+def phi(x, feature_map="softmax"):
+    """Feature map over the last (feature) axis.  Sec. 3.1: softmax (the layer's choice);
+    Sec. 4.5 ablation: ReLU and identity."""
     x = np.asarray(x, dtype=np.float64)
-    m = np.max(x, axis=-1, keepdims=True)
-    e = np.exp(x - m)
-    return e / np.sum(e, axis=-1, keepdims=True)
+    if feature_map == "softmax":
+        m = np.max(x, axis=-1, keepdims=True)
+        e = np.exp(x - m)
+        return e / np.sum(e, axis=-1, keepdims=True)
+    if feature_map == "relu":
+        return np.maximum(x, 0.0)
+    if feature_map == "identity":
+        return x.copy()
+    raise ValueError(f"unknown feature map {feature_map!r}")
+
+
+def phi_bwd(x, f, df, feature_map="softmax"):
+    """Gradient with respect to x of sum(phi(x) * df), f = phi(x), rows on the last axis.
+    softmax: f*(df - <df, f>);  ReLU: df where x > 0 (0 at x = 0);  identity: df."""
+    if feature_map == "softmax":
+        return f * (df - np.sum(df * f, axis=-1, keepdims=True))
+    if feature_map == "relu":
+        return np.where(np.asarray(x) > 0.0, df, 0.0)
+    if feature_map == "identity":
+        return np.array(df, dtype=np.float64)
+    raise ValueError(f"unknown feature map {feature_map!r}")
 
 
 def rms(x, gamma, eps):
@@ -57,7 +81,7 @@ def _gains(g, H, D):
 
 
 # ----------------------------------------------------------------------------- O1: explicit loops
-def fwd_loops(q, k, v, W, scale=1.0, eps=1e-6, gamma_swa=None, gamma_rla=None):
+def fwd_loops(q, k, v, W, scale=1.0, eps=1e-6, gamma_swa=None, gamma_rla=None, feature_map="softmax"):
     """The layer written out token by token (tiny inputs only).
 
     softmax branch: Sec. 2.1 SWA formula;  linear branch: Eq. 4 unrolled with
@@ -85,10 +109,10 @@ def fwd_loops(q, k, v, W, scale=1.0, eps=1e-6, gamma_swa=None, gamma_rla=None):
                         num += wgt * v[b, s, g]
                     xs[b, t, h] = num / e.sum()
                 # explicit sum over the out-of-window tokens
-                qf = phi(qt)
+                qf = phi(qt, feature_map)
                 acc = np.zeros(D)
                 for s in range(0, t - W + 1):
-                    acc += np.dot(qf, phi(k[b, s, g])) * v[b, s, g]
+                    acc += np.dot(qf, phi(k[b, s, g], feature_map)) * v[b, s, g]
                 xr[b, t, h] = acc
                 ys, _ = rms(xs[b, t, h], gs[h], eps)
                 yr, _ = rms(xr[b, t, h], gr[h], eps)
@@ -106,7 +130,7 @@ def _masks(rows, T, W):
 
 
 def fwd_dense(q, k, v, W, scale=1.0, eps=1e-6, gamma_swa=None, gamma_rla=None,
-              rows=None, heads=None, batches=None, row_block=1024):
+              rows=None, heads=None, batches=None, row_block=1024, feature_map="softmax"):
     """Same definition as fwd_loops, with the sums over keys written as masked matrix
     products per head (rows of queries are independent, so they are taken in batches).
 
@@ -127,7 +151,7 @@ def fwd_dense(q, k, v, W, scale=1.0, eps=1e-6, gamma_swa=None, gamma_rla=None,
         for h in heads:
             g = h // G
             kk = k[b, :, g]; vv = v[b, :, g]
-            kf = phi(kk)
+            kf = phi(kk, feature_map)
             for r0 in range(0, len(rows), row_block):
                 rr_ = rows[r0:r0 + row_block]
                 win, res = _masks(rr_, T, W)
@@ -142,7 +166,7 @@ def fwd_dense(q, k, v, W, scale=1.0, eps=1e-6, gamma_swa=None, gamma_rla=None,
                     lse[b, h, rr_] = (m + np.log(z))[:, 0]
                 else:
                     x_s = np.zeros((len(rr_), D))
-                c = np.where(res, phi(qq) @ kf.T, 0.0)
+                c = np.where(res, phi(qq, feature_map) @ kf.T, 0.0)
                 x_r = c @ vv
                 ys, r_s = rms(x_s, gs[h], eps)
                 yr, r_r = rms(x_r, gr[h], eps)
@@ -153,7 +177,7 @@ def fwd_dense(q, k, v, W, scale=1.0, eps=1e-6, gamma_swa=None, gamma_rla=None,
 
 
 # ----------------------------------------------------------------------------- linear branch, other forms
-def rla_recurrent(q, k, v, W):
+def rla_recurrent(q, k, v, W, feature_map="softmax"):
     """Eq. 4 as a recurrence: S_t = S_{t-1} + phi(k_t)^T v_t, readout phi(q_t) S_{t-W}
     (0-based: state that has absorbed keys 0..t-W).  S before any key is 0 (Sec. 2.2)."""
     q = np.asarray(q, np.float64); k = np.asarray(k, np.float64); v = np.asarray(v, np.float64)
@@ -166,12 +190,12 @@ def rla_recurrent(q, k, v, W):
             S = np.zeros((D, D))
             for t in range(T):
                 if t - W >= 0:
-                    S = S + np.outer(phi(k[b, t - W, g]), v[b, t - W, g])
-                out[b, t, h] = phi(q[b, t, h]) @ S
+                    S = S + np.outer(phi(k[b, t - W, g], feature_map), v[b, t - W, g])
+                out[b, t, h] = phi(q[b, t, h], feature_map) @ S
     return out
 
 
-def rla_chunkwise(q, k, v, W, C):
+def rla_chunkwise(q, k, v, W, C, feature_map="softmax"):
     """Eqs. 2-3 at lag W.  Key chunk j holds keys jC..(j+1)C-1; S_[j] is the sum over
     chunks before j; the query paired with key position p = t-W sits in chunk p // C and
     adds the intra-chunk masked product with M[t', s'] = 1 if s' <= t' (diagonal kept,
@@ -192,24 +216,24 @@ def rla_chunkwise(q, k, v, W, C):
             for j in range(nch):
                 lo, hi = j * C, min((j + 1) * C, Tp)
                 n = hi - lo
-                Qt = phi(q[b, lo + W:hi + W, h])
-                Kt = phi(k[b, lo:hi, g]); V = v[b, lo:hi, g]
+                Qt = phi(q[b, lo + W:hi + W, h], feature_map)
+                Kt = phi(k[b, lo:hi, g], feature_map); V = v[b, lo:hi, g]
                 out[b, lo + W:hi + W, h] = Qt @ S + ((Qt @ Kt.T) * M[:n, :n]) @ V
                 S = S + Kt.T @ V
     return out
 
 
-def linear_attention_eq1(q, k, v):
+def linear_attention_eq1(q, k, v, feature_map="softmax"):
     """Eq. 1: o_t = phi(q_t) S_t with S_t the running sum of phi(k)^T v (current token
     included), written with a cumulative sum of outer products.  Single head [T, D]."""
-    kf = phi(k); qf = phi(q)
+    kf = phi(k, feature_map); qf = phi(q, feature_map)
     S = np.cumsum(kf[:, :, None] * np.asarray(v, np.float64)[:, None, :], axis=0)
     return np.einsum('tf,tfd->td', qf, S)
 
 
 # ----------------------------------------------------------------------------- backward
 def bwd_dense(q, k, v, dO, W, scale=1.0, eps=1e-6, gamma_swa=None, gamma_rla=None,
-              heads=None, batches=None, rows=None, row_block=1024):
+              heads=None, batches=None, rows=None, row_block=1024, feature_map="softmax"):
     """Analytic gradient of sum(o * dO) for the layer of fwd_dense.
 
     Epilogue (Sec. 3.2): y = g*x*r, r = (mean x^2 + eps)^-1/2  =>
@@ -217,7 +241,7 @@ def bwd_dense(q, k, v, dO, W, scale=1.0, eps=1e-6, gamma_swa=None, gamma_rla=Non
     Softmax branch (Sec. 2.1): dv_s += p dx,  dp = <dx, v_s>,  da = p (dp - sum p dp),
         dq += scale*da k_s,  dk_s += scale*da q_t.
     Linear branch (Eq. 4 unrolled): dv_s += c dx, dc = <dx, v_s>, dphi(q) += dc phi(k_s),
-        dphi(k_s) += dc phi(q); through phi = softmax: dx_in = f*(df - <df, f>).
+        dphi(k_s) += dc phi(q); then through phi (phi_bwd; for softmax dx_in = f*(df - <df, f>)).
     `rows` restricts the set of query rows whose contributions are included (dq of other
     rows stays 0; dk/dv then hold only the contributions of those rows).
     Returns dict(dq, dk, dv, dgamma_swa, dgamma_rla).
@@ -236,13 +260,13 @@ def bwd_dense(q, k, v, dO, W, scale=1.0, eps=1e-6, gamma_swa=None, gamma_rla=Non
         for h in heads:
             g = h // G
             kk = k[b, :, g]; vv = v[b, :, g]
-            kf = phi(kk)
+            kf = phi(kk, feature_map)
             dkf = np.zeros((T, D))
             for r0 in range(0, len(rows), row_block):
                 rr_ = rows[r0:r0 + row_block]
                 win, res = _masks(rr_, T, W)
                 qq = q[b, rr_, h]; dy = dO[b, rr_, h]
-                qf = phi(qq)
+                qf = phi(qq, feature_map)
                 # forward pieces
                 if W > 0:
                     a = np.where(win, scale * (qq @ kk.T), -np.inf)
@@ -272,14 +296,14 @@ def bwd_dense(q, k, v, dO, W, scale=1.0, eps=1e-6, gamma_swa=None, gamma_rla=Non
                 dc = np.where(res, dxr @ vv.T, 0.0)
                 dqf = dc @ kf
                 dkf += dc.T @ qf
-                dq[b, rr_, h] += qf * (dqf - np.sum(dqf * qf, axis=1, keepdims=True))
-            dk[b, :, g] += kf * (dkf - np.sum(dkf * kf, axis=1, keepdims=True))
+                dq[b, rr_, h] += phi_bwd(qq, qf, dqf, feature_map)
+            dk[b, :, g] += phi_bwd(kk, kf, dkf, feature_map)
     return dict(dq=dq, dk=dk, dv=dv, dgamma_swa=dgs, dgamma_rla=dgr)
 
 
 # ----------------------------------------------------------------------------- decode
 def decode_step(q, k_new, v_new, pos, k_ring, v_ring, state, W, scale=1.0, eps=1e-6,
-                gamma_swa=None, gamma_rla=None):
+                gamma_swa=None, gamma_rla=None, feature_map="softmax"):
     """One generated token per sequence with constant memory (Sec. 2.1 window cache of the
     last W keys, Sec. 2.2 fixed-size state; the paper leaves the procedure to the reader).
 
@@ -303,7 +327,7 @@ def decode_step(q, k_new, v_new, pos, k_ring, v_ring, state, W, scale=1.0, eps=1
         p = int(pos[n]); slot = p % W
         for g in range(Hkv):
             if p >= W:
-                state[n, g] += np.outer(phi(k_ring[n, g, slot]), v_ring[n, g, slot])
+                state[n, g] += np.outer(phi(k_ring[n, g, slot], feature_map), v_ring[n, g, slot])
             k_ring[n, g, slot] = k_new[n, g]; v_ring[n, g, slot] = v_new[n, g]
             nvalid = min(p + 1, W)
             for hh in range(G):
@@ -311,13 +335,13 @@ def decode_step(q, k_new, v_new, pos, k_ring, v_ring, state, W, scale=1.0, eps=1
                 a = scale * (k_ring[n, g, :nvalid] @ q[n, h])
                 e = np.exp(a - a.max())
                 x_s = (e / e.sum()) @ v_ring[n, g, :nvalid]
-                x_r = phi(q[n, h]) @ state[n, g]
+                x_r = phi(q[n, h], feature_map) @ state[n, g]
                 ys, _ = rms(x_s, gs[h], eps); yr, _ = rms(x_r, gr[h], eps)
                 o[n, h] = ys + yr
     return o, k_ring, v_ring, state
 
 
-def prefill_export(k, v, W):
+def prefill_export(k, v, W, feature_map="softmax"):
     """What a decode step at pos = T expects after a prompt of T tokens (the hand-over the paper's
     inference discussion implies, Sec. 2.1 / 2.2 / 4.4): rings with key/value s in slot s % W for the last
     min(T, W) tokens (other slots zero), and the state sum_{s < T-W} phi(k_s)^T v_s (rows = feature,
@@ -332,7 +356,7 @@ def prefill_export(k, v, W):
             for s in range(max(0, T - W), T):
                 k_ring[b, g, s % W] = k[b, s, g]; v_ring[b, g, s % W] = v[b, s, g]
             for s in range(0, T - W):
-                state[b, g] += np.outer(phi(k[b, s, g]), v[b, s, g])
+                state[b, g] += np.outer(phi(k[b, s, g], feature_map), v[b, s, g])
     return k_ring, v_ring, state
 
 

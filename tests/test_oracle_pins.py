@@ -347,3 +347,127 @@ def test_prefill_export_state_is_cumulative_outer_products():
     _, _, S = orc.prefill_export(k, v, 5)
     f = np.exp(k[0, :7, 0]); f /= f.sum(axis=1, keepdims=True)      # softmax rows of the 7 out-of-window keys
     assert np.allclose(S[0, 0], f.T @ v[0, :7, 0], rtol=1e-12, atol=1e-12)
+
+
+# ------------------------------------------------------------------------------ feature-map variants (Sec. 4.5 ablation)
+TORCH_PHI = {"softmax": lambda x: torch.softmax(x, -1), "relu": torch.relu, "identity": lambda x: x}
+NUMPY_PHI = {"softmax": lambda x: scipy.special.softmax(x, axis=-1), "relu": lambda x: np.where(x > 0, x, 0.0),
+             "identity": lambda x: x}
+VARIANTS = ("relu", "identity")
+
+
+def test_variant_feature_maps_on_printed_values():
+    x = np.array([[-1.5, 0.0, 2.0, -0.0, 3.25]])
+    assert np.array_equal(orc.phi(x, "relu"), [[0.0, 0.0, 2.0, 0.0, 3.25]])
+    assert np.array_equal(orc.phi(x, "identity"), x)
+    assert orc.phi(x, "identity") is not x
+    with pytest.raises(ValueError):
+        orc.phi(x, "elu")
+    # gradients through phi against autograd, every map
+    rng = np.random.default_rng(40)
+    xx = rng.standard_normal((6, 9)); df = rng.standard_normal((6, 9))
+    for name, fn in TORCH_PHI.items():
+        t = torch.tensor(xx, requires_grad=True)
+        (fn(t) * torch.from_numpy(df)).sum().backward()
+        np.testing.assert_allclose(orc.phi_bwd(xx, orc.phi(xx, name), df, name), t.grad.numpy(), rtol=1e-12, atol=1e-14,
+                                   err_msg=name)
+
+
+@pytest.mark.parametrize("fm", VARIANTS)
+@pytest.mark.parametrize("W,C", [(0, 4), (3, 4), (8, 8), (7, 16), (40, 8)])
+def test_variant_linear_branch_forms_agree_and_match_cumulative_sums(fm, W, C):
+    """Recurrent (Eq. 4), masked and chunkwise (Eqs. 2-3) forms agree for the ablation's maps, and all equal the
+    textbook expression phi(q_t) . cumsum_s(phi(k_s)^T v_s)[t - W] written with library cumsum/einsum."""
+    rng = np.random.default_rng(41)
+    q, k, v = rand_layer(rng, 2, 37, 4, 2, 8)
+    rec = orc.rla_recurrent(q, k, v, W, feature_map=fm)
+    dense = orc.fwd_dense(q, k, v, W, feature_map=fm)["xr"]
+    chk = orc.rla_chunkwise(q, k, v, W, C, feature_map=fm)
+    loops = orc.fwd_loops(q[:1, :12], k[:1, :12], v[:1, :12], W, feature_map=fm)["xr"]
+    np.testing.assert_allclose(rec, dense, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(chk, dense, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(loops, dense[:1, :12], rtol=1e-11, atol=1e-12)
+    f = NUMPY_PHI[fm]
+    S = np.cumsum(np.einsum('btgf,btgd->btgfd', f(k), v), axis=1)            # S[b, s] = sum over keys <= s
+    G = q.shape[2] // k.shape[2]
+    for t in (0, W, W + 1, 20, 36):
+        if t >= 37:
+            continue
+        for h in range(q.shape[2]):
+            ref = np.zeros((2, 8)) if t - W < 0 else np.einsum('bf,bfd->bd', f(q[:, t, h]), S[:, t - W, h // G])
+            np.testing.assert_allclose(dense[:, t, h], ref, rtol=1e-11, atol=1e-12)
+
+
+def test_variant_special_cases():
+    rng = np.random.default_rng(42)
+    q, k, v = rand_layer(rng, 1, 20, 2, 1, 6)
+    # positive q and k: ReLU is the identity map
+    a = orc.fwd_dense(np.abs(q), np.abs(k), v, 5, feature_map="relu")
+    b = orc.fwd_dense(np.abs(q), np.abs(k), v, 5, feature_map="identity")
+    np.testing.assert_allclose(a["o"], b["o"], rtol=1e-13, atol=0)
+    # keys with no positive feature contribute nothing under ReLU: the linear branch vanishes, and o = RMS_s(x^s)
+    c = orc.fwd_dense(q, -np.abs(k), v, 5, feature_map="relu")
+    assert np.all(c["xr"] == 0.0)
+    np.testing.assert_allclose(c["o"], orc.rms(c["xs"], 1.0, 1e-6)[0], rtol=1e-13, atol=0)
+    # identity: the branch is bilinear in (q, k) - softmax is not - and the softmax branch does not depend on the map
+    d1 = orc.fwd_dense(q, k, v, 5, feature_map="identity")
+    d2 = orc.fwd_dense(2.0 * q, k, v, 5, feature_map="identity")
+    d3 = orc.fwd_dense(q, -3.0 * k, v, 5, feature_map="identity")
+    np.testing.assert_allclose(d2["xr"], 2.0 * d1["xr"], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(d3["xr"], -3.0 * d1["xr"], rtol=1e-12, atol=1e-13)
+    s0 = orc.fwd_dense(q, k, v, 5)
+    assert np.array_equal(s0["xs"], d1["xs"]) and np.array_equal(s0["lse"], d1["lse"])
+    assert not np.allclose(s0["xr"], d1["xr"])
+
+
+def torch_layer_fm(q, k, v, W, scale, eps, gs, gr, fm):
+    """torch_layer with the feature map of the linear branch exchanged."""
+    B, T, Hq, D = q.shape
+    G = Hq // k.shape[2]
+    kx = k.repeat_interleave(G, dim=2); vx = v.repeat_interleave(G, dim=2)
+    t = torch.arange(T)[:, None]; s = torch.arange(T)[None, :]
+    win = (s <= t) & (s > t - W); res = s <= t - W
+    a = (torch.einsum('bthd,bshd->bhts', q, kx) * scale).masked_fill(~win, float('-inf'))
+    xs = torch.einsum('bhts,bshd->bthd', torch.softmax(a, dim=-1), vx)
+    c = torch.einsum('bthd,bshd->bhts', TORCH_PHI[fm](q), TORCH_PHI[fm](kx)) * res
+    xr = torch.einsum('bhts,bshd->bthd', c, vx)
+    n = lambda x, g: g * x * torch.rsqrt((x * x).mean(-1, keepdim=True) + eps)
+    return n(xs, gs) + n(xr, gr)
+
+
+@pytest.mark.parametrize("fm", VARIANTS)
+@pytest.mark.parametrize("W,Hq,Hkv", [(1, 2, 2), (4, 4, 2), (7, 3, 1)])
+def test_variant_backward_matches_autograd(fm, W, Hq, Hkv):
+    rng = np.random.default_rng(43)
+    B, T, D = 2, 21, 8
+    q, k, v = rand_layer(rng, B, T, Hq, Hkv, D)
+    dO = rng.standard_normal(q.shape)
+    gs = 1 + 0.3 * rng.standard_normal((Hq, D)); gr = 1 + 0.3 * rng.standard_normal((Hq, D))
+    scale, eps = 0.4, 1e-5
+    g = orc.bwd_dense(q, k, v, dO, W, scale=scale, eps=eps, gamma_swa=gs, gamma_rla=gr, feature_map=fm)
+    tq, tk, tv, tgs, tgr = [torch.tensor(x, requires_grad=True) for x in (q, k, v, gs, gr)]
+    out = torch_layer_fm(tq, tk, tv, W, scale, eps, tgs, tgr, fm)
+    ref = orc.fwd_dense(q, k, v, W, scale=scale, eps=eps, gamma_swa=gs, gamma_rla=gr, feature_map=fm)["o"]
+    np.testing.assert_allclose(out.detach().numpy(), ref, rtol=1e-10, atol=1e-12)
+    out.backward(torch.from_numpy(dO))
+    for name, tt in (("dq", tq), ("dk", tk), ("dv", tv), ("dgamma_swa", tgs), ("dgamma_rla", tgr)):
+        np.testing.assert_allclose(g[name], tt.grad.numpy(), rtol=1e-9, atol=1e-11, err_msg=name)
+
+
+@pytest.mark.parametrize("fm", VARIANTS)
+def test_variant_decode_chain_and_export(fm):
+    rng = np.random.default_rng(44)
+    N, T, Hq, Hkv, D, W = 2, 15, 4, 2, 6, 4
+    q, k, v = rand_layer(rng, N, T, Hq, Hkv, D)
+    ref = orc.fwd_dense(q, k, v, W, scale=0.5, feature_map=fm)["o"]
+    kr = np.zeros((N, Hkv, W, D)); vr = np.zeros((N, Hkv, W, D)); S = np.zeros((N, Hkv, D, D))
+    for t in range(T):
+        if t == 11:
+            kr2, vr2, S2 = orc.prefill_export(k[:, :t], v[:, :t], W, feature_map=fm)
+            assert np.array_equal(kr, kr2) and np.array_equal(vr, vr2)
+            np.testing.assert_allclose(S, S2, rtol=1e-12, atol=1e-13)
+        o, kr, vr, S = orc.decode_step(q[:, t], k[:, t], v[:, t], np.full(N, t), kr, vr, S, W, scale=0.5,
+                                       feature_map=fm)
+        np.testing.assert_allclose(o, ref[:, t], rtol=1e-10, atol=1e-12)
+    Sref = np.einsum('nsgf,nsgd->ngfd', NUMPY_PHI[fm](k[:, :T - W]), v[:, :T - W])
+    np.testing.assert_allclose(S, Sref, rtol=1e-11, atol=1e-13)
