@@ -46,6 +46,11 @@ typedef enum {
 
 typedef enum { RATTN_F32 = 0, RATTN_BF16 = 1 } rattn_dtype;
 
+/* Feature map phi of the linear branch, applied to every q and k row over its D features.  The layer uses the
+ * softmax map (Sec. 3.1, "Parameterization"); the other two are the alternatives of the ablation (Sec. 4.5):
+ * ReLU = max(x, 0) per feature, identity = x.  Zero-initialised parameter structs select the softmax map. */
+typedef enum { RATTN_PHI_SOFTMAX = 0, RATTN_PHI_RELU = 1, RATTN_PHI_IDENTITY = 2 } rattn_feature_map;
+
 typedef struct {
   int32_t B, T, Hq, Hkv, D;
   int32_t window;        /* W >= 1 (see conventions)                                                   */
@@ -55,6 +60,8 @@ typedef struct {
   float softmax_scale;   /* multiplies q.k in the softmax branch only (the paper's formula is 1.0)     */
   float rms_eps;         /* > 0                                                                        */
   int32_t save_for_bwd;  /* rattn_fwd also fills `saved` (needed by rattn_bwd)                         */
+  int32_t feature_map;   /* rattn_feature_map; RATTN_PHI_RELU / RATTN_PHI_IDENTITY run on the general
+                            (vector-ALU) kernels for every shape                                       */
 } rattn_params;
 
 /* Sizes in bytes of the scratch `workspace` rattn_fwd / rattn_bwd need and of the opaque
@@ -94,6 +101,7 @@ typedef struct {
   int32_t dtype;         /* of q, k_new, v_new, rings, o                             */
   float softmax_scale;
   float rms_eps;
+  int32_t feature_map;   /* rattn_feature_map, as in rattn_params                    */
 } rattn_decode_params;
 
 /* One generated token per sequence with constant memory (Sec. 2.1: a cache of the last W

@@ -12,6 +12,8 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "librattn.so")
 
 RATTN_F32, RATTN_BF16 = 0, 1
+# rattn_feature_map: the layer's softmax map (Sec. 3.1) and the ablation's two alternatives (Sec. 4.5)
+FEATURE_MAPS = {"softmax": 0, "relu": 1, "identity": 2}
 _DTYPES = {torch.float32: RATTN_F32, torch.bfloat16: RATTN_BF16}
 
 EXPORTS = ["rattn_workspace_bytes", "rattn_fwd", "rattn_bwd", "rattn_decode_step",
@@ -26,13 +28,13 @@ class RattnParams(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("T", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
                 ("D", ctypes.c_int32), ("window", ctypes.c_int32), ("chunk", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("rms_eps", ctypes.c_float),
-                ("save_for_bwd", ctypes.c_int32)]
+                ("save_for_bwd", ctypes.c_int32), ("feature_map", ctypes.c_int32)]
 
 
 class RattnDecodeParams(ctypes.Structure):
     _fields_ = [("N", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("D", ctypes.c_int32),
                 ("window", ctypes.c_int32), ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
-                ("rms_eps", ctypes.c_float)]
+                ("rms_eps", ctypes.c_float), ("feature_map", ctypes.c_int32)]
 
 
 class RattnError(RuntimeError):
@@ -104,10 +106,10 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def make_params(q, k, window, chunk=0, softmax_scale=1.0, rms_eps=1e-6, save_for_bwd=False):
+def make_params(q, k, window, chunk=0, softmax_scale=1.0, rms_eps=1e-6, save_for_bwd=False, feature_map="softmax"):
     B, T, Hq, D = q.shape
     return RattnParams(B, T, Hq, k.shape[2], D, window, chunk, _DTYPES[q.dtype], softmax_scale, rms_eps,
-                       1 if save_for_bwd else 0)
+                       1 if save_for_bwd else 0, FEATURE_MAPS[feature_map])
 
 
 def rattn_workspace_bytes(params):
@@ -141,12 +143,12 @@ def _bytes(n, dev):
 
 
 def rattn_fwd(q, k, v, window, gamma_swa=None, gamma_rla=None, chunk=0, softmax_scale=1.0, rms_eps=1e-6,
-              save_for_bwd=False, out=None, saved=None, workspace=None):
+              save_for_bwd=False, out=None, saved=None, workspace=None, feature_map="softmax"):
     """o = RMS(SWA(q,k,v)) + RMS(RLA(q,k,v)); returns o, or (o, saved) when save_for_bwd.
 
     out / saved / workspace may be passed in to reuse buffers (uint8 tensors for the latter two)."""
     _check_layer(q, k, v)
-    p = make_params(q, k, window, chunk, softmax_scale, rms_eps, save_for_bwd)
+    p = make_params(q, k, window, chunk, softmax_scale, rms_eps, save_for_bwd, feature_map)
     fwd_b, _, saved_b = rattn_workspace_bytes(p)
     dev = q.device
     o = torch.empty_like(q) if out is None else out
@@ -162,12 +164,12 @@ def rattn_fwd(q, k, v, window, gamma_swa=None, gamma_rla=None, chunk=0, softmax_
 
 
 def rattn_bwd(q, k, v, saved, dO, window, gamma_swa=None, gamma_rla=None, chunk=0, softmax_scale=1.0,
-              rms_eps=1e-6, want_dgamma=True, workspace=None, out=None):
+              rms_eps=1e-6, want_dgamma=True, workspace=None, out=None, feature_map="softmax"):
     """(dq, dk, dv, dgamma_swa, dgamma_rla) for upstream gradient dO; `saved` from rattn_fwd."""
     _check_layer(q, k, v)
     if dO.shape != q.shape or dO.dtype != q.dtype or not dO.is_contiguous():
         raise ValueError("dO must match q")
-    p = make_params(q, k, window, chunk, softmax_scale, rms_eps, True)
+    p = make_params(q, k, window, chunk, softmax_scale, rms_eps, True, feature_map)
     _, bwd_b, saved_b = rattn_workspace_bytes(p)
     if saved is None or saved.numel() < saved_b:
         raise ValueError("saved buffer missing or too small")
@@ -189,7 +191,7 @@ def rattn_bwd(q, k, v, saved, dO, window, gamma_swa=None, gamma_rla=None, chunk=
 
 
 def rattn_decode_step(q, k_new, v_new, pos, k_ring, v_ring, state, gamma_swa=None, gamma_rla=None,
-                      softmax_scale=1.0, rms_eps=1e-6, out=None):
+                      softmax_scale=1.0, rms_eps=1e-6, out=None, feature_map="softmax"):
     """One decode step; k_ring, v_ring, state are updated in place; returns o [N,Hq,D]."""
     N, Hq, D = q.shape
     Hkv, W = k_ring.shape[1], k_ring.shape[2]
@@ -204,7 +206,7 @@ def rattn_decode_step(q, k_new, v_new, pos, k_ring, v_ring, state, gamma_swa=Non
         raise ValueError("state must be float32 and pos int32")
     if q.dtype not in _DTYPES or any(t.dtype != q.dtype for t in (k_new, v_new, k_ring, v_ring)):
         raise ValueError("q, k_new, v_new and the rings must share dtype float32 or bfloat16")
-    p = RattnDecodeParams(N, Hq, Hkv, D, W, _DTYPES[q.dtype], softmax_scale, rms_eps)
+    p = RattnDecodeParams(N, Hq, Hkv, D, W, _DTYPES[q.dtype], softmax_scale, rms_eps, FEATURE_MAPS[feature_map])
     o = torch.empty_like(q) if out is None else out
     gs = _gain(gamma_swa, Hq, D, q.device)
     gr = _gain(gamma_rla, Hq, D, q.device)
@@ -213,7 +215,7 @@ def rattn_decode_step(q, k_new, v_new, pos, k_ring, v_ring, state, gamma_swa=Non
     return o
 
 
-def rattn_prefill_export(k, v, window, k_ring=None, v_ring=None, state=None):
+def rattn_prefill_export(k, v, window, k_ring=None, v_ring=None, state=None, feature_map="softmax"):
     """Rings and lagged state a decode step at pos = T expects after the prompt k, v [B,T,Hkv,D].
     Returns (k_ring [B,Hkv,W,D], v_ring, state [B,Hkv,D,D] fp32); ring slots the prompt does not reach are zero
     when the rings are allocated here."""
@@ -223,7 +225,7 @@ def rattn_prefill_export(k, v, window, k_ring=None, v_ring=None, state=None):
             raise ValueError(f"{name} must be a contiguous device tensor")
     if v.shape != k.shape or v.dtype != k.dtype or k.dtype not in _DTYPES:
         raise ValueError("k and v must share shape and dtype float32 or bfloat16")
-    p = RattnParams(B, T, Hkv, Hkv, D, window, 0, _DTYPES[k.dtype], 1.0, 1e-6, 0)
+    p = RattnParams(B, T, Hkv, Hkv, D, window, 0, _DTYPES[k.dtype], 1.0, 1e-6, 0, FEATURE_MAPS[feature_map])
     if k_ring is None:
         k_ring = torch.zeros(B, Hkv, window, D, dtype=k.dtype, device=k.device)
     if v_ring is None:
@@ -239,7 +241,7 @@ def rattn_prefill_export(k, v, window, k_ring=None, v_ring=None, state=None):
 
 
 def rattn_prefill_chunk(q, k, v, window, pos0, k_ring, v_ring, state, gamma_swa=None, gamma_rla=None, chunk=0,
-                        softmax_scale=1.0, rms_eps=1e-6, workspace=None, out=None):
+                        softmax_scale=1.0, rms_eps=1e-6, workspace=None, out=None, feature_map="softmax"):
     """Layer output for tokens pos0 .. pos0+T-1 (q [B,T,Hq,D], k, v [B,T,Hkv,D]) of sequences whose first pos0
     tokens live in k_ring, v_ring [B,Hkv,W,D] and state [B,Hkv,D,D] fp32; those three are updated in place to
     position pos0 + T.  Returns o [B,T,Hq,D]."""
@@ -254,7 +256,7 @@ def rattn_prefill_chunk(q, k, v, window, pos0, k_ring, v_ring, state, gamma_swa=
         raise ValueError("k_ring, v_ring must be [B,Hkv,window,D] in the dtype of q")
     if tuple(state.shape) != (B, Hkv, D, D) or state.dtype != torch.float32:
         raise ValueError("state must be fp32 [B,Hkv,D,D]")
-    p = make_params(q, k, window, chunk, softmax_scale, rms_eps, False)
+    p = make_params(q, k, window, chunk, softmax_scale, rms_eps, False, feature_map)
     nbytes = ctypes.c_size_t()
     _check(lib().rattn_prefill_chunk_workspace_bytes(ctypes.byref(p), int(pos0), ctypes.byref(nbytes)))
     if workspace is None:

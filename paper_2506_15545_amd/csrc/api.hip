@@ -85,6 +85,8 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
   if (p->window < 1) return fail(RATTN_ERR_INVALID_ARG, "window must be >= 1 (got %d)", p->window);
   if (p->chunk < 0) return fail(RATTN_ERR_INVALID_ARG, "chunk must be >= 0 (got %d)", p->chunk);
   if (p->dtype != RATTN_F32 && p->dtype != RATTN_BF16) return fail(RATTN_ERR_UNSUPPORTED, "unknown dtype %d", p->dtype);
+  if (p->feature_map < RATTN_PHI_SOFTMAX || p->feature_map > RATTN_PHI_IDENTITY)
+    return fail(RATTN_ERR_UNSUPPORTED, "unknown feature_map %d", p->feature_map);
   if (!(p->rms_eps > 0.f)) return fail(RATTN_ERR_INVALID_ARG, "rms_eps must be > 0");
   if (!(p->softmax_scale == p->softmax_scale) || p->softmax_scale == 0.f)
     return fail(RATTN_ERR_INVALID_ARG, "softmax_scale must be a non-zero number");
@@ -97,7 +99,7 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
   dm.C = p->chunk > 0 ? p->chunk : 64;
   const int Tp = p->T > p->window ? p->T - p->window : 0;
   dm.nst = Tp > 0 ? (Tp - 1) / dm.C + 1 : 0;
-  dm.scale = p->softmax_scale; dm.eps = p->rms_eps;
+  dm.scale = p->softmax_scale; dm.eps = p->rms_eps; dm.phi = p->feature_map;
   L->esize = p->dtype == RATTN_F32 ? 4 : 2;
 
   L->dmf = dm;
@@ -112,8 +114,11 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
   const size_t nq_f = (size_t)dmf.B * dmf.T * dmf.Hq * dmf.D, nkv_f = (size_t)dmf.B * dmf.T * dmf.Hkv * dmf.D;
   const size_t nrow_f = (size_t)dmf.B * dmf.Hq * dmf.T;
   size_t off = 0;
-  L->sv_xs = off; off += align_up(nq_f * L->esize);
-  L->sv_xr = off; off += align_up(nq_f * L->esize);
+  // pre-norm branch outputs: tensor dtype where the matrix-core kernels may run (the general kernels, if forced,
+  // then store the tensor dtype too), fp32 where only the general kernels can
+  const size_t sv_esize = L->fast_fwd ? L->esize : 4;
+  L->sv_xs = off; off += align_up(nq_f * sv_esize);
+  L->sv_xr = off; off += align_up(nq_f * sv_esize);
   L->sv_lse = off; off += align_up(nrow_f * 4);
   L->sv_rs = off; off += align_up(nrow_f * 4);
   L->sv_rr = off; off += align_up(nrow_f * 4);
@@ -179,7 +184,7 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
 }
 
 rattn::SavedPtrs saved_views(const Layout& L, void* saved) {
-  rattn::SavedPtrs sv = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  rattn::SavedPtrs sv = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, !L.fast_fwd};
   if (saved) {
     char* s = (char*)saved;
     sv.xs = s + L.sv_xs; sv.xr = s + L.sv_xr;
@@ -366,6 +371,8 @@ rattn_status rattn_decode_step(const rattn_decode_params* p, const void* q, cons
   if (p->D != 64 && p->D != 128) return fail(RATTN_ERR_UNSUPPORTED, "head_dim D must be 64 or 128 (got %d)", p->D);
   if (p->window < 1) return fail(RATTN_ERR_INVALID_ARG, "window must be >= 1 (got %d)", p->window);
   if (p->dtype != RATTN_F32 && p->dtype != RATTN_BF16) return fail(RATTN_ERR_UNSUPPORTED, "unknown dtype %d", p->dtype);
+  if (p->feature_map < RATTN_PHI_SOFTMAX || p->feature_map > RATTN_PHI_IDENTITY)
+    return fail(RATTN_ERR_UNSUPPORTED, "unknown feature_map %d", p->feature_map);
   if (!(p->rms_eps > 0.f)) return fail(RATTN_ERR_INVALID_ARG, "rms_eps must be > 0");
   if (!(p->softmax_scale == p->softmax_scale) || p->softmax_scale == 0.f)
     return fail(RATTN_ERR_INVALID_ARG, "softmax_scale must be a non-zero number");
@@ -379,7 +386,7 @@ rattn_status rattn_decode_step(const rattn_decode_params* p, const void* q, cons
     return fail(RATTN_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
   rattn::DecodeDims dd;
   dd.N = p->N; dd.Hq = p->Hq; dd.Hkv = p->Hkv; dd.D = p->D; dd.W = p->window; dd.G = p->Hq / p->Hkv;
-  dd.scale = p->softmax_scale; dd.eps = p->rms_eps;
+  dd.scale = p->softmax_scale; dd.eps = p->rms_eps; dd.phi = p->feature_map;
   rattn::decode_step(dd, p->dtype, q, k_new, v_new, pos, k_ring, v_ring, state, gamma_swa, gamma_rla, o,
                      (hipStream_t)stream);
   return check_launch("rattn_decode_step");
@@ -441,7 +448,7 @@ rattn_status rattn_prefill_chunk(const rattn_params* p, int32_t pos0, const void
   // state) the carried state enters as the initial value of the state scan.  Only K and V are gathered.
   if (C.L2.fast_fwd && !C.L2.pad && !force_generic() && C.R % 128 == 0 && (!carried || p->window % 128 == 0)) {
     rattn::chunk_concat(dm, p->dtype, p->T, C.R, pos0, nullptr, k, v, k_ring, v_ring, nullptr, w + C.kc, w + C.vc, st);
-    rattn::SavedPtrs none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    rattn::SavedPtrs none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, false};
     rattn::fast_fwd(dm, q, w + C.kc, w + C.vc, gamma_swa, gamma_rla, o, none, (float*)(w + C.fwdws + C.L2.ff_u),
                     w + C.fwdws + C.L2.ff_states, st, C.R / 128, carried ? state : nullptr);
     rattn::prefill_export(dm, p->dtype, w + C.kc, w + C.vc, k_ring, v_ring, state, (float*)(w + C.partial), st,

@@ -68,15 +68,15 @@ __global__ __launch_bounds__(256) void chunk_copy_out_kernel(const uint4* __rest
 
 // New rows with the carried state added to the linear branch.  grid (ceil(Tc / 64), Hq, B), 256 threads: the
 // work-group stages S0[b, g] (fp32 [feature][value]) in LDS, every wave takes 16 rows, a lane owns value columns
-// lane and lane + 64.  Per row: phi(q) (softmax over the D features), x_r = x_r(saved) + phi(q) S0, second RMS
+// lane and lane + 64.  Per row: phi(q) (softmax over the D features, or the ablation's ReLU / identity), x_r = x_r(saved) + phi(q) S0, second RMS
 // recomputed, o = gs * x_s * r_s + gr * x_r * r_r (Sec. 3.2) with x_s, r_s as the forward saved them (in tensors of
 // Ls >= R + Tc rows per sequence: the forward may have run on a zero-padded copy).
-template <typename IO, int D>
-__global__ __launch_bounds__(256) void chunk_fixup_kernel(const IO* __restrict__ qc, const IO* __restrict__ xs,
-                                                          const IO* __restrict__ xr, const float* __restrict__ rs,
+template <typename IO, typename ST, int D>
+__global__ __launch_bounds__(256) void chunk_fixup_kernel(const IO* __restrict__ qc, const ST* __restrict__ xs,
+                                                          const ST* __restrict__ xr, const float* __restrict__ rs,
                                                           const float* __restrict__ state, const float* __restrict__ gs,
                                                           const float* __restrict__ gr, IO* __restrict__ o, int Tc, int R,
-                                                          int Ls, int Hq, int Hkv, float eps) {
+                                                          int Ls, int Hq, int Hkv, float eps, int phi) {
   constexpr int NE = D / 64;  // elements per lane
   extern __shared__ __align__(16) float s0[];  // [D][D]
   const int hq = blockIdx.y, b = blockIdx.z, G = Hq / Hkv, g = hq / G;
@@ -102,19 +102,10 @@ __global__ __launch_bounds__(256) void chunk_fixup_kernel(const IO* __restrict__
     float x[NE];
 #pragma unroll
     for (int e = 0; e < NE; ++e) x[e] = io_traits<IO>::ld(qc + roff + lane + 64 * e);
-    float m = x[0];
-#pragma unroll
-    for (int e = 1; e < NE; ++e) m = fmaxf(m, x[e]);
-    m = wave_max(m);
-    float sum = 0.f;
-#pragma unroll
-    for (int e = 0; e < NE; ++e) { x[e] = expf(x[e] - m); sum += x[e]; }
-    const float inv = 1.f / wave_sum(sum);
-#pragma unroll
-    for (int e = 0; e < NE; ++e) x[e] *= inv;
+    feature_row<NE>(x, x, phi);
     float acc[NE];
 #pragma unroll
-    for (int e = 0; e < NE; ++e) acc[e] = io_traits<IO>::ld(xr + soff + lane + 64 * e);
+    for (int e = 0; e < NE; ++e) acc[e] = io_traits<ST>::ld(xr + soff + lane + 64 * e);
 #pragma unroll
     for (int fe = 0; fe < NE; ++fe) {
       for (int fl = 0; fl < 64; ++fl) {
@@ -132,7 +123,7 @@ __global__ __launch_bounds__(256) void chunk_fixup_kernel(const IO* __restrict__
     const size_t ooff = ((size_t)(b * Tc + t) * Hq + hq) * D;
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
-      const float a = io_traits<IO>::ld(xs + soff + lane + 64 * e);
+      const float a = io_traits<ST>::ld(xs + soff + lane + 64 * e);
       io_traits<IO>::st(o + ooff + lane + 64 * e, g1[e] * a * r_s + g2[e] * acc[e] * r_r);
     }
   }
@@ -252,7 +243,7 @@ void chunk_copy_out(const LayerDims& dmc, int dtype, int Tc, int R, const void* 
 void chunk_fixup(const LayerDims& dmc, int dtype, int Tc, int R, int Ls, const void* qc, const SavedPtrs& sv,
                  const float* state, const float* gs, const float* gr, void* o, hipStream_t st) {
   ProfScope ps("chunk_fixup_kernel", st);
-  if (dtype == 1 && dmc.D == 128 && dmc.T % 128 == 0 && Ls == dmc.T) {
+  if (dtype == 1 && dmc.D == 128 && dmc.T % 128 == 0 && Ls == dmc.T && dmc.phi == PHI_SOFTMAX && !sv.f32) {
     const dim3 tiles(dmc.T / 128 - R / 128, dmc.Hq, dmc.B);
     chunk_fixup_mfma_kernel<<<tiles, 256, 0, st>>>((const uint16_t*)qc, (const uint16_t*)sv.xs, (const uint16_t*)sv.xr, sv.rs,
                                                    state, gs, gr, (uint16_t*)o, Tc, R, dmc.Hq, dmc.Hkv, dmc.eps);
@@ -260,13 +251,15 @@ void chunk_fixup(const LayerDims& dmc, int dtype, int Tc, int R, int Ls, const v
   }
   const dim3 grid((Tc + 63) / 64, dmc.Hq, dmc.B);
   const size_t lds = (size_t)dmc.D * dmc.D * sizeof(float);
-#define RATTN_FIXUP(IO, DD)                                                                                          \
-  chunk_fixup_kernel<IO, DD><<<grid, 256, lds, st>>>((const IO*)qc, (const IO*)sv.xs, (const IO*)sv.xr, sv.rs, state, gs, \
-                                                     gr, (IO*)o, Tc, R, Ls, dmc.Hq, dmc.Hkv, dmc.eps)
+#define RATTN_FIXUP(IO, ST, DD)                                                                                      \
+  chunk_fixup_kernel<IO, ST, DD><<<grid, 256, lds, st>>>((const IO*)qc, (const ST*)sv.xs, (const ST*)sv.xr, sv.rs, state, \
+                                                         gs, gr, (IO*)o, Tc, R, Ls, dmc.Hq, dmc.Hkv, dmc.eps, dmc.phi)
   if (dtype == 0) {
-    if (dmc.D == 64) RATTN_FIXUP(float, 64); else RATTN_FIXUP(float, 128);
+    if (dmc.D == 64) RATTN_FIXUP(float, float, 64); else RATTN_FIXUP(float, float, 128);
+  } else if (sv.f32) {
+    if (dmc.D == 64) RATTN_FIXUP(bf16_t, float, 64); else RATTN_FIXUP(bf16_t, float, 128);
   } else {
-    if (dmc.D == 64) RATTN_FIXUP(bf16_t, 64); else RATTN_FIXUP(bf16_t, 128);
+    if (dmc.D == 64) RATTN_FIXUP(bf16_t, bf16_t, 64); else RATTN_FIXUP(bf16_t, bf16_t, 128);
   }
 #undef RATTN_FIXUP
 }

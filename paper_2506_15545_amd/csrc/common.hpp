@@ -57,6 +57,38 @@ __device__ __forceinline__ float wave_max(float x) {
 __device__ __forceinline__ float bcast(float x, int l) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), l));
 }
+// Feature map of the linear branch: softmax over the features (Sec. 3.1), or the ablation's ReLU / identity
+// (Sec. 4.5).  Every map is written phi(x)[f] = feat(x[f], m) / z with row statistics (m, z): the row maximum and
+// the sum of exponentials for softmax, (0, 1) for the other two.  `phi` is uniform over a launch.
+enum { PHI_SOFTMAX = 0, PHI_RELU = 1, PHI_IDENTITY = 2 };
+__device__ __forceinline__ float feat(float x, float m, int phi) {
+  if (phi == PHI_SOFTMAX) return expf(x - m);
+  return phi == PHI_RELU ? fmaxf(x, 0.f) : x;
+}
+// d/dx of sum_f phi(x)[f] df[f] for one element: x the input, f = phi(x)[f], inner = <df, phi(x)> (softmax only)
+__device__ __forceinline__ float feat_bwd(float x, float f, float df, float inner, int phi) {
+  if (phi == PHI_SOFTMAX) return f * (df - inner);
+  return (phi == PHI_IDENTITY || x > 0.f) ? df : 0.f;
+}
+// phi of a row of 64*EPL features spread over the wave (element d in lane d % 64, register d / 64)
+template <int EPL>
+__device__ __forceinline__ void feature_row(const float (&x)[EPL], float (&f)[EPL], int phi) {
+  if (phi == PHI_SOFTMAX) {
+    float m = x[0];
+#pragma unroll
+    for (int e = 1; e < EPL; ++e) m = fmaxf(m, x[e]);
+    m = wave_max(m);
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) { f[e] = expf(x[e] - m); s += f[e]; }
+    s = 1.f / wave_sum(s);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) f[e] *= s;
+  } else {
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) f[e] = phi == PHI_RELU ? fmaxf(x[e], 0.f) : x[e];
+  }
+}
 __device__ __forceinline__ int wave_id() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63); }
 

@@ -49,21 +49,17 @@ __global__ __launch_bounds__(256) void decode_kernel(const IO* __restrict__ q, c
       float x[EPL];
       const IO* src = item < nh ? q + (size_t)(n * Hq + g * G + hb + item) * D : kr + (size_t)slot * D;
       if (item < nh || evict) {
-        float m = -INFINITY;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) { x[e] = io_traits<IO>::ld(src + lane + 64 * e); m = fmaxf(m, x[e]); }
-        m = wave_max(m);
-        float ex[EPL], s = 0.f;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) { ex[e] = expf(x[e] - m); s += ex[e]; }
-        s = 1.f / wave_sum(s);
+        for (int e = 0; e < EPL; ++e) x[e] = io_traits<IO>::ld(src + lane + 64 * e);
+        float ex[EPL];
+        feature_row<EPL>(x, ex, dd.phi);
         if (item < nh) {
 #pragma unroll
-          for (int e = 0; e < EPL; ++e) { qs[item][lane + 64 * e] = x[e]; qf[item][lane + 64 * e] = ex[e] * s; }
+          for (int e = 0; e < EPL; ++e) { qs[item][lane + 64 * e] = x[e]; qf[item][lane + 64 * e] = ex[e]; }
         } else {
 #pragma unroll
           for (int e = 0; e < EPL; ++e) {
-            kfo[lane + 64 * e] = ex[e] * s;
+            kfo[lane + 64 * e] = ex[e];
             vo[lane + 64 * e] = io_traits<IO>::ld(vr + (size_t)slot * D + lane + 64 * e);
           }
         }
@@ -272,21 +268,17 @@ __global__ __launch_bounds__(256, 4) void decode_kernel_2pass(const IO* __restri
     float x[EPL];
     const IO* src = item < G ? q + (size_t)(n * Hq + g * G + item) * D : kr + (size_t)slot * D;
     if (item < G || evict) {
-      float m = -INFINITY;
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) { x[e] = io_traits<IO>::ld(src + lane + 64 * e); m = fmaxf(m, x[e]); }
-      m = wave_max(m);
-      float ex[EPL], s = 0.f;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) { ex[e] = expf(x[e] - m); s += ex[e]; }
-      s = 1.f / wave_sum(s);
+      for (int e = 0; e < EPL; ++e) x[e] = io_traits<IO>::ld(src + lane + 64 * e);
+      float ex[EPL];
+      feature_row<EPL>(x, ex, dd.phi);
       if (item < G) {
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) { qs[item][lane + 64 * e] = x[e]; qf[item][lane + 64 * e] = ex[e] * s; }
+        for (int e = 0; e < EPL; ++e) { qs[item][lane + 64 * e] = x[e]; qf[item][lane + 64 * e] = ex[e]; }
       } else {
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
-          kfo[lane + 64 * e] = ex[e] * s;
+          kfo[lane + 64 * e] = ex[e];
           vo[lane + 64 * e] = io_traits<IO>::ld(vr + (size_t)slot * D + lane + 64 * e);
         }
       }

@@ -30,12 +30,12 @@ __global__ __launch_bounds__(256) void export_ring_kernel(const uint4* __restric
 }
 
 // Partial state of one key segment.  grid (nseg, Hkv, B), 256 threads.  Keys are staged KB at a time: LPR lanes
-// per key row compute phi (row softmax) into LDS, then every thread adds KB rank-one terms to the NR x 4 state
+// per key row compute phi (row softmax, or the ablation's ReLU / identity) into LDS, then every thread adds KB rank-one terms to the NR x 4 state
 // entries it owns (rows rg + RG*j, columns 4*cg .. 4*cg+3).
 template <typename IO, int D>
 __global__ __launch_bounds__(256) void export_state_partial_kernel(const IO* __restrict__ k, const IO* __restrict__ v,
                                                                    float* __restrict__ partial, int T, int Hkv,
-                                                                   int Tp, int seg_len) {
+                                                                   int Tp, int seg_len, int phi) {
   constexpr int LPR = D / 8, KB = 256 / LPR;
   constexpr int CG = D / 4, RG = 256 / CG, NR = D / RG;
   __shared__ float kf[KB][D];
@@ -65,10 +65,10 @@ __global__ __launch_bounds__(256) void export_state_partial_kernel(const IO* __r
     for (int o = LPR / 2; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
     float sum = 0.f;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { x[e] = s < hi ? expf(x[e] - m) : 0.f; sum += x[e]; }
+    for (int e = 0; e < 8; ++e) { x[e] = s < hi ? feat(x[e], m, phi) : 0.f; sum += x[e]; }
 #pragma unroll
     for (int o = LPR / 2; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
-    const float inv = s < hi ? 1.f / sum : 0.f;
+    const float inv = s < hi ? (phi == PHI_SOFTMAX ? 1.f / sum : 1.f) : 0.f;
     __syncthreads();  // the previous batch has been consumed
 #pragma unroll
     for (int e = 0; e < 8; ++e) { kf[kr][8 * li + e] = x[e] * inv; vs[kr][8 * li + e] = y[e]; }
@@ -132,7 +132,7 @@ void prefill_export(const LayerDims& dm, int dtype, const void* k, const void* v
     ProfScope ps("export_state_partial_kernel", st);
 #define RATTN_EXPORT(IO, DD)                                                                                        \
   export_state_partial_kernel<IO, DD><<<grid, 256, 0, st>>>((const IO*)k, (const IO*)v, partial, dm.T, dm.Hkv, pl.Tp, \
-                                                            pl.seg_len)
+                                                            pl.seg_len, dm.phi)
     if (dtype == 0) {
       if (dm.D == 64) RATTN_EXPORT(float, 64); else RATTN_EXPORT(float, 128);
     } else {

@@ -438,6 +438,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
 bool fast_fwd_supported(const LayerDims& dm, int dtype) {
   if (dtype != 1 || dm.D != 128 || dm.T % 128 != 0) return false;
   if (!(dm.scale > 0.f)) return false;
+  if (dm.phi != PHI_SOFTMAX) return false;  // the ablation's feature maps run on the general kernels
   // Windows below 8 keys stay on the general path: their softmax rows are close to one-hot, so the backward's
   // dS = P (dP - delta) is a near-cancellation (exact for W = 1) that bf16 operands turn into rounding noise
   // above the gradient tolerance (measured: worst element 4 % of RMS at W = 2, 3 % at W = 4, 2.5 % from W = 8 on)

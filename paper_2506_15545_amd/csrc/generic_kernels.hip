@@ -4,7 +4,8 @@
 // the MFMA kernels do not cover; they follow the same decomposition:
 //   softmax branch  : Sec. 2.1 (windowed softmax, online normalisation)
 //   linear branch   : Eqs. 2-4 (chunk states S_[j], inter-chunk product + intra-chunk masked product,
-//                     read at lag W), phi = row softmax computed in-kernel, never stored
+//                     read at lag W), phi (row softmax, or the ablation's ReLU / identity of Sec. 4.5)
+//                     computed in-kernel, never stored
 //   combination     : Sec. 3.2 (two RMS norms with per-head gains)
 // Element d of a row lives in lane d % 64, register d / 64.
 #include "common.hpp"
@@ -36,20 +37,8 @@ template <typename IO, int D> struct Row {
     for (int e = 0; e < EPL; ++e) s += x[e] * o.x[e];
     return wave_sum(s);
   }
-  // in place softmax over the D features
-  __device__ __forceinline__ void softmax() {
-    float m = x[0];
-#pragma unroll
-    for (int e = 1; e < EPL; ++e) m = fmaxf(m, x[e]);
-    m = wave_max(m);
-    float s = 0.f;
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) { x[e] = expf(x[e] - m); s += x[e]; }
-    s = wave_sum(s);
-    float inv = 1.f / s;
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) x[e] *= inv;
-  }
+  // in place feature map over the D features
+  __device__ __forceinline__ void feature(int phi) { feature_row<EPL>(x, x, phi); }
 };
 
 // <row held across the wave, row read privately by this lane>
@@ -66,9 +55,10 @@ __device__ __forceinline__ float lane_dot(const Row<RT, D>& r, const IO2* own) {
   return a;
 }
 
-// max and sum(exp(x - max)) of the row this lane reads privately
+// row statistics (m, z) of the row this lane reads privately: max and sum(exp(x - max)) for softmax, (0, 1) otherwise
 template <int D, typename IO>
-__device__ __forceinline__ void lane_softmax_stats(const IO* own, float& m, float& z) {
+__device__ __forceinline__ void lane_feature_stats(const IO* own, float& m, float& z, int phi) {
+  if (phi != PHI_SOFTMAX) { m = 0.f; z = 1.f; return; }
   m = -INFINITY;
 #pragma unroll
   for (int c = 0; c < D / 8; ++c) {
@@ -87,16 +77,16 @@ __device__ __forceinline__ void lane_softmax_stats(const IO* own, float& m, floa
   }
 }
 
-// sum_f r[f] * exp(own[f] - m)   (r spread over the wave, own row private)
+// sum_f r[f] * feat(own[f], m)   (r spread over the wave, own row private)
 template <typename RT, int D, typename IO>
-__device__ __forceinline__ float lane_dot_exp(const Row<RT, D>& r, const IO* own, float m) {
+__device__ __forceinline__ float lane_dot_feat(const Row<RT, D>& r, const IO* own, float m, int phi) {
   float a = 0.f;
 #pragma unroll
   for (int c = 0; c < D / 8; ++c) {
     float t[8];
     io_traits<IO>::ld8(own + c * 8, t);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) a += r.get(c * 8 + i) * expf(t[i] - m);
+    for (int i = 0; i < 8; ++i) a += r.get(c * 8 + i) * feat(t[i], m, phi);
   }
   return a;
 }
@@ -110,7 +100,7 @@ __device__ __forceinline__ float lane_dot_exp(const Row<RT, D>& r, const IO* own
 template <typename AT, typename BT, int D, bool REV>
 __global__ __launch_bounds__(256) void gen_scan_kernel(const AT* __restrict__ a, const BT* __restrict__ bsrc,
                                                        float* __restrict__ out, int T, int H, int GA, int off,
-                                                       int Tp, int C, int nst) {
+                                                       int Tp, int C, int nst, int phi) {
   constexpr int TB = 16;
   constexpr int CPT = D / 16;    // state columns per thread
   constexpr int TPR = 16 / CPT;  // threads per state row
@@ -138,7 +128,7 @@ __global__ __launch_bounds__(256) void gen_scan_kernel(const AT* __restrict__ a,
         for (int tt = w; tt < n; tt += 4) {
           Row<AT, D> r;
           r.load(a + ((size_t)(b * T + t0 + tt + off) * H + head) * D);
-          r.softmax();
+          r.feature(phi);
 #pragma unroll
           for (int e = 0; e < D / 64; ++e) af[tt][lane_id() + 64 * e] = r.x[e];
         }
@@ -161,12 +151,12 @@ __global__ __launch_bounds__(256) void gen_scan_kernel(const AT* __restrict__ a,
 // Forward: one wave per query row, QPW rows per wave.  grid (ceil(T/(4*QPW)), Hq, B), 256 threads.
 constexpr int GEN_QPW = 4;
 
-template <typename IO, int D>
+template <typename IO, typename ST, int D>
 __global__ __launch_bounds__(256) void gen_fwd_kernel(const IO* __restrict__ q, const IO* __restrict__ k,
                                                       const IO* __restrict__ v, const float* __restrict__ gs,
                                                       const float* __restrict__ gr,
                                                       const float* __restrict__ states, IO* __restrict__ o,
-                                                      IO* __restrict__ xs_out, IO* __restrict__ xr_out,
+                                                      ST* __restrict__ xs_out, ST* __restrict__ xr_out,
                                                       float* __restrict__ lse_out, float* __restrict__ rs_out,
                                                       float* __restrict__ rr_out, LayerDims dm) {
   constexpr int EPL = D / 64;
@@ -216,7 +206,7 @@ __global__ __launch_bounds__(256) void gen_fwd_kernel(const IO* __restrict__ q, 
     const int pidx = t - W;
     if (pidx >= 0) {
       Row<IO, D> qf = qv;
-      qf.softmax();
+      qf.feature(dm.phi);
       const int j = pidx / C;
       const float* S = states + ((size_t)(b * Hkv + g) * dm.nst + j) * D * D;
 #pragma unroll 8
@@ -231,8 +221,8 @@ __global__ __launch_bounds__(256) void gen_fwd_kernel(const IO* __restrict__ q, 
         const int sc = valid ? s : pidx;
         const IO* kr = k + ((size_t)(b * T + sc) * Hkv + g) * D;
         float mk, zk;
-        lane_softmax_stats<D>(kr, mk, zk);
-        float c = lane_dot_exp(qf, kr, mk) / zk;
+        lane_feature_stats<D>(kr, mk, zk, dm.phi);
+        float c = lane_dot_feat(qf, kr, mk, dm.phi) / zk;
         c = valid ? c : 0.f;
         const int n = min(64, pidx - base + 1);
         for (int jj = 0; jj < n; ++jj) {
@@ -258,8 +248,8 @@ __global__ __launch_bounds__(256) void gen_fwd_kernel(const IO* __restrict__ q, 
     if (xs_out) {
 #pragma unroll
       for (int e = 0; e < EPL; ++e) {
-        io_traits<IO>::st(xs_out + qoff + lane + 64 * e, xs.x[e]);
-        io_traits<IO>::st(xr_out + qoff + lane + 64 * e, xr.x[e]);
+        io_traits<ST>::st(xs_out + qoff + lane + 64 * e, xs.x[e]);
+        io_traits<ST>::st(xr_out + qoff + lane + 64 * e, xr.x[e]);
       }
       if (lane == 0) {
         const size_t so = (size_t)(b * Hq + h) * T + t;
@@ -276,9 +266,9 @@ __global__ __launch_bounds__(256) void gen_fwd_kernel(const IO* __restrict__ q, 
 //   dx = r*(g*dy) - x*r^3*mean(g*dy*x),   dgamma += dy*x*r,   delta = <dx_s, x_s>.
 // grid (RB, Hq): block rb walks rows rb, rb+RB, ... of the B*T rows of head h; each wave keeps
 // per-feature dgamma partials, combined across the 4 waves at the end -> dgpart[2][RB][Hq][D].
-template <typename IO, int D>
-__global__ __launch_bounds__(256) void gen_bwd_prep_kernel(const IO* __restrict__ dO, const IO* __restrict__ xs_in,
-                                                           const IO* __restrict__ xr_in,
+template <typename IO, typename ST, int D>
+__global__ __launch_bounds__(256) void gen_bwd_prep_kernel(const IO* __restrict__ dO, const ST* __restrict__ xs_in,
+                                                           const ST* __restrict__ xr_in,
                                                            const float* __restrict__ rs_in,
                                                            const float* __restrict__ rr_in,
                                                            const float* __restrict__ gs, const float* __restrict__ gr,
@@ -300,7 +290,8 @@ __global__ __launch_bounds__(256) void gen_bwd_prep_kernel(const IO* __restrict_
     const int b = r / dm.T, t = r % dm.T;
     const size_t off = ((size_t)r * dm.Hq + h) * D;
     const size_t so = (size_t)(b * dm.Hq + h) * dm.T + t;
-    Row<IO, D> dy, xs, xr;
+    Row<IO, D> dy;
+    Row<ST, D> xs, xr;
     dy.load(dO + off); xs.load(xs_in + off); xr.load(xr_in + off);
     const float r_s = rs_in[so], r_r = rr_in[so];
     float m1 = 0.f, m2 = 0.f;
@@ -347,6 +338,7 @@ __global__ void gen_dgamma_reduce_kernel(const float* __restrict__ dgpart, float
 //   softmax branch: p = exp(scale q.k - lse), dp = <dx_s, v_s>, da = p(dp - delta), dq += scale*da*k_s
 //                   (delta recomputed from p and dp, and written back, when the window fits one pass: W <= 64)
 //   linear branch : dphi(q) = S_[j] dx_r + sum_{intra} <dx_r, v_s> phi(k_s);  dq += phi(q)*(dphi - <dphi,phi(q)>)
+//                   (softmax map; ReLU passes dphi where q > 0, identity passes it unchanged)
 template <typename IO, int D>
 __global__ __launch_bounds__(256) void gen_bwd_dq_kernel(const IO* __restrict__ q, const IO* __restrict__ k,
                                                          const IO* __restrict__ v, const float* __restrict__ dxs,
@@ -402,7 +394,7 @@ __global__ __launch_bounds__(256) void gen_bwd_dq_kernel(const IO* __restrict__ 
     const int pidx = t - W;
     if (pidx >= 0) {
       Row<IO, D> qf = qv;
-      qf.softmax();
+      qf.feature(dm.phi);
       const int j = pidx / C;
       const float* S = states + ((size_t)(b * Hkv + g) * dm.nst + j) * D * D;
       Row<float, D> dqf;
@@ -414,7 +406,7 @@ __global__ __launch_bounds__(256) void gen_bwd_dq_kernel(const IO* __restrict__ 
         const int sc = valid ? s : pidx;
         const size_t ko = ((size_t)(b * T + sc) * Hkv + g) * D;
         float mk, zk;
-        lane_softmax_stats<D>(k + ko, mk, zk);
+        lane_feature_stats<D>(k + ko, mk, zk, dm.phi);
         float coef = lane_dot(gxr, v + ko) / zk;
         coef = valid ? coef : 0.f;
         const int n = min(64, pidx - base + 1);
@@ -422,7 +414,7 @@ __global__ __launch_bounds__(256) void gen_bwd_dq_kernel(const IO* __restrict__ 
           const float cf = bcast(coef, jj), mj = bcast(mk, jj);
           const IO* kr = k + ((size_t)(b * T + base + jj) * Hkv + g) * D;
 #pragma unroll
-          for (int e = 0; e < EPL; ++e) dqf.x[e] += cf * expf(io_traits<IO>::ld(kr + lane + 64 * e) - mj);
+          for (int e = 0; e < EPL; ++e) dqf.x[e] += cf * feat(io_traits<IO>::ld(kr + lane + 64 * e), mj, dm.phi);
         }
       }
       float inner = 0.f;
@@ -430,7 +422,7 @@ __global__ __launch_bounds__(256) void gen_bwd_dq_kernel(const IO* __restrict__ 
       for (int e = 0; e < EPL; ++e) inner += dqf.x[e] * qf.x[e];
       inner = wave_sum(inner);
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) acc[e] += qf.x[e] * (dqf.x[e] - inner);
+      for (int e = 0; e < EPL; ++e) acc[e] += feat_bwd(qv.x[e], qf.x[e], dqf.x[e], inner, dm.phi);
     }
 #pragma unroll
     for (int e = 0; e < EPL; ++e) io_traits<IO>::st(dq + qoff + lane + 64 * e, acc[e]);
@@ -461,7 +453,7 @@ __global__ __launch_bounds__(256) void gen_bwd_dkv_kernel(const IO* __restrict__
     Row<IO, D> kv, vv;
     kv.load(k + koff); vv.load(v + koff);
     Row<IO, D> kf = kv;
-    kf.softmax();
+    kf.feature(dm.phi);
     float dka[EPL], dva[EPL];
     Row<float, D> dkf;
 #pragma unroll
@@ -500,8 +492,8 @@ __global__ __launch_bounds__(256) void gen_bwd_dkv_kernel(const IO* __restrict__
           const int t = (valid ? tp : tpmax) + W;
           const size_t qo = ((size_t)(b * T + t) * Hq + h) * D;
           float mq, zq;
-          lane_softmax_stats<D>(q + qo, mq, zq);
-          float c = lane_dot_exp(kf, q + qo, mq) / zq;
+          lane_feature_stats<D>(q + qo, mq, zq, dm.phi);
+          float c = lane_dot_feat(kf, q + qo, mq, dm.phi) / zq;
           float coef = lane_dot(vv, dxr + qo) / zq;
           c = valid ? c : 0.f;
           coef = valid ? coef : 0.f;
@@ -512,7 +504,7 @@ __global__ __launch_bounds__(256) void gen_bwd_dkv_kernel(const IO* __restrict__
 #pragma unroll
             for (int e = 0; e < EPL; ++e) {
               dva[e] += cj * dxr[ro + lane + 64 * e];
-              dkf.x[e] += cf * expf(io_traits<IO>::ld(q + ro + lane + 64 * e) - mj);
+              dkf.x[e] += cf * feat(io_traits<IO>::ld(q + ro + lane + 64 * e), mj, dm.phi);
             }
           }
         }
@@ -535,7 +527,8 @@ __global__ __launch_bounds__(256) void gen_bwd_dkv_kernel(const IO* __restrict__
     inner = wave_sum(inner);
 #pragma unroll
     for (int e = 0; e < EPL; ++e) {
-      io_traits<IO>::st(dk + koff + lane + 64 * e, dm.scale * dka[e] + kf.x[e] * (dkf.x[e] - inner));
+      io_traits<IO>::st(dk + koff + lane + 64 * e,
+                        dm.scale * dka[e] + feat_bwd(kv.x[e], kf.x[e], dkf.x[e], inner, dm.phi));
       io_traits<IO>::st(dv + koff + lane + 64 * e, dva[e]);
     }
   }
@@ -543,29 +536,29 @@ __global__ __launch_bounds__(256) void gen_bwd_dkv_kernel(const IO* __restrict__
 
 // ------------------------------------------------------------------------------------------------
 // host launchers
-template <typename IO, int D>
+template <typename IO, typename ST, int D>
 static void launch_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, const float* gs,
                        const float* gr, void* o, const SavedPtrs& sv, float* states, hipStream_t st) {
   if (dm.nst > 0) {
     ProfScope ps("gen_scan_kernel", st);
     gen_scan_kernel<IO, IO, D, false><<<dim3(D / 16, dm.Hkv, dm.B), 256, 0, st>>>(
-        (const IO*)k, (const IO*)v, states, dm.T, dm.Hkv, 1, 0, dm.T - dm.W, dm.C, dm.nst);
+        (const IO*)k, (const IO*)v, states, dm.T, dm.Hkv, 1, 0, dm.T - dm.W, dm.C, dm.nst, dm.phi);
   }
   dim3 grid((dm.T + 4 * GEN_QPW - 1) / (4 * GEN_QPW), dm.Hq, dm.B);
   ProfScope ps("gen_fwd_kernel", st);
-  gen_fwd_kernel<IO, D><<<grid, 256, 0, st>>>((const IO*)q, (const IO*)k, (const IO*)v, gs, gr, states, (IO*)o,
-                                              (IO*)sv.xs, (IO*)sv.xr, sv.lse, sv.rs, sv.rr, dm);
+  gen_fwd_kernel<IO, ST, D><<<grid, 256, 0, st>>>((const IO*)q, (const IO*)k, (const IO*)v, gs, gr, states, (IO*)o,
+                                                  (ST*)sv.xs, (ST*)sv.xr, sv.lse, sv.rs, sv.rr, dm);
 }
 
-template <typename IO, int D>
+template <typename IO, typename ST, int D>
 static void launch_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, const float* gs,
                        const float* gr, const SavedPtrs& sv, const void* dO, void* dq, void* dk, void* dv,
                        float* dgs, float* dgr, const GenericBwdWs& ws, hipStream_t st) {
   {
     ProfScope ps("gen_bwd_prep_kernel", st);
-    gen_bwd_prep_kernel<IO, D><<<dim3(ws.RB, dm.Hq), 256, 0, st>>>((const IO*)dO, (const IO*)sv.xs,
-                                                                   (const IO*)sv.xr, sv.rs, sv.rr, gs, gr, ws.dxs,
-                                                                   ws.dxr, ws.delta, ws.dgpart, dm);
+    gen_bwd_prep_kernel<IO, ST, D><<<dim3(ws.RB, dm.Hq), 256, 0, st>>>((const IO*)dO, (const ST*)sv.xs,
+                                                                       (const ST*)sv.xr, sv.rs, sv.rr, gs, gr, ws.dxs,
+                                                                       ws.dxr, ws.delta, ws.dgpart, dm);
   }
   if (dgs || dgr) {
     const int HD = dm.Hq * D;
@@ -574,9 +567,9 @@ static void launch_bwd(const LayerDims& dm, const void* q, const void* k, const 
   if (dm.nst > 0) {
     ProfScope ps("gen_scan_kernel(x2)", st);
     gen_scan_kernel<IO, IO, D, false><<<dim3(D / 16, dm.Hkv, dm.B), 256, 0, st>>>(
-        (const IO*)k, (const IO*)v, ws.states, dm.T, dm.Hkv, 1, 0, dm.T - dm.W, dm.C, dm.nst);
+        (const IO*)k, (const IO*)v, ws.states, dm.T, dm.Hkv, 1, 0, dm.T - dm.W, dm.C, dm.nst, dm.phi);
     gen_scan_kernel<IO, float, D, true><<<dim3(D / 16, dm.Hkv, dm.B), 256, 0, st>>>(
-        (const IO*)q, ws.dxr, ws.rstates, dm.T, dm.Hq, dm.G, dm.W, dm.T - dm.W, dm.C, dm.nst);
+        (const IO*)q, ws.dxr, ws.rstates, dm.T, dm.Hq, dm.G, dm.W, dm.T - dm.W, dm.C, dm.nst, dm.phi);
   }
   dim3 gq((dm.T + 4 * GEN_QPW - 1) / (4 * GEN_QPW), dm.Hq, dm.B);
   {
@@ -593,11 +586,14 @@ static void launch_bwd(const LayerDims& dm, const void* q, const void* k, const 
 void generic_fwd(const LayerDims& dm, int dtype, const void* q, const void* k, const void* v, const float* gs,
                  const float* gr, void* o, const SavedPtrs& sv, float* states, hipStream_t st) {
   if (dtype == 0) {
-    if (dm.D == 64) launch_fwd<float, 64>(dm, q, k, v, gs, gr, o, sv, states, st);
-    else launch_fwd<float, 128>(dm, q, k, v, gs, gr, o, sv, states, st);
+    if (dm.D == 64) launch_fwd<float, float, 64>(dm, q, k, v, gs, gr, o, sv, states, st);
+    else launch_fwd<float, float, 128>(dm, q, k, v, gs, gr, o, sv, states, st);
+  } else if (sv.f32) {
+    if (dm.D == 64) launch_fwd<bf16_t, float, 64>(dm, q, k, v, gs, gr, o, sv, states, st);
+    else launch_fwd<bf16_t, float, 128>(dm, q, k, v, gs, gr, o, sv, states, st);
   } else {
-    if (dm.D == 64) launch_fwd<bf16_t, 64>(dm, q, k, v, gs, gr, o, sv, states, st);
-    else launch_fwd<bf16_t, 128>(dm, q, k, v, gs, gr, o, sv, states, st);
+    if (dm.D == 64) launch_fwd<bf16_t, bf16_t, 64>(dm, q, k, v, gs, gr, o, sv, states, st);
+    else launch_fwd<bf16_t, bf16_t, 128>(dm, q, k, v, gs, gr, o, sv, states, st);
   }
 }
 
@@ -605,11 +601,14 @@ void generic_bwd(const LayerDims& dm, int dtype, const void* q, const void* k, c
                  const float* gr, const SavedPtrs& sv, const void* dO, void* dq, void* dk, void* dv, float* dgs,
                  float* dgr, const GenericBwdWs& ws, hipStream_t st) {
   if (dtype == 0) {
-    if (dm.D == 64) launch_bwd<float, 64>(dm, q, k, v, gs, gr, sv, dO, dq, dk, dv, dgs, dgr, ws, st);
-    else launch_bwd<float, 128>(dm, q, k, v, gs, gr, sv, dO, dq, dk, dv, dgs, dgr, ws, st);
+    if (dm.D == 64) launch_bwd<float, float, 64>(dm, q, k, v, gs, gr, sv, dO, dq, dk, dv, dgs, dgr, ws, st);
+    else launch_bwd<float, float, 128>(dm, q, k, v, gs, gr, sv, dO, dq, dk, dv, dgs, dgr, ws, st);
+  } else if (sv.f32) {
+    if (dm.D == 64) launch_bwd<bf16_t, float, 64>(dm, q, k, v, gs, gr, sv, dO, dq, dk, dv, dgs, dgr, ws, st);
+    else launch_bwd<bf16_t, float, 128>(dm, q, k, v, gs, gr, sv, dO, dq, dk, dv, dgs, dgr, ws, st);
   } else {
-    if (dm.D == 64) launch_bwd<bf16_t, 64>(dm, q, k, v, gs, gr, sv, dO, dq, dk, dv, dgs, dgr, ws, st);
-    else launch_bwd<bf16_t, 128>(dm, q, k, v, gs, gr, sv, dO, dq, dk, dv, dgs, dgr, ws, st);
+    if (dm.D == 64) launch_bwd<bf16_t, bf16_t, 64>(dm, q, k, v, gs, gr, sv, dO, dq, dk, dv, dgs, dgr, ws, st);
+    else launch_bwd<bf16_t, bf16_t, 128>(dm, q, k, v, gs, gr, sv, dO, dq, dk, dv, dgs, dgr, ws, st);
   }
 }
 

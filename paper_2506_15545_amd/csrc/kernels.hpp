@@ -19,9 +19,13 @@ struct LayerDims {
   int B, T, Hq, Hkv, D, W, C, G;
   int nst;  // number of chunk states per (batch, kv head): ceil(max(T-W,0) / C)
   float scale, eps;
+  int phi;  // feature map of the linear branch: PHI_SOFTMAX (Sec. 3.1), PHI_RELU, PHI_IDENTITY (Sec. 4.5 ablation)
 };
 
-// views into the opaque `saved` buffer: pre-norm branch outputs (I/O dtype, [B,T,Hq,D]) and the
+// views into the opaque `saved` buffer: pre-norm branch outputs ([B,T,Hq,D]; the I/O dtype on the MFMA path, fp32
+// on the general path: the backward through the second RMS norm projects the upstream gradient off x^r, and where
+// the state has very low rank - the first rows past the window - rounding x^r to bf16 leaves an error that the
+// state multiplies back up) and the
 // row statistics (fp32, [B,Hq,T]): log-sum-exp of the softmax branch and the two RMS reciprocals; on the MFMA
 // path also the linear-branch chunk states (bf16, transposed), so that backward does not rebuild them
 struct SavedPtrs {
@@ -31,6 +35,7 @@ struct SavedPtrs {
   float* rs;
   float* rr;
   void* states;  // null on the general path
+  bool f32;      // x^s, x^r are stored as fp32 whatever the tensor dtype
 };
 
 struct GenericBwdWs {
@@ -126,6 +131,7 @@ double probe_mfma(float* sink, int iters, int blocks, hipStream_t st);
 struct DecodeDims {
   int N, Hq, Hkv, D, W, G;
   float scale, eps;
+  int phi;  // as LayerDims::phi
 };
 void decode_step(const DecodeDims& dd, int dtype, const void* q, const void* k_new, const void* v_new,
                  const int32_t* pos, void* k_ring, void* v_ring, float* state, const float* gs, const float* gr,

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 
 def params(**kw):
     d = dict(B=2, T=300, Hq=4, Hkv=2, D=64, window=32, chunk=0, dtype=rb.RATTN_F32, softmax_scale=1.0,
-             rms_eps=1e-6, save_for_bwd=0)
+             rms_eps=1e-6, save_for_bwd=0, feature_map=0)
     d.update(kw)
     return rb.RattnParams(**d)
 
@@ -48,6 +48,7 @@ def test_workspace_sizes_scale_with_shape():
 @pytest.mark.parametrize("kw,code", [
     (dict(B=0), -1), (dict(T=0), -1), (dict(Hq=3, Hkv=2), -1), (dict(window=0), -1), (dict(chunk=-1), -1),
     (dict(rms_eps=0.0), -1), (dict(softmax_scale=0.0), -1), (dict(D=96), -2), (dict(dtype=7), -2),
+    (dict(feature_map=3), -2), (dict(feature_map=-1), -2),
 ])
 def test_bad_params_rejected(kw, code):
     with pytest.raises(rb.RattnError) as e:
@@ -68,6 +69,9 @@ def test_null_pointers_rejected_before_any_launch():
     assert st == -1
     dp.D = 80
     assert L.rattn_decode_step(ctypes.byref(dp), *([None] * 11)) == -2
+    dp.D = 64
+    dp.feature_map = 5
+    assert L.rattn_decode_step(ctypes.byref(dp), *([None] * 11)) == -2 and b"feature_map" in L.rattn_last_error()
 
 
 def test_small_workspace_rejected():
