@@ -49,6 +49,8 @@ def test_workspace_sizes_scale_with_shape():
     (dict(B=0), -1), (dict(T=0), -1), (dict(Hq=3, Hkv=2), -1), (dict(window=0), -1), (dict(chunk=-1), -1),
     (dict(rms_eps=0.0), -1), (dict(softmax_scale=0.0), -1), (dict(D=96), -2), (dict(dtype=7), -2),
     (dict(feature_map=3), -2), (dict(feature_map=-1), -2),
+    (dict(B=60000, T=10000), -2),      # more rows than 32-bit row indexing covers
+    (dict(B=70000), -2), (dict(Hq=70000, Hkv=70000), -2),   # grid dimensions
 ])
 def test_bad_params_rejected(kw, code):
     with pytest.raises(rb.RattnError) as e:
@@ -70,6 +72,9 @@ def test_null_pointers_rejected_before_any_launch():
     dp.D = 80
     assert L.rattn_decode_step(ctypes.byref(dp), *([None] * 11)) == -2
     dp.D = 64
+    dp.N = 70000
+    assert L.rattn_decode_step(ctypes.byref(dp), *([None] * 11)) == -2 and b"N must be" in L.rattn_last_error()
+    dp.N = 4
     dp.feature_map = 5
     assert L.rattn_decode_step(ctypes.byref(dp), *([None] * 11)) == -2 and b"feature_map" in L.rattn_last_error()
 
