@@ -334,20 +334,20 @@ def main():
         torch.cuda.empty_cache()
         other = {}
 
-        def run_layer(c, with_bwd, gains=False):
+        def run_layer(c, with_bwd, gains=False, feature_map="softmax"):
             t = [x_.cuda() for x_ in synth.make_layer_inputs(c, with_dO=with_bwd)]
             gs_ = (1.0 + 0.1 * torch.randn(c.Hq, c.D, device="cuda")) if gains else None
             gr_ = (1.0 + 0.1 * torch.randn(c.Hq, c.D, device="cuda")) if gains else None
-            pp = rb.make_params(t[0], t[1], c.W, 0, c.scale, 1e-6, with_bwd)
+            pp = rb.make_params(t[0], t[1], c.W, 0, c.scale, 1e-6, with_bwd, feature_map)
             fb, bb, sb = rb.rattn_workspace_bytes(pp)
             w_ = torch.empty(max(fb, bb, 16), dtype=torch.uint8, device="cuda")
             sv_ = torch.empty(max(sb, 16), dtype=torch.uint8, device="cuda") if with_bwd else None
             o_ = torch.empty_like(t[0])
             g_ = (torch.empty_like(t[0]), torch.empty_like(t[1]), torch.empty_like(t[2])) if with_bwd else None
             f_ = lambda: rb.rattn_fwd(t[0], t[1], t[2], c.W, gs_, gr_, softmax_scale=c.scale, save_for_bwd=with_bwd,
-                                      out=o_, saved=sv_, workspace=w_)
+                                      out=o_, saved=sv_, workspace=w_, feature_map=feature_map)
             b_ = lambda: rb.rattn_bwd(t[0], t[1], t[2], sv_, t[3], c.W, gs_, gr_, softmax_scale=c.scale,
-                                      want_dgamma=gains, workspace=w_, out=g_)
+                                      want_dgamma=gains, workspace=w_, out=g_, feature_map=feature_map)
             for _ in range(5):
                 f_()
                 if with_bwd:
@@ -369,6 +369,8 @@ def main():
         # and without them by the same (shorter) timing method for comparison
         other["layer3b_t4096_w512_gains"] = run_layer(cfg, True, gains=True)
         other["layer3b_t4096_w512"] = run_layer(cfg, True)
+        # the ablation's ReLU feature map (Sec. 4.5) on the same kernels, same FLOP formula
+        other["layer3b_t4096_w512_relu"] = run_layer(cfg, True, feature_map="relu")
         for W_ in (128, 512, 1024, 4096, 8192):
             c_ = synth.sweep_config(W_)
             other[c_.name] = run_layer(c_, True)

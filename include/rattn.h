@@ -60,8 +60,8 @@ typedef struct {
   float softmax_scale;   /* multiplies q.k in the softmax branch only (the paper's formula is 1.0)     */
   float rms_eps;         /* > 0                                                                        */
   int32_t save_for_bwd;  /* rattn_fwd also fills `saved` (needed by rattn_bwd)                         */
-  int32_t feature_map;   /* rattn_feature_map; RATTN_PHI_RELU / RATTN_PHI_IDENTITY run on the general
-                            (vector-ALU) kernels for every shape                                       */
+  int32_t feature_map;   /* rattn_feature_map; RATTN_PHI_IDENTITY runs on the general (vector-ALU)
+                            kernels for every shape                                                    */
 } rattn_params;
 
 /* Sizes in bytes of the scratch `workspace` rattn_fwd / rattn_bwd need and of the opaque

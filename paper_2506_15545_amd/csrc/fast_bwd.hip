@@ -63,6 +63,7 @@ __global__ __launch_bounds__(256) void dgamma_reduce_kernel(const float* __restr
 
 // row `src` (128 bf16) re-read in accumulator layout: lane keeps features 32ft + 8*i4 + 4h + e -> x[ft*16 + 4*i4 + e];
 // phi of that row (the row's other half sits in lane ^ 32)
+template <bool RELU>
 __device__ __forceinline__ void phi_row_clayout(const uint16_t* src, int h, float (&x)[64]) {
 #pragma unroll
   for (int ft = 0; ft < 4; ++ft)
@@ -73,6 +74,11 @@ __device__ __forceinline__ void phi_row_clayout(const uint16_t* src, int h, floa
 #pragma unroll
       for (int e = 0; e < 4; ++e) x[ft * 16 + 4 * i4 + e] = f[e];
     }
+  if (RELU) {
+#pragma unroll
+    for (int i = 0; i < 64; ++i) x[i] = fmaxf(x[i], 0.f);
+    return;
+  }
   float m = x[0];
 #pragma unroll
   for (int i = 1; i < 64; ++i) m = fmaxf(m, x[i]);
@@ -86,8 +92,17 @@ __device__ __forceinline__ void phi_row_clayout(const uint16_t* src, int h, floa
   for (int i = 0; i < 64; ++i) x[i] *= inv;
 }
 
-// acc <- f .* (acc - <acc, f>)   (softmax Jacobian applied to a gradient held in accumulator layout)
+// acc <- f .* (acc - <acc, f>)   (softmax Jacobian applied to a gradient held in accumulator layout);
+// ReLU map: acc <- acc where the input was positive, i.e. where f = max(x, 0) > 0
+template <bool RELU>
 __device__ __forceinline__ void phi_jacobian(f32x16_t (&acc)[4], const float (&f)[64]) {
+  if (RELU) {
+#pragma unroll
+    for (int ft = 0; ft < 4; ++ft)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[ft][i] = f[ft * 16 + i] > 0.f ? acc[ft][i] : 0.f;
+    return;
+  }
   float inner = 0.f;
 #pragma unroll
   for (int ft = 0; ft < 4; ++ft)
@@ -247,7 +262,7 @@ __device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, int hq, size_
 }
 
 // GAINS: RMS gains other than one and/or gain gradients (see rms_bwd_rows)
-template <bool GAINS>
+template <bool GAINS, bool RELU>
 __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
   __shared__ __align__(16) unsigned char smem[65536];
   const int lane = lane_id(), w = wave_id();
@@ -347,8 +362,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
       tile_load_async<4>(kbase + (size_t)(j0 + 64) * kstride, kstride, smem + 16384, w * 4, lane);
       wait_vmem();
       __syncthreads();
-      if (has_state) phi_tile_inplace(smem, 128);
-      else phi_tile_inplace(smem + 16384, 64);
+      if (has_state) phi_tile_inplace<RELU>(smem, 128);
+      else phi_tile_inplace<RELU>(smem + 16384, 64);
       __syncthreads();
       for (int u = has_state ? 0 : 2; u <= min(3, u_hi); ++u)
         intra_unit(smem + (u >> 1) * 16384, smem + 32768 + (u >> 1) * 16384, u & 1, u);
@@ -359,14 +374,14 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
       tile_load_async<4>(vbase + (size_t)(j0 + 128) * kstride, kstride, smem + 32768, w * 4, lane);
       wait_vmem();
       __syncthreads();
-      phi_tile_inplace(smem, 64);
+      phi_tile_inplace<RELU>(smem, 64);
       __syncthreads();
       for (int u = 4; u <= min(5, u_hi); ++u) intra_unit(smem, smem + 32768, u & 1, u);
       __syncthreads();
     }
     float qf[64];
-    phi_row_clayout(a.q + myrow_off, h, qf);
-    phi_jacobian(acc, qf);
+    phi_row_clayout<RELU>(a.q + myrow_off, h, qf);
+    phi_jacobian<RELU>(acc, qf);
   }
 
   // ---- softmax branch
@@ -422,6 +437,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
 
 // ------------------------------------------------------------------------------------------------
 // phi in place on the first `nrows` rows of an LDS tile with 512 threads: four threads per row, 32 elements each
+template <bool RELU>
 __device__ __forceinline__ void phi_tile_inplace_512(unsigned char* tile, int nrows) {
   const int row = threadIdx.x >> 2, part = threadIdx.x & 3;
   if (row < nrows) {
@@ -431,19 +447,24 @@ __device__ __forceinline__ void phi_tile_inplace_512(unsigned char* tile, int nr
 #pragma unroll
     for (int j = 0; j < 4; ++j)
       unpack_bf16x8(*reinterpret_cast<const bf16x8_t*>(rp + (((4 * part + j) ^ sw) << 4)), &x[8 * j]);
-    float m = x[0];
+    if (RELU) {
 #pragma unroll
-    for (int i = 1; i < 32; ++i) m = fmaxf(m, x[i]);
-    m = fmaxf(m, __shfl_xor(m, 1, 64));
-    m = fmaxf(m, __shfl_xor(m, 2, 64));
-    float sum = 0.f;
+      for (int i = 0; i < 32; ++i) x[i] = fmaxf(x[i], 0.f);
+    } else {
+      float m = x[0];
 #pragma unroll
-    for (int i = 0; i < 32; ++i) { x[i] = fast_exp2((x[i] - m) * LOG2E); sum += x[i]; }
-    sum += __shfl_xor(sum, 1, 64);
-    sum += __shfl_xor(sum, 2, 64);
-    const float inv = 1.f / sum;
+      for (int i = 1; i < 32; ++i) m = fmaxf(m, x[i]);
+      m = fmaxf(m, __shfl_xor(m, 1, 64));
+      m = fmaxf(m, __shfl_xor(m, 2, 64));
+      float sum = 0.f;
 #pragma unroll
-    for (int i = 0; i < 32; ++i) x[i] *= inv;
+      for (int i = 0; i < 32; ++i) { x[i] = fast_exp2((x[i] - m) * LOG2E); sum += x[i]; }
+      sum += __shfl_xor(sum, 1, 64);
+      sum += __shfl_xor(sum, 2, 64);
+      const float inv = 1.f / sum;
+#pragma unroll
+      for (int i = 0; i < 32; ++i) x[i] *= inv;
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j)
       *reinterpret_cast<bf16x8_t*>(rp + (((4 * part + j) ^ sw) << 4)) = pack_bf16x8(&x[8 * j]);
@@ -474,6 +495,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // (every wave has then left tile s-1, whose buffer it takes) and each wave waits for its share of tile s+1
 // before the second barrier of step s, so no further barrier is needed.  The loop has no other vector-memory
 // operation (row statistics arrive with the tiles), which is what makes the explicit counter waits exact.
+template <bool RELU>
 __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* pex = smem + DKV_PEX_OFF;
@@ -544,7 +566,7 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
       float x[64];
 #pragma unroll
       for (int c = 0; c < 8; ++c) unpack_bf16x8(xop[c], &x[8 * c]);
-      phi_rows(x, xop);
+      phi_rows<RELU>(x, xop);
     }
     unsigned char* const qA = smem;
     unsigned char* const dA = smem + 32768;
@@ -603,7 +625,7 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
       }
       const bool pre = pass_is_pre(vh);
       const int nrow = pre ? 64 : nq, qb0 = pre ? -64 : 0;
-      phi_tile_inplace_512(qb, nrow);
+      phi_tile_inplace_512<RELU>(qb, nrow);
       __syncthreads();
       const unsigned char* mine = krole ? db : qb;    // rows contracted with xop
       const unsigned char* other = krole ? qb : db;   // rows accumulated into acc
@@ -635,8 +657,8 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
     }
     if (krole) {
       float kf[64];
-      phi_row_clayout(a.k + myrow_off, h, kf);
-      phi_jacobian(acc, kf);
+      phi_row_clayout<RELU>(a.k + myrow_off, h, kf);
+      phi_jacobian<RELU>(acc, kf);
     } else {
       load_bop(a.k + myrow_off, h, xop);
     }
@@ -787,10 +809,17 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
   a.dO = (const uint16_t*)dO; a.xs = (const uint16_t*)sv.xs; a.xr = (const uint16_t*)sv.xr;
   a.rs = sv.rs; a.rr = sv.rr; a.gs = gs; a.gr = gr;
   a.dgpart = (dgs || dgr) ? ws.dgpart : nullptr;
+  const bool relu = dm.phi == PHI_RELU;
   {
     ProfScope ps("bwd_dq_kernel", st);
-    if (gains) bwd_dq_kernel<true><<<dim3(a.ntile * dm.Hq * dm.B), 256, 0, st>>>(a);
-    else bwd_dq_kernel<false><<<dim3(a.ntile * dm.Hq * dm.B), 256, 0, st>>>(a);
+    const dim3 grid(a.ntile * dm.Hq * dm.B);
+    if (relu) {
+      if (gains) bwd_dq_kernel<true, true><<<grid, 256, 0, st>>>(a);
+      else bwd_dq_kernel<false, true><<<grid, 256, 0, st>>>(a);
+    } else {
+      if (gains) bwd_dq_kernel<true, false><<<grid, 256, 0, st>>>(a);
+      else bwd_dq_kernel<false, false><<<grid, 256, 0, st>>>(a);
+    }
   }
   if (dgs || dgr) {
     const int HD = dm.Hq * 128;
@@ -799,10 +828,13 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
   }
   rla_reverse_states(dm, pl.fwd.W, pl.nk, q, ws.dxr, ws.U, ws.rstates, st);
   static const hipError_t lds_attr = hipFuncSetAttribute(
-      reinterpret_cast<const void*>(bwd_dkv_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS_BYTES);
-  (void)lds_attr;
+      reinterpret_cast<const void*>(bwd_dkv_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS_BYTES);
+  static const hipError_t lds_attr_relu = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(bwd_dkv_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS_BYTES);
+  (void)lds_attr; (void)lds_attr_relu;
   ProfScope ps("bwd_dkv_kernel", st);
-  bwd_dkv_kernel<<<dim3(a.ntile * dm.Hkv * dm.B), 512, DKV_LDS_BYTES, st>>>(a);
+  if (relu) bwd_dkv_kernel<true><<<dim3(a.ntile * dm.Hkv * dm.B), 512, DKV_LDS_BYTES, st>>>(a);
+  else bwd_dkv_kernel<false><<<dim3(a.ntile * dm.Hkv * dm.B), 512, DKV_LDS_BYTES, st>>>(a);
 }
 
 }  // namespace rattn

@@ -180,8 +180,9 @@ __device__ __forceinline__ void store_tile_direct(const f32x16_t (&acc)[4], uint
     }
 }
 
-// GAP: the window is not a multiple of 64 (a.gap > 0); the aligned case compiles without the extra key tile
-template <bool GAP>
+// GAP: the window is not a multiple of 64 (a.gap > 0); the aligned case compiles without the extra key tile.
+// RELU: the linear branch uses the ablation's ReLU feature map instead of the softmax map.
+template <bool GAP, bool RELU>
 __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
   __shared__ __align__(16) unsigned char smem[65536];
   const int lane = lane_id(), w = wave_id();
@@ -318,10 +319,10 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
       float x[64];
 #pragma unroll
       for (int dk = 0; dk < 8; ++dk) unpack_bf16x8(qop[dk], &x[8 * dk]);
-      phi_rows(x, qfop);
+      phi_rows<RELU>(x, qfop);
     }
     const bool has_res = j0 > -128;  // the resident tiles hold keys of this chunk
-    if (has_res) phi_tiles_inplace(has_state ? smem + buf0 * 16384 : nullptr, smem + (buf0 ^ 1) * 16384);
+    if (has_res) phi_tiles_inplace<RELU>(has_state ? smem + buf0 * 16384 : nullptr, smem + (buf0 ^ 1) * 16384);
     __syncthreads();
     // Key sub-tile u (keys j0 + 32u .. +31) meets query block w when 32u <= 32w + 31 + gap; a query sees
     // key_local <= q_local + gap.  Sub-tiles 0..3 are resident; with gap > 0 the top queries also reach
@@ -360,7 +361,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
       tile_load_async<4>(vbase + (size_t)(j0 + 128) * kstride, kstride, smem + 32768, w * 4, lane);
       wait_vmem();
       __syncthreads();
-      phi_tiles_inplace(smem, nullptr);
+      phi_tiles_inplace<RELU>(smem, nullptr);
       __syncthreads();
       for (int u = 4; u <= min(5, u_hi); ++u) intra_unit(smem, smem + 32768, u & 1, u);
       __syncthreads();
@@ -438,7 +439,9 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
 bool fast_fwd_supported(const LayerDims& dm, int dtype) {
   if (dtype != 1 || dm.D != 128 || dm.T % 128 != 0) return false;
   if (!(dm.scale > 0.f)) return false;
-  if (dm.phi != PHI_SOFTMAX) return false;  // the ablation's feature maps run on the general kernels
+  // The identity map stays on the general kernels: its features are of size ~1 instead of ~1/D, and the backward of
+  // the first rows past the window (state of rank 1, 2, ...) is a cancellation that needs the fp32 x^r kept there
+  if (dm.phi != PHI_SOFTMAX && dm.phi != PHI_RELU) return false;
   // Windows below 8 keys stay on the general path: their softmax rows are close to one-hot, so the backward's
   // dS = P (dP - delta) is a near-cancellation (exact for W = 1) that bf16 operands turn into rounding noise
   // above the gradient tolerance (measured: worst element 4 % of RMS at W = 2, 3 % at W = 4, 2.5 % from W = 8 on)
@@ -475,8 +478,14 @@ void fast_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
   a.scale_log2 = dm.scale * LOG2E; a.eps = dm.eps;
   ProfScope ps("fwd_fused_kernel", st);
   const dim3 grid((a.ntile - qt0) * dm.Hq * dm.B);
-  if (a.gap > 0) fwd_fused_kernel<true><<<grid, 256, 0, st>>>(a);
-  else fwd_fused_kernel<false><<<grid, 256, 0, st>>>(a);
+  const bool relu = dm.phi == PHI_RELU;
+  if (a.gap > 0) {
+    if (relu) fwd_fused_kernel<true, true><<<grid, 256, 0, st>>>(a);
+    else fwd_fused_kernel<true, false><<<grid, 256, 0, st>>>(a);
+  } else {
+    if (relu) fwd_fused_kernel<false, true><<<grid, 256, 0, st>>>(a);
+    else fwd_fused_kernel<false, false><<<grid, 256, 0, st>>>(a);
+  }
 }
 
 }  // namespace rattn

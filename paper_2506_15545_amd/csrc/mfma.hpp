@@ -198,19 +198,26 @@ constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
 // phi = softmax over the 128 features of a row whose two halves sit in lanes l and l^32 (64 values
-// each, any fixed order); result packed as 8 MFMA operand registers in the same order
+// each, any fixed order); result packed as 8 MFMA operand registers in the same order.
+// RELU selects max(x, 0) per feature instead, the ablation's ReLU map (Sec. 4.5).
+template <bool RELU = false>
 __device__ __forceinline__ void phi_rows(float (&x)[64], bf16x8_t (&op)[8]) {
-  float m = x[0];
+  if (RELU) {
 #pragma unroll
-  for (int i = 1; i < 64; ++i) m = fmaxf(m, x[i]);
-  m = half_max(m);
-  float s = 0.f;
+    for (int i = 0; i < 64; ++i) x[i] = fmaxf(x[i], 0.f);
+  } else {
+    float m = x[0];
 #pragma unroll
-  for (int i = 0; i < 64; ++i) { x[i] = fast_exp2((x[i] - m) * LOG2E); s += x[i]; }
-  s = half_sum(s);
-  const float inv = 1.f / s;
+    for (int i = 1; i < 64; ++i) m = fmaxf(m, x[i]);
+    m = half_max(m);
+    float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < 64; ++i) x[i] *= inv;
+    for (int i = 0; i < 64; ++i) { x[i] = fast_exp2((x[i] - m) * LOG2E); s += x[i]; }
+    s = half_sum(s);
+    const float inv = 1.f / s;
+#pragma unroll
+    for (int i = 0; i < 64; ++i) x[i] *= inv;
+  }
 #pragma unroll
   for (int c = 0; c < 8; ++c) op[c] = pack_bf16x8(&x[8 * c]);
 }
@@ -218,6 +225,7 @@ __device__ __forceinline__ void phi_rows(float (&x)[64], bf16x8_t (&op)[8]) {
 // phi applied in place to LDS tile rows, two threads per row: thread pair r works on row r of tile A
 // (r < 64) or row r-64 of tile B (r >= 64); a null tile pointer skips that half.  Tiles A and B
 // contiguous = one 128-row tile.  Call with all 256 threads; the caller synchronises before and after.
+template <bool RELU = false>
 __device__ __forceinline__ void phi_tiles_inplace(unsigned char* tileA, unsigned char* tileB) {
   const int r = threadIdx.x >> 1, half = threadIdx.x & 1;
   unsigned char* tile = r < 64 ? tileA : tileB;
@@ -229,25 +237,31 @@ __device__ __forceinline__ void phi_tiles_inplace(unsigned char* tileA, unsigned
 #pragma unroll
     for (int j = 0; j < 8; ++j)
       unpack_bf16x8(*reinterpret_cast<const bf16x8_t*>(rp + (((8 * half + j) ^ sw) << 4)), &x[8 * j]);
-    float m = x[0];
+    if (RELU) {
 #pragma unroll
-    for (int i = 1; i < 64; ++i) m = fmaxf(m, x[i]);
-    m = fmaxf(m, __shfl_xor(m, 1, 64));
-    float s = 0.f;
+      for (int i = 0; i < 64; ++i) x[i] = fmaxf(x[i], 0.f);
+    } else {
+      float m = x[0];
 #pragma unroll
-    for (int i = 0; i < 64; ++i) { x[i] = fast_exp2((x[i] - m) * LOG2E); s += x[i]; }
-    s += __shfl_xor(s, 1, 64);
-    const float inv = 1.f / s;
+      for (int i = 1; i < 64; ++i) m = fmaxf(m, x[i]);
+      m = fmaxf(m, __shfl_xor(m, 1, 64));
+      float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < 64; ++i) x[i] *= inv;
+      for (int i = 0; i < 64; ++i) { x[i] = fast_exp2((x[i] - m) * LOG2E); s += x[i]; }
+      s += __shfl_xor(s, 1, 64);
+      const float inv = 1.f / s;
+#pragma unroll
+      for (int i = 0; i < 64; ++i) x[i] *= inv;
+    }
 #pragma unroll
     for (int j = 0; j < 8; ++j)
       *reinterpret_cast<bf16x8_t*>(rp + (((8 * half + j) ^ sw) << 4)) = pack_bf16x8(&x[8 * j]);
   }
 }
 // first `nrows` (64 or 128) rows of one contiguous tile
+template <bool RELU = false>
 __device__ __forceinline__ void phi_tile_inplace(unsigned char* tile, int nrows) {
-  phi_tiles_inplace(tile, nrows > 64 ? tile + 64 * ROW_BYTES : nullptr);
+  phi_tiles_inplace<RELU>(tile, nrows > 64 ? tile + 64 * ROW_BYTES : nullptr);
 }
 
 // Write a [128 rows x 128] bf16 tile held transposed in accumulators (lane = tile row 32w + lane%32,
