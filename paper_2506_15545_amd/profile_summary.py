@@ -6,12 +6,19 @@ Runs on the CPU over directories a profiling run left behind; it launches nothin
     python -m paper_2506_15545_amd.profile_summary stats   <rocprofv3 -d dir> <out.txt> "<command>"
     python -m paper_2506_15545_amd.profile_summary traffic <FETCH_SIZE dir> <WRITE_SIZE dir> <out.txt> \
            <workload> "<fetch command>" "<write command>"
+    python -m paper_2506_15545_amd.profile_summary mfma    <SQ counters dir> <out.txt> "<command>"
 
 `stats` lists calls / average / min / max duration per kernel from the `--kernel-trace --stats` run.
 `traffic` averages the FETCH_SIZE and WRITE_SIZE readings per dispatch of every kernel and scales them by
 what the same counters read for the calibration pass of `bench.py --calibrate-copy` (an out-of-place
 elementwise kernel that reads and writes 256 MiB); the result is HBM-side bytes per launch.  The table is
 followed by the same rows as JSON after a `---JSON---` line, which `bench.py` reads for `roofline.traffic`.
+`mfma` reads one `--pmc` run with SQ_BUSY_CYCLES, SQ_VALU_MFMA_BUSY_CYCLES, SQ_INSTS_MFMA and, if present,
+SQ_INSTS_VALU, SQ_INSTS_LDS, SQ_INSTS_SALU, and lists per kernel how busy the
+matrix pipes were: MFMA busy cycles per SIMD (1024 SIMDs) over the kernel's busy cycles (SQ_BUSY_CYCLES is summed
+over the 32 shader engines), the matrix FLOP/s actually executed (32x32x16 MFMAs, 32768 FLOP each), and the other
+instruction classes per MFMA.  Kernels run serialised under the counters, so durations are a little longer than
+in the timing runs.
 """
 import collections
 import csv
@@ -89,10 +96,46 @@ def traffic(dfetch, dwrite, out, workload, cmd_fetch, cmd_write):
         fo.write("\n---JSON---\n" + json.dumps(table, indent=1) + "\n")
 
 
+def mfma(d, out, command):
+    names = ("SQ_BUSY_CYCLES", "SQ_VALU_MFMA_BUSY_CYCLES", "SQ_INSTS_MFMA", "SQ_INSTS_VALU", "SQ_INSTS_LDS",
+             "SQ_INSTS_SALU")
+    means = {c: counter_means(d, c)[0] for c in names}
+    dur, nd = collections.defaultdict(float), collections.Counter()
+    for f in find(d, "counter_collection.csv"):
+        seen = set()
+        for r in csv.DictReader(open(f)):
+            if r["Dispatch_Id"] in seen:
+                continue
+            seen.add(r["Dispatch_Id"])
+            n = short_name(r["Kernel_Name"])
+            dur[n] += int(r["End_Timestamp"]) - int(r["Start_Timestamp"]); nd[n] += 1
+    SIMDS, SES, FLOP = 1024, 32, 2 * 32 * 32 * 16
+    with open(out, "w") as fo:
+        fo.write(f"command: {command}\n")
+        fo.write("source: rocprofv3 counter_collection.csv, means per dispatch; busy = SQ_VALU_MFMA_BUSY_CYCLES / 1024 SIMDs "
+                 "over SQ_BUSY_CYCLES / 32 shader engines\n\n")
+        fo.write(f"{'kernel':24s} {'disp':>5s} {'avg_us':>8s} {'MFMA_insts':>11s} {'MFMA_TFLOPs':>11s} {'pipe_busy':>9s} "
+                 f"{'VALU/MFMA':>9s} {'LDS/MFMA':>8s} {'SALU/MFMA':>9s}\n")
+        for n in means["SQ_INSTS_MFMA"]:
+            m = means["SQ_INSTS_MFMA"][n]
+            if m <= 0 or n not in means["SQ_BUSY_CYCLES"]:
+                continue
+            us = dur[n] / nd[n] / 1e3
+            busy = means["SQ_BUSY_CYCLES"][n] / SES
+            frac = means["SQ_VALU_MFMA_BUSY_CYCLES"].get(n, 0.0) / SIMDS / busy
+            per = lambda c: (f"{means[c][n] / m:.2f}" if n in means[c] else "-")
+            # vector instructions other than MFMAs (the MFMA count is part of SQ_INSTS_VALU)
+            valu = f"{(means['SQ_INSTS_VALU'][n] - m) / m:.2f}" if n in means["SQ_INSTS_VALU"] else "-"
+            fo.write(f"{n:24s} {nd[n]:5d} {us:8.1f} {m:11.0f} {m * FLOP / (us * 1e-6) / 1e12:11.0f} {frac:9.3f} "
+                     f"{valu:>9s} {per('SQ_INSTS_LDS'):>8s} {per('SQ_INSTS_SALU'):>9s}\n")
+
+
 if __name__ == "__main__":
     if len(sys.argv) >= 5 and sys.argv[1] == "stats":
         stats(sys.argv[2], sys.argv[3], sys.argv[4])
     elif len(sys.argv) >= 8 and sys.argv[1] == "traffic":
         traffic(*sys.argv[2:8])
+    elif len(sys.argv) >= 5 and sys.argv[1] == "mfma":
+        mfma(sys.argv[2], sys.argv[3], sys.argv[4])
     else:
         raise SystemExit(__doc__)
