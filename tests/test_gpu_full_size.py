@@ -100,6 +100,32 @@ def test_layer3b_literal_window_513():
             assert emax <= GRAD_TOL_MAX and erms <= GRAD_TOL_RMS, (name, b, g, emax, erms)
 
 
+def test_layer3b_relu_feature_map():
+    """The 3B-shaped layer with the ablation's ReLU feature map (Sec. 4.5) on the matrix-core kernels: forward and
+    backward of the whole tensor, one group checked against the oracle."""
+    cfg = synth.CONFIGS["layer3b_t4096_w512"]
+    q, k, v, dO = synth.make_layer_inputs(cfg, with_dO=True)
+    print("layer3b, ReLU map: forward + backward on the GPU", flush=True)
+    o, saved = rb.rattn_fwd(q.cuda(), k.cuda(), v.cuda(), cfg.W, softmax_scale=cfg.scale, save_for_bwd=True,
+                            feature_map="relu")
+    rb.rattn_profile_enable(True)
+    dq, dk, dv, _, _ = rb.rattn_bwd(q.cuda(), k.cuda(), v.cuda(), saved, dO.cuda(), cfg.W, softmax_scale=cfg.scale,
+                                    want_dgamma=False, feature_map="relu")
+    torch.cuda.synchronize()
+    names = [n for n, _ in rb.rattn_profile_records()]
+    rb.rattn_profile_enable(False)
+    assert "bwd_dkv_kernel" in names
+    b, g = 2, 5
+    print(f"  oracle fwd + bwd batch {b} kv-group {g}", flush=True)
+    args = [np64(group(cfg, t, b, g)) for t in (q, k, v)]
+    ref = orc.fwd_dense(*args, cfg.W, scale=cfg.scale, feature_map="relu")
+    assert out_err(group(cfg, o, b, g), ref["o"]) <= OUT_TOL
+    gref = orc.bwd_dense(*args, np64(group(cfg, dO, b, g)), cfg.W, scale=cfg.scale, feature_map="relu")
+    for name, got in (("dq", dq), ("dk", dk), ("dv", dv)):
+        emax, erms = grad_err(group(cfg, got, b, g), gref[name])
+        assert emax <= GRAD_TOL_MAX and erms <= GRAD_TOL_RMS, (name, emax, erms)
+
+
 _cache = {}
 
 
