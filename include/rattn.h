@@ -16,7 +16,11 @@
  *  - Layer tensors are contiguous [B, T, H, D], D fastest.  Query head h reads KV head
  *    h / (Hq/Hkv).  D is 64 or 128.
  *  - dtype is the element type of q,k,v,o,dO,dq,dk,dv (and of the decode ring buffers).
- *    Accumulators, linear-attention states, softmax/RMS statistics and gains are fp32.
+ *    Accumulators, softmax/RMS statistics and gains are fp32.  Linear-attention states are
+ *    accumulated in fp32; the decode, prefill-export and general kernels also keep them in
+ *    fp32, while the matrix-core layer kernels (bf16, D = 128) store each per-128-key chunk
+ *    state once as a bf16 matrix-core operand (a carried-in fp32 state of rattn_prefill_chunk
+ *    is rounded the same way where it enters those kernels).
  *  - Every pointer is a DEVICE pointer unless stated otherwise.  The caller owns all
  *    buffers; the library never allocates, frees or synchronises.  All work is enqueued
  *    on `stream` (a hipStream_t passed as void*; NULL = the default stream).  Outputs are
@@ -62,7 +66,13 @@ typedef struct {
   int32_t save_for_bwd;  /* rattn_fwd also fills `saved` (needed by rattn_bwd)                         */
   int32_t feature_map;   /* rattn_feature_map; RATTN_PHI_IDENTITY runs on the general (vector-ALU)
                             kernels for every shape                                                    */
+  int32_t kernel_path;   /* rattn_kernel_path: 0 = the library chooses (matrix-core kernels where the
+                            shape allows); RATTN_PATH_GENERAL forces the general kernels (a second,
+                            independent implementation used by tests).  It changes what `saved` holds:
+                            rattn_fwd and rattn_bwd of one step must be given the same value           */
 } rattn_params;
+
+typedef enum { RATTN_PATH_AUTO = 0, RATTN_PATH_GENERAL = 1 } rattn_kernel_path;
 
 /* Sizes in bytes of the scratch `workspace` rattn_fwd / rattn_bwd need and of the opaque
  * `saved` buffer rattn_fwd fills for rattn_bwd.  Any of the three out pointers (HOST) may
@@ -85,8 +95,7 @@ rattn_status rattn_fwd(const rattn_params* p, const void* q, const void* k, cons
 /* Backward of the layer: gradients of sum(o * dO) w.r.t. q, k, v and the gains.
  * Derived from Sec. 2.1, Eq. 4 and Sec. 3.2 (the linear-branch state gradients are the
  * reverse-time counterpart of Eqs. 2-3).
- *   saved: as written by rattn_fwd with the same params and inputs, in the same process
- *          environment (the RATTN_FORCE_GENERIC debugging switch changes what `saved` holds)
+ *   saved: as written by rattn_fwd with the same params (incl. kernel_path) and inputs
  *   dq [B,T,Hq,D]; dk,dv [B,T,Hkv,D] (summed over the query heads of each group)
  *   dgamma_swa, dgamma_rla: fp32 [Hq,D], each may be NULL (then not computed) */
 rattn_status rattn_bwd(const rattn_params* p, const void* q, const void* k, const void* v,
@@ -169,10 +178,13 @@ rattn_status rattn_step_time_model(double batch, double cache_bytes, double para
                                    double bandwidth, double flops, double* out);
 
 /* Per-kernel timing (tracing aid; off by default).  While enabled, every kernel the library
- * launches is bracketed by a pair of HIP events recorded on the launch stream.  Records pile up
- * until rattn_profile_reset().  rattn_profile_get waits for record `idx` to finish and returns
+ * launches is bracketed by a pair of HIP events recorded on the launch stream.  rattn_profile_enable(1)
+ * creates a fixed pool of RATTN_PROFILE_MAX_RECORDS event pairs (the only allocation; the layer calls
+ * themselves never allocate); records pile up until rattn_profile_reset(), launches beyond the pool
+ * are not recorded.  rattn_profile_get waits for record `idx` to finish and returns
  * its kernel name (library-owned HOST string) and duration in milliseconds; it returns
  * RATTN_ERR_INVALID_ARG for an index outside [0, rattn_profile_count()).  Not thread-safe. */
+#define RATTN_PROFILE_MAX_RECORDS 16384
 void rattn_profile_enable(int on);
 void rattn_profile_reset(void);
 int rattn_profile_count(void);
@@ -181,7 +193,8 @@ rattn_status rattn_profile_get(int idx, const char** name, float* ms);
 /* Machine probe for benchmarks: enqueues a kernel of `blocks` work-groups (256 threads) in which every wave issues
  * 16 * iters bf16 matrix-core instructions (v_mfma_f32_32x32x16_bf16) and nothing else; *flops (HOST, may be NULL)
  * receives the floating-point operations issued.  The caller times the stream.  sink: >= 16 bytes of device
- * memory (never written in practice).  Context for the MFMA roofline (Sec. 3.2 argues from matrix-unit rates). */
+ * memory (never written in practice).  A measurement aid, not an operation of the paper: the benchmark reports
+ * the rate this loop sustains next to the published matrix-core peak. */
 rattn_status rattn_probe_mfma(void* sink, int iters, int blocks, double* flops, void* stream);
 
 /* Static description of a status code. */

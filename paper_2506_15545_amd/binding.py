@@ -14,6 +14,8 @@ LIB_PATH = os.path.join(_PKG, "librattn.so")
 RATTN_F32, RATTN_BF16 = 0, 1
 # rattn_feature_map: the layer's softmax map (Sec. 3.1) and the ablation's two alternatives (Sec. 4.5)
 FEATURE_MAPS = {"softmax": 0, "relu": 1, "identity": 2}
+# rattn_kernel_path: "auto" lets the library choose, "general" forces the general kernels (tests)
+KERNEL_PATHS = {"auto": 0, "general": 1}
 _DTYPES = {torch.float32: RATTN_F32, torch.bfloat16: RATTN_BF16}
 
 EXPORTS = ["rattn_workspace_bytes", "rattn_fwd", "rattn_bwd", "rattn_decode_step",
@@ -28,7 +30,7 @@ class RattnParams(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("T", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
                 ("D", ctypes.c_int32), ("window", ctypes.c_int32), ("chunk", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("rms_eps", ctypes.c_float),
-                ("save_for_bwd", ctypes.c_int32), ("feature_map", ctypes.c_int32)]
+                ("save_for_bwd", ctypes.c_int32), ("feature_map", ctypes.c_int32), ("kernel_path", ctypes.c_int32)]
 
 
 class RattnDecodeParams(ctypes.Structure):
@@ -106,10 +108,11 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def make_params(q, k, window, chunk=0, softmax_scale=1.0, rms_eps=1e-6, save_for_bwd=False, feature_map="softmax"):
+def make_params(q, k, window, chunk=0, softmax_scale=1.0, rms_eps=1e-6, save_for_bwd=False, feature_map="softmax",
+                kernel_path="auto"):
     B, T, Hq, D = q.shape
     return RattnParams(B, T, Hq, k.shape[2], D, window, chunk, _DTYPES[q.dtype], softmax_scale, rms_eps,
-                       1 if save_for_bwd else 0, FEATURE_MAPS[feature_map])
+                       1 if save_for_bwd else 0, FEATURE_MAPS[feature_map], KERNEL_PATHS[kernel_path])
 
 
 def rattn_workspace_bytes(params):
@@ -143,12 +146,12 @@ def _bytes(n, dev):
 
 
 def rattn_fwd(q, k, v, window, gamma_swa=None, gamma_rla=None, chunk=0, softmax_scale=1.0, rms_eps=1e-6,
-              save_for_bwd=False, out=None, saved=None, workspace=None, feature_map="softmax"):
+              save_for_bwd=False, out=None, saved=None, workspace=None, feature_map="softmax", kernel_path="auto"):
     """o = RMS(SWA(q,k,v)) + RMS(RLA(q,k,v)); returns o, or (o, saved) when save_for_bwd.
 
     out / saved / workspace may be passed in to reuse buffers (uint8 tensors for the latter two)."""
     _check_layer(q, k, v)
-    p = make_params(q, k, window, chunk, softmax_scale, rms_eps, save_for_bwd, feature_map)
+    p = make_params(q, k, window, chunk, softmax_scale, rms_eps, save_for_bwd, feature_map, kernel_path)
     fwd_b, _, saved_b = rattn_workspace_bytes(p)
     dev = q.device
     o = torch.empty_like(q) if out is None else out
@@ -164,12 +167,12 @@ def rattn_fwd(q, k, v, window, gamma_swa=None, gamma_rla=None, chunk=0, softmax_
 
 
 def rattn_bwd(q, k, v, saved, dO, window, gamma_swa=None, gamma_rla=None, chunk=0, softmax_scale=1.0,
-              rms_eps=1e-6, want_dgamma=True, workspace=None, out=None, feature_map="softmax"):
-    """(dq, dk, dv, dgamma_swa, dgamma_rla) for upstream gradient dO; `saved` from rattn_fwd."""
+              rms_eps=1e-6, want_dgamma=True, workspace=None, out=None, feature_map="softmax", kernel_path="auto"):
+    """(dq, dk, dv, dgamma_swa, dgamma_rla) for upstream gradient dO; `saved` from rattn_fwd (same kernel_path)."""
     _check_layer(q, k, v)
     if dO.shape != q.shape or dO.dtype != q.dtype or not dO.is_contiguous():
         raise ValueError("dO must match q")
-    p = make_params(q, k, window, chunk, softmax_scale, rms_eps, True, feature_map)
+    p = make_params(q, k, window, chunk, softmax_scale, rms_eps, True, feature_map, kernel_path)
     _, bwd_b, saved_b = rattn_workspace_bytes(p)
     if saved is None or saved.numel() < saved_b:
         raise ValueError("saved buffer missing or too small")
@@ -261,9 +264,13 @@ def rattn_prefill_chunk(q, k, v, window, pos0, k_ring, v_ring, state, gamma_swa=
     _check(lib().rattn_prefill_chunk_workspace_bytes(ctypes.byref(p), int(pos0), ctypes.byref(nbytes)))
     if workspace is None:
         workspace = torch.empty(max(nbytes.value, 16), dtype=torch.uint8, device=q.device)
+    elif not (workspace.is_cuda and workspace.is_contiguous() and workspace.dtype == torch.uint8):
+        raise ValueError("workspace must be a contiguous uint8 device tensor")
     o = torch.empty_like(q) if out is None else out
-    _check(lib().rattn_prefill_chunk(ctypes.byref(p), int(pos0), _ptr(q), _ptr(k), _ptr(v), _ptr(gamma_swa),
-                                     _ptr(gamma_rla), _ptr(k_ring), _ptr(v_ring), _ptr(state), _ptr(o), _ptr(workspace),
+    gs = _gain(gamma_swa, Hq, D, q.device)   # fp32 [Hq,D] on the device, kept alive until the call has been enqueued
+    gr = _gain(gamma_rla, Hq, D, q.device)
+    _check(lib().rattn_prefill_chunk(ctypes.byref(p), int(pos0), _ptr(q), _ptr(k), _ptr(v), _ptr(gs),
+                                     _ptr(gr), _ptr(k_ring), _ptr(v_ring), _ptr(state), _ptr(o), _ptr(workspace),
                                      ctypes.c_size_t(workspace.numel()), _stream()))
     return o
 

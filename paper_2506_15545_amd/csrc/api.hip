@@ -4,28 +4,32 @@
 #include <stdlib.h>
 #include <string.h>
 
-#include <vector>
-
 #include "kernels.hpp"
 #include "rattn.h"
 
 namespace rattn {
 namespace {
+// Event pairs come from a pool created by rattn_profile_enable(1): recording inside the layer calls allocates nothing.
 struct ProfRec { const char* name; hipEvent_t a, b; };
 bool g_prof_on = false;
-std::vector<ProfRec> g_prof;
+ProfRec g_pool[RATTN_PROFILE_MAX_RECORDS];
+int g_pool_size = 0;   // event pairs that exist
+int g_prof_count = 0;  // records in use
+bool g_prof_open = false;
 }  // namespace
 void prof_begin(const char* name, hipStream_t st) {
-  if (!g_prof_on) return;
-  ProfRec r;
+  g_prof_open = false;
+  if (!g_prof_on || g_prof_count >= g_pool_size) return;
+  ProfRec& r = g_pool[g_prof_count];
   r.name = name;
-  if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
-  (void)hipEventRecord(r.a, st);  // tracing aid: a failed record shows up as a failed rattn_profile_get
-  g_prof.push_back(r);
+  if (hipEventRecord(r.a, st) != hipSuccess) return;  // tracing aid: the launch itself is not affected
+  ++g_prof_count;
+  g_prof_open = true;
 }
 void prof_end(hipStream_t st) {
-  if (!g_prof_on || g_prof.empty()) return;
-  (void)hipEventRecord(g_prof.back().b, st);
+  if (!g_prof_on || !g_prof_open) return;
+  (void)hipEventRecord(g_pool[g_prof_count - 1].b, st);
+  g_prof_open = false;
 }
 }  // namespace rattn
 
@@ -68,11 +72,6 @@ struct Layout {
   size_t fwd_bytes, bwd_bytes;
 };
 
-bool force_generic() {
-  const char* e = getenv("RATTN_FORCE_GENERIC");
-  return e && e[0] && e[0] != '0';
-}
-
 rattn_status make_layout(const rattn_params* p, Layout* L) {
   if (!p) return fail(RATTN_ERR_INVALID_ARG, "params is NULL");
   if (p->B < 1 || p->T < 1 || p->Hq < 1 || p->Hkv < 1)
@@ -87,6 +86,8 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
   if (p->dtype != RATTN_F32 && p->dtype != RATTN_BF16) return fail(RATTN_ERR_UNSUPPORTED, "unknown dtype %d", p->dtype);
   if (p->feature_map < RATTN_PHI_SOFTMAX || p->feature_map > RATTN_PHI_IDENTITY)
     return fail(RATTN_ERR_UNSUPPORTED, "unknown feature_map %d", p->feature_map);
+  if (p->kernel_path != RATTN_PATH_AUTO && p->kernel_path != RATTN_PATH_GENERAL)
+    return fail(RATTN_ERR_UNSUPPORTED, "unknown kernel_path %d", p->kernel_path);
   if (!(p->rms_eps > 0.f)) return fail(RATTN_ERR_INVALID_ARG, "rms_eps must be > 0");
   if (!(p->softmax_scale == p->softmax_scale) || p->softmax_scale == 0.f)
     return fail(RATTN_ERR_INVALID_ARG, "softmax_scale must be a non-zero number");
@@ -106,16 +107,15 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
   L->pad = p->dtype == RATTN_BF16 && dm.D == 128 && dm.T % 128 != 0 && dm.T >= PAD_MIN_T;
   if (L->pad) L->dmf.T = (dm.T + 127) / 128 * 128;
   const rattn::LayerDims& dmf = L->dmf;
-  L->fast_fwd = rattn::fast_fwd_supported(dmf, p->dtype);
+  L->fast_fwd = p->kernel_path != RATTN_PATH_GENERAL && rattn::fast_fwd_supported(dmf, p->dtype);
   if (!L->fast_fwd) { L->pad = false; L->dmf = dm; }
-  // `saved` is sized for the padded length (the general kernels, if forced, use the front of each part)
+  // `saved` is sized for the padded length
   const size_t nq = (size_t)dm.B * dm.T * dm.Hq * dm.D;
   const size_t nrow = (size_t)dm.B * dm.Hq * dm.T;
   const size_t nq_f = (size_t)dmf.B * dmf.T * dmf.Hq * dmf.D, nkv_f = (size_t)dmf.B * dmf.T * dmf.Hkv * dmf.D;
   const size_t nrow_f = (size_t)dmf.B * dmf.Hq * dmf.T;
   size_t off = 0;
-  // pre-norm branch outputs: tensor dtype where the matrix-core kernels may run (the general kernels, if forced,
-  // then store the tensor dtype too), fp32 where only the general kernels can
+  // pre-norm branch outputs: tensor dtype for the matrix-core kernels, fp32 for the general kernels
   const size_t sv_esize = L->fast_fwd ? L->esize : 4;
   L->sv_xs = off; off += align_up(nq_f * sv_esize);
   L->sv_xr = off; off += align_up(nq_f * sv_esize);
@@ -177,9 +177,8 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
     }
     L->fast_bwd_bytes = off;
   }
-  // the general-shape kernels stay selectable (RATTN_FORCE_GENERIC=1), so size for both
-  L->fwd_bytes = L->gen_fwd_bytes > L->fast_fwd_bytes ? L->gen_fwd_bytes : L->fast_fwd_bytes;
-  L->bwd_bytes = L->gen_bwd_bytes > L->fast_bwd_bytes ? L->gen_bwd_bytes : L->fast_bwd_bytes;
+  L->fwd_bytes = L->fast_fwd ? L->fast_fwd_bytes : L->gen_fwd_bytes;
+  L->bwd_bytes = L->fast_fwd ? L->fast_bwd_bytes : L->gen_bwd_bytes;
   return RATTN_OK;
 }
 
@@ -252,17 +251,25 @@ const char* rattn_status_string(rattn_status s) {
 const char* rattn_last_error(void) { return g_err; }
 
 void rattn_profile_reset(void) {
-  for (auto& r : rattn::g_prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
-  rattn::g_prof.clear();
+  rattn::g_prof_count = 0;
+  rattn::g_prof_open = false;
 }
 void rattn_profile_enable(int on) {
   rattn_profile_reset();
+  if (on) {  // fill the event pool once; the layer calls only record into it
+    while (rattn::g_pool_size < RATTN_PROFILE_MAX_RECORDS) {
+      rattn::ProfRec& r = rattn::g_pool[rattn::g_pool_size];
+      if (hipEventCreate(&r.a) != hipSuccess) break;
+      if (hipEventCreate(&r.b) != hipSuccess) { (void)hipEventDestroy(r.a); break; }
+      ++rattn::g_pool_size;
+    }
+  }
   rattn::g_prof_on = on != 0;
 }
-int rattn_profile_count(void) { return (int)rattn::g_prof.size(); }
+int rattn_profile_count(void) { return rattn::g_prof_count; }
 rattn_status rattn_profile_get(int idx, const char** name, float* ms) {
-  if (idx < 0 || idx >= (int)rattn::g_prof.size()) return fail(RATTN_ERR_INVALID_ARG, "profile index %d out of range", idx);
-  const auto& r = rattn::g_prof[idx];
+  if (idx < 0 || idx >= rattn::g_prof_count) return fail(RATTN_ERR_INVALID_ARG, "profile index %d out of range", idx);
+  const auto& r = rattn::g_pool[idx];
   if (hipEventSynchronize(r.b) != hipSuccess) return fail(RATTN_ERR_HIP, "hipEventSynchronize failed");
   float t = 0.f;
   if (hipEventElapsedTime(&t, r.a, r.b) != hipSuccess) return fail(RATTN_ERR_HIP, "hipEventElapsedTime failed");
@@ -296,7 +303,7 @@ rattn_status rattn_fwd(const rattn_params* p, const void* q, const void* k, cons
     return fail(RATTN_ERR_WORKSPACE, "forward needs %zu workspace bytes, got %zu", L.fwd_bytes, workspace_bytes);
   hipStream_t st = (hipStream_t)stream;
   rattn::SavedPtrs sv = saved_views(L, p->save_for_bwd ? saved : nullptr);
-  if (L.fast_fwd && !force_generic()) {
+  if (L.fast_fwd) {
     char* w = (char*)workspace;
     const void *qf = q, *kf = k, *vf = v;
     void* of = o;
@@ -331,7 +338,7 @@ rattn_status rattn_bwd(const rattn_params* p, const void* q, const void* k, cons
   hipStream_t st = (hipStream_t)stream;
   rattn::SavedPtrs sv = saved_views(L, const_cast<void*>(saved));
   char* w = (char*)workspace;
-  if (L.fast_fwd && !force_generic()) {
+  if (L.fast_fwd) {
     rattn::FastBwdWs fw;
     fw.dxs = w + L.fb_dxs; fw.dxr = w + L.fb_dxr; fw.delta = (float*)(w + L.fb_delta); fw.U = (float*)(w + L.fb_u);
     fw.states = w + L.fb_states; fw.rstates = w + L.fb_rstates; fw.dgpart = (float*)(w + L.fb_dgpart);
@@ -446,7 +453,7 @@ rattn_status rattn_prefill_chunk(const rattn_params* p, int32_t pos0, const void
   // Direct route on the matrix-core kernels: ring and chunk are whole 128-row tiles, so the forward computes the
   // chunk's query tiles only, straight from q into o, and (window a multiple of 128: every such tile reads a chunk
   // state) the carried state enters as the initial value of the state scan.  Only K and V are gathered.
-  if (C.L2.fast_fwd && !C.L2.pad && !force_generic() && C.R % 128 == 0 && (!carried || p->window % 128 == 0)) {
+  if (C.L2.fast_fwd && !C.L2.pad && C.R % 128 == 0 && (!carried || p->window % 128 == 0)) {
     rattn::chunk_concat(dm, p->dtype, p->T, C.R, pos0, nullptr, k, v, k_ring, v_ring, nullptr, w + C.kc, w + C.vc, st);
     rattn::SavedPtrs none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, false};
     rattn::fast_fwd(dm, q, w + C.kc, w + C.vc, gamma_swa, gamma_rla, o, none, (float*)(w + C.fwdws + C.L2.ff_u),
@@ -462,7 +469,7 @@ rattn_status rattn_prefill_chunk(const rattn_params* p, int32_t pos0, const void
                 C.L2.fwd_bytes, stream);
   if (s != RATTN_OK) return s;
   if (carried)
-    rattn::chunk_fixup(dm, p->dtype, p->T, C.R, (C.L2.fast_fwd && !force_generic()) ? C.L2.dmf.T : dm.T, w + C.qc,
+    rattn::chunk_fixup(dm, p->dtype, p->T, C.R, C.L2.fast_fwd ? C.L2.dmf.T : dm.T, w + C.qc,
                        saved_views(C.L2, w + C.saved), state, gamma_swa, gamma_rla, o, st);
   else
     rattn::chunk_copy_out(dm, p->dtype, p->T, C.R, w + C.oc, o, st);

@@ -189,13 +189,20 @@ __device__ __forceinline__ float sum16(float x) {
 // Backward of the two RMS norms (Sec. 3.2) for 32 consecutive query rows of one head, by one wave: 16 lanes per row,
 // 8 features each, four rows per pass (row-contiguous 16-byte accesses).  With y = g * x * r, r = rsqrt(mean x^2 +
 // eps):  dx = r g dy - x r^3 mean(g dy x),  dg += dy x r.  Stores d xs, d xr (bf16) and delta = rowsum(d xs * xs)
-// to global memory for the later kernels and, if `stage` is given, d xr also into rows 0..31 of that LDS tile
-// (swizzled row layout), from where the wave takes it as an MFMA operand without waiting for the global stores.
+// to global memory for the later kernels and also into LDS: d xs in two 16-row pieces at `stage_s` and
+// `stage_s` + 16 KB (rows 0..15 of each, swizzled row layout; the caller passes a 16-row-aligned address: these are
+// exactly the LDS rows into which the same wave later loads its share of two 64-key tiles, so no other wave's
+// tile load can land on rows that are still being read) and, if `stage_r` is given, d xr into rows 0..31 of that
+// tile, delta into dl_stage[0..31]; the wave
+// takes them from there as MFMA operands / row statistics without waiting for (or re-reading) the global stores.
+// dO, x_s, x_r are read once and d xs, d xr are not read again by this kernel: their accesses are marked
+// non-temporal so that they do not push the K/V tiles, which neighbouring work-groups share, out of the L2.
 // GAINS: gains other than one and/or gain gradients; the wave's gradient partials (sums over its 32 rows) go to
 // dgp_s / dgp_r (128 floats each) when those are given.
 template <bool GAINS>
 __device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, int hq, size_t row0_off, size_t qstride, size_t stat0,
-                                             unsigned char* stage, float* dgp_s, float* dgp_r, int lane) {
+                                             unsigned char* stage_s, unsigned char* stage_r, float* dl_stage,
+                                             float* dgp_s, float* dgp_r, int lane) {
   const int sub = lane >> 4, c = lane & 15;
   uint16_t* dxs_w = const_cast<uint16_t*>(a.dxs);
   uint16_t* dxr_w = const_cast<uint16_t*>(a.dxr);
@@ -212,9 +219,9 @@ __device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, int hq, size_
     const int r = 4 * it + sub;
     const size_t off = row0_off + (size_t)r * qstride + 8 * c;
     float dy[8], xs[8], xr[8];
-    unpack_bf16x8(*reinterpret_cast<const bf16x8_t*>(a.dO + off), dy);
-    unpack_bf16x8(*reinterpret_cast<const bf16x8_t*>(a.xs + off), xs);
-    unpack_bf16x8(*reinterpret_cast<const bf16x8_t*>(a.xr + off), xr);
+    unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(a.dO + off)), dy);
+    unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(a.xs + off)), xs);
+    unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(a.xr + off)), xr);
     const float r_s = a.rs[stat0 + r], r_r = a.rr[stat0 + r];
     float m1 = 0.f, m2 = 0.f;
 #pragma unroll
@@ -242,11 +249,15 @@ __device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, int hq, size_
     unpack_bf16x8(apk, av);
 #pragma unroll
     for (int e = 0; e < 8; ++e) dl = fmaf(av[e], xs[e], dl);
-    *reinterpret_cast<bf16x8_t*>(dxs_w + off) = apk;
-    *reinterpret_cast<bf16x8_t*>(dxr_w + off) = cpk;
-    if (stage) *reinterpret_cast<bf16x8_t*>(stage + r * ROW_BYTES + ((c ^ swz(r)) << 4)) = cpk;
+    __builtin_nontemporal_store(apk, reinterpret_cast<bf16x8_t*>(dxs_w + off));
+    __builtin_nontemporal_store(cpk, reinterpret_cast<bf16x8_t*>(dxr_w + off));
+    {  // staged in two 16-row pieces, see dxs_stage_addr
+      const int R = r & 15;
+      *reinterpret_cast<bf16x8_t*>(stage_s + (r >> 4) * 16384 + R * ROW_BYTES + ((c ^ swz(R)) << 4)) = apk;
+    }
+    if (stage_r) *reinterpret_cast<bf16x8_t*>(stage_r + r * ROW_BYTES + ((c ^ swz(r)) << 4)) = cpk;
     dl = sum16(dl);
-    if (c == 0) delta_w[stat0 + r] = dl;
+    if (c == 0) { delta_w[stat0 + r] = dl; dl_stage[r] = dl; }
   }
   if (GAINS && dgp_s) {
 #pragma unroll
@@ -265,6 +276,7 @@ __device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, int hq, size_
 template <bool GAINS, bool RELU>
 __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
   __shared__ __align__(16) unsigned char smem[65536];
+  __shared__ float dl_stage[128];
   const int lane = lane_id(), w = wave_id();
   const int r32 = lane & 31, h = lane >> 5;
   const LaneOff lo = make_lane_off(lane);
@@ -298,10 +310,22 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
       dgp_r = dgp_s + (size_t)4 * a.ntile * a.B * Hq * 128;
     }
     rms_bwd_rows<GAINS>(a, hq, qtile_off + (size_t)(32 * w) * qstride, qstride, stat_off - r32,
-                        has_lin ? smem + 32 * w * ROW_BYTES : nullptr, dgp_s, dgp_r, lane);
+                        smem + 32768 + 16 * w * ROW_BYTES, has_lin ? smem + 32 * w * ROW_BYTES : nullptr,
+                        dl_stage + 32 * w, dgp_s, dgp_r, lane);
   }
-  bf16x8_t qop[8];
-  load_bop(a.q + myrow_off, h, qop);
+  // own rows, staged by this wave in the prologue: LDS executes a wave's accesses in order, and the reads below are
+  // complete (lgkmcnt wait) before this wave's tile loads may overwrite the rows.  Every later tile load of wave w
+  // covers rows 16w..16w+15 of a 64-key tile (or rows 32w..32w+31 of the 128-row state tile): the staged d xs rows
+  // sit in rows 16w..16w+15 of the two V tiles at 32 KB and 48 KB, the staged d xr rows in rows 32w..32w+31 of the
+  // tile at 0, so a wave only ever overwrites its own staging rows.
+  bf16x8_t dxsop[8];
+  {
+    const int R = 16 * w + (r32 & 15);  // query row r32 of this wave sits in row R of piece r32 / 16
+    const unsigned char* rowp = smem + 32768 + (r32 >> 4) * 16384 + R * ROW_BYTES;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) dxsop[c] = *reinterpret_cast<const bf16x8_t*>(rowp + (((2 * c + h) ^ swz(R)) << 4));
+  }
+  const float dl = dl_stage[32 * w + r32];
   f32x16_t acc[4] = {{0}, {0}, {0}, {0}};
 
   // ---- linear branch: d phi(q)
@@ -313,11 +337,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
     const bool has_state = j0 >= 0, has_res = j0 > -128;
     const int u_hi = w + ((31 + gap) >> 5);
     bf16x8_t dxrop[8];
-    // own rows, staged by this wave in the prologue: LDS executes a wave's accesses in order, and the reads are
-    // complete before the tile loads below may overwrite the rows
 #pragma unroll
     for (int c = 0; c < 8; ++c) dxrop[c] = lds_row(smem, lo, 32 * w, c);
-    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the staged rows are in registers
     // key sub-tile u (keys j0 + 32u .. +31): dC = V dXr^T, masked, then d phi(q)^T += phi(K)^T dC
     auto intra_unit = [&](const unsigned char* kt, const unsigned char* vt, int ks, int u) {
       f32x16_t c = {0};
@@ -385,13 +407,10 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
   }
 
   // ---- softmax branch
-  // The wave reads back d xs and delta of its own rows: its stores are complete after a full vector-memory wait
-  // (the linear branch has had several), and the vector cache is the wave's own.
-  if (!has_lin) wait_vmem();
-  bf16x8_t dxsop[8];
-  load_bop(a.dxs + myrow_off, h, dxsop);
+  if (!has_lin) __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the staged rows are in registers
+  bf16x8_t qop[8];
+  load_bop(a.q + myrow_off, h, qop);
   const float lse2 = a.lse[stat_off] * LOG2E;
-  const float dl = a.delta[stat_off];
   const int kt_lo = max(0, t0 - W);
   const int ntiles = (t0 + 128 - kt_lo) / 64;
   {

@@ -11,9 +11,10 @@
 //                               state pre-pass), Qf/Kf = phi(Q)/phi(K) computed on the operand registers
 //   combination (Sec. 3.2)   :  o = gs * x_s * r_s + gr * x_r * r_r, transposed through LDS for
 //                               coalesced stores
-// K/V tiles (64 keys) stream through a double buffer in LDS with direct-to-LDS loads; the linear
-// branch runs first (its normalised result is carried as packed bf16), then the softmax branch walks
-// its key tiles from the diagonal downwards, so every row's running maximum is finite from the start.
+// K/V tiles (64 keys) stream through a double buffer in LDS with direct-to-LDS loads; the softmax branch
+// walks its key tiles from the diagonal downwards (every row's running maximum is finite from the start),
+// then the linear branch runs on the two lowest tiles, which are still resident; the normalised softmax-branch
+// result stays in fp32 registers meanwhile, so the output is rounded to bf16 once.
 #include "common.hpp"
 #include "kernels.hpp"
 #include "mfma.hpp"
@@ -296,14 +297,9 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
       store_tile_transposed(smem, vals, a.xs_out + qtile_off, qstride, w, lane);
     }
   }
-  bf16x2_t ys[4][8];  // x_s * r_s, packed
+  // x_s * r_s stays in fp32 across the linear branch: the output is rounded once, after the sum of the branches
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      f32x2_t f = {oacc[dt][2 * i] * rs_val, oacc[dt][2 * i + 1] * rs_val};
-      ys[dt][i] = __builtin_convertvector(f, bf16x2_t);
-    }
+  for (int dt = 0; dt < 4; ++dt) oacc[dt] *= rs_val;
   const float lse_val = (m + log2f(l)) * LN2;
 
   // ------------------------------------------------------------------ linear branch
@@ -406,7 +402,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) vals[dt][i] = __builtin_fmaf(rr_val, xr[dt][i], (float)ys[dt][i >> 1][i & 1]);
+        for (int i = 0; i < 16; ++i) vals[dt][i] = __builtin_fmaf(rr_val, xr[dt][i], oacc[dt][i]);
     } else {
       // the head's two gain rows go through LDS (free since the last barrier; the store below uses [0, 32K))
       float* gl = reinterpret_cast<float*>(smem + 32768);
@@ -426,7 +422,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int i = 4 * i4 + e;
-            vals[dt][i] = ga[e] * (float)ys[dt][i >> 1][i & 1] + gb[e] * xr[dt][i];
+            vals[dt][i] = ga[e] * oacc[dt][i] + gb[e] * xr[dt][i];
           }
         }
     }

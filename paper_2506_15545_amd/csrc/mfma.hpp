@@ -27,6 +27,7 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef float f32x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 
 #define RATTN_LDS(p) ((__attribute__((address_space(3))) void*)(p))
 
@@ -288,8 +289,9 @@ __device__ __forceinline__ void store_tile_transposed(unsigned char* smem, const
     const int id = tid + 256 * i;
     const int r = id >> 4, p = id & 15;
     const int c = p ^ swz(r);
-    const uint4 val = *reinterpret_cast<const uint4*>(smem + r * ROW_BYTES + (p << 4));
-    *reinterpret_cast<uint4*>(dst + (size_t)r * row_stride + c * 8) = val;
+    const u32x4_t val = *reinterpret_cast<const u32x4_t*>(smem + r * ROW_BYTES + (p << 4));
+    // written once, not read again by the kernel that writes it: keep it from displacing the shared K/V tiles in L2
+    __builtin_nontemporal_store(val, reinterpret_cast<u32x4_t*>(dst + (size_t)r * row_stride + c * 8));
   }
   __syncthreads();
 }

@@ -2,7 +2,6 @@
 fp64 oracle, on shapes that span several query tiles, both state alignments (W % 128 == 0 and 64),
 the causal degenerate case and GQA; plus agreement with the general-shape kernels."""
 import math
-import os
 import numpy as np
 import pytest
 import torch
@@ -10,6 +9,8 @@ import torch
 from oracle import rattn_oracle as orc
 from paper_2506_15545_amd import binding as rb
 from paper_2506_15545_amd import synth
+import bf16_error_model as em
+import parity_metrics as pm
 
 pytestmark = pytest.mark.gpu
 
@@ -19,9 +20,8 @@ def np64(t):
 
 
 def bf16_err(got, ref):
-    """max |got-ref| after taking off the storage rounding of a bf16 value (2^-8 |ref|)."""
-    e = np.abs(np64(got) - ref)
-    return float(np.max(np.maximum(e - np.abs(ref) / 256.0, 0.0)))
+    """max |got-ref| beyond the storage rounding of the bf16 value itself (saved tensors, relative checks)."""
+    return pm.out_err_bf16(np64(got), ref)["beyond_storage"]
 
 
 CASES = [
@@ -56,7 +56,7 @@ def test_fast_fwd_matches_oracle(B, T, Hq, Hkv, W):
     torch.cuda.synchronize()
     ref = orc.fwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), W, scale=scale, gamma_swa=np64(gs), gamma_rla=np64(gr))
     gmax = max(float(gs.abs().max()), float(gr.abs().max()), 1.0)
-    assert bf16_err(o, ref["o"]) <= 2e-2 * gmax
+    pm.assert_out_bf16(np64(o), ref["o"], gmax)
     # saved tensors: pre-norm branch outputs and row statistics
     n = B * T * Hq * D
     xs = saved[:2 * n].view(torch.bfloat16).view(B, T, Hq, D)
@@ -87,11 +87,7 @@ def test_fast_and_general_kernels_agree():
     q, k, v = x["q"].cuda(), x["k"].cuda(), x["v"].cuda()
     scale = 1.0 / math.sqrt(D)
     o_fast = rb.rattn_fwd(q, k, v, W, softmax_scale=scale)
-    os.environ["RATTN_FORCE_GENERIC"] = "1"
-    try:
-        o_gen = rb.rattn_fwd(q, k, v, W, softmax_scale=scale)
-    finally:
-        del os.environ["RATTN_FORCE_GENERIC"]
+    o_gen = rb.rattn_fwd(q, k, v, W, softmax_scale=scale, kernel_path="general")
     torch.cuda.synchronize()
     assert float((o_fast.float() - o_gen.float()).abs().max()) <= 4e-2
     rb.rattn_profile_enable(True)
@@ -109,15 +105,11 @@ def test_fast_fwd_is_deterministic():
     assert torch.equal(a, b)
 
 
-def grad_err(got, ref):
-    """Gradients are not unit-scale: early tokens carry large terms that cancel, so with bf16 MFMA
-    operands (dx, P, dS rounded to 8 bits) the error of an element scales with its terms, not with
-    the tensor RMS.  Two numbers: the worst element against a mixed bound RMS + |ref| (must be <= 3e-2:
-    four independent 2^-9 roundings -- saved x, dx, P/dS, stored result -- at the 5-sigma element), and
-    the RMS error over the tensor relative to RMS(ref) (must be <= 5e-3: catches anything systematic)."""
-    rms = math.sqrt(float(np.mean(ref ** 2))) + 1e-30
-    e = np.abs(np64(got) - ref)
-    return float(np.max(e / (rms + np.abs(ref)))), math.sqrt(float(np.mean(e ** 2))) / rms
+def model_grads(x, W, scale, gains=True, feature_map="softmax"):
+    """The bf16 error model (oracle arithmetic with the matrix-core path's roundings) on the same input."""
+    kw = dict(gamma_swa=np64(x["gamma_swa"]), gamma_rla=np64(x["gamma_rla"])) if gains else {}
+    return em.model_fwd_bwd(np64(x["q"]), np64(x["k"]), np64(x["v"]), np64(x["dO"]), W, scale=scale,
+                            feature_map=feature_map, **kw)
 
 
 BWD_CASES = [
@@ -156,10 +148,9 @@ def test_fast_bwd_matches_oracle(B, T, Hq, Hkv, W):
     assert "bwd_dkv_kernel" in names and "gen_bwd_dkv_kernel" not in names
     ref = orc.bwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), np64(x["dO"]), W, scale=scale,
                         gamma_swa=np64(gs), gamma_rla=np64(gr))
-    errs = {n: grad_err(g_, ref[n]) for n, g_ in (("dq", dq), ("dk", dk), ("dv", dv))}
-    print(errs, flush=True)
-    for n, (emax, erms) in errs.items():
-        assert emax <= 3e-2 and erms <= 5e-3, f"{n}: max {emax} rms {erms}"
+    model = model_grads(x, W, scale)
+    for n, g_ in (("dq", dq), ("dk", dk), ("dv", dv)):
+        pm.assert_grad_bf16(np64(g_), ref[n], n, model[n])
     for n, g_ in (("dgamma_swa", dgs), ("dgamma_rla", dgr)):
         if np.all(ref[n] == 0):
             assert float(g_.abs().max()) <= 1e-6
@@ -186,15 +177,14 @@ def test_fast_bwd_unit_gains_no_dgamma(B, T, Hq, Hkv, W):
     assert "bwd_dkv_kernel" in names and "bwd_prep_kernel" not in names
     assert dgs is None and dgr is None
     ref = orc.bwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), np64(x["dO"]), W, scale=scale)
-    errs = {n: grad_err(g_, ref[n]) for n, g_ in (("dq", dq), ("dk", dk), ("dv", dv))}
-    print(errs, flush=True)
-    for n, (emax, erms) in errs.items():
-        assert emax <= 3e-2 and erms <= 5e-3, f"{n}: max {emax} rms {erms}"
+    model = model_grads(x, W, scale, gains=False)
+    for n, g_ in (("dq", dq), ("dk", dk), ("dv", dv)):
+        pm.assert_grad_bf16(np64(g_), ref[n], n, model[n])
     # asking for the gain gradients takes the separate pass; dq, dk, dv agree to rounding of the row sums
     dq2, dk2, dv2, dgs2, dgr2 = rb.rattn_bwd(q, k, v, saved, dO, W, softmax_scale=scale, want_dgamma=True)
     for n, g1, g2 in (("dq", dq, dq2), ("dk", dk, dk2), ("dv", dv, dv2)):
-        emax, erms = grad_err(g1, np64(g2))
-        assert emax <= 1e-2 and erms <= 2e-3, f"{n} fused vs separate: max {emax} rms {erms}"
+        e = pm.grad_err_bf16(np64(g1), np64(g2))
+        assert e["worst"] <= 1e-2 and e["rms"] <= 2e-3, f"{n} with and without gain gradients: {e}"
 
 
 def test_fast_bwd_is_deterministic():
@@ -227,11 +217,11 @@ def test_ragged_length_runs_on_padded_copies(B, T, Hq, Hkv, W):
     kw = dict(scale=scale, gamma_swa=np64(gs), gamma_rla=np64(gr))
     ref = orc.fwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), W, **kw)
     gmax = max(float(gs.abs().max()), float(gr.abs().max()), 1.0)
-    assert bf16_err(o, ref["o"]) <= 2e-2 * gmax
+    pm.assert_out_bf16(np64(o), ref["o"], gmax)
     refb = orc.bwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), np64(x["dO"]), W, **kw)
+    model = model_grads(x, W, scale)
     for n, g_ in (("dq", dq), ("dk", dk), ("dv", dv)):
-        emax, erms = grad_err(g_, refb[n])
-        assert emax <= 3e-2 and erms <= 5e-3, f"{n}: max {emax} rms {erms}"
+        pm.assert_grad_bf16(np64(g_), refb[n], n, model[n])
     for n, g_ in (("dgamma_swa", dgs), ("dgamma_rla", dgr)):
         if np.all(refb[n] == 0):
             assert float(g_.abs().max()) <= 1e-6
@@ -297,14 +287,14 @@ def test_step_can_be_captured_in_a_graph():
         torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("std,scale,gmax,grms", [(3.0, 1.0 / math.sqrt(128), 6e-2, 8e-3), (1.0, 1.0, 6e-2, 8e-3),
-                                                 (0.05, 1.0 / math.sqrt(128), 3e-2, 5e-3)])
-def test_fast_path_peaked_and_flat_softmax(std, scale, gmax, grms):
+@pytest.mark.parametrize("std,scale", [(3.0, 1.0 / math.sqrt(128)), (1.0, 1.0), (0.05, 1.0 / math.sqrt(128))])
+def test_fast_path_peaked_and_flat_softmax(std, scale):
     """Large logits (rows close to one-hot, frequent raises of the running maximum inside a tile, exponent arguments
     far below zero), the paper's unscaled logits, and nearly flat rows: forward and backward against the oracle.
-    The forward keeps its bound.  For the peaked cases the gradient bound is wider: with one-hot-like rows
+    The forward keeps its bound.  For the peaked cases the gradient error is larger: with one-hot-like rows
     dS = P (dP - delta) is a near-cancellation, and the bf16 rounding of P and dP (2^-9 of values that cancel)
-    is what is left of it -- the same effect that keeps windows below 8 keys off this path."""
+    is what is left of it -- the same effect that keeps windows below 8 keys off this path.  The error model shows
+    the same on these inputs, so the bound relative to the model applies; the absolute caps are doubled."""
     B, T, Hq, Hkv, D, W = 1, 512, 2, 1, 128, 192
     x = synth.make_random_layer(B, T, Hq, Hkv, D, "bf16", 3100 + int(100 * std), std=std, with_dO=True)
     q, k, v, dO = x["q"].cuda(), x["k"].cuda(), x["v"].cuda(), x["dO"].cuda()
@@ -313,10 +303,10 @@ def test_fast_path_peaked_and_flat_softmax(std, scale, gmax, grms):
     torch.cuda.synchronize()
     ref = orc.fwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), W, scale=scale)
     assert np.isfinite(np64(o)).all()
-    assert bf16_err(o, ref["o"]) <= 2e-2
+    pm.assert_out_bf16(np64(o), ref["o"])
     refb = orc.bwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), np64(x["dO"]), W, scale=scale)
+    model = model_grads(x, W, scale, gains=False)
     for n, g_ in (("dq", dq), ("dk", dk), ("dv", dv)):
         assert np.isfinite(np64(g_)).all(), n
-        emax, erms = grad_err(g_, refb[n])
-        print(std, scale, n, emax, erms, flush=True)
-        assert emax <= gmax and erms <= grms, f"{n}: max {emax} rms {erms}"
+        pm.assert_grad_bf16(np64(g_), refb[n], f"std {std} scale {scale:.3f} {n}", model[n],
+                            worst_tol=2 * pm.GRAD_WORST_TOL, rms_tol=2 * pm.GRAD_RMS_TOL)
