@@ -103,6 +103,20 @@ rattn_status rattn_bwd(const rattn_params* p, const void* q, const void* k, cons
                        const void* dO, void* dq, void* dk, void* dv, float* dgamma_swa,
                        float* dgamma_rla, void* workspace, size_t workspace_bytes, void* stream);
 
+/* rattn_fwd for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, result and errors as rattn_fwd
+ * (bit-identical output: the same kernels run), but the scratch memory is a buffer of RATTN_STATIC_SCRATCH_BYTES
+ * that lives inside the library's device image (one copy per GPU, held until the process ends); the call itself
+ * allocates and frees nothing.  Shapes whose forward workspace (rattn_workspace_bytes: fwd_bytes) exceeds that
+ * size are rejected with RATTN_ERR_WORKSPACE before anything is launched.  The first call on a device looks the
+ * buffer's address up once (make that call outside graph capture).  All calls on one GPU share the buffer:
+ * calls that may overlap on the same GPU (different streams, different threads) race and must be serialised
+ * by the caller; its contents are undefined between calls. */
+#define RATTN_STATIC_SCRATCH_BYTES ((size_t)96 << 20)
+rattn_status rattn_fwd_static(const rattn_params* p, const void* q, const void* k, const void* v,
+                              const float* gamma_swa, const float* gamma_rla, void* o, void* saved,
+                              void* stream);
+
 typedef struct {
   int32_t N;             /* sequences in the batch                                   */
   int32_t Hq, Hkv, D;

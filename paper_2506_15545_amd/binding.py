@@ -18,7 +18,7 @@ FEATURE_MAPS = {"softmax": 0, "relu": 1, "identity": 2}
 KERNEL_PATHS = {"auto": 0, "general": 1}
 _DTYPES = {torch.float32: RATTN_F32, torch.bfloat16: RATTN_BF16}
 
-EXPORTS = ["rattn_workspace_bytes", "rattn_fwd", "rattn_bwd", "rattn_decode_step",
+EXPORTS = ["rattn_workspace_bytes", "rattn_fwd", "rattn_fwd_static", "rattn_bwd", "rattn_decode_step",
            "rattn_prefill_export_workspace_bytes", "rattn_prefill_export",
            "rattn_prefill_chunk_workspace_bytes", "rattn_prefill_chunk", "rattn_probe_mfma",
            "rattn_cache_bytes", "rattn_step_time_model",
@@ -62,6 +62,8 @@ def lib():
     L.rattn_workspace_bytes.argtypes = [ctypes.POINTER(RattnParams)] + [ctypes.POINTER(sz)] * 3
     L.rattn_fwd.restype = ctypes.c_int
     L.rattn_fwd.argtypes = [ctypes.POINTER(RattnParams)] + [vp] * 8 + [sz, vp]
+    L.rattn_fwd_static.restype = ctypes.c_int
+    L.rattn_fwd_static.argtypes = [ctypes.POINTER(RattnParams)] + [vp] * 8
     L.rattn_bwd.restype = ctypes.c_int
     L.rattn_bwd.argtypes = [ctypes.POINTER(RattnParams)] + [vp] * 13 + [sz, vp]
     L.rattn_decode_step.restype = ctypes.c_int
@@ -164,6 +166,27 @@ def rattn_fwd(q, k, v, window, gamma_swa=None, gamma_rla=None, chunk=0, softmax_
     _check(lib().rattn_fwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(gs), _ptr(gr), _ptr(o), _ptr(sv),
                            _ptr(ws), ws.numel(), _stream()))
     return (o, sv) if save_for_bwd else o
+
+
+STATIC_SCRATCH_BYTES = 96 << 20
+
+
+def rattn_fwd_static(q, k, v, window, out, gamma_swa=None, gamma_rla=None, chunk=0, softmax_scale=1.0, rms_eps=1e-6,
+                     saved=None, feature_map="softmax"):
+    """rattn_fwd on the library's built-in scratch buffer: nothing is allocated here or in the library.  `out`
+    (and `saved`, which switches save_for_bwd on) are the caller's tensors; gains must already be fp32 [Hq,D] device
+    tensors.  Returns out."""
+    _check_layer(q, k, v)
+    for g in (gamma_swa, gamma_rla):
+        if g is not None and not (g.is_cuda and g.is_contiguous() and g.dtype == torch.float32
+                                  and tuple(g.shape) == (q.shape[2], q.shape[3])):
+            raise ValueError("gains must be contiguous fp32 [Hq, D] device tensors")
+    if out.shape != q.shape or out.dtype != q.dtype or not (out.is_cuda and out.is_contiguous()):
+        raise ValueError("out must match q")
+    p = make_params(q, k, window, chunk, softmax_scale, rms_eps, saved is not None, feature_map)
+    _check(lib().rattn_fwd_static(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(gamma_swa), _ptr(gamma_rla),
+                                  _ptr(out), _ptr(saved), _stream()))
+    return out
 
 
 def rattn_bwd(q, k, v, saved, dO, window, gamma_swa=None, gamma_rla=None, chunk=0, softmax_scale=1.0,

@@ -322,6 +322,40 @@ rattn_status rattn_fwd(const rattn_params* p, const void* q, const void* k, cons
   return check_launch("rattn_fwd");
 }
 
+// ---- rattn_fwd_static: the forward with its scratch memory inside the library's device image
+// BEGIN-STATIC-ENTRY
+namespace {
+// One copy per GPU that loads this library, alive until the process ends.  In host code the array's name is only
+// a handle for hipGetSymbolAddress; the kernels get the looked-up device address like any other workspace.
+static __device__ __align__(256) unsigned char scratch[RATTN_STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES] = {nullptr};  // device address of `scratch`, per device, looked up once
+}  // namespace
+
+rattn_status rattn_fwd_static(const rattn_params* p, const void* q, const void* k, const void* v,
+                              const float* gamma_swa, const float* gamma_rla, void* o, void* saved, void* stream) {
+  Layout L;
+  rattn_status s = make_layout(p, &L);
+  if (s != RATTN_OK) return s;
+  if (L.fwd_bytes > RATTN_STATIC_SCRATCH_BYTES)
+    return fail(RATTN_ERR_WORKSPACE, "rattn_fwd_static: this shape needs %zu bytes of forward scratch, the built-in buffer "
+                "holds %zu; use rattn_fwd with a caller-provided workspace", L.fwd_bytes, (size_t)RATTN_STATIC_SCRATCH_BYTES);
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES)
+    return fail(RATTN_ERR_HIP, "rattn_fwd_static: no current HIP device (or device index >= %d)", MAX_DEVICES);
+  void* ws = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+  if (!ws) {  // first call on this device (every thread that gets here looks up the same address)
+    const hipError_t e = hipGetSymbolAddress(&ws, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ws)
+      return fail(RATTN_ERR_HIP, "rattn_fwd_static: hipGetSymbolAddress failed: %s", hipGetErrorString(e));
+    __atomic_store_n(&g_scratch_ptr[dev], ws, __ATOMIC_RELEASE);
+  }
+  // Every part of the scratch that the forward kernels read is written earlier in the same call (chunk products,
+  // then the scanned states, then - for ragged lengths - the padded copies), so nothing has to be cleared.
+  return rattn_fwd(p, q, k, v, gamma_swa, gamma_rla, o, saved, ws, RATTN_STATIC_SCRATCH_BYTES, stream);
+}
+// END-STATIC-ENTRY
+
 rattn_status rattn_bwd(const rattn_params* p, const void* q, const void* k, const void* v, const float* gamma_swa,
                        const float* gamma_rla, const void* saved, const void* dO, void* dq, void* dk, void* dv,
                        float* dgamma_swa, float* dgamma_rla, void* workspace, size_t workspace_bytes, void* stream) {
