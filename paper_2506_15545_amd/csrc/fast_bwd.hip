@@ -788,9 +788,9 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
       const int id = tid + 512 * i;
       const int which = id >> 11, r = (id >> 4) & 127, pch = id & 15;
       const int c = pch ^ swz(r);
-      const uint4 val = *reinterpret_cast<const uint4*>(smem + which * 32768 + r * ROW_BYTES + (pch << 4));
+      const u32x4_t val = *reinterpret_cast<const u32x4_t*>(smem + which * 32768 + r * ROW_BYTES + (pch << 4));
       uint16_t* dst = (which ? a.dk : a.dv) + ktile_off;
-      *reinterpret_cast<uint4*>(dst + (size_t)r * kstride + c * 8) = val;
+      __builtin_nontemporal_store(val, reinterpret_cast<u32x4_t*>(dst + (size_t)r * kstride + c * 8));
     }
   }
 }
