@@ -47,14 +47,14 @@ def layer_flops(B, T, Hq, Hkv, D, W, C=NOMINAL_CHUNK):
 
 
 def kernel_algorithmic_flops(name, fl):
-    """Algorithmic FLOPs one launch of a named kernel is responsible for (None = not a contraction)."""
+    """Algorithmic FLOPs one launch of a named kernel is responsible for (None = not one of the contraction kernels:
+    the chunk-state kernels are bound by HBM traffic, their few matrix FLOPs are credited to the step as a whole)."""
     table = {
         "gen_fwd_kernel": fl["fwd_swa"] + fl["fwd_rla_out"],
         "gen_scan_kernel": fl["fwd_state"],
         "gen_bwd_dq_kernel": 0.4 * fl["bwd_swa"] + 0.5 * fl["bwd_rla_q"],
         "gen_bwd_dkv_kernel": 0.6 * fl["bwd_swa"] + 0.5 * fl["bwd_rla_q"] + 0.5 * fl["bwd_rla_kv"],
         "fwd_fused_kernel": fl["fwd_swa"] + fl["fwd_rla_out"],
-        "rla_state_kernel": fl["fwd_state"],
         "bwd_dq_kernel": 0.4 * fl["bwd_swa"] + 0.5 * fl["bwd_rla_q"],
         "bwd_dkv_kernel": 0.6 * fl["bwd_swa"] + 0.5 * fl["bwd_rla_q"] + 0.5 * fl["bwd_rla_kv"],
     }
@@ -62,15 +62,21 @@ def kernel_algorithmic_flops(name, fl):
 
 
 def measured_traffic(kernel, workload):
-    """HBM bytes per launch of `kernel` from the committed counter summary (FETCH_SIZE + WRITE_SIZE, scaled by
-    what the same counters read for a plain copy of known size), or None when no summary covers it."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    """HBM bytes per launch of `kernel` from the committed counter summary (FETCH_SIZE + WRITE_SIZE, scaled by what the
+    same counters read for a plain copy of known size), with where the figure comes from: it is NOT measured in this
+    run (rocprofv3 counters need a run of their own), so the summary's digest of the kernel sources is compared with
+    the sources in the tree and a mismatch is reported as stale.  (None, info) when no summary covers the kernel."""
+    rel = f"profiles/hbm_traffic_{workload}.txt"
+    info = {"file": rel, "measured_in_this_run": False}
     try:
-        with open(path) as f:
+        with open(os.path.join(ROOT, rel)) as f:
             rows = json.loads(f.read().split("---JSON---", 1)[1])
-        return rows.get(kernel, {}).get("hbm_bytes_per_launch")
     except (OSError, IndexError, ValueError):
-        return None
+        return None, info
+    from paper_2506_15545_amd import profile_summary
+    info["kernel_sources_of_summary"] = rows.get("_kernel_sources")
+    info["stale"] = rows.get("_kernel_sources") != profile_summary.kernel_sources_digest()
+    return rows.get(kernel, {}).get("hbm_bytes_per_launch"), info
 
 
 def decode_bytes(N, Hkv, Hq, D, W, esize, nvalid_sum=None):
@@ -80,30 +86,80 @@ def decode_bytes(N, Hkv, Hq, D, W, esize, nvalid_sum=None):
     return ring + state + vec
 
 
-def cpu_baseline(cfg, heads):
-    """The fp64 oracle, as it stands, on a bounded sample: fwd+bwd of `heads` query heads of batch 0
-    over the full sequence (heads are independent, so FLOP/s carries over to the whole tensor)."""
-    import numpy as np
-    import torch
+_CPU_INPUTS = None   # set in the parent before the worker pool forks
+
+
+def _cpu_unit(unit):
+    """One (batch row, query head) of the fp64 oracle, forward + backward, on one thread."""
     from oracle import rattn_oracle as orc
-    from paper_2506_15545_amd import synth
-    q, k, v, dO = synth.make_layer_inputs(cfg, with_dO=True, B=1)
-    f64 = lambda t: t.to(torch.float64).numpy()
-    q, k, v, dO = f64(q), f64(k), f64(v), f64(dO)
-    t0 = time.perf_counter()
-    orc.fwd_dense(q, k, v, cfg.W, scale=cfg.scale, heads=heads, batches=[0])
-    orc.bwd_dense(q, k, v, dO, cfg.W, scale=cfg.scale, heads=heads, batches=[0])
-    dt = time.perf_counter() - t0
-    fl = layer_flops(1, cfg.T, len(heads), 0, cfg.D, cfg.W)
-    flops = fl["fwd"] + fl["bwd"]
     try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        from threadpoolctl import threadpool_limits
+        limit = threadpool_limits(limits=1)
     except Exception:
-        cores = os.cpu_count() or 1
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"fp64 numpy oracle fwd+bwd, {len(heads)} query head(s) of batch 0, full T={cfg.T}, "
-                      f"{dt:.1f} s wall", "seconds": dt}
+        limit = None
+    cfg, q, k, v, dO = _CPU_INPUTS
+    b, h = unit
+    t0 = time.perf_counter()
+    orc.fwd_dense(q, k, v, cfg.W, scale=cfg.scale, heads=[h], batches=[b])
+    orc.bwd_dense(q, k, v, dO, cfg.W, scale=cfg.scale, heads=[h], batches=[b])
+    dt = time.perf_counter() - t0
+    del limit
+    return dt
+
+
+def host_cores():
+    n = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    for var in ("OMP_NUM_THREADS", "MAX_JOBS"):   # the box's CPU share, where it is smaller than what nproc shows
+        try:
+            n = min(n, int(os.environ[var]))
+        except (KeyError, ValueError):
+            pass
+    return max(n, 1)
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(cfg, units_per_core=2):
+    """The fp64 oracle, as it stands, on a bounded sample of the benchmark workload: a process pool over
+    (batch row, query head) units on all host cores (one thread each), `units_per_core` units per core, each unit the
+    full sequence, forward + backward.  Units are independent and equal in work, so the measured rate carries over to
+    all B * Hq units: the extrapolated whole-tensor time is reported next to the measured one.
+    Must run before this process touches the GPU (the pool forks)."""
+    global _CPU_INPUTS
+    import multiprocessing as mp
+    import torch
+    from paper_2506_15545_amd import synth
+    cores = host_cores()
+    all_units = [(b, h) for b in range(cfg.B) for h in range(cfg.Hq)]
+    units = all_units[:min(len(all_units), units_per_core * cores)]
+    f64 = lambda t: t.to(torch.float64).numpy()
+    _CPU_INPUTS = (cfg,) + tuple(f64(t) for t in synth.make_layer_inputs(cfg, with_dO=True, B=units[-1][0] + 1))
+    t0 = time.perf_counter()
+    with mp.get_context("fork").Pool(cores) as pool:
+        unit_s = pool.map(_cpu_unit, units, chunksize=1)
+    dt = time.perf_counter() - t0
+    _CPU_INPUTS = None
+    fl = layer_flops(1, cfg.T, 1, 0, cfg.D, cfg.W)
+    # the per-KV-head state products are shared by the G heads of a group in the method; the oracle recomputes them per
+    # query head, the FLOP count credits them once per group as everywhere else in this file
+    unit_flops = fl["fwd"] + fl["bwd"] + (layer_flops(1, cfg.T, 0, 1, cfg.D, cfg.W)["fwd"]
+                                          + layer_flops(1, cfg.T, 0, 1, cfg.D, cfg.W)["bwd"]) * cfg.Hkv / cfg.Hq
+    flops = unit_flops * len(units)
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"fp64 numpy oracle fwd+bwd, {len(units)} of {len(all_units)} (batch row, query head) units, full "
+                      f"T={cfg.T}, process pool of {cores} single-thread workers, {dt:.1f} s wall",
+            "seconds": dt, "units": len(units), "unit_seconds_mean": sum(unit_s) / len(unit_s),
+            "whole_tensor_seconds_extrapolated": dt * len(all_units) / len(units),
+            "cpu_model": cpu_model(), "nproc": os.cpu_count()}
 
 
 def main():
@@ -116,7 +172,8 @@ def main():
                     help="skip the reported-only prefill hand-over and chunked-prefill timings (profiling runs: keeps "
                          "every forward launch in the trace on the headline workload)")
     ap.add_argument("--no-decode", action="store_true")
-    ap.add_argument("--cpu-heads", type=int, default=24)
+    ap.add_argument("--cpu-units-per-core", type=int, default=2,
+                    help="(batch row, query head) units of the oracle per host core in the cpu_baseline sample")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="skip the reported-only timings of the 12B-shaped layer and the window sweep")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -127,8 +184,14 @@ def main():
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
+    from paper_2506_15545_amd import synth
+    # the CPU baseline forks a worker pool: it runs first, before this process has touched the GPU
+    cpu_base = None
+    if not args.no_cpu_baseline:
+        cpu_base = cpu_baseline(synth.CONFIGS["layer3b_t4096_w512"], args.cpu_units_per_core)
+
     import torch
-    from paper_2506_15545_amd import binding as rb, synth
+    from paper_2506_15545_amd import binding as rb
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
@@ -209,14 +272,21 @@ def main():
         a[0] += ms; a[1] += 1
     kernels = {n: {"avg_ms": s / c, "launches_per_step": c / args.steps} for n, (s, c) in agg.items()}
     dom = max(kernels, key=lambda n: kernels[n]["avg_ms"] * kernels[n]["launches_per_step"])
-    dom_fl = kernel_algorithmic_flops(dom, fl)
     mfma_path = not dom.startswith("gen_")
     peak = PEAK_BF16_MFMA if mfma_path else PEAK_FP32_VALU
-    achieved = (dom_fl or 0.0) / (kernels[dom]["avg_ms"] * 1e-3)
-    roofline = {"bound": "mfma" if mfma_path else "alu", "kernel": dom, "achieved": achieved / 1e12,
-                "peak": peak / 1e12, "unit": "TFLOP/s", "frac": achieved / peak,
-                "traffic": measured_traffic(dom, cfg.name), "avg_ms": kernels[dom]["avg_ms"],
-                "algorithmic_flops": dom_fl}
+
+    def kernel_roofline(name):
+        kfl = kernel_algorithmic_flops(name, fl)
+        achieved = (kfl or 0.0) / (kernels[name]["avg_ms"] * 1e-3)
+        traffic, src = measured_traffic(name, cfg.name)
+        return {"bound": "mfma" if mfma_path else "alu", "kernel": name, "achieved": achieved / 1e12,
+                "peak": peak / 1e12, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": traffic,
+                "traffic_source": src, "avg_ms": kernels[name]["avg_ms"], "algorithmic_flops": kfl}
+
+    roofline = kernel_roofline(dom)
+    # every kernel that carries algorithmic matrix work, and the one furthest below the roof
+    per_kernel = {n: kernel_roofline(n) for n in kernels if kernel_algorithmic_flops(n, fl)}
+    lowest = min(per_kernel.values(), key=lambda r: r["frac"]) if per_kernel else None
 
     out = {
         "metric": "fused SWA+RLA fwd+bwd TFLOP/s & % MFMA peak @T=4096,w=512,d=128",
@@ -235,6 +305,9 @@ def main():
                 "frac_mfma_peak": fl["bwd"] / (bwd_ms * 1e-3) / PEAK_BF16_MFMA},
         "kernels": kernels,
         "roofline": roofline,
+        "roofline_lowest_kernel": lowest,
+        "roofline_per_kernel": {n: {"frac": r["frac"], "achieved": r["achieved"], "avg_ms": r["avg_ms"],
+                                    "traffic": r["traffic"]} for n, r in per_kernel.items()},
     }
 
     if not args.no_decode:
@@ -261,7 +334,8 @@ def main():
                          "step_time_model_us": nbytes / PEAK_HBM * 1e6,
                          "roofline": {"bound": "hbm", "kernel": "decode_kernel", "achieved": nbytes / (us * 1e-6) / 1e9,
                                       "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": nbytes / (us * 1e-6) / PEAK_HBM,
-                                      "traffic": measured_traffic("decode_kernel", dcfg.name),
+                                      "traffic": measured_traffic("decode_kernel", dcfg.name)[0],
+                                      "traffic_source": measured_traffic("decode_kernel", dcfg.name)[1],
                                       "algorithmic_bytes": nbytes}}
 
     if not args.no_decode:
@@ -418,8 +492,8 @@ def main():
         out["calibration"] = {"kernel": "elementwise add, out-of-place", "bytes_read": src.numel() * 4,
                               "bytes_written": dst.numel() * 4}
 
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, list(range(args.cpu_heads)))
+    if cpu_base is not None:
+        out["cpu_baseline"] = cpu_base
     print(json.dumps(out))
 
 

@@ -4,6 +4,8 @@
 #include <stdint.h>
 #include <stddef.h>
 
+#include "kernels.hpp"
+
 namespace rattn {
 
 typedef uint16_t bf16_t;  // raw bfloat16 bits
@@ -60,7 +62,6 @@ __device__ __forceinline__ float bcast(float x, int l) {
 // Feature map of the linear branch: softmax over the features (Sec. 3.1), or the ablation's ReLU / identity
 // (Sec. 4.5).  Every map is written phi(x)[f] = feat(x[f], m) / z with row statistics (m, z): the row maximum and
 // the sum of exponentials for softmax, (0, 1) for the other two.  `phi` is uniform over a launch.
-enum { PHI_SOFTMAX = 0, PHI_RELU = 1, PHI_IDENTITY = 2 };
 __device__ __forceinline__ float feat(float x, float m, int phi) {
   if (phi == PHI_SOFTMAX) return expf(x - m);
   return phi == PHI_RELU ? fmaxf(x, 0.f) : x;

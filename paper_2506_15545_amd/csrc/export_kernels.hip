@@ -103,18 +103,6 @@ __global__ __launch_bounds__(256) void export_state_reduce_kernel(const float4* 
 
 }  // namespace
 
-ExportPlan export_plan(const LayerDims& dm) {
-  ExportPlan pl;
-  pl.Tp = dm.T > dm.W ? dm.T - dm.W : 0;
-  const int kb = 256 / (dm.D / 8);
-  int nseg = (pl.Tp + 4 * kb - 1) / (4 * kb);  // at least four key batches per segment
-  if (nseg > 64) nseg = 64;
-  pl.nseg = nseg;
-  pl.seg_len = nseg > 0 ? ((pl.Tp + nseg - 1) / nseg + kb - 1) / kb * kb : 0;
-  pl.partial_bytes = (size_t)dm.B * dm.Hkv * nseg * dm.D * dm.D * sizeof(float);
-  return pl;
-}
-
 void prefill_export(const LayerDims& dm, int dtype, const void* k, const void* v, void* k_ring, void* v_ring,
                     float* state, float* partial, hipStream_t st, int tok0, bool accumulate) {
   const ExportPlan pl = export_plan(dm);

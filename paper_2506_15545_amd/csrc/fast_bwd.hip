@@ -797,18 +797,6 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
 
 }  // namespace
 
-FastBwdPlan fast_bwd_plan(const LayerDims& dm) {
-  FastBwdPlan p;
-  p.fwd = fast_fwd_plan(dm);
-  const int Tp = dm.T - p.fwd.W;
-  p.nk = Tp > 0 ? (Tp + 127) / 128 : 0;
-  const int nch = p.fwd.nchunks > p.nk - 1 ? p.fwd.nchunks : p.nk - 1;
-  p.u_bytes = (size_t)dm.B * dm.Hkv * (nch > 0 ? nch : 0) * 16384 * 4;
-  p.rstate_bytes = (size_t)dm.B * dm.Hkv * p.nk * 16384 * 2;
-  p.RB = 4 * (dm.T / 128) * dm.B;  // one gain-gradient partial per wave of the dq kernel
-  return p;
-}
-
 void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, const float* gs, const float* gr,
               const SavedPtrs& sv, const void* dO, void* dq, void* dk, void* dv, float* dgs, float* dgr,
               const FastBwdWs& ws, hipStream_t st) {

@@ -432,33 +432,6 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
 
 }  // namespace
 
-bool fast_fwd_supported(const LayerDims& dm, int dtype) {
-  if (dtype != 1 || dm.D != 128 || dm.T % 128 != 0) return false;
-  if (!(dm.scale > 0.f)) return false;
-  // The identity map stays on the general kernels: its features are of size ~1 instead of ~1/D, and the backward of
-  // the first rows past the window (state of rank 1, 2, ...) is a cancellation that needs the fp32 x^r kept there
-  if (dm.phi != PHI_SOFTMAX && dm.phi != PHI_RELU) return false;
-  // Windows below 8 keys stay on the general path: their softmax rows are close to one-hot, so the backward's
-  // dS = P (dP - delta) is a near-cancellation (exact for W = 1) that bf16 operands turn into rounding noise
-  // above the gradient tolerance (measured: worst element 4 % of RMS at W = 2, 3 % at W = 4, 2.5 % from W = 8 on)
-  if (dm.W < 8) return false;
-  return true;
-}
-
-FastFwdPlan fast_fwd_plan(const LayerDims& dm) {
-  FastFwdPlan p;
-  const int wt = dm.W >= dm.T ? dm.T : dm.W;
-  p.W = (wt + 63) / 64 * 64;
-  p.gap = p.W - wt;
-  p.base = p.W % 128;
-  p.nstf = dm.T / 128 - (p.W + 127) / 128;
-  if (p.nstf < 0) p.nstf = 0;
-  p.nchunks = p.nstf > 0 ? (p.nstf - 1) + (p.base > 0 ? 1 : 0) : 0;
-  p.u_bytes = (size_t)dm.B * dm.Hkv * p.nchunks * 16384 * 4;
-  p.state_bytes = (size_t)dm.B * dm.Hkv * p.nstf * 16384 * 2;
-  return p;
-}
-
 void fast_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, const float* gs, const float* gr,
               void* o, const SavedPtrs& sv, float* U, void* states, hipStream_t st, int qt0, const float* state0) {
   const FastFwdPlan pl = fast_fwd_plan(dm);

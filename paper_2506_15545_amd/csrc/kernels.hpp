@@ -15,6 +15,9 @@ struct ProfScope {
   ~ProfScope() { prof_end(st); }
 };
 
+// feature map of the linear branch (values of rattn_feature_map)
+enum { PHI_SOFTMAX = 0, PHI_RELU = 1, PHI_IDENTITY = 2 };
+
 struct LayerDims {
   int B, T, Hq, Hkv, D, W, C, G;
   int nst;  // number of chunk states per (batch, kv head): ceil(max(T-W,0) / C)

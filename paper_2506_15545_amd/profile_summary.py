@@ -28,7 +28,22 @@ import os
 import re
 import sys
 
+import hashlib
+
 CAL_BYTES = 256 * 2 ** 20
+
+
+def kernel_sources_digest():
+    """sha256 over the library's kernel sources (csrc/*, sorted by name): written into every summary, so that a
+    reader (and bench.py) can tell whether a summary was taken from the kernels that are in the tree now."""
+    d = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".hpp")):
+            h.update(name.encode())
+            with open(os.path.join(d, name), "rb") as f:
+                h.update(f.read())
+    return h.hexdigest()[:16]
 ALIASES = {"decode_kernel_2pass": "decode_kernel"}   # the name bench.py reports the decode launch under
 WORKLOAD_KERNELS = {"decode_b128_w512": ("decode_kernel",)}
 
@@ -87,12 +102,14 @@ def traffic(dfetch, dwrite, out, workload, cmd_fetch, cmd_write):
         table[n] = {"dispatches": nf[n], "fetch_bytes": rd, "write_bytes": wr, "hbm_bytes_per_launch": rd + wr}
     with open(out, "w") as fo:
         fo.write(f"workload: {workload}\ncommand (FETCH_SIZE): {cmd_fetch}\ncommand (WRITE_SIZE): {cmd_write}\n")
+        fo.write(f"kernel sources (sha256 of csrc/*.hip, *.hpp): {kernel_sources_digest()}\n")
         fo.write(f"calibration: the 256 MiB out-of-place elementwise pass read FETCH_SIZE={fetch[cal]:.0f} and "
                  f"WRITE_SIZE={write[cal]:.0f}; bytes per count = {kf:.1f} (fetch), {kw:.1f} (write)\n\n")
         fo.write(f"{'kernel':28s} {'dispatches':>10s} {'fetch_MB':>10s} {'write_MB':>10s} {'total_MB':>10s}\n")
         for n, r in table.items():
             fo.write(f"{n:28s} {r['dispatches']:10d} {r['fetch_bytes'] / 1e6:10.2f} {r['write_bytes'] / 1e6:10.2f} "
                      f"{r['hbm_bytes_per_launch'] / 1e6:10.2f}\n")
+        table["_kernel_sources"] = kernel_sources_digest()
         fo.write("\n---JSON---\n" + json.dumps(table, indent=1) + "\n")
 
 
@@ -111,7 +128,7 @@ def mfma(d, out, command):
             dur[n] += int(r["End_Timestamp"]) - int(r["Start_Timestamp"]); nd[n] += 1
     SIMDS, SES, FLOP = 1024, 32, 2 * 32 * 32 * 16
     with open(out, "w") as fo:
-        fo.write(f"command: {command}\n")
+        fo.write(f"command: {command}\nkernel sources (sha256 of csrc/*.hip, *.hpp): {kernel_sources_digest()}\n")
         fo.write("source: rocprofv3 counter_collection.csv, means per dispatch; busy = SQ_VALU_MFMA_BUSY_CYCLES / 1024 SIMDs "
                  "over SQ_BUSY_CYCLES / 32 shader engines\n\n")
         fo.write(f"{'kernel':24s} {'disp':>5s} {'avg_us':>8s} {'MFMA_insts':>11s} {'MFMA_TFLOPs':>11s} {'pipe_busy':>9s} "
