@@ -128,7 +128,7 @@ def cpu_model():
     return "unknown"
 
 
-def cpu_baseline(cfg, units_per_core=2):
+def cpu_baseline(cfg, units_per_core=6):
     """The fp64 oracle, as it stands, on a bounded sample of the benchmark workload: a process pool over
     (batch row, query head) units on all host cores (one thread each), `units_per_core` units per core, each unit the
     full sequence, forward + backward.  Units are independent and equal in work, so the measured rate carries over to
@@ -172,7 +172,7 @@ def main():
                     help="skip the reported-only prefill hand-over and chunked-prefill timings (profiling runs: keeps "
                          "every forward launch in the trace on the headline workload)")
     ap.add_argument("--no-decode", action="store_true")
-    ap.add_argument("--cpu-units-per-core", type=int, default=2,
+    ap.add_argument("--cpu-units-per-core", type=int, default=6,
                     help="(batch row, query head) units of the oracle per host core in the cpu_baseline sample")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="skip the reported-only timings of the 12B-shaped layer and the window sweep")
@@ -443,18 +443,24 @@ def main():
         # and without them by the same (shorter) timing method for comparison
         other["layer3b_t4096_w512_gains"] = run_layer(cfg, True, gains=True)
         other["layer3b_t4096_w512"] = run_layer(cfg, True)
-        # the ablation's ReLU feature map (Sec. 4.5) on the same kernels, same FLOP formula
+        # the ablation's ReLU and identity feature maps (Sec. 4.5) on the same kernels, same FLOP formula
         other["layer3b_t4096_w512_relu"] = run_layer(cfg, True, feature_map="relu")
+        other["layer3b_t4096_w512_identity"] = run_layer(cfg, True, feature_map="identity")
+        # shapes that reach the matrix-core kernels through zero-padded copies: a ragged length (4000 -> 4096 rows)
+        # and head size 64 (rows widened to 128 features; FLOPs counted at head size 64)
+        other["layer3b_t4000_w512_ragged"] = run_layer(dataclasses.replace(cfg, name="layer3b_t4000_w512", T=4000), True)
+        other["layer3b_t4096_w512_d64"] = run_layer(dataclasses.replace(cfg, name="layer3b_t4096_w512_d64", D=64,
+                                                                        scale=0.125), True)
         for W_ in (128, 512, 1024, 4096, 8192):
             c_ = synth.sweep_config(W_)
             other[c_.name] = run_layer(c_, True)
         # chunk-size enumeration of the linear branch (Sec. 3.2's search over C) on the general kernels, which take the
-        # chunk as a parameter (the matrix-core path fixes one state per 128 keys): D = 64 forces that path
+        # chunk as a parameter (the matrix-core path fixes one state per 128 keys)
         xg = synth.make_random_layer(1, 4096, 8, 2, 64, "bf16", 11)
         qg, kg, vg = xg["q"].cuda(), xg["k"].cuda(), xg["v"].cuda()
         sweep_c = {}
         for c_ in (16, 32, 64, 128, 256, 512):
-            fg = lambda: rb.rattn_fwd(qg, kg, vg, 512, chunk=c_, softmax_scale=0.125)
+            fg = lambda: rb.rattn_fwd(qg, kg, vg, 512, chunk=c_, softmax_scale=0.125, kernel_path="general")
             for _ in range(3):
                 fg()
             sweep_c[str(c_)] = timed(fg, 10)

@@ -14,7 +14,10 @@
  *    branch covers keys 0..t-W.  The paper's symbol is w = W-1.  W >= T leaves the
  *    linear branch empty (its output and RMS are exactly 0) = causal attention.
  *  - Layer tensors are contiguous [B, T, H, D], D fastest.  Query head h reads KV head
- *    h / (Hq/Hkv).  D is 64 or 128.
+ *    h / (Hq/Hkv).  D is 64 or 128.  The matrix-core kernels take bf16 tensors with D = 128
+ *    and T a multiple of 128 directly; bf16 with T >= 1024 not a multiple of 128, and bf16
+ *    with D = 64 (T a multiple of 128, or >= 1024), run on them through zero-padded copies
+ *    that live in the workspace; every other shape runs on the general (vector-ALU) kernels.
  *  - dtype is the element type of q,k,v,o,dO,dq,dk,dv (and of the decode ring buffers).
  *    Accumulators, softmax/RMS statistics and gains are fp32.  Linear-attention states are
  *    accumulated in fp32; the decode, prefill-export and general kernels also keep them in
@@ -64,8 +67,7 @@ typedef struct {
   float softmax_scale;   /* multiplies q.k in the softmax branch only (the paper's formula is 1.0)     */
   float rms_eps;         /* > 0                                                                        */
   int32_t save_for_bwd;  /* rattn_fwd also fills `saved` (needed by rattn_bwd)                         */
-  int32_t feature_map;   /* rattn_feature_map; RATTN_PHI_IDENTITY runs on the general (vector-ALU)
-                            kernels for every shape                                                    */
+  int32_t feature_map;   /* rattn_feature_map                                                          */
   int32_t kernel_path;   /* rattn_kernel_path: 0 = the library chooses (matrix-core kernels where the
                             shape allows); RATTN_PATH_GENERAL forces the general kernels (a second,
                             independent implementation used by tests).  It changes what `saved` holds:

@@ -56,11 +56,14 @@ struct Layout {
   rattn::LayerDims dm;
   rattn::LayerDims dmf;  // what the matrix-core kernels see: dm with T rounded up to 128 when `pad`
   bool pad;
-  size_t pf_q, pf_k, pf_v, pf_o;                          // padded copies, forward workspace
+  bool pad_d;                                             // head size 64 widened to 128 (implies pad)
+  size_t pf_q, pf_k, pf_v, pf_o, pf_gs, pf_gr;            // padded copies, forward workspace (gains only if pad_d)
   size_t pb_q, pb_k, pb_v, pb_dO, pb_dq, pb_dk, pb_dv;    // padded copies, backward workspace
+  size_t pb_gs, pb_gr, pb_dgs, pb_dgr;                    // padded gains and gain gradients (pad_d)
   size_t esize;
   // saved
-  size_t sv_xs, sv_xr, sv_lse, sv_rs, sv_rr, sv_states, saved_bytes;
+  size_t sv_xs, sv_xr, sv_lse, sv_rs, sv_rr, sv_states, sv_xr_lo, saved_bytes;
+  bool has_xr_lo;
   // generic forward / backward workspace
   size_t gf_states, gen_fwd_bytes;
   size_t gb_states, gb_rstates, gb_dxs, gb_dxr, gb_delta, gb_dgpart, gen_bwd_bytes;
@@ -103,12 +106,18 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
   dm.scale = p->softmax_scale; dm.eps = p->rms_eps; dm.phi = p->feature_map;
   L->esize = p->dtype == RATTN_F32 ? 4 : 2;
 
+  // What the matrix-core kernels would see: the sequence length rounded up to whole 128-row tiles (ragged lengths from
+  // PAD_MIN_T on) and a head size of 64 widened to 128, both through zero-padded copies in the workspace
+  dm.Dv = dm.D;
   L->dmf = dm;
-  L->pad = p->dtype == RATTN_BF16 && dm.D == 128 && dm.T % 128 != 0 && dm.T >= PAD_MIN_T;
+  const bool ragged = dm.T % 128 != 0;
+  L->pad_d = p->dtype == RATTN_BF16 && dm.D == 64 && (!ragged || dm.T >= PAD_MIN_T);
+  L->pad = p->dtype == RATTN_BF16 && ((dm.D == 128 && ragged && dm.T >= PAD_MIN_T) || L->pad_d);
   if (L->pad) L->dmf.T = (dm.T + 127) / 128 * 128;
+  if (L->pad_d) L->dmf.D = 128;
   const rattn::LayerDims& dmf = L->dmf;
   L->fast_fwd = p->kernel_path != RATTN_PATH_GENERAL && rattn::fast_fwd_supported(dmf, p->dtype);
-  if (!L->fast_fwd) { L->pad = false; L->dmf = dm; }
+  if (!L->fast_fwd) { L->pad = L->pad_d = false; L->dmf = dm; }
   // `saved` is sized for the padded length
   const size_t nq = (size_t)dm.B * dm.T * dm.Hq * dm.D;
   const size_t nrow = (size_t)dm.B * dm.Hq * dm.T;
@@ -124,6 +133,9 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
   L->sv_rr = off; off += align_up(nrow_f * 4);
   L->sv_states = off;
   if (L->fast_fwd) off += align_up(rattn::fast_fwd_plan(dmf).state_bytes);
+  L->has_xr_lo = L->fast_fwd && dm.phi == rattn::PHI_IDENTITY;
+  L->sv_xr_lo = off;
+  if (L->has_xr_lo) off += align_up(nq_f * L->esize);
   L->saved_bytes = off;
 
   const size_t nstate = (size_t)dm.B * dm.Hkv * dm.nst * dm.D * dm.D;
@@ -152,6 +164,8 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
       L->pf_k = off; off += align_up(nkv_f * 2);
       L->pf_v = off; off += align_up(nkv_f * 2);
       L->pf_o = off; off += align_up(nq_f * 2);
+      L->pf_gs = off; off += align_up((size_t)dmf.Hq * 128 * 4);
+      L->pf_gr = off; off += align_up((size_t)dmf.Hq * 128 * 4);
     }
     L->fast_fwd_bytes = off;
   }
@@ -174,6 +188,10 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
       L->pb_dq = off; off += align_up(nq_f * 2);
       L->pb_dk = off; off += align_up(nkv_f * 2);
       L->pb_dv = off; off += align_up(nkv_f * 2);
+      L->pb_gs = off; off += align_up((size_t)dmf.Hq * 128 * 4);
+      L->pb_gr = off; off += align_up((size_t)dmf.Hq * 128 * 4);
+      L->pb_dgs = off; off += align_up((size_t)dmf.Hq * 128 * 4);
+      L->pb_dgr = off; off += align_up((size_t)dmf.Hq * 128 * 4);
     }
     L->fast_bwd_bytes = off;
   }
@@ -183,12 +201,13 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
 }
 
 rattn::SavedPtrs saved_views(const Layout& L, void* saved) {
-  rattn::SavedPtrs sv = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, !L.fast_fwd};
+  rattn::SavedPtrs sv = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, !L.fast_fwd, nullptr};
   if (saved) {
     char* s = (char*)saved;
     sv.xs = s + L.sv_xs; sv.xr = s + L.sv_xr;
     sv.lse = (float*)(s + L.sv_lse); sv.rs = (float*)(s + L.sv_rs); sv.rr = (float*)(s + L.sv_rr);
     if (L.fast_fwd) sv.states = s + L.sv_states;
+    if (L.has_xr_lo) sv.xr_lo = s + L.sv_xr_lo;
   }
   return sv;
 }
@@ -211,6 +230,9 @@ rattn_status make_chunk_layout(const rattn_params* p, int32_t pos0, ChunkLayout*
   C->p2 = *p;
   C->p2.T = C->R + p->T;
   C->p2.save_for_bwd = 1;
+  // chunked prefill reads the forward's saved tensors in the caller's head size: a head size of 64, which the
+  // matrix-core kernels would run on widened copies, stays on the general kernels here
+  if (p->D == 64) C->p2.kernel_path = RATTN_PATH_GENERAL;
   s = make_layout(&C->p2, &C->L2);
   if (s != RATTN_OK) return s;
   const rattn::LayerDims& dm = C->L2.dm;
@@ -307,16 +329,21 @@ rattn_status rattn_fwd(const rattn_params* p, const void* q, const void* k, cons
     char* w = (char*)workspace;
     const void *qf = q, *kf = k, *vf = v;
     void* of = o;
-    const size_t qrow = (size_t)L.dm.Hq * L.dm.D * 2, kvrow = (size_t)L.dm.Hkv * L.dm.D * 2;
+    const float *gsf = gamma_swa, *grf = gamma_rla;
+    const size_t hb = (size_t)L.dm.D * 2, hbp = (size_t)L.dmf.D * 2;  // bytes of one head row, caller's and padded
     if (L.pad) {
-      rattn::pad_rows(q, w + L.pf_q, L.dm.B, L.dm.T, L.dmf.T, qrow, st);
-      rattn::pad_rows(k, w + L.pf_k, L.dm.B, L.dm.T, L.dmf.T, kvrow, st);
-      rattn::pad_rows(v, w + L.pf_v, L.dm.B, L.dm.T, L.dmf.T, kvrow, st);
+      rattn::pad_rows(q, w + L.pf_q, L.dm.B, L.dm.T, L.dmf.T, L.dm.Hq, hb, hbp, st);
+      rattn::pad_rows(k, w + L.pf_k, L.dm.B, L.dm.T, L.dmf.T, L.dm.Hkv, hb, hbp, st);
+      rattn::pad_rows(v, w + L.pf_v, L.dm.B, L.dm.T, L.dmf.T, L.dm.Hkv, hb, hbp, st);
       qf = w + L.pf_q; kf = w + L.pf_k; vf = w + L.pf_v; of = w + L.pf_o;
+      if (L.pad_d) {  // gains are [Hq, 64] fp32: widened to [Hq, 128] (the padding features of x are zero)
+        if (gamma_swa) { rattn::pad_rows(gamma_swa, w + L.pf_gs, 1, L.dm.Hq, L.dm.Hq, 1, 256, 512, st); gsf = (const float*)(w + L.pf_gs); }
+        if (gamma_rla) { rattn::pad_rows(gamma_rla, w + L.pf_gr, 1, L.dm.Hq, L.dm.Hq, 1, 256, 512, st); grf = (const float*)(w + L.pf_gr); }
+      }
     }
-    rattn::fast_fwd(L.dmf, qf, kf, vf, gamma_swa, gamma_rla, of, sv, (float*)(w + L.ff_u),
+    rattn::fast_fwd(L.dmf, qf, kf, vf, gsf, grf, of, sv, (float*)(w + L.ff_u),
                     sv.states ? sv.states : (void*)(w + L.ff_states), st);
-    if (L.pad) rattn::unpad_rows(of, o, L.dm.B, L.dm.T, L.dmf.T, qrow, st);
+    if (L.pad) rattn::unpad_rows(of, o, L.dm.B, L.dm.T, L.dmf.T, L.dm.Hq, hb, hbp, st);
   } else
     rattn::generic_fwd(L.dm, p->dtype, q, k, v, gamma_swa, gamma_rla, o, sv, (float*)((char*)workspace + L.gf_states), st);
   return check_launch("rattn_fwd");
@@ -376,17 +403,28 @@ rattn_status rattn_bwd(const rattn_params* p, const void* q, const void* k, cons
     rattn::FastBwdWs fw;
     fw.dxs = w + L.fb_dxs; fw.dxr = w + L.fb_dxr; fw.delta = (float*)(w + L.fb_delta); fw.U = (float*)(w + L.fb_u);
     fw.states = w + L.fb_states; fw.rstates = w + L.fb_rstates; fw.dgpart = (float*)(w + L.fb_dgpart);
-    const size_t qrow = (size_t)L.dm.Hq * L.dm.D * 2, kvrow = (size_t)L.dm.Hkv * L.dm.D * 2;
+    const size_t hb = (size_t)L.dm.D * 2, hbp = (size_t)L.dmf.D * 2;  // bytes of one head row, caller's and padded
     if (L.pad) {
-      rattn::pad_rows(q, w + L.pb_q, L.dm.B, L.dm.T, L.dmf.T, qrow, st);
-      rattn::pad_rows(k, w + L.pb_k, L.dm.B, L.dm.T, L.dmf.T, kvrow, st);
-      rattn::pad_rows(v, w + L.pb_v, L.dm.B, L.dm.T, L.dmf.T, kvrow, st);
-      rattn::pad_rows(dO, w + L.pb_dO, L.dm.B, L.dm.T, L.dmf.T, qrow, st);
-      rattn::fast_bwd(L.dmf, w + L.pb_q, w + L.pb_k, w + L.pb_v, gamma_swa, gamma_rla, sv, w + L.pb_dO, w + L.pb_dq,
-                      w + L.pb_dk, w + L.pb_dv, dgamma_swa, dgamma_rla, fw, st);
-      rattn::unpad_rows(w + L.pb_dq, dq, L.dm.B, L.dm.T, L.dmf.T, qrow, st);
-      rattn::unpad_rows(w + L.pb_dk, dk, L.dm.B, L.dm.T, L.dmf.T, kvrow, st);
-      rattn::unpad_rows(w + L.pb_dv, dv, L.dm.B, L.dm.T, L.dmf.T, kvrow, st);
+      const int B = L.dm.B, T = L.dm.T, Tp = L.dmf.T, Hq = L.dm.Hq, Hkv = L.dm.Hkv;
+      rattn::pad_rows(q, w + L.pb_q, B, T, Tp, Hq, hb, hbp, st);
+      rattn::pad_rows(k, w + L.pb_k, B, T, Tp, Hkv, hb, hbp, st);
+      rattn::pad_rows(v, w + L.pb_v, B, T, Tp, Hkv, hb, hbp, st);
+      rattn::pad_rows(dO, w + L.pb_dO, B, T, Tp, Hq, hb, hbp, st);
+      const float *gsf = gamma_swa, *grf = gamma_rla;
+      float *dgs = dgamma_swa, *dgr = dgamma_rla;
+      if (L.pad_d) {  // gains and gain gradients are [Hq, 64] fp32 for the caller, [Hq, 128] for the kernels
+        if (gamma_swa) { rattn::pad_rows(gamma_swa, w + L.pb_gs, 1, Hq, Hq, 1, 256, 512, st); gsf = (const float*)(w + L.pb_gs); }
+        if (gamma_rla) { rattn::pad_rows(gamma_rla, w + L.pb_gr, 1, Hq, Hq, 1, 256, 512, st); grf = (const float*)(w + L.pb_gr); }
+        if (dgamma_swa) dgs = (float*)(w + L.pb_dgs);
+        if (dgamma_rla) dgr = (float*)(w + L.pb_dgr);
+      }
+      rattn::fast_bwd(L.dmf, w + L.pb_q, w + L.pb_k, w + L.pb_v, gsf, grf, sv, w + L.pb_dO, w + L.pb_dq,
+                      w + L.pb_dk, w + L.pb_dv, dgs, dgr, fw, st);
+      rattn::unpad_rows(w + L.pb_dq, dq, B, T, Tp, Hq, hb, hbp, st);
+      rattn::unpad_rows(w + L.pb_dk, dk, B, T, Tp, Hkv, hb, hbp, st);
+      rattn::unpad_rows(w + L.pb_dv, dv, B, T, Tp, Hkv, hb, hbp, st);
+      if (L.pad_d && dgamma_swa) rattn::unpad_rows(dgs, dgamma_swa, 1, Hq, Hq, 1, 256, 512, st);
+      if (L.pad_d && dgamma_rla) rattn::unpad_rows(dgr, dgamma_rla, 1, Hq, Hq, 1, 256, 512, st);
     } else {
       rattn::fast_bwd(L.dm, q, k, v, gamma_swa, gamma_rla, sv, dO, dq, dk, dv, dgamma_swa, dgamma_rla, fw, st);
     }
@@ -489,7 +527,7 @@ rattn_status rattn_prefill_chunk(const rattn_params* p, int32_t pos0, const void
   // state) the carried state enters as the initial value of the state scan.  Only K and V are gathered.
   if (C.L2.fast_fwd && !C.L2.pad && C.R % 128 == 0 && (!carried || p->window % 128 == 0)) {
     rattn::chunk_concat(dm, p->dtype, p->T, C.R, pos0, nullptr, k, v, k_ring, v_ring, nullptr, w + C.kc, w + C.vc, st);
-    rattn::SavedPtrs none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, false};
+    rattn::SavedPtrs none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, false, nullptr};
     rattn::fast_fwd(dm, q, w + C.kc, w + C.vc, gamma_swa, gamma_rla, o, none, (float*)(w + C.fwdws + C.L2.ff_u),
                     w + C.fwdws + C.L2.ff_states, st, C.R / 128, carried ? state : nullptr);
     rattn::prefill_export(dm, p->dtype, w + C.kc, w + C.vc, k_ring, v_ring, state, (float*)(w + C.partial), st,

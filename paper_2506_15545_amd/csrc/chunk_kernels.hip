@@ -133,7 +133,7 @@ __global__ __launch_bounds__(256) void chunk_fixup_kernel(const IO* __restrict__
 // transposed formulation of the forward kernel (lane = query row): X^T += S0^T phi(Q)^T with S0^T rounded to bf16
 // like the chunk states of the forward.  grid (tiles, Hq, B), 256 threads; tile i covers concatenated rows
 // 128 (i + R / 128) .. +127, rows before the chunk (j < R) are computed and dropped.
-template <bool RELU>
+template <int FM>
 __global__ __launch_bounds__(256) void chunk_fixup_mfma_kernel(const uint16_t* __restrict__ qc, const uint16_t* __restrict__ xs,
                                                                const uint16_t* __restrict__ xr, const float* __restrict__ rs,
                                                                const float* __restrict__ state, const float* __restrict__ gs,
@@ -166,7 +166,7 @@ __global__ __launch_bounds__(256) void chunk_fixup_mfma_kernel(const uint16_t* _
 #pragma unroll
     for (int c = 0; c < 8; ++c)
       unpack_bf16x8(*reinterpret_cast<const bf16x8_t*>(qc + roff + 16 * c + 8 * h), &x[8 * c]);
-    phi_rows<RELU>(x, qfop);
+    phi_rows<FM>(x, qfop);
   }
   __syncthreads();
   f32x16_t acc[4] = {{0}, {0}, {0}, {0}};
@@ -244,14 +244,17 @@ void chunk_copy_out(const LayerDims& dmc, int dtype, int Tc, int R, const void* 
 void chunk_fixup(const LayerDims& dmc, int dtype, int Tc, int R, int Ls, const void* qc, const SavedPtrs& sv,
                  const float* state, const float* gs, const float* gr, void* o, hipStream_t st) {
   ProfScope ps("chunk_fixup_kernel", st);
-  if (dtype == 1 && dmc.D == 128 && dmc.T % 128 == 0 && Ls == dmc.T && dmc.phi != PHI_IDENTITY && !sv.f32) {
+  if (dtype == 1 && dmc.D == 128 && dmc.Dv == 128 && dmc.T % 128 == 0 && Ls == dmc.T && !sv.f32) {
     const dim3 tiles(dmc.T / 128 - R / 128, dmc.Hq, dmc.B);
-    if (dmc.phi == PHI_RELU)
-      chunk_fixup_mfma_kernel<true><<<tiles, 256, 0, st>>>((const uint16_t*)qc, (const uint16_t*)sv.xs, (const uint16_t*)sv.xr,
-                                                           sv.rs, state, gs, gr, (uint16_t*)o, Tc, R, dmc.Hq, dmc.Hkv, dmc.eps);
-    else
-      chunk_fixup_mfma_kernel<false><<<tiles, 256, 0, st>>>((const uint16_t*)qc, (const uint16_t*)sv.xs, (const uint16_t*)sv.xr,
-                                                            sv.rs, state, gs, gr, (uint16_t*)o, Tc, R, dmc.Hq, dmc.Hkv, dmc.eps);
+#define RATTN_FIXUP_MFMA(FM_)                                                                                          \
+  chunk_fixup_mfma_kernel<FM_><<<tiles, 256, 0, st>>>((const uint16_t*)qc, (const uint16_t*)sv.xs, (const uint16_t*)sv.xr, \
+                                                      sv.rs, state, gs, gr, (uint16_t*)o, Tc, R, dmc.Hq, dmc.Hkv, dmc.eps)
+    switch (feature_map_variant(dmc)) {
+      case FM_RELU: RATTN_FIXUP_MFMA(FM_RELU); break;
+      case FM_IDENTITY: RATTN_FIXUP_MFMA(FM_IDENTITY); break;
+      default: RATTN_FIXUP_MFMA(FM_SOFTMAX); break;
+    }
+#undef RATTN_FIXUP_MFMA
     return;
   }
   const dim3 grid((Tc + 63) / 64, dmc.Hq, dmc.B);

@@ -28,8 +28,10 @@ struct FastBwdArgs {
   float scale, scale_log2;
   // inputs of the RMS-norm backward in the dq kernel's prologue, which fills dxs, dxr and delta above
   const uint16_t *dO, *xs, *xr;
+  const uint16_t* xr_lo;           // low-order part of the saved x_r (identity feature map), NULL otherwise
   const float *rs, *rr, *gs, *gr;  // gains: NULL = ones
   float* dgpart;                   // gain-gradient partials [2][4 * ntile * B][Hq][128], NULL = not wanted
+  float inv_d;                     // 1 / head size the RMS norms average over (1/64 for rows zero-padded from 64)
 };
 
 // ------------------------------------------------------------------------------------------------
@@ -62,8 +64,8 @@ __global__ __launch_bounds__(256) void dgamma_reduce_kernel(const float* __restr
 }
 
 // row `src` (128 bf16) re-read in accumulator layout: lane keeps features 32ft + 8*i4 + 4h + e -> x[ft*16 + 4*i4 + e];
-// phi of that row (the row's other half sits in lane ^ 32)
-template <bool RELU>
+// phi of that row (the row's other half sits in lane ^ 32).  FM_SOFTMAX64: features 64..127 (ft >= 2) are padding.
+template <int FM>
 __device__ __forceinline__ void phi_row_clayout(const uint16_t* src, int h, float (&x)[64]) {
 #pragma unroll
   for (int ft = 0; ft < 4; ++ft)
@@ -74,29 +76,35 @@ __device__ __forceinline__ void phi_row_clayout(const uint16_t* src, int h, floa
 #pragma unroll
       for (int e = 0; e < 4; ++e) x[ft * 16 + 4 * i4 + e] = f[e];
     }
-  if (RELU) {
+  if (FM == FM_IDENTITY) return;
+  if (FM == FM_RELU) {
 #pragma unroll
     for (int i = 0; i < 64; ++i) x[i] = fmaxf(x[i], 0.f);
     return;
   }
+  constexpr int NV = FM == FM_SOFTMAX64 ? 32 : 64;
   float m = x[0];
 #pragma unroll
-  for (int i = 1; i < 64; ++i) m = fmaxf(m, x[i]);
+  for (int i = 1; i < NV; ++i) m = fmaxf(m, x[i]);
   m = half_max(m);
   float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < 64; ++i) { x[i] = fast_exp2((x[i] - m) * LOG2E); s += x[i]; }
+  for (int i = 0; i < NV; ++i) { x[i] = fast_exp2((x[i] - m) * LOG2E); s += x[i]; }
   s = half_sum(s);
   const float inv = 1.f / s;
 #pragma unroll
-  for (int i = 0; i < 64; ++i) x[i] *= inv;
+  for (int i = 0; i < NV; ++i) x[i] *= inv;
+#pragma unroll
+  for (int i = NV; i < 64; ++i) x[i] = 0.f;
 }
 
-// acc <- f .* (acc - <acc, f>)   (softmax Jacobian applied to a gradient held in accumulator layout);
-// ReLU map: acc <- acc where the input was positive, i.e. where f = max(x, 0) > 0
-template <bool RELU>
+// acc <- f .* (acc - <acc, f>)   (softmax Jacobian applied to a gradient held in accumulator layout; padding features
+// have f = 0 and come out as 0);  ReLU map: acc <- acc where the input was positive, i.e. where f = max(x, 0) > 0;
+// identity map: acc unchanged
+template <int FM>
 __device__ __forceinline__ void phi_jacobian(f32x16_t (&acc)[4], const float (&f)[64]) {
-  if (RELU) {
+  if (FM == FM_IDENTITY) return;
+  if (FM == FM_RELU) {
 #pragma unroll
     for (int ft = 0; ft < 4; ++ft)
 #pragma unroll
@@ -222,6 +230,12 @@ __device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, int hq, size_
     unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(a.dO + off)), dy);
     unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(a.xs + off)), xs);
     unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(a.xr + off)), xr);
+    if (a.xr_lo) {  // wave-uniform
+      float lo[8];
+      unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(a.xr_lo + off)), lo);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) xr[e] += lo[e];
+    }
     const float r_s = a.rs[stat0 + r], r_r = a.rr[stat0 + r];
     float m1 = 0.f, m2 = 0.f;
 #pragma unroll
@@ -233,8 +247,8 @@ __device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, int hq, size_
       m1 = fmaf(g1[e] * dy[e], xs[e], m1);
       m2 = fmaf(g2[e] * dy[e], xr[e], m2);
     }
-    m1 = sum16(m1) * (1.f / 128.f);
-    m2 = sum16(m2) * (1.f / 128.f);
+    m1 = sum16(m1) * a.inv_d;
+    m2 = sum16(m2) * a.inv_d;
     const float b_s = r_s * r_s * r_s * m1, b_r = r_r * r_r * r_r * m2;
     float av[8], cv[8], dl = 0.f;
 #pragma unroll
@@ -272,8 +286,8 @@ __device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, int hq, size_
   }
 }
 
-// GAINS: RMS gains other than one and/or gain gradients (see rms_bwd_rows)
-template <bool GAINS, bool RELU>
+// GAINS: RMS gains other than one and/or gain gradients (see rms_bwd_rows); FM: feature map (FM_* in mfma.hpp)
+template <bool GAINS, int FM>
 __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
   __shared__ __align__(16) unsigned char smem[65536];
   __shared__ float dl_stage[128];
@@ -384,8 +398,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
       tile_load_async<4>(kbase + (size_t)(j0 + 64) * kstride, kstride, smem + 16384, w * 4, lane);
       wait_vmem();
       __syncthreads();
-      if (has_state) phi_tile_inplace<RELU>(smem, 128);
-      else phi_tile_inplace<RELU>(smem + 16384, 64);
+      if (has_state) phi_tile_inplace<FM>(smem, 128);
+      else phi_tile_inplace<FM>(smem + 16384, 64);
       __syncthreads();
       for (int u = has_state ? 0 : 2; u <= min(3, u_hi); ++u)
         intra_unit(smem + (u >> 1) * 16384, smem + 32768 + (u >> 1) * 16384, u & 1, u);
@@ -396,14 +410,14 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
       tile_load_async<4>(vbase + (size_t)(j0 + 128) * kstride, kstride, smem + 32768, w * 4, lane);
       wait_vmem();
       __syncthreads();
-      phi_tile_inplace<RELU>(smem, 64);
+      phi_tile_inplace<FM>(smem, 64);
       __syncthreads();
       for (int u = 4; u <= min(5, u_hi); ++u) intra_unit(smem, smem + 32768, u & 1, u);
       __syncthreads();
     }
     float qf[64];
-    phi_row_clayout<RELU>(a.q + myrow_off, h, qf);
-    phi_jacobian<RELU>(acc, qf);
+    phi_row_clayout<FM>(a.q + myrow_off, h, qf);
+    phi_jacobian<FM>(acc, qf);
   }
 
   // ---- softmax branch
@@ -456,8 +470,10 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
 
 // ------------------------------------------------------------------------------------------------
 // phi in place on the first `nrows` rows of an LDS tile with 512 threads: four threads per row, 32 elements each
-template <bool RELU>
+// (FM_SOFTMAX64: the two threads on features 64..127 leave the padding zeros alone)
+template <int FM>
 __device__ __forceinline__ void phi_tile_inplace_512(unsigned char* tile, int nrows) {
+  if (FM == FM_IDENTITY) return;
   const int row = threadIdx.x >> 2, part = threadIdx.x & 3;
   if (row < nrows) {
     float x[32];
@@ -466,7 +482,7 @@ __device__ __forceinline__ void phi_tile_inplace_512(unsigned char* tile, int nr
 #pragma unroll
     for (int j = 0; j < 4; ++j)
       unpack_bf16x8(*reinterpret_cast<const bf16x8_t*>(rp + (((4 * part + j) ^ sw) << 4)), &x[8 * j]);
-    if (RELU) {
+    if (FM == FM_RELU) {
 #pragma unroll
       for (int i = 0; i < 32; ++i) x[i] = fmaxf(x[i], 0.f);
     } else {
@@ -474,19 +490,21 @@ __device__ __forceinline__ void phi_tile_inplace_512(unsigned char* tile, int nr
 #pragma unroll
       for (int i = 1; i < 32; ++i) m = fmaxf(m, x[i]);
       m = fmaxf(m, __shfl_xor(m, 1, 64));
-      m = fmaxf(m, __shfl_xor(m, 2, 64));
+      if (FM == FM_SOFTMAX) m = fmaxf(m, __shfl_xor(m, 2, 64));
       float sum = 0.f;
 #pragma unroll
       for (int i = 0; i < 32; ++i) { x[i] = fast_exp2((x[i] - m) * LOG2E); sum += x[i]; }
       sum += __shfl_xor(sum, 1, 64);
-      sum += __shfl_xor(sum, 2, 64);
+      if (FM == FM_SOFTMAX) sum += __shfl_xor(sum, 2, 64);
       const float inv = 1.f / sum;
 #pragma unroll
       for (int i = 0; i < 32; ++i) x[i] *= inv;
     }
+    if (!(FM == FM_SOFTMAX64 && part >= 2)) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      *reinterpret_cast<bf16x8_t*>(rp + (((4 * part + j) ^ sw) << 4)) = pack_bf16x8(&x[8 * j]);
+      for (int j = 0; j < 4; ++j)
+        *reinterpret_cast<bf16x8_t*>(rp + (((4 * part + j) ^ sw) << 4)) = pack_bf16x8(&x[8 * j]);
+    }
   }
 }
 
@@ -514,7 +532,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // (every wave has then left tile s-1, whose buffer it takes) and each wave waits for its share of tile s+1
 // before the second barrier of step s, so no further barrier is needed.  The loop has no other vector-memory
 // operation (row statistics arrive with the tiles), which is what makes the explicit counter waits exact.
-template <bool RELU>
+template <int FM>
 __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* pex = smem + DKV_PEX_OFF;
@@ -585,7 +603,7 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
       float x[64];
 #pragma unroll
       for (int c = 0; c < 8; ++c) unpack_bf16x8(xop[c], &x[8 * c]);
-      phi_rows<RELU>(x, xop);
+      phi_rows<FM>(x, xop);
     }
     unsigned char* const qA = smem;
     unsigned char* const dA = smem + 32768;
@@ -644,7 +662,7 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
       }
       const bool pre = pass_is_pre(vh);
       const int nrow = pre ? 64 : nq, qb0 = pre ? -64 : 0;
-      phi_tile_inplace_512<RELU>(qb, nrow);
+      phi_tile_inplace_512<FM>(qb, nrow);
       __syncthreads();
       const unsigned char* mine = krole ? db : qb;    // rows contracted with xop
       const unsigned char* other = krole ? qb : db;   // rows accumulated into acc
@@ -676,8 +694,8 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
     }
     if (krole) {
       float kf[64];
-      phi_row_clayout<RELU>(a.k + myrow_off, h, kf);
-      phi_jacobian<RELU>(acc, kf);
+      phi_row_clayout<FM>(a.k + myrow_off, h, kf);
+      phi_jacobian<FM>(acc, kf);
     } else {
       load_bop(a.k + myrow_off, h, xop);
     }
@@ -814,19 +832,26 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
   a.nstf = pl.fwd.nstf; a.nk = pl.nk; a.ntile = dm.T / 128;
   a.scale = dm.scale; a.scale_log2 = dm.scale * LOG2E;
   a.dO = (const uint16_t*)dO; a.xs = (const uint16_t*)sv.xs; a.xr = (const uint16_t*)sv.xr;
+  a.xr_lo = (const uint16_t*)sv.xr_lo;
   a.rs = sv.rs; a.rr = sv.rr; a.gs = gs; a.gr = gr;
   a.dgpart = (dgs || dgr) ? ws.dgpart : nullptr;
-  const bool relu = dm.phi == PHI_RELU;
+  a.inv_d = 1.f / (float)dm.Dv;
+  const int fm = feature_map_variant(dm);
   {
     ProfScope ps("bwd_dq_kernel", st);
     const dim3 grid(a.ntile * dm.Hq * dm.B);
-    if (relu) {
-      if (gains) bwd_dq_kernel<true, true><<<grid, 256, 0, st>>>(a);
-      else bwd_dq_kernel<false, true><<<grid, 256, 0, st>>>(a);
-    } else {
-      if (gains) bwd_dq_kernel<true, false><<<grid, 256, 0, st>>>(a);
-      else bwd_dq_kernel<false, false><<<grid, 256, 0, st>>>(a);
+#define RATTN_DQ_LAUNCH(FM_)                                                   \
+  do {                                                                         \
+    if (gains) bwd_dq_kernel<true, FM_><<<grid, 256, 0, st>>>(a);              \
+    else bwd_dq_kernel<false, FM_><<<grid, 256, 0, st>>>(a);                   \
+  } while (0)
+    switch (fm) {
+      case FM_RELU: RATTN_DQ_LAUNCH(FM_RELU); break;
+      case FM_IDENTITY: RATTN_DQ_LAUNCH(FM_IDENTITY); break;
+      case FM_SOFTMAX64: RATTN_DQ_LAUNCH(FM_SOFTMAX64); break;
+      default: RATTN_DQ_LAUNCH(FM_SOFTMAX); break;
     }
+#undef RATTN_DQ_LAUNCH
   }
   if (dgs || dgr) {
     const int HD = dm.Hq * 128;
@@ -834,14 +859,25 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
     dgamma_reduce_kernel<<<dim3(HD / 32, 2), 256, 0, st>>>(ws.dgpart, dgs, dgr, pl.RB, HD);
   }
   rla_reverse_states(dm, pl.fwd.W, pl.nk, q, ws.dxr, ws.U, ws.rstates, st);
-  static const hipError_t lds_attr = hipFuncSetAttribute(
-      reinterpret_cast<const void*>(bwd_dkv_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS_BYTES);
-  static const hipError_t lds_attr_relu = hipFuncSetAttribute(
-      reinterpret_cast<const void*>(bwd_dkv_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS_BYTES);
-  (void)lds_attr; (void)lds_attr_relu;
+  // the dk/dv kernel needs more LDS than a launch gets by default: raised once per instantiation
+  static const bool lds_attr = [] {
+    const void* fns[] = {reinterpret_cast<const void*>(bwd_dkv_kernel<FM_SOFTMAX>),
+                         reinterpret_cast<const void*>(bwd_dkv_kernel<FM_RELU>),
+                         reinterpret_cast<const void*>(bwd_dkv_kernel<FM_IDENTITY>),
+                         reinterpret_cast<const void*>(bwd_dkv_kernel<FM_SOFTMAX64>)};
+    bool ok = true;
+    for (const void* f : fns) ok &= hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS_BYTES) == hipSuccess;
+    return ok;
+  }();
+  (void)lds_attr;
   ProfScope ps("bwd_dkv_kernel", st);
-  if (relu) bwd_dkv_kernel<true><<<dim3(a.ntile * dm.Hkv * dm.B), 512, DKV_LDS_BYTES, st>>>(a);
-  else bwd_dkv_kernel<false><<<dim3(a.ntile * dm.Hkv * dm.B), 512, DKV_LDS_BYTES, st>>>(a);
+  const dim3 kgrid(a.ntile * dm.Hkv * dm.B);
+  switch (fm) {
+    case FM_RELU: bwd_dkv_kernel<FM_RELU><<<kgrid, 512, DKV_LDS_BYTES, st>>>(a); break;
+    case FM_IDENTITY: bwd_dkv_kernel<FM_IDENTITY><<<kgrid, 512, DKV_LDS_BYTES, st>>>(a); break;
+    case FM_SOFTMAX64: bwd_dkv_kernel<FM_SOFTMAX64><<<kgrid, 512, DKV_LDS_BYTES, st>>>(a); break;
+    default: bwd_dkv_kernel<FM_SOFTMAX><<<kgrid, 512, DKV_LDS_BYTES, st>>>(a); break;
+  }
 }
 
 }  // namespace rattn

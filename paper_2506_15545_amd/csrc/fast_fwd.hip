@@ -27,11 +27,13 @@ struct FastFwdArgs {
   const uint16_t *q, *k, *v;
   const float *gs, *gr;
   uint16_t *o, *xs_out, *xr_out;
+  uint16_t* xr_lo_out;  // low-order part of the saved x_r (identity feature map only, else null)
   float *lse_out, *rs_out, *rr_out;
   const uint16_t* states;  // [B,Hkv,nstf,128 (value d),128 (feature f)] bf16: S^T at key position base+128*i
   int B, T, Hq, Hkv, G, W, gap, nstf, ntile;  // W: window rounded up to 64; true window = W - gap
   int qt0;  // first query tile that is computed; q, o and the saved tensors hold rows 128 qt0 .. T-1 only
   float scale_log2, eps;
+  float inv_d;  // 1 / head size the RMS norms average over (1/64 when the rows are zero-padded from 64 to 128)
 };
 
 // One 32-key sub-tile of the softmax branch for this wave's 32 queries (lane = query):
@@ -182,8 +184,8 @@ __device__ __forceinline__ void store_tile_direct(const f32x16_t (&acc)[4], uint
 }
 
 // GAP: the window is not a multiple of 64 (a.gap > 0); the aligned case compiles without the extra key tile.
-// RELU: the linear branch uses the ablation's ReLU feature map instead of the softmax map.
-template <bool GAP, bool RELU>
+// FM: feature map of the linear branch (FM_* in mfma.hpp).
+template <bool GAP, int FM>
 __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
   __shared__ __align__(16) unsigned char smem[65536];
   const int lane = lane_id(), w = wave_id();
@@ -279,7 +281,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
     for (int i = 0; i < 16; ++i) ss += oacc[dt][i] * oacc[dt][i];
   }
   ss = half_sum(ss);
-  const float rs_val = rsqrtf(ss * (1.f / 128.f) + a.eps);
+  const float rs_val = rsqrtf(ss * a.inv_d + a.eps);
   // key tile of the intra-chunk part starts at j0 = t0 - W; when W % 128 == 64 the first query tile that
   // reaches past the window has j0 = -64: no state yet (S = 0) and only its upper 64 keys exist
   // (with gap > 0 the tile at j0 = -128 reaches keys too: only through the extra 64 keys fetched below)
@@ -315,10 +317,10 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
       float x[64];
 #pragma unroll
       for (int dk = 0; dk < 8; ++dk) unpack_bf16x8(qop[dk], &x[8 * dk]);
-      phi_rows<RELU>(x, qfop);
+      phi_rows<FM>(x, qfop);
     }
     const bool has_res = j0 > -128;  // the resident tiles hold keys of this chunk
-    if (has_res) phi_tiles_inplace<RELU>(has_state ? smem + buf0 * 16384 : nullptr, smem + (buf0 ^ 1) * 16384);
+    if (has_res) phi_tiles_inplace<FM>(has_state ? smem + buf0 * 16384 : nullptr, smem + (buf0 ^ 1) * 16384);
     __syncthreads();
     // Key sub-tile u (keys j0 + 32u .. +31) meets query block w when 32u <= 32w + 31 + gap; a query sees
     // key_local <= q_local + gap.  Sub-tiles 0..3 are resident; with gap > 0 the top queries also reach
@@ -357,7 +359,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
       tile_load_async<4>(vbase + (size_t)(j0 + 128) * kstride, kstride, smem + 32768, w * 4, lane);
       wait_vmem();
       __syncthreads();
-      phi_tiles_inplace<RELU>(smem, nullptr);
+      phi_tiles_inplace<FM>(smem, nullptr);
       __syncthreads();
       for (int u = 4; u <= min(5, u_hi); ++u) intra_unit(smem, smem + 32768, u & 1, u);
       __syncthreads();
@@ -379,7 +381,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) sr += xr[dt][i] * xr[dt][i];
     sr = half_sum(sr);
-    rr_val = rsqrtf(sr * (1.f / 128.f) + a.eps);
+    rr_val = rsqrtf(sr * a.inv_d + a.eps);
   }
   if (a.xs_out) {
     float vals[4][16];
@@ -388,6 +390,13 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) vals[dt][i] = xr[dt][i];
     store_tile_transposed(smem, vals, a.xr_out + qtile_off, qstride, w, lane);
+    if (FM == FM_IDENTITY && a.xr_lo_out) {  // what the bf16 value above leaves of x_r, as a second bf16 tensor
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) vals[dt][i] = xr[dt][i] - (float)(__bf16)xr[dt][i];
+      store_tile_transposed(smem, vals, a.xr_lo_out + qtile_off, qstride, w, lane);
+    }
     if (h == 0) {
       a.lse_out[stat_off] = lse_val;
       a.rs_out[stat_off] = rs_val;
@@ -440,6 +449,7 @@ void fast_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
   a.gs = gs; a.gr = gr;
   a.o = (uint16_t*)o; a.xs_out = (uint16_t*)sv.xs; a.xr_out = (uint16_t*)sv.xr;
+  a.xr_lo_out = (uint16_t*)sv.xr_lo;
   a.lse_out = sv.lse; a.rs_out = sv.rs; a.rr_out = sv.rr;
   a.states = (const uint16_t*)states;
   a.B = dm.B; a.T = dm.T; a.Hq = dm.Hq; a.Hkv = dm.Hkv; a.G = dm.G; a.W = pl.W; a.gap = pl.gap; a.nstf = pl.nstf;
@@ -447,14 +457,19 @@ void fast_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
   a.scale_log2 = dm.scale * LOG2E; a.eps = dm.eps;
   ProfScope ps("fwd_fused_kernel", st);
   const dim3 grid((a.ntile - qt0) * dm.Hq * dm.B);
-  const bool relu = dm.phi == PHI_RELU;
-  if (a.gap > 0) {
-    if (relu) fwd_fused_kernel<true, true><<<grid, 256, 0, st>>>(a);
-    else fwd_fused_kernel<true, false><<<grid, 256, 0, st>>>(a);
-  } else {
-    if (relu) fwd_fused_kernel<false, true><<<grid, 256, 0, st>>>(a);
-    else fwd_fused_kernel<false, false><<<grid, 256, 0, st>>>(a);
+  a.inv_d = 1.f / (float)dm.Dv;
+#define RATTN_FWD_LAUNCH(FM_)                                             \
+  do {                                                                    \
+    if (a.gap > 0) fwd_fused_kernel<true, FM_><<<grid, 256, 0, st>>>(a);  \
+    else fwd_fused_kernel<false, FM_><<<grid, 256, 0, st>>>(a);           \
+  } while (0)
+  switch (feature_map_variant(dm)) {
+    case FM_RELU: RATTN_FWD_LAUNCH(FM_RELU); break;
+    case FM_IDENTITY: RATTN_FWD_LAUNCH(FM_IDENTITY); break;
+    case FM_SOFTMAX64: RATTN_FWD_LAUNCH(FM_SOFTMAX64); break;
+    default: RATTN_FWD_LAUNCH(FM_SOFTMAX); break;
   }
+#undef RATTN_FWD_LAUNCH
 }
 
 }  // namespace rattn

@@ -20,6 +20,8 @@ enum { PHI_SOFTMAX = 0, PHI_RELU = 1, PHI_IDENTITY = 2 };
 
 struct LayerDims {
   int B, T, Hq, Hkv, D, W, C, G;
+  int Dv;   // features of a head that carry data: D, or 64 when the matrix-core kernels run a head size of 64
+            // on rows zero-padded to D = 128 (the RMS norms and the softmax feature map then cover Dv features)
   int nst;  // number of chunk states per (batch, kv head): ceil(max(T-W,0) / C)
   float scale, eps;
   int phi;  // feature map of the linear branch: PHI_SOFTMAX (Sec. 3.1), PHI_RELU, PHI_IDENTITY (Sec. 4.5 ablation)
@@ -39,6 +41,10 @@ struct SavedPtrs {
   float* rr;
   void* states;  // null on the general path
   bool f32;      // x^s, x^r are stored as fp32 whatever the tensor dtype
+  void* xr_lo;   // matrix-core path with the identity feature map only (else null): x^r - bf16(x^r), itself rounded
+                 // to bf16, so that backward reads x^r to 16 significant bits.  With features of size ~1 the first
+                 // rows past the window (state of rank 1, 2, ...) turn the backward through the second RMS norm into
+                 // a cancellation that a bf16 x^r alone resolves to only ~10 % of the gradient's RMS
 };
 
 struct GenericBwdWs {
@@ -56,6 +62,13 @@ void generic_fwd(const LayerDims& dm, int dtype, const void* q, const void* k, c
 void generic_bwd(const LayerDims& dm, int dtype, const void* q, const void* k, const void* v, const float* gs,
                  const float* gr, const SavedPtrs& sv, const void* dO, void* dq, void* dk, void* dv, float* dgs,
                  float* dgr, const GenericBwdWs& ws, hipStream_t st);
+
+// compile-time feature-map variant (FM_* in mfma.hpp) the matrix-core kernels use for these dimensions
+inline int feature_map_variant(const LayerDims& dm) {
+  if (dm.phi == PHI_RELU) return 1;
+  if (dm.phi == PHI_IDENTITY) return 2;
+  return dm.Dv == 64 ? 3 : 0;
+}
 
 // MFMA forward path (bf16, D = 128, T % 128 == 0, any W >= 8)
 struct FastFwdPlan {
@@ -124,9 +137,12 @@ void chunk_copy_out(const LayerDims& dmc, int dtype, int Tc, int R, const void* 
 void chunk_fixup(const LayerDims& dmc, int dtype, int Tc, int R, int Ls, const void* qc, const SavedPtrs& sv,
                  const float* state, const float* gs, const float* gr, void* o, hipStream_t st);
 
-// [B,T,row] <-> [B,Tp,row] with zero rows t >= T (row_bytes a multiple of 16)
-void pad_rows(const void* src, void* dst, int B, int T, int Tp, size_t row_bytes, hipStream_t st);
-void unpad_rows(const void* src, void* dst, int B, int T, int Tp, size_t row_bytes, hipStream_t st);
+// [B,T,H,head] <-> [B,Tp,H,head_padded] with zeros at t >= T and past `head_bytes` of every head row (both sizes
+// multiples of 16 bytes)
+void pad_rows(const void* src, void* dst, int B, int T, int Tp, int H, size_t head_bytes, size_t head_bytes_padded,
+              hipStream_t st);
+void unpad_rows(const void* src, void* dst, int B, int T, int Tp, int H, size_t head_bytes, size_t head_bytes_padded,
+                hipStream_t st);
 
 // launches the matrix-core probe loop; returns the FLOPs it issues
 double probe_mfma(float* sink, int iters, int blocks, hipStream_t st);

@@ -198,26 +198,36 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
-// phi = softmax over the 128 features of a row whose two halves sit in lanes l and l^32 (64 values
-// each, any fixed order); result packed as 8 MFMA operand registers in the same order.
-// RELU selects max(x, 0) per feature instead, the ablation's ReLU map (Sec. 4.5).
-template <bool RELU = false>
+// Feature map of the linear branch as a compile-time choice of the matrix-core kernels:
+//   FM_SOFTMAX    softmax over the 128 features of a row (Sec. 3.1)
+//   FM_RELU       max(x, 0) per feature, FM_IDENTITY  x itself (the ablation's maps, Sec. 4.5)
+//   FM_SOFTMAX64  softmax over the FIRST 64 features; features 64..127 are padding (the caller's head size is 64 and
+//                 rows arrive zero-padded to 128): their phi is 0, so they drop out of every product.  The other two
+//                 maps need no such variant: they map a padding zero to zero by themselves.
+enum { FM_SOFTMAX = 0, FM_RELU = 1, FM_IDENTITY = 2, FM_SOFTMAX64 = 3 };
+
+// phi of a row whose two halves sit in lanes l and l^32 (64 values each: x[8c + e] = feature 16c + 8h + e);
+// result packed as 8 MFMA operand registers in the same order.
+template <int FM = FM_SOFTMAX>
 __device__ __forceinline__ void phi_rows(float (&x)[64], bf16x8_t (&op)[8]) {
-  if (RELU) {
+  if (FM == FM_RELU) {
 #pragma unroll
     for (int i = 0; i < 64; ++i) x[i] = fmaxf(x[i], 0.f);
-  } else {
+  } else if (FM == FM_SOFTMAX || FM == FM_SOFTMAX64) {
+    constexpr int NV = FM == FM_SOFTMAX64 ? 32 : 64;  // this lane's valid features: c < 4 are features < 64
     float m = x[0];
 #pragma unroll
-    for (int i = 1; i < 64; ++i) m = fmaxf(m, x[i]);
+    for (int i = 1; i < NV; ++i) m = fmaxf(m, x[i]);
     m = half_max(m);
     float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < 64; ++i) { x[i] = fast_exp2((x[i] - m) * LOG2E); s += x[i]; }
+    for (int i = 0; i < NV; ++i) { x[i] = fast_exp2((x[i] - m) * LOG2E); s += x[i]; }
     s = half_sum(s);
     const float inv = 1.f / s;
 #pragma unroll
-    for (int i = 0; i < 64; ++i) x[i] *= inv;
+    for (int i = 0; i < NV; ++i) x[i] *= inv;
+#pragma unroll
+    for (int i = NV; i < 64; ++i) x[i] = 0.f;
   }
 #pragma unroll
   for (int c = 0; c < 8; ++c) op[c] = pack_bf16x8(&x[8 * c]);
@@ -226,30 +236,32 @@ __device__ __forceinline__ void phi_rows(float (&x)[64], bf16x8_t (&op)[8]) {
 // phi applied in place to LDS tile rows, two threads per row: thread pair r works on row r of tile A
 // (r < 64) or row r-64 of tile B (r >= 64); a null tile pointer skips that half.  Tiles A and B
 // contiguous = one 128-row tile.  Call with all 256 threads; the caller synchronises before and after.
-template <bool RELU = false>
+template <int FM = FM_SOFTMAX>
 __device__ __forceinline__ void phi_tiles_inplace(unsigned char* tileA, unsigned char* tileB) {
+  if (FM == FM_IDENTITY) return;
   const int r = threadIdx.x >> 1, half = threadIdx.x & 1;
   unsigned char* tile = r < 64 ? tileA : tileB;
   const int row = r & 63;
-  if (tile) {
+  // FM_SOFTMAX64: the thread with features 64..127 has nothing to do (padding zeros stay zeros)
+  if (tile && !(FM == FM_SOFTMAX64 && half == 1)) {
     float x[64];
     unsigned char* rp = tile + row * ROW_BYTES;
     const int sw = swz(row);
 #pragma unroll
     for (int j = 0; j < 8; ++j)
       unpack_bf16x8(*reinterpret_cast<const bf16x8_t*>(rp + (((8 * half + j) ^ sw) << 4)), &x[8 * j]);
-    if (RELU) {
+    if (FM == FM_RELU) {
 #pragma unroll
       for (int i = 0; i < 64; ++i) x[i] = fmaxf(x[i], 0.f);
     } else {
       float m = x[0];
 #pragma unroll
       for (int i = 1; i < 64; ++i) m = fmaxf(m, x[i]);
-      m = fmaxf(m, __shfl_xor(m, 1, 64));
+      if (FM == FM_SOFTMAX) m = fmaxf(m, __shfl_xor(m, 1, 64));
       float s = 0.f;
 #pragma unroll
       for (int i = 0; i < 64; ++i) { x[i] = fast_exp2((x[i] - m) * LOG2E); s += x[i]; }
-      s += __shfl_xor(s, 1, 64);
+      if (FM == FM_SOFTMAX) s += __shfl_xor(s, 1, 64);
       const float inv = 1.f / s;
 #pragma unroll
       for (int i = 0; i < 64; ++i) x[i] *= inv;
@@ -260,9 +272,9 @@ __device__ __forceinline__ void phi_tiles_inplace(unsigned char* tileA, unsigned
   }
 }
 // first `nrows` (64 or 128) rows of one contiguous tile
-template <bool RELU = false>
+template <int FM = FM_SOFTMAX>
 __device__ __forceinline__ void phi_tile_inplace(unsigned char* tile, int nrows) {
-  phi_tiles_inplace<RELU>(tile, nrows > 64 ? tile + 64 * ROW_BYTES : nullptr);
+  phi_tiles_inplace<FM>(tile, nrows > 64 ? tile + 64 * ROW_BYTES : nullptr);
 }
 
 // Write a [128 rows x 128] bf16 tile held transposed in accumulators (lane = tile row 32w + lane%32,

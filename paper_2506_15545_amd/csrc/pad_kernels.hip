@@ -1,6 +1,9 @@
-// Row padding for sequence lengths that are not a multiple of the matrix-core kernels' 128-row tiles: the layer is
-// causal, so rows appended after the last token change nothing before them, and zero rows of dO contribute nothing
-// to any gradient.  Tensors are [B, T, H*D]; the padded copy is [B, Tp, H*D] with zero rows t >= T.
+// Zero-padded copies for shapes that the matrix-core kernels do not take directly:
+//  * sequence lengths that are not a multiple of their 128-row tiles: the layer is causal, so rows appended after the
+//    last token change nothing before them, and zero rows of dO contribute nothing to any gradient;
+//  * a head size of 64: rows are widened to 128 features with zeros, which add nothing to any dot product; the
+//    kernels are told that only 64 features carry data (RMS norms, softmax feature map).
+// Tensors are [B, T, H, D]; the padded copy is [B, Tp, H, Dp] with zeros at t >= T and in features >= D.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -8,25 +11,29 @@ namespace rattn {
 
 namespace {
 
-// one thread per 16 bytes of the destination
+// one thread per 16 bytes of the destination; hv / hvp = 16-byte vectors per head row in the source / destination
 __global__ __launch_bounds__(256) void pad_rows_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int B, int T,
-                                                       int Tp, long long row_vecs) {
-  const long long total = (long long)B * Tp * row_vecs;
+                                                       int Tp, int H, int hv, int hvp) {
+  const long long total = (long long)B * Tp * H * hvp;
   for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
-    const long long c = i % row_vecs, r = i / row_vecs;
+    const int c = (int)(i % hvp);
+    long long r = i / hvp;
+    const int h = (int)(r % H); r /= H;
     const int t = (int)(r % Tp), b = (int)(r / Tp);
-    dst[i] = t < T ? src[((long long)b * T + t) * row_vecs + c] : make_uint4(0u, 0u, 0u, 0u);
+    dst[i] = (t < T && c < hv) ? src[(((long long)b * T + t) * H + h) * hv + c] : make_uint4(0u, 0u, 0u, 0u);
   }
 }
 
 // one thread per 16 bytes of the destination (the unpadded tensor)
 __global__ __launch_bounds__(256) void unpad_rows_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int B,
-                                                         int T, int Tp, long long row_vecs) {
-  const long long total = (long long)B * T * row_vecs;
+                                                         int T, int Tp, int H, int hv, int hvp) {
+  const long long total = (long long)B * T * H * hv;
   for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
-    const long long c = i % row_vecs, r = i / row_vecs;
+    const int c = (int)(i % hv);
+    long long r = i / hv;
+    const int h = (int)(r % H); r /= H;
     const int t = (int)(r % T), b = (int)(r / T);
-    dst[i] = src[((long long)b * Tp + t) * row_vecs + c];
+    dst[i] = src[(((long long)b * Tp + t) * H + h) * hvp + c];
   }
 }
 
@@ -37,16 +44,18 @@ int blocks_for(long long total) {
 
 }  // namespace
 
-void pad_rows(const void* src, void* dst, int B, int T, int Tp, size_t row_bytes, hipStream_t st) {
-  const long long rv = (long long)(row_bytes / 16);
+void pad_rows(const void* src, void* dst, int B, int T, int Tp, int H, size_t head_bytes, size_t head_bytes_padded,
+              hipStream_t st) {
+  const int hv = (int)(head_bytes / 16), hvp = (int)(head_bytes_padded / 16);
   ProfScope ps("pad_rows_kernel", st);
-  pad_rows_kernel<<<blocks_for((long long)B * Tp * rv), 256, 0, st>>>((const uint4*)src, (uint4*)dst, B, T, Tp, rv);
+  pad_rows_kernel<<<blocks_for((long long)B * Tp * H * hvp), 256, 0, st>>>((const uint4*)src, (uint4*)dst, B, T, Tp, H, hv, hvp);
 }
 
-void unpad_rows(const void* src, void* dst, int B, int T, int Tp, size_t row_bytes, hipStream_t st) {
-  const long long rv = (long long)(row_bytes / 16);
+void unpad_rows(const void* src, void* dst, int B, int T, int Tp, int H, size_t head_bytes, size_t head_bytes_padded,
+                hipStream_t st) {
+  const int hv = (int)(head_bytes / 16), hvp = (int)(head_bytes_padded / 16);
   ProfScope ps("unpad_rows_kernel", st);
-  unpad_rows_kernel<<<blocks_for((long long)B * T * rv), 256, 0, st>>>((const uint4*)src, (uint4*)dst, B, T, Tp, rv);
+  unpad_rows_kernel<<<blocks_for((long long)B * T * H * hv), 256, 0, st>>>((const uint4*)src, (uint4*)dst, B, T, Tp, H, hv, hvp);
 }
 
 }  // namespace rattn

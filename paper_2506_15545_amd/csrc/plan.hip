@@ -5,12 +5,11 @@
 
 namespace rattn {
 
+// dm: the dimensions the kernels would see, i.e. after any zero-padding of the sequence length to whole tiles and of
+// a head size of 64 to 128 (dm.D = 128, dm.Dv = 64)
 bool fast_fwd_supported(const LayerDims& dm, int dtype) {
   if (dtype != 1 || dm.D != 128 || dm.T % 128 != 0) return false;
   if (!(dm.scale > 0.f)) return false;
-  // The identity map stays on the general kernels: its features are of size ~1 instead of ~1/D, and the backward of
-  // the first rows past the window (state of rank 1, 2, ...) is a cancellation that needs the fp32 x^r kept there
-  if (dm.phi != PHI_SOFTMAX && dm.phi != PHI_RELU) return false;
   // Windows below 8 keys stay on the general path: their softmax rows are close to one-hot, so the backward's
   // dS = P (dP - delta) is a near-cancellation (exact for W = 1) that bf16 operands turn into rounding noise
   // above the gradient tolerance (measured: worst element 4 % of RMS at W = 2, 3 % at W = 4, 2.5 % from W = 8 on)

@@ -20,7 +20,7 @@ struct ChunkArgs {
 };
 
 // grid (nchunks, Hkv, B), 256 threads.  Wave w owns rows d in [32w, 32w+32) of U^T.
-template <bool RELU>
+template <int FM>
 __global__ __launch_bounds__(256) void rla_chunk_kernel(ChunkArgs p) {
   __shared__ __align__(16) unsigned char smem[65536];
   unsigned char* At = smem;
@@ -43,7 +43,7 @@ __global__ __launch_bounds__(256) void rla_chunk_kernel(ChunkArgs p) {
     }
     wait_vmem();
     __syncthreads();
-    phi_tile_inplace<RELU>(At, ntok);
+    phi_tile_inplace<FM>(At, ntok);
     __syncthreads();
     for (int ks = 0; ks < ntok / 16; ++ks) {
       const int k0 = 16 * ks + 8 * h;
@@ -103,6 +103,15 @@ __global__ __launch_bounds__(256) void rla_scan_kernel(const float* __restrict__
   }
 }
 
+void launch_chunk_kernel(int fm, dim3 grid, const ChunkArgs& p, hipStream_t st) {
+  switch (fm) {
+    case FM_RELU: rla_chunk_kernel<FM_RELU><<<grid, 256, 0, st>>>(p); break;
+    case FM_IDENTITY: rla_chunk_kernel<FM_IDENTITY><<<grid, 256, 0, st>>>(p); break;
+    case FM_SOFTMAX64: rla_chunk_kernel<FM_SOFTMAX64><<<grid, 256, 0, st>>>(p); break;
+    default: rla_chunk_kernel<FM_SOFTMAX><<<grid, 256, 0, st>>>(p); break;
+  }
+}
+
 }  // namespace
 
 void rla_forward_states(const LayerDims& dm, const FastFwdPlan& pl, const void* k, const void* v, float* U,
@@ -114,8 +123,7 @@ void rla_forward_states(const LayerDims& dm, const FastFwdPlan& pl, const void* 
     p.T = dm.T; p.H = dm.Hkv; p.GA = 1; p.tok_off = 0;
     p.first_lo = 0; p.first_n = pl.base > 0 ? 64 : 128; p.rest_lo = pl.base > 0 ? 64 : 128; p.tok_end = 1 << 30;
     ProfScope ps("rla_chunk_kernel", st);
-    if (dm.phi == PHI_RELU) rla_chunk_kernel<true><<<dim3(pl.nchunks, dm.Hkv, dm.B), 256, 0, st>>>(p);
-    else rla_chunk_kernel<false><<<dim3(pl.nchunks, dm.Hkv, dm.B), 256, 0, st>>>(p);
+    launch_chunk_kernel(feature_map_variant(dm), dim3(pl.nchunks, dm.Hkv, dm.B), p, st);
   }
   ProfScope ps("rla_scan_kernel", st);
   rla_scan_kernel<false><<<dim3(16, dm.Hkv, dm.B), 256, 0, st>>>(U, (uint16_t*)states, pl.nchunks, pl.nstf,
@@ -132,8 +140,7 @@ void rla_reverse_states(const LayerDims& dm, int W, int nk, const void* q, const
     p.T = dm.T; p.H = dm.Hq; p.GA = dm.G; p.tok_off = W;
     p.first_lo = 128; p.first_n = 128; p.rest_lo = 256; p.tok_end = Tp;
     ProfScope ps("rla_chunk_kernel(rev)", st);
-    if (dm.phi == PHI_RELU) rla_chunk_kernel<true><<<dim3(nk - 1, dm.Hkv, dm.B), 256, 0, st>>>(p);
-    else rla_chunk_kernel<false><<<dim3(nk - 1, dm.Hkv, dm.B), 256, 0, st>>>(p);
+    launch_chunk_kernel(feature_map_variant(dm), dim3(nk - 1, dm.Hkv, dm.B), p, st);
   }
   ProfScope ps("rla_scan_kernel(rev)", st);
   rla_scan_kernel<true><<<dim3(16, dm.Hkv, dm.B), 256, 0, st>>>(U, (uint16_t*)rstates, nk - 1, nk, 0, nullptr);

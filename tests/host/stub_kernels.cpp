@@ -30,8 +30,8 @@ void chunk_concat(const LayerDims&, int, int, int, int, const void*, const void*
 void chunk_copy_out(const LayerDims&, int, int, int, const void*, void*, hipStream_t) { ++g_stub_launches; }
 void chunk_fixup(const LayerDims&, int, int, int, int, const void*, const SavedPtrs&, const float*, const float*,
                  const float*, void*, hipStream_t) { ++g_stub_launches; }
-void pad_rows(const void*, void*, int, int, int, size_t, hipStream_t) { ++g_stub_launches; }
-void unpad_rows(const void*, void*, int, int, int, size_t, hipStream_t) { ++g_stub_launches; }
+void pad_rows(const void*, void*, int, int, int, int, size_t, size_t, hipStream_t) { ++g_stub_launches; }
+void unpad_rows(const void*, void*, int, int, int, int, size_t, size_t, hipStream_t) { ++g_stub_launches; }
 double probe_mfma(float*, int iters, int blocks, hipStream_t) { ++g_stub_launches; return 16.0 * iters * blocks * 4 * 32768.0; }
 void decode_step(const DecodeDims&, int, const void*, const void*, const void*, const int32_t*, void*, void*, float*,
                  const float*, const float*, void*, hipStream_t) { ++g_stub_launches; }

@@ -187,6 +187,51 @@ def test_fast_bwd_unit_gains_no_dgamma(B, T, Hq, Hkv, W):
         assert e["worst"] <= 1e-2 and e["rms"] <= 2e-3, f"{n} with and without gain gradients: {e}"
 
 
+@pytest.mark.parametrize("B,T,Hq,Hkv,W", [
+    (1, 256, 4, 2, 32),       # the tiny configuration's head size and window, in bf16
+    (2, 384, 2, 1, 100),      # window no tile multiple
+    (1, 128, 2, 2, 512),      # causal
+    (1, 640, 6, 2, 192),      # GQA 3, states at the 64 alignment
+    (1, 1100, 3, 1, 300),     # ragged length and head size 64 together
+])
+def test_head_size_64_runs_on_the_matrix_cores(B, T, Hq, Hkv, W):
+    """Head size 64 (bf16, whole tiles or long enough for padded copies): rows are widened to 128 features with zeros
+    and run on the matrix-core kernels, which are told that 64 features carry data (RMS norms over 64, softmax feature
+    map over 64).  Forward, backward and gain gradients against the oracle at head size 64."""
+    D = 64
+    x = synth.make_random_layer(B, T, Hq, Hkv, D, "bf16", 2700 + T + W, with_dO=True, with_gains=True)
+    scale = 1.0 / math.sqrt(D)
+    gs, gr = x["gamma_swa"], x["gamma_rla"]
+    print(f"head size 64 case B={B} T={T} Hq={Hq} Hkv={Hkv} W={W}", flush=True)
+    q, k, v, dO = x["q"].cuda(), x["k"].cuda(), x["v"].cuda(), x["dO"].cuda()
+    rb.rattn_profile_enable(True)
+    o, saved = rb.rattn_fwd(q, k, v, W, gs.cuda(), gr.cuda(), softmax_scale=scale, save_for_bwd=True)
+    dq, dk, dv, dgs, dgr = rb.rattn_bwd(q, k, v, saved, dO, W, gs.cuda(), gr.cuda(), softmax_scale=scale)
+    torch.cuda.synchronize()
+    names = [n for n, _ in rb.rattn_profile_records()]
+    rb.rattn_profile_enable(False)
+    assert "fwd_fused_kernel" in names and "bwd_dkv_kernel" in names and "pad_rows_kernel" in names
+    assert "gen_fwd_kernel" not in names
+    kw = dict(scale=scale, gamma_swa=np64(gs), gamma_rla=np64(gr))
+    ref = orc.fwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), W, **kw)
+    gmax = max(float(gs.abs().max()), float(gr.abs().max()), 1.0)
+    pm.assert_out_bf16(np64(o), ref["o"], gmax)
+    refb = orc.bwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), np64(x["dO"]), W, **kw)
+    model = model_grads(x, W, scale)
+    for n, g_ in (("dq", dq), ("dk", dk), ("dv", dv)):
+        pm.assert_grad_bf16(np64(g_), refb[n], n, model[n])
+    for n, g_ in (("dgamma_swa", dgs), ("dgamma_rla", dgr)):
+        assert tuple(g_.shape) == (Hq, D)
+        if np.all(refb[n] == 0):
+            assert float(g_.abs().max()) <= 1e-6
+        else:
+            rms = math.sqrt(float(np.mean(refb[n] ** 2)))
+            assert float(np.max(np.abs(np64(g_) - refb[n]))) / rms <= 2e-2, n
+    # the same input on the general kernels agrees
+    o_gen = rb.rattn_fwd(q, k, v, W, gs.cuda(), gr.cuda(), softmax_scale=scale, kernel_path="general")
+    assert float((o.float() - o_gen.float()).abs().max()) <= 4e-2 * gmax
+
+
 def test_fast_bwd_is_deterministic():
     x = synth.make_random_layer(1, 512, 4, 2, 128, "bf16", 6, with_dO=True)
     q, k, v, dO = x["q"].cuda(), x["k"].cuda(), x["v"].cuda(), x["dO"].cuda()

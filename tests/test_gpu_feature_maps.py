@@ -92,17 +92,18 @@ def test_layer_f32(fm, B, T, Hq, Hkv, D, W, chunk):
 @pytest.mark.parametrize("fm", MAPS)
 @pytest.mark.parametrize("B,T,Hq,Hkv,D,W", [(1, 256, 4, 2, 128, 64), (2, 333, 2, 1, 64, 20), (1, 1100, 2, 1, 128, 100)])
 def test_layer_bf16(fm, B, T, Hq, Hkv, D, W):
-    # head size 128 in whole tiles (or long enough for padded copies): the ReLU map runs on the matrix-core kernels
-    layer_case(fm, B, T, Hq, Hkv, D, W, "bf16", 950 + T, mfma=(fm == "relu" and D == 128))
+    # head size 128 in whole tiles (or long enough for padded copies): both maps run on the matrix-core kernels
+    layer_case(fm, B, T, Hq, Hkv, D, W, "bf16", 950 + T, mfma=(D == 128))
 
 
 @pytest.mark.parametrize("B,T,Hq,Hkv,W", [
     (1, 128, 2, 1, 64), (2, 512, 4, 2, 128), (1, 1024, 3, 1, 192), (1, 768, 2, 1, 512), (1, 384, 2, 2, 384),
     (1, 1024, 2, 1, 513), (1, 384, 3, 1, 100), (2, 256, 2, 2, 10), (1, 896, 2, 1, 320), (1, 256, 2, 1, 250),
 ])
-def test_relu_map_on_the_matrix_core_kernels(B, T, Hq, Hkv, W):
+@pytest.mark.parametrize("fm", MAPS)
+def test_variant_maps_on_the_matrix_core_kernels(fm, B, T, Hq, Hkv, W):
     """Both state alignments, windows that are no tile multiples, a half-full last key tile, causal degenerate case."""
-    layer_case("relu", B, T, Hq, Hkv, 128, W, "bf16", 1900 + T + W, mfma=True)
+    layer_case(fm, B, T, Hq, Hkv, 128, W, "bf16", 1900 + T + W, mfma=True)
 
 
 def test_kernel_selection_and_maps_differ():
@@ -111,8 +112,7 @@ def test_kernel_selection_and_maps_differ():
     outs = {}
     for fm in ("softmax",) + MAPS:
         outs[fm], names = kernels_of(lambda: rb.rattn_fwd(q, k, v, 64, softmax_scale=0.09, feature_map=fm))
-        # the identity map stays on the general kernels (its backward needs the fp32 x^r kept there)
-        assert ("fwd_fused_kernel" in names) == (fm != "identity") and ("gen_fwd_kernel" in names) == (fm == "identity")
+        assert "fwd_fused_kernel" in names and "gen_fwd_kernel" not in names   # all three maps on the matrix cores
     # rows inside the first window have no linear branch: the map cannot matter there; later rows differ
     assert torch.equal(outs["relu"][:, :64], outs["softmax"][:, :64])
     assert float((outs["relu"][:, :64].float() - outs["identity"][:, :64].float()).abs().max()) <= 2e-2

@@ -52,7 +52,9 @@ LAYER_CASES = [
     (1, 384, 3, 1, 128, 100, "bf16", "auto"),      # gap > 0, states at the 64 alignment
     (1, 256, 2, 1, 128, 250, "bf16", "auto"),      # window rounds up to T
     (1, 384, 2, 2, 128, 1000, "bf16", "auto"),     # causal: no linear branch, no states
-    (2, 200, 4, 2, 64, 32, "bf16", "auto"),        # general kernels (D = 64)
+    (2, 200, 4, 2, 64, 32, "bf16", "auto"),        # general kernels (D = 64, ragged and short)
+    (1, 256, 4, 2, 64, 100, "bf16", "auto"),       # head size 64 on the matrix-core kernels: widened copies, gains too
+    (1, 1030, 2, 1, 64, 200, "bf16", "auto"),      # head size 64 and a ragged length together
     (1, 300, 2, 1, 128, 77, "f32", "auto"),        # general kernels, fp32
     (1, 512, 4, 2, 128, 128, "bf16", "general"),   # general kernels forced on a matrix-core shape
 ]
