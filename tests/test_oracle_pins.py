@@ -321,6 +321,30 @@ def test_text_closed_forms():
     assert orc.state_equivalent_window(128, 128) == 64
 
 
+def test_state_equivalent_window_counts_cache_elements():
+    """Sec. 2.2: the state is as large as the key/value cache of that many tokens.  Pinned by counting array elements:
+    the first window length whose cache of keys and values (one row of d each per token) holds as many numbers as
+    the d' x d state."""
+    for d_feat, d in ((128, 128), (256, 128), (64, 64), (128, 64)):
+        state_numbers = np.zeros((d_feat, d)).size
+        n = next(n for n in range(1, 10000) if np.zeros((n, 2, d)).size >= state_numbers)
+        assert orc.state_equivalent_window(d_feat, d) == n, (d_feat, d)
+
+
+def test_decode_step_time_hand_evaluated_cases():
+    """Sec. 4.4 step-time model, two cases worked by hand (cache term + the larger of the compute and weight terms).
+    Hardware: 2e12 B/s, 1e15 FLOP/s; model: 3e9 parameters in 6e9 bytes; cache 1e9 bytes per sequence.
+      batch 4096: cache 4096e9/2e12 = 2.048 s; compute 2*4096*3e9/1e15 = 0.024576 s > weights 6e9/2e12 = 0.003 s
+                  -> 2.072576 s (compute-bound)
+      batch 1:    cache 1e9/2e12 = 0.0005 s; compute 2*3e9/1e15 = 0.000006 s < weights 0.003 s -> 0.0035 s (weight-bound)"""
+    assert abs(orc.decode_step_time(4096, 1e9, 3e9, 6e9, 2e12, 1e15) - 2.072576) < 1e-12
+    assert abs(orc.decode_step_time(1, 1e9, 3e9, 6e9, 2e12, 1e15) - 0.0035) < 1e-15
+    # a faster matrix unit moves only the compute-bound case; a wider memory system moves both
+    assert abs(orc.decode_step_time(4096, 1e9, 3e9, 6e9, 2e12, 2e15) - (2.048 + 0.012288)) < 1e-12
+    assert abs(orc.decode_step_time(1, 1e9, 3e9, 6e9, 2e12, 2e15) - 0.0035) < 1e-15
+    assert abs(orc.decode_step_time(1, 1e9, 3e9, 6e9, 4e12, 1e15) - 0.00175) < 1e-15
+
+
 # ------------------------------------------------------------------------------ prefill -> decode hand-over
 @pytest.mark.parametrize("T,W", [(3, 8), (8, 8), (9, 8), (21, 4), (16, 1)])
 def test_prefill_export_equals_decode_chain(T, W):
