@@ -408,20 +408,22 @@ def main():
         torch.cuda.empty_cache()
         other = {}
 
-        def run_layer(c, with_bwd, gains=False, feature_map="softmax"):
+        def run_layer(c, with_bwd, gains=False, feature_map="softmax", chunk=0, state_policy="keep"):
             t = [x_.cuda() for x_ in synth.make_layer_inputs(c, with_dO=with_bwd)]
             gs_ = (1.0 + 0.1 * torch.randn(c.Hq, c.D, device="cuda")) if gains else None
             gr_ = (1.0 + 0.1 * torch.randn(c.Hq, c.D, device="cuda")) if gains else None
-            pp = rb.make_params(t[0], t[1], c.W, 0, c.scale, 1e-6, with_bwd, feature_map)
+            pp = rb.make_params(t[0], t[1], c.W, chunk, c.scale, 1e-6, with_bwd, feature_map, "auto", state_policy)
             fb, bb, sb = rb.rattn_workspace_bytes(pp)
             w_ = torch.empty(max(fb, bb, 16), dtype=torch.uint8, device="cuda")
             sv_ = torch.empty(max(sb, 16), dtype=torch.uint8, device="cuda") if with_bwd else None
             o_ = torch.empty_like(t[0])
             g_ = (torch.empty_like(t[0]), torch.empty_like(t[1]), torch.empty_like(t[2])) if with_bwd else None
             f_ = lambda: rb.rattn_fwd(t[0], t[1], t[2], c.W, gs_, gr_, softmax_scale=c.scale, save_for_bwd=with_bwd,
-                                      out=o_, saved=sv_, workspace=w_, feature_map=feature_map)
+                                      out=o_, saved=sv_, workspace=w_, feature_map=feature_map, chunk=chunk,
+                                      state_policy=state_policy)
             b_ = lambda: rb.rattn_bwd(t[0], t[1], t[2], sv_, t[3], c.W, gs_, gr_, softmax_scale=c.scale,
-                                      want_dgamma=gains, workspace=w_, out=g_, feature_map=feature_map)
+                                      want_dgamma=gains, workspace=w_, out=g_, feature_map=feature_map, chunk=chunk,
+                                      state_policy=state_policy)
             for _ in range(5):
                 f_()
                 if with_bwd:
@@ -434,6 +436,7 @@ def main():
                 r["bwd_tflops"] = fl_["bwd"] / (r["bwd_ms"] * 1e-3) / 1e12
                 r["fwd_bwd_tflops"] = (fl_["fwd"] + fl_["bwd"]) / ((r["fwd_ms"] + r["bwd_ms"]) * 1e-3) / 1e12
             r["tokens_per_s"] = c.B * c.T / ((r["fwd_ms"] + r.get("bwd_ms", 0.0)) * 1e-3)
+            r["saved_MB"] = sb / 1e6
             return r
 
         other["layer12b_t8192_w512"] = run_layer(synth.CONFIGS["layer12b_t8192_w512"], True)
@@ -454,6 +457,23 @@ def main():
         for W_ in (128, 512, 1024, 4096, 8192):
             c_ = synth.sweep_config(W_)
             other[c_.name] = run_layer(c_, True)
+        # The paper's search over what is stored of the chunk states and over the chunk size (Sec. 3.2, Fig. 3: best
+        # setting ~15 % faster than storing every state at C = 256), on the matrix-core kernels: chunk states kept in
+        # `saved` for backward or rebuilt there, chunk products of 128 or 64 keys; both benchmark layers, fwd + bwd
+        search = {}
+        for c_ in (cfg, synth.CONFIGS["layer12b_t8192_w512"]):
+            rows = {}
+            for pol in ("keep", "rebuild"):
+                for ck in (128, 64):
+                    r_ = run_layer(c_, True, chunk=ck, state_policy=pol)
+                    rows[f"{pol}_C{ck}"] = {"fwd_ms": r_["fwd_ms"], "bwd_ms": r_["bwd_ms"],
+                                            "step_ms": r_["fwd_ms"] + r_["bwd_ms"], "saved_MB": r_["saved_MB"]}
+            best = min(rows, key=lambda n_: rows[n_]["step_ms"])
+            worst = max(rows, key=lambda n_: rows[n_]["step_ms"])
+            search[c_.name] = {"variants": rows, "best": best, "default": "keep_C128",
+                               "best_over_worst_gain": rows[worst]["step_ms"] / rows[best]["step_ms"] - 1.0,
+                               "saved_MB_not_kept": rows["keep_C128"]["saved_MB"] - rows["rebuild_C128"]["saved_MB"]}
+        other["state_pipeline_search"] = search
         # chunk-size enumeration of the linear branch (Sec. 3.2's search over C) on the general kernels, which take the
         # chunk as a parameter (the matrix-core path fixes one state per 128 keys)
         xg = synth.make_random_layer(1, 4096, 8, 2, 64, "bf16", 11)

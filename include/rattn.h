@@ -61,8 +61,9 @@ typedef enum { RATTN_PHI_SOFTMAX = 0, RATTN_PHI_RELU = 1, RATTN_PHI_IDENTITY = 2
 typedef struct {
   int32_t B, T, Hq, Hkv, D;
   int32_t window;        /* W >= 1 (see conventions)                                                   */
-  int32_t chunk;         /* linear-branch chunk hint for Eqs. 2-3 (0 = library chooses); the result
-                            does not depend on it beyond rounding                                      */
+  int32_t chunk;         /* linear-branch chunk size C of Eqs. 2-3 (0 = library chooses); the result does not
+                            depend on it beyond rounding.  General kernels: any value; matrix-core kernels:
+                            64 or 128 keys per chunk product (other values mean 128)                   */
   int32_t dtype;         /* rattn_dtype                                                                */
   float softmax_scale;   /* multiplies q.k in the softmax branch only (the paper's formula is 1.0)     */
   float rms_eps;         /* > 0                                                                        */
@@ -72,9 +73,20 @@ typedef struct {
                             shape allows); RATTN_PATH_GENERAL forces the general kernels (a second,
                             independent implementation used by tests).  It changes what `saved` holds:
                             rattn_fwd and rattn_bwd of one step must be given the same value           */
+  int32_t state_policy;  /* rattn_state_policy: what rattn_fwd keeps of the linear-branch chunk states for
+                            rattn_bwd (matrix-core kernels; ignored by the general kernels, which always rebuild).
+                            Same value in both calls: it changes what `saved` holds                           */
 } rattn_params;
 
 typedef enum { RATTN_PATH_AUTO = 0, RATTN_PATH_GENERAL = 1 } rattn_kernel_path;
+
+/* The paper's kernel stores chunk states only every m-th chunk and recomputes the others to save accelerator memory,
+ * "storing more leads to faster backward passes ... at a higher memory cost" (Sec. 3.2, Fig. 3); it searches over m and
+ * the chunk size C.  Here the two ends of that trade are selectable: KEEP stores every chunk state (one per 128 keys,
+ * bf16) in `saved` so that backward reads them; REBUILD stores none and backward builds them again from k and v (any
+ * subset in between would cost the same rebuild).  The chunk size of the state-building kernels is the `chunk`
+ * parameter: 64 selects 64-key chunk products (two per stored state), anything else 128-key products. */
+typedef enum { RATTN_STATES_KEEP = 0, RATTN_STATES_REBUILD = 1 } rattn_state_policy;
 
 /* Sizes in bytes of the scratch `workspace` rattn_fwd / rattn_bwd need and of the opaque
  * `saved` buffer rattn_fwd fills for rattn_bwd.  Any of the three out pointers (HOST) may

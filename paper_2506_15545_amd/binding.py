@@ -16,6 +16,8 @@ RATTN_F32, RATTN_BF16 = 0, 1
 FEATURE_MAPS = {"softmax": 0, "relu": 1, "identity": 2}
 # rattn_kernel_path: "auto" lets the library choose, "general" forces the general kernels (tests)
 KERNEL_PATHS = {"auto": 0, "general": 1}
+# rattn_state_policy: keep the chunk states in `saved` for backward, or rebuild them there (Sec. 3.2 trade-off)
+STATE_POLICIES = {"keep": 0, "rebuild": 1}
 _DTYPES = {torch.float32: RATTN_F32, torch.bfloat16: RATTN_BF16}
 
 EXPORTS = ["rattn_workspace_bytes", "rattn_fwd", "rattn_fwd_static", "rattn_bwd", "rattn_decode_step",
@@ -30,7 +32,8 @@ class RattnParams(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("T", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
                 ("D", ctypes.c_int32), ("window", ctypes.c_int32), ("chunk", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("rms_eps", ctypes.c_float),
-                ("save_for_bwd", ctypes.c_int32), ("feature_map", ctypes.c_int32), ("kernel_path", ctypes.c_int32)]
+                ("save_for_bwd", ctypes.c_int32), ("feature_map", ctypes.c_int32), ("kernel_path", ctypes.c_int32),
+                ("state_policy", ctypes.c_int32)]
 
 
 class RattnDecodeParams(ctypes.Structure):
@@ -111,10 +114,11 @@ def _stream():
 
 
 def make_params(q, k, window, chunk=0, softmax_scale=1.0, rms_eps=1e-6, save_for_bwd=False, feature_map="softmax",
-                kernel_path="auto"):
+                kernel_path="auto", state_policy="keep"):
     B, T, Hq, D = q.shape
     return RattnParams(B, T, Hq, k.shape[2], D, window, chunk, _DTYPES[q.dtype], softmax_scale, rms_eps,
-                       1 if save_for_bwd else 0, FEATURE_MAPS[feature_map], KERNEL_PATHS[kernel_path])
+                       1 if save_for_bwd else 0, FEATURE_MAPS[feature_map], KERNEL_PATHS[kernel_path],
+                       STATE_POLICIES[state_policy])
 
 
 def rattn_workspace_bytes(params):
@@ -148,12 +152,13 @@ def _bytes(n, dev):
 
 
 def rattn_fwd(q, k, v, window, gamma_swa=None, gamma_rla=None, chunk=0, softmax_scale=1.0, rms_eps=1e-6,
-              save_for_bwd=False, out=None, saved=None, workspace=None, feature_map="softmax", kernel_path="auto"):
+              save_for_bwd=False, out=None, saved=None, workspace=None, feature_map="softmax", kernel_path="auto",
+              state_policy="keep"):
     """o = RMS(SWA(q,k,v)) + RMS(RLA(q,k,v)); returns o, or (o, saved) when save_for_bwd.
 
     out / saved / workspace may be passed in to reuse buffers (uint8 tensors for the latter two)."""
     _check_layer(q, k, v)
-    p = make_params(q, k, window, chunk, softmax_scale, rms_eps, save_for_bwd, feature_map, kernel_path)
+    p = make_params(q, k, window, chunk, softmax_scale, rms_eps, save_for_bwd, feature_map, kernel_path, state_policy)
     fwd_b, _, saved_b = rattn_workspace_bytes(p)
     dev = q.device
     o = torch.empty_like(q) if out is None else out
@@ -190,12 +195,13 @@ def rattn_fwd_static(q, k, v, window, out, gamma_swa=None, gamma_rla=None, chunk
 
 
 def rattn_bwd(q, k, v, saved, dO, window, gamma_swa=None, gamma_rla=None, chunk=0, softmax_scale=1.0,
-              rms_eps=1e-6, want_dgamma=True, workspace=None, out=None, feature_map="softmax", kernel_path="auto"):
+              rms_eps=1e-6, want_dgamma=True, workspace=None, out=None, feature_map="softmax", kernel_path="auto",
+              state_policy="keep"):
     """(dq, dk, dv, dgamma_swa, dgamma_rla) for upstream gradient dO; `saved` from rattn_fwd (same kernel_path)."""
     _check_layer(q, k, v)
     if dO.shape != q.shape or dO.dtype != q.dtype or not dO.is_contiguous():
         raise ValueError("dO must match q")
-    p = make_params(q, k, window, chunk, softmax_scale, rms_eps, True, feature_map, kernel_path)
+    p = make_params(q, k, window, chunk, softmax_scale, rms_eps, True, feature_map, kernel_path, state_policy)
     _, bwd_b, saved_b = rattn_workspace_bytes(p)
     if saved is None or saved.numel() < saved_b:
         raise ValueError("saved buffer missing or too small")
@@ -251,7 +257,7 @@ def rattn_prefill_export(k, v, window, k_ring=None, v_ring=None, state=None, fea
             raise ValueError(f"{name} must be a contiguous device tensor")
     if v.shape != k.shape or v.dtype != k.dtype or k.dtype not in _DTYPES:
         raise ValueError("k and v must share shape and dtype float32 or bfloat16")
-    p = RattnParams(B, T, Hkv, Hkv, D, window, 0, _DTYPES[k.dtype], 1.0, 1e-6, 0, FEATURE_MAPS[feature_map])
+    p = RattnParams(B, T, Hkv, Hkv, D, window, 0, _DTYPES[k.dtype], 1.0, 1e-6, 0, FEATURE_MAPS[feature_map], 0, 0)
     if k_ring is None:
         k_ring = torch.zeros(B, Hkv, window, D, dtype=k.dtype, device=k.device)
     if v_ring is None:

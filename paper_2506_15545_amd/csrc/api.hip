@@ -63,7 +63,7 @@ struct Layout {
   size_t esize;
   // saved
   size_t sv_xs, sv_xr, sv_lse, sv_rs, sv_rr, sv_states, sv_xr_lo, saved_bytes;
-  bool has_xr_lo;
+  bool has_xr_lo, keep_states;
   // generic forward / backward workspace
   size_t gf_states, gen_fwd_bytes;
   size_t gb_states, gb_rstates, gb_dxs, gb_dxr, gb_delta, gb_dgpart, gen_bwd_bytes;
@@ -91,6 +91,8 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
     return fail(RATTN_ERR_UNSUPPORTED, "unknown feature_map %d", p->feature_map);
   if (p->kernel_path != RATTN_PATH_AUTO && p->kernel_path != RATTN_PATH_GENERAL)
     return fail(RATTN_ERR_UNSUPPORTED, "unknown kernel_path %d", p->kernel_path);
+  if (p->state_policy != RATTN_STATES_KEEP && p->state_policy != RATTN_STATES_REBUILD)
+    return fail(RATTN_ERR_UNSUPPORTED, "unknown state_policy %d", p->state_policy);
   if (!(p->rms_eps > 0.f)) return fail(RATTN_ERR_INVALID_ARG, "rms_eps must be > 0");
   if (!(p->softmax_scale == p->softmax_scale) || p->softmax_scale == 0.f)
     return fail(RATTN_ERR_INVALID_ARG, "softmax_scale must be a non-zero number");
@@ -132,7 +134,8 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
   L->sv_rs = off; off += align_up(nrow_f * 4);
   L->sv_rr = off; off += align_up(nrow_f * 4);
   L->sv_states = off;
-  if (L->fast_fwd) off += align_up(rattn::fast_fwd_plan(dmf).state_bytes);
+  L->keep_states = L->fast_fwd && p->state_policy == RATTN_STATES_KEEP;
+  if (L->keep_states) off += align_up(rattn::fast_fwd_plan(dmf).state_bytes);
   L->has_xr_lo = L->fast_fwd && dm.phi == rattn::PHI_IDENTITY;
   L->sv_xr_lo = off;
   if (L->has_xr_lo) off += align_up(nq_f * L->esize);
@@ -206,7 +209,7 @@ rattn::SavedPtrs saved_views(const Layout& L, void* saved) {
     char* s = (char*)saved;
     sv.xs = s + L.sv_xs; sv.xr = s + L.sv_xr;
     sv.lse = (float*)(s + L.sv_lse); sv.rs = (float*)(s + L.sv_rs); sv.rr = (float*)(s + L.sv_rr);
-    if (L.fast_fwd) sv.states = s + L.sv_states;
+    if (L.keep_states) sv.states = s + L.sv_states;
     if (L.has_xr_lo) sv.xr_lo = s + L.sv_xr_lo;
   }
   return sv;

@@ -826,7 +826,9 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
   a.dxs = (const uint16_t*)ws.dxs; a.dxr = (const uint16_t*)ws.dxr;
   a.lse = sv.lse; a.delta = ws.delta;
-  a.states = (const uint16_t*)sv.states; a.rstates = (const uint16_t*)ws.rstates;
+  // chunk states of the forward pass: kept in `saved`, or (state policy "rebuild") built again here from k and v
+  if (!sv.states && pl.fwd.nstf > 0) rla_forward_states(dm, pl.fwd, k, v, ws.U, ws.states, st);
+  a.states = (const uint16_t*)(sv.states ? sv.states : ws.states); a.rstates = (const uint16_t*)ws.rstates;
   a.dq = (uint16_t*)dq; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv;
   a.B = dm.B; a.T = dm.T; a.Hq = dm.Hq; a.Hkv = dm.Hkv; a.G = dm.G; a.W = pl.fwd.W; a.gap = pl.fwd.gap;
   a.nstf = pl.fwd.nstf; a.nk = pl.nk; a.ntile = dm.T / 128;
@@ -858,7 +860,7 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
     ProfScope ps("dgamma_reduce_kernel", st);
     dgamma_reduce_kernel<<<dim3(HD / 32, 2), 256, 0, st>>>(ws.dgpart, dgs, dgr, pl.RB, HD);
   }
-  rla_reverse_states(dm, pl.fwd.W, pl.nk, q, ws.dxr, ws.U, ws.rstates, st);
+  rla_reverse_states(dm, pl, q, ws.dxr, ws.U, ws.rstates, st);
   // the dk/dv kernel needs more LDS than a launch gets by default: raised once per instantiation
   static const bool lds_attr = [] {
     const void* fns[] = {reinterpret_cast<const void*>(bwd_dkv_kernel<FM_SOFTMAX>),

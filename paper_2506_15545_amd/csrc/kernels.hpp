@@ -76,6 +76,7 @@ struct FastFwdPlan {
   int gap;      // that minus the true window (0..63): masks and the reach of the intra-chunk part
   int base;     // key position of state 0 (0 or 64); state i sits at base + 128*i
   int nstf;     // number of states per (batch, kv head) = query tiles that have a linear branch
+  int ckeys;    // keys per chunk-local product (64 or 128): the chunk size C of Eqs. 2-3 on this path
   int nchunks;  // chunk-local products needed to build them
   size_t u_bytes, state_bytes;
 };
@@ -92,15 +93,11 @@ void fast_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
 // linear-branch chunk states for the MFMA paths (bf16 [d][f] per state, fp32 scratch U per chunk)
 void rla_forward_states(const LayerDims& dm, const FastFwdPlan& pl, const void* k, const void* v, float* U,
                         void* states, hipStream_t st, const float* state0 = nullptr);
-// reverse-time states R_i = sum over t' >= 128(i+1) and over the group's heads of phi(q_{t'+W})^T dxr_{t'+W},
-// i in [0, nk), nk = ceil((T-W)/128); stored transposed [d][f] bf16.  U needs (nk-1) chunks.
-void rla_reverse_states(const LayerDims& dm, int W, int nk, const void* q, const void* dxr, float* U,
-                        void* rstates, hipStream_t st);
-
 // MFMA backward path (same shape class as the MFMA forward)
 struct FastBwdPlan {
   FastFwdPlan fwd;
   int nk;  // key tiles that have a linear branch = number of reverse states
+  int nrchunks;  // reverse-time chunk-local products
   int RB;  // row blocks of the prep kernel (dgamma partials)
   size_t u_bytes, rstate_bytes;
 };
@@ -112,6 +109,10 @@ struct FastBwdWs {
   float* dgpart;         // [2,RB,Hq,128]
 };
 FastBwdPlan fast_bwd_plan(const LayerDims& dm);
+// reverse-time states R_i = sum over t' >= 128(i+1) and over the group's heads of phi(q_{t'+W})^T dxr_{t'+W},
+// i in [0, nk), nk = ceil((T-W)/128); stored transposed [d][f] bf16.  U needs (nk-1) chunks.
+void rla_reverse_states(const LayerDims& dm, const FastBwdPlan& pl, const void* q, const void* dxr, float* U,
+                        void* rstates, hipStream_t st);
 void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, const float* gs, const float* gr,
               const SavedPtrs& sv, const void* dO, void* dq, void* dk, void* dv, float* dgs, float* dgr,
               const FastBwdWs& ws, hipStream_t st);

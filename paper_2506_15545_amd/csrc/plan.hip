@@ -25,7 +25,10 @@ FastFwdPlan fast_fwd_plan(const LayerDims& dm) {
   p.base = p.W % 128;
   p.nstf = dm.T / 128 - (p.W + 127) / 128;
   if (p.nstf < 0) p.nstf = 0;
-  p.nchunks = p.nstf > 0 ? (p.nstf - 1) + (p.base > 0 ? 1 : 0) : 0;
+  // chunk-local products of `ckeys` keys each (the `chunk` parameter: 64, else 128); with 128 and states at the 64
+  // alignment the first product covers the 64 keys in front of state 0
+  p.ckeys = dm.C == 64 ? 64 : 128;
+  p.nchunks = p.nstf > 0 ? (p.nstf - 1) * (128 / p.ckeys) + (p.base > 0 ? 1 : 0) : 0;
   p.u_bytes = (size_t)dm.B * dm.Hkv * p.nchunks * 16384 * 4;
   p.state_bytes = (size_t)dm.B * dm.Hkv * p.nstf * 16384 * 2;
   return p;
@@ -36,7 +39,9 @@ FastBwdPlan fast_bwd_plan(const LayerDims& dm) {
   p.fwd = fast_fwd_plan(dm);
   const int Tp = dm.T - p.fwd.W;
   p.nk = Tp > 0 ? (Tp + 127) / 128 : 0;
-  const int nch = p.fwd.nchunks > p.nk - 1 ? p.fwd.nchunks : p.nk - 1;
+  // reverse-time chunk products: query rows t' in [128, Tp) in pieces of ckeys
+  p.nrchunks = Tp > 128 ? (Tp - 128 + p.fwd.ckeys - 1) / p.fwd.ckeys : 0;
+  const int nch = p.fwd.nchunks > p.nrchunks ? p.fwd.nchunks : p.nrchunks;
   p.u_bytes = (size_t)dm.B * dm.Hkv * (nch > 0 ? nch : 0) * 16384 * 4;
   p.rstate_bytes = (size_t)dm.B * dm.Hkv * p.nk * 16384 * 2;
   p.RB = 4 * (dm.T / 128) * dm.B;  // one gain-gradient partial per wave of the dq kernel

@@ -16,7 +16,8 @@ struct ChunkArgs {
   float* U;            // [B,Hkv,nchunks,128,128] fp32, U^T = B^T phi(A)
   int T, H, GA;        // heads in a/b, heads summed per kv head
   int tok_off;         // token index = t' + tok_off
-  int first_lo, first_n, rest_lo, tok_end;  // chunk 0 = [first_lo, +first_n); chunk c>0 starts at rest_lo+128(c-1)
+  int first_lo, first_n, rest_lo, ckeys, tok_end;  // chunk 0 = [first_lo, +first_n); chunk c > 0 = ckeys tokens from
+                                                   // rest_lo + ckeys (c-1); every chunk is clipped at tok_end
 };
 
 // grid (nchunks, Hkv, B), 256 threads.  Wave w owns rows d in [32w, 32w+32) of U^T.
@@ -28,8 +29,8 @@ __global__ __launch_bounds__(256) void rla_chunk_kernel(ChunkArgs p) {
   const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z, nchunks = gridDim.x, Hkv = gridDim.y;
   const int lane = lane_id(), w = wave_id();
   const int r32 = lane & 31, h = lane >> 5;
-  const int lo = c == 0 ? p.first_lo : p.rest_lo + 128 * (c - 1);
-  const int ntok = min(c == 0 ? p.first_n : 128, p.tok_end - lo);  // 64 or 128
+  const int lo = c == 0 ? p.first_lo : p.rest_lo + p.ckeys * (c - 1);
+  const int ntok = min(c == 0 ? p.first_n : p.ckeys, p.tok_end - lo);  // 64 or 128
   const size_t rstride = (size_t)p.H * 128;
   f32x16_t acc[4] = {{0}, {0}, {0}, {0}};
   for (int ga = 0; ga < p.GA; ++ga) {
@@ -62,14 +63,16 @@ __global__ __launch_bounds__(256) void rla_chunk_kernel(ChunkArgs p) {
     }
 }
 
-// Exclusive scan over chunks, every state element independently, fp32 accumulation, bf16 output.
-//   forward: state[0] = (head ? U[0] : 0); state[i+1] = state[i] + U[c++]
-//   reverse: state[n-1] = 0; state[i] = state[i+1] + U[i]
+// Exclusive scan over chunks, every state element independently, fp32 accumulation, bf16 output.  A state spans
+// `per` chunk products (1, or 2 when the products cover 64 keys each).
+//   forward: state[0] = sum of the `head` products in front of it; state[i+1] = state[i] + the next `per` products
+//   reverse: state[n-1] = 0; state[i] = state[i+1] + products per*i .. per*i + per - 1 (those that exist)
 // grid (16, Hkv, B), 256 threads, 4 elements per thread.
 // init (forward only, may be NULL): a state that precedes chunk 0, fp32 [B,Hkv,f,d] (not transposed).
 template <bool REV>
 __global__ __launch_bounds__(256) void rla_scan_kernel(const float* __restrict__ U, uint16_t* __restrict__ states,
-                                                       int nchunks, int nst, int head, const float* __restrict__ init) {
+                                                       int nchunks, int nst, int head, int per,
+                                                       const float* __restrict__ init) {
   const int g = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
   const int e4 = (blockIdx.x * 256 + threadIdx.x) * 4;
   const float* Ub = U + (size_t)(b * Hkv + g) * nchunks * 16384 + e4;
@@ -90,15 +93,18 @@ __global__ __launch_bounds__(256) void rla_scan_kernel(const float* __restrict__
   };
   if (!REV) {
     int c = 0;
-    if (head) { add(0); c = 1; }
+    for (; c < head; ++c) add(c);
     for (int i = 0; i < nst; ++i) {
       put(i);
-      if (i + 1 < nst) add(c++);
+      if (i + 1 < nst)
+        for (int r = 0; r < per; ++r) add(c++);
     }
   } else {
     for (int i = nst - 1; i >= 0; --i) {
       put(i);
-      if (i > 0) add(i - 1);
+      if (i > 0)
+        for (int r = per - 1; r >= 0; --r)
+          if (per * (i - 1) + r < nchunks) add(per * (i - 1) + r);
     }
   }
 }
@@ -117,33 +123,37 @@ void launch_chunk_kernel(int fm, dim3 grid, const ChunkArgs& p, hipStream_t st) 
 void rla_forward_states(const LayerDims& dm, const FastFwdPlan& pl, const void* k, const void* v, float* U,
                         void* states, hipStream_t st, const float* state0) {
   if (pl.nstf <= 0) return;
+  const int head = pl.base > 0 ? 1 : 0;  // products in front of state 0: the 64 keys before it when it sits at key 64
   if (pl.nchunks > 0) {
     ChunkArgs p;
     p.a = (const uint16_t*)k; p.b = (const uint16_t*)v; p.U = U;
     p.T = dm.T; p.H = dm.Hkv; p.GA = 1; p.tok_off = 0;
-    p.first_lo = 0; p.first_n = pl.base > 0 ? 64 : 128; p.rest_lo = pl.base > 0 ? 64 : 128; p.tok_end = 1 << 30;
+    p.ckeys = pl.ckeys;
+    p.first_lo = 0; p.first_n = head ? 64 : pl.ckeys; p.rest_lo = p.first_n; p.tok_end = 1 << 30;
     ProfScope ps("rla_chunk_kernel", st);
     launch_chunk_kernel(feature_map_variant(dm), dim3(pl.nchunks, dm.Hkv, dm.B), p, st);
   }
   ProfScope ps("rla_scan_kernel", st);
-  rla_scan_kernel<false><<<dim3(16, dm.Hkv, dm.B), 256, 0, st>>>(U, (uint16_t*)states, pl.nchunks, pl.nstf,
-                                                                  pl.base > 0 ? 1 : 0, state0);
+  rla_scan_kernel<false><<<dim3(16, dm.Hkv, dm.B), 256, 0, st>>>(U, (uint16_t*)states, pl.nchunks, pl.nstf, head,
+                                                                  128 / pl.ckeys, state0);
 }
 
-void rla_reverse_states(const LayerDims& dm, int W, int nk, const void* q, const void* dxr, float* U, void* rstates,
-                        hipStream_t st) {
-  if (nk <= 0) return;
-  const int Tp = dm.T - W;
-  if (nk > 1) {
+void rla_reverse_states(const LayerDims& dm, const FastBwdPlan& pl, const void* q, const void* dxr, float* U,
+                        void* rstates, hipStream_t st) {
+  if (pl.nk <= 0) return;
+  const int W = pl.fwd.W, Tp = dm.T - W, ck = pl.fwd.ckeys;
+  if (pl.nrchunks > 0) {
     ChunkArgs p;
     p.a = (const uint16_t*)q; p.b = (const uint16_t*)dxr; p.U = U;
     p.T = dm.T; p.H = dm.Hq; p.GA = dm.G; p.tok_off = W;
-    p.first_lo = 128; p.first_n = 128; p.rest_lo = 256; p.tok_end = Tp;
+    p.ckeys = ck;
+    p.first_lo = 128; p.first_n = ck; p.rest_lo = 128 + ck; p.tok_end = Tp;
     ProfScope ps("rla_chunk_kernel(rev)", st);
-    launch_chunk_kernel(feature_map_variant(dm), dim3(nk - 1, dm.Hkv, dm.B), p, st);
+    launch_chunk_kernel(feature_map_variant(dm), dim3(pl.nrchunks, dm.Hkv, dm.B), p, st);
   }
   ProfScope ps("rla_scan_kernel(rev)", st);
-  rla_scan_kernel<true><<<dim3(16, dm.Hkv, dm.B), 256, 0, st>>>(U, (uint16_t*)rstates, nk - 1, nk, 0, nullptr);
+  rla_scan_kernel<true><<<dim3(16, dm.Hkv, dm.B), 256, 0, st>>>(U, (uint16_t*)rstates, pl.nrchunks, pl.nk, 0, 128 / ck,
+                                                                 nullptr);
 }
 
 }  // namespace rattn

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 
 def params(**kw):
     d = dict(B=2, T=300, Hq=4, Hkv=2, D=64, window=32, chunk=0, dtype=rb.RATTN_F32, softmax_scale=1.0,
-             rms_eps=1e-6, save_for_bwd=0, feature_map=0, kernel_path=0)
+             rms_eps=1e-6, save_for_bwd=0, feature_map=0, kernel_path=0, state_policy=0)
     d.update(kw)
     return rb.RattnParams(**d)
 
@@ -48,7 +48,7 @@ def test_workspace_sizes_scale_with_shape():
 @pytest.mark.parametrize("kw,code", [
     (dict(B=0), -1), (dict(T=0), -1), (dict(Hq=3, Hkv=2), -1), (dict(window=0), -1), (dict(chunk=-1), -1),
     (dict(rms_eps=0.0), -1), (dict(softmax_scale=0.0), -1), (dict(D=96), -2), (dict(dtype=7), -2),
-    (dict(feature_map=3), -2), (dict(feature_map=-1), -2), (dict(kernel_path=2), -2),
+    (dict(feature_map=3), -2), (dict(feature_map=-1), -2), (dict(kernel_path=2), -2), (dict(state_policy=2), -2),
     (dict(B=60000, T=10000), -2),      # more rows than 32-bit row indexing covers
     (dict(B=70000), -2), (dict(Hq=70000, Hkv=70000), -2),   # grid dimensions
 ])

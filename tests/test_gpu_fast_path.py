@@ -232,6 +232,43 @@ def test_head_size_64_runs_on_the_matrix_cores(B, T, Hq, Hkv, W):
     assert float((o.float() - o_gen.float()).abs().max()) <= 4e-2 * gmax
 
 
+@pytest.mark.parametrize("policy,chunk", [("keep", 64), ("rebuild", 0), ("rebuild", 64)])
+@pytest.mark.parametrize("B,T,Hq,Hkv,W", [(1, 1024, 3, 1, 192), (2, 512, 4, 2, 128), (1, 1024, 2, 1, 513), (1, 896, 2, 1, 320)])
+def test_state_policy_and_chunk_size_variants(policy, chunk, B, T, Hq, Hkv, W):
+    """The two tunables of the linear-branch state pipeline (Sec. 3.2: which chunk states are stored, chunk size C):
+    states kept in `saved` or rebuilt in backward, chunk products of 64 or 128 keys.  Every variant against the oracle
+    to the same bars as the default; rebuilding changes no bit; `saved` shrinks by the states when they are not kept."""
+    D = 128
+    x = synth.make_random_layer(B, T, Hq, Hkv, D, "bf16", 3300 + T + W, with_dO=True)
+    scale = 1.0 / math.sqrt(D)
+    print(f"state variants: policy={policy} chunk={chunk} B={B} T={T} Hq={Hq} Hkv={Hkv} W={W}", flush=True)
+    q, k, v, dO = x["q"].cuda(), x["k"].cuda(), x["v"].cuda(), x["dO"].cuda()
+    kw = dict(softmax_scale=scale, chunk=chunk, state_policy=policy)
+    o, saved = rb.rattn_fwd(q, k, v, W, save_for_bwd=True, **kw)
+    rb.rattn_profile_enable(True)
+    dq, dk, dv, _, _ = rb.rattn_bwd(q, k, v, saved, dO, W, want_dgamma=False, **kw)
+    torch.cuda.synchronize()
+    names = [n for n, _ in rb.rattn_profile_records()]
+    rb.rattn_profile_enable(False)
+    assert "bwd_dkv_kernel" in names
+    assert ("rla_chunk_kernel" in names) == (policy == "rebuild")     # forward states rebuilt only under that policy
+    ref = orc.fwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), W, scale=scale)
+    pm.assert_out_bf16(np64(o), ref["o"])
+    refb = orc.bwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), np64(x["dO"]), W, scale=scale)
+    model = model_grads(x, W, scale, gains=False)
+    for n, g_ in (("dq", dq), ("dk", dk), ("dv", dv)):
+        pm.assert_grad_bf16(np64(g_), refb[n], n, model[n])
+    # against the default variant: same chunk size => the same bits, whether the states are kept or rebuilt
+    o0, saved0 = rb.rattn_fwd(q, k, v, W, save_for_bwd=True, softmax_scale=scale, chunk=chunk)
+    g0 = rb.rattn_bwd(q, k, v, saved0, dO, W, want_dgamma=False, softmax_scale=scale, chunk=chunk)
+    assert torch.equal(o, o0)
+    for a_, b_ in zip((dq, dk, dv), g0[:3]):
+        assert torch.equal(a_, b_)
+    if policy == "rebuild":
+        nst = T // 128 - (min(W, T) + 63) // 64 * 64 // 128 - ((min(W, T) + 63) // 64 * 64 % 128 > 0)
+        assert saved0.numel() - saved.numel() >= max(nst, 0) * B * Hkv * 128 * 128 * 2
+
+
 def test_fast_bwd_is_deterministic():
     x = synth.make_random_layer(1, 512, 4, 2, 128, "bf16", 6, with_dO=True)
     q, k, v, dO = x["q"].cuda(), x["k"].cuda(), x["v"].cuda(), x["dO"].cuda()

@@ -12,7 +12,7 @@ from paper_2506_15545_amd import synth
 
 
 def _params(B, T, Hq, Hkv, D, W):
-    return rb.RattnParams(B, T, Hq, Hkv, D, W, 0, rb.RATTN_BF16, 1.0 / math.sqrt(D), 1e-6, 0, 0, 0)
+    return rb.RattnParams(B, T, Hq, Hkv, D, W, 0, rb.RATTN_BF16, 1.0 / math.sqrt(D), 1e-6, 0, 0, 0, 0)
 
 
 def test_static_entry_rejects_shapes_beyond_its_buffer():
