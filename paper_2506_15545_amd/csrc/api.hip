@@ -103,6 +103,7 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
   dm.B = p->B; dm.T = p->T; dm.Hq = p->Hq; dm.Hkv = p->Hkv; dm.D = p->D;
   dm.W = p->window; dm.G = p->Hq / p->Hkv;
   dm.C = p->chunk > 0 ? p->chunk : 64;
+  dm.chunk_req = p->chunk;
   const int Tp = p->T > p->window ? p->T - p->window : 0;
   dm.nst = Tp > 0 ? (Tp - 1) / dm.C + 1 : 0;
   dm.scale = p->softmax_scale; dm.eps = p->rms_eps; dm.phi = p->feature_map;

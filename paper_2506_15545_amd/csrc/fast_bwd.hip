@@ -65,17 +65,23 @@ __global__ __launch_bounds__(256) void dgamma_reduce_kernel(const float* __restr
 
 // row `src` (128 bf16) re-read in accumulator layout: lane keeps features 32ft + 8*i4 + 4h + e -> x[ft*16 + 4*i4 + e];
 // phi of that row (the row's other half sits in lane ^ 32).  FM_SOFTMAX64: features 64..127 (ft >= 2) are padding.
-template <int FM>
-__device__ __forceinline__ void phi_row_clayout(const uint16_t* src, int h, float (&x)[64]) {
+// the 16 8-byte pieces of row `src` that a lane holds in accumulator layout (piece 4 ft + i4 = features
+// 32ft + 8*i4 + 4h .. +3): fetched ahead of their use, unpacked by phi_row_clayout
+__device__ __forceinline__ void load_row_clayout(const uint16_t* src, int h, bf16x4_t (&raw)[16]) {
 #pragma unroll
   for (int ft = 0; ft < 4; ++ft)
 #pragma unroll
-    for (int i4 = 0; i4 < 4; ++i4) {
-      const bf16x4_t v = *reinterpret_cast<const bf16x4_t*>(src + 32 * ft + 8 * i4 + 4 * h);
-      f32x4_t f = __builtin_convertvector(v, f32x4_t);
+    for (int i4 = 0; i4 < 4; ++i4) raw[4 * ft + i4] = *reinterpret_cast<const bf16x4_t*>(src + 32 * ft + 8 * i4 + 4 * h);
+}
+
+template <int FM>
+__device__ __forceinline__ void phi_row_clayout(const bf16x4_t (&raw)[16], float (&x)[64]) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) x[ft * 16 + 4 * i4 + e] = f[e];
-    }
+  for (int j = 0; j < 16; ++j) {
+    f32x4_t f = __builtin_convertvector(raw[j], f32x4_t);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x[4 * j + e] = f[e];
+  }
   if (FM == FM_IDENTITY) return;
   if (FM == FM_RELU) {
 #pragma unroll
@@ -416,7 +422,11 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
       __syncthreads();
     }
     float qf[64];
-    phi_row_clayout<FM>(a.q + myrow_off, h, qf);
+    {
+      bf16x4_t qraw[16];
+      load_row_clayout(a.q + myrow_off, h, qraw);
+      phi_row_clayout<FM>(qraw, qf);
+    }
     phi_jacobian<FM>(acc, qf);
   }
 
@@ -559,6 +569,11 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
   bf16x8_t xop[8];  // V-role: K rows (phi(K) rows during the linear branch); K-role: V rows
   load_bop((krole ? a.v : a.k) + myrow_off, h, xop);
   f32x16_t acc[4] = {{0}, {0}, {0}, {0}};  // V-role: dV^T; K-role: dK^T
+  // what each role needs of its K rows right after the linear branch, fetched now so that no global load sits on the
+  // path between the two branches: the K-role the row in accumulator layout (softmax Jacobian), the V-role a copy of
+  // the raw rows (xop holds phi(K) meanwhile)
+  // (one register set for both roles: 8 x 16 bytes)
+  bf16x8_t kkeep[8];
 
   // ---- request machinery of the softmax branch (query tiles of 64 rows from s0 up to the last row that still
   // sees these keys); defined first because the linear branch already requests the first tiles
@@ -599,11 +614,11 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
   if (has_main || has_pre) {
     const int nq = has_main ? min(128, Tp - s0) : 0;  // head rows
     const int np = (has_pre ? 1 : 0) + (has_main ? 1 : 0), NV = G * np;
-    if (!krole) {
-      float x[64];
+    if (krole) {
+      bf16x4_t kraw[16];
+      load_row_clayout(a.k + myrow_off, h, kraw);
 #pragma unroll
-      for (int c = 0; c < 8; ++c) unpack_bf16x8(xop[c], &x[8 * c]);
-      phi_rows<FM>(x, xop);
+      for (int j = 0; j < 8; ++j) kkeep[j] = __builtin_shufflevector(kraw[2 * j], kraw[2 * j + 1], 0, 1, 2, 3, 4, 5, 6, 7);
     }
     unsigned char* const qA = smem;
     unsigned char* const dA = smem + 32768;
@@ -626,6 +641,12 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
       tile_load_async<4>(rbase, 128, dB, w8 * 4, lane);
     }
     issue_pass(0, qA, dA);
+    if (!krole) {  // phi of the own K rows while the first tiles are on their way
+      float x[64];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) { kkeep[c] = xop[c]; unpack_bf16x8(xop[c], &x[8 * c]); }
+      phi_rows<FM>(x, xop);
+    }
     wait_vmem();
     __syncthreads();
     if (has_main) {
@@ -694,10 +715,17 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
     }
     if (krole) {
       float kf[64];
-      phi_row_clayout<FM>(a.k + myrow_off, h, kf);
+      bf16x4_t kraw[16];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        kraw[2 * j] = __builtin_shufflevector(kkeep[j], kkeep[j], 0, 1, 2, 3);
+        kraw[2 * j + 1] = __builtin_shufflevector(kkeep[j], kkeep[j], 4, 5, 6, 7);
+      }
+      phi_row_clayout<FM>(kraw, kf);
       phi_jacobian<FM>(acc, kf);
     } else {
-      load_bop(a.k + myrow_off, h, xop);
+#pragma unroll
+      for (int c = 0; c < 8; ++c) xop[c] = kkeep[c];
     }
   }
 

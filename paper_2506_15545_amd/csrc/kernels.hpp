@@ -22,6 +22,7 @@ struct LayerDims {
   int B, T, Hq, Hkv, D, W, C, G;
   int Dv;   // features of a head that carry data: D, or 64 when the matrix-core kernels run a head size of 64
             // on rows zero-padded to D = 128 (the RMS norms and the softmax feature map then cover Dv features)
+  int chunk_req;  // the caller's `chunk` parameter as given (0 = unspecified); C above is what the general kernels use
   int nst;  // number of chunk states per (batch, kv head): ceil(max(T-W,0) / C)
   float scale, eps;
   int phi;  // feature map of the linear branch: PHI_SOFTMAX (Sec. 3.1), PHI_RELU, PHI_IDENTITY (Sec. 4.5 ablation)

@@ -25,9 +25,9 @@ FastFwdPlan fast_fwd_plan(const LayerDims& dm) {
   p.base = p.W % 128;
   p.nstf = dm.T / 128 - (p.W + 127) / 128;
   if (p.nstf < 0) p.nstf = 0;
-  // chunk-local products of `ckeys` keys each (the `chunk` parameter: 64, else 128); with 128 and states at the 64
+  // chunk-local products of `ckeys` keys each (128 unless the caller asks for `chunk` = 64); with 128 and states at the 64
   // alignment the first product covers the 64 keys in front of state 0
-  p.ckeys = dm.C == 64 ? 64 : 128;
+  p.ckeys = dm.chunk_req == 64 ? 64 : 128;
   p.nchunks = p.nstf > 0 ? (p.nstf - 1) * (128 / p.ckeys) + (p.base > 0 ? 1 : 0) : 0;
   p.u_bytes = (size_t)dm.B * dm.Hkv * p.nchunks * 16384 * 4;
   p.state_bytes = (size_t)dm.B * dm.Hkv * p.nstf * 16384 * 2;

@@ -22,7 +22,7 @@ struct ChunkArgs {
 
 // grid (nchunks, Hkv, B), 256 threads.  Wave w owns rows d in [32w, 32w+32) of U^T.
 template <int FM>
-__global__ __launch_bounds__(256) void rla_chunk_kernel(ChunkArgs p) {
+__global__ __launch_bounds__(256, 2) void rla_chunk_kernel(ChunkArgs p) {
   __shared__ __align__(16) unsigned char smem[65536];
   unsigned char* At = smem;
   unsigned char* Bt = smem + 32768;
@@ -46,6 +46,9 @@ __global__ __launch_bounds__(256) void rla_chunk_kernel(ChunkArgs p) {
     __syncthreads();
     phi_tile_inplace<FM>(At, ntok);
     __syncthreads();
+    // rolled on purpose: fully unrolled, the operand reads of all sub-blocks are hoisted and the kernel needs twice
+    // the registers, which halves the work-groups per CU of a kernel that lives on memory-level parallelism
+#pragma unroll 1
     for (int ks = 0; ks < ntok / 16; ++ks) {
       const int k0 = 16 * ks + 8 * h;
       const bf16x8_t aop = lds_tr_pair(Bt, k0, k0 + 4, 32 * w, lane);
@@ -64,14 +67,14 @@ __global__ __launch_bounds__(256) void rla_chunk_kernel(ChunkArgs p) {
 }
 
 // Exclusive scan over chunks, every state element independently, fp32 accumulation, bf16 output.  A state spans
-// `per` chunk products (1, or 2 when the products cover 64 keys each).
+// PER chunk products (1, or 2 when the products cover 64 keys each).
 //   forward: state[0] = sum of the `head` products in front of it; state[i+1] = state[i] + the next `per` products
 //   reverse: state[n-1] = 0; state[i] = state[i+1] + products per*i .. per*i + per - 1 (those that exist)
 // grid (16, Hkv, B), 256 threads, 4 elements per thread.
 // init (forward only, may be NULL): a state that precedes chunk 0, fp32 [B,Hkv,f,d] (not transposed).
-template <bool REV>
+template <bool REV, int PER>
 __global__ __launch_bounds__(256) void rla_scan_kernel(const float* __restrict__ U, uint16_t* __restrict__ states,
-                                                       int nchunks, int nst, int head, int per,
+                                                       int nchunks, int nst, int head,
                                                        const float* __restrict__ init) {
   const int g = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
   const int e4 = (blockIdx.x * 256 + threadIdx.x) * 4;
@@ -87,24 +90,43 @@ __global__ __launch_bounds__(256) void rla_scan_kernel(const float* __restrict__
     f32x4_t f = {acc.x, acc.y, acc.z, acc.w};
     *reinterpret_cast<bf16x4_t*>(Sb + (size_t)i * 16384) = __builtin_convertvector(f, bf16x4_t);
   };
-  auto add = [&](int c) {
-    const float4 u = *reinterpret_cast<const float4*>(Ub + (size_t)c * 16384);
-    acc.x += u.x; acc.y += u.y; acc.z += u.z; acc.w += u.w;
+  auto ld = [&](int c) {  // product c, or zero when it does not exist
+    return (c >= 0 && c < nchunks) ? *reinterpret_cast<const float4*>(Ub + (size_t)c * 16384) : make_float4(0.f, 0.f, 0.f, 0.f);
   };
+  auto add = [&](const float4& u) { acc.x += u.x; acc.y += u.y; acc.z += u.z; acc.w += u.w; };
+  // States are walked in groups of GRP: the group's products are all requested before the first is added, so the
+  // loads of a group are in flight together (the additions keep their fixed order).
+  constexpr int GRP = 4;
   if (!REV) {
-    int c = 0;
-    for (; c < head; ++c) add(c);
-    for (int i = 0; i < nst; ++i) {
-      put(i);
-      if (i + 1 < nst)
-        for (int r = 0; r < per; ++r) add(c++);
+    for (int c = 0; c < head; ++c) add(ld(c));
+    // state i is stored, then products head + PER*i .. + PER - 1 are added to reach state i + 1
+    for (int i0 = 0; i0 < nst; i0 += GRP) {
+      float4 u[GRP][PER];
+#pragma unroll
+      for (int j = 0; j < GRP; ++j)
+#pragma unroll
+        for (int r = 0; r < PER; ++r) u[j][r] = (i0 + j + 1 < nst) ? ld(head + PER * (i0 + j) + r) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int j = 0; j < GRP; ++j) {
+        if (i0 + j < nst) put(i0 + j);
+#pragma unroll
+        for (int r = 0; r < PER; ++r) add(u[j][r]);
+      }
     }
   } else {
-    for (int i = nst - 1; i >= 0; --i) {
-      put(i);
-      if (i > 0)
-        for (int r = per - 1; r >= 0; --r)
-          if (per * (i - 1) + r < nchunks) add(per * (i - 1) + r);
+    // state nst-1 = 0; state i = state i+1 + products PER*i .. PER*i + PER - 1 (descending order of addition)
+    for (int i0 = nst - 1; i0 >= 0; i0 -= GRP) {
+      float4 u[GRP][PER];
+#pragma unroll
+      for (int j = 0; j < GRP; ++j)
+#pragma unroll
+        for (int r = 0; r < PER; ++r) u[j][r] = (i0 - j > 0) ? ld(PER * (i0 - j - 1) + r) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int j = 0; j < GRP; ++j) {
+        if (i0 - j >= 0) put(i0 - j);
+#pragma unroll
+        for (int r = PER - 1; r >= 0; --r) add(u[j][r]);
+      }
     }
   }
 }
@@ -134,8 +156,9 @@ void rla_forward_states(const LayerDims& dm, const FastFwdPlan& pl, const void* 
     launch_chunk_kernel(feature_map_variant(dm), dim3(pl.nchunks, dm.Hkv, dm.B), p, st);
   }
   ProfScope ps("rla_scan_kernel", st);
-  rla_scan_kernel<false><<<dim3(16, dm.Hkv, dm.B), 256, 0, st>>>(U, (uint16_t*)states, pl.nchunks, pl.nstf, head,
-                                                                  128 / pl.ckeys, state0);
+  const dim3 sgrid(16, dm.Hkv, dm.B);
+  if (pl.ckeys == 64) rla_scan_kernel<false, 2><<<sgrid, 256, 0, st>>>(U, (uint16_t*)states, pl.nchunks, pl.nstf, head, state0);
+  else rla_scan_kernel<false, 1><<<sgrid, 256, 0, st>>>(U, (uint16_t*)states, pl.nchunks, pl.nstf, head, state0);
 }
 
 void rla_reverse_states(const LayerDims& dm, const FastBwdPlan& pl, const void* q, const void* dxr, float* U,
@@ -152,8 +175,9 @@ void rla_reverse_states(const LayerDims& dm, const FastBwdPlan& pl, const void* 
     launch_chunk_kernel(feature_map_variant(dm), dim3(pl.nrchunks, dm.Hkv, dm.B), p, st);
   }
   ProfScope ps("rla_scan_kernel(rev)", st);
-  rla_scan_kernel<true><<<dim3(16, dm.Hkv, dm.B), 256, 0, st>>>(U, (uint16_t*)rstates, pl.nrchunks, pl.nk, 0, 128 / ck,
-                                                                 nullptr);
+  const dim3 sgrid(16, dm.Hkv, dm.B);
+  if (ck == 64) rla_scan_kernel<true, 2><<<sgrid, 256, 0, st>>>(U, (uint16_t*)rstates, pl.nrchunks, pl.nk, 0, nullptr);
+  else rla_scan_kernel<true, 1><<<sgrid, 256, 0, st>>>(U, (uint16_t*)rstates, pl.nrchunks, pl.nk, 0, nullptr);
 }
 
 }  // namespace rattn

@@ -181,3 +181,21 @@ def test_inference_closed_forms_match_the_oracle_and_the_text():
     assert rb.lib().rattn_step_time_model(1.0, 1.0, 1.0, 1.0, 0.0, 1.0, ctypes.byref(out)) == -1
     assert rb.lib().rattn_cache_bytes(4, 4, -1, 8, 0, 1, 64, 2, ctypes.byref(out)) == -1
     assert rb.lib().rattn_cache_bytes(4, 4, 1, 8, 0, 1, 64, 2, None) == -1
+
+
+def test_matrix_core_chunk_size_defaults_to_128_keys():
+    """On the matrix-core path the chunk products cover 128 keys unless the caller asks for 64 (then there are twice
+    as many, and the forward scratch that holds them doubles); other values mean 128."""
+    base = dict(B=2, T=2048, Hq=4, Hkv=2, D=128, window=256, dtype=rb.RATTN_BF16)
+    f0, _, _ = rb.rattn_workspace_bytes(params(**base))
+    f64, _, _ = rb.rattn_workspace_bytes(params(chunk=64, **base))
+    f128, _, _ = rb.rattn_workspace_bytes(params(chunk=128, **base))
+    f32, _, _ = rb.rattn_workspace_bytes(params(chunk=32, **base))
+    nst = 2048 // 128 - 2
+    state_bytes = 2 * 2 * nst * 128 * 128 * 2
+    assert f0 == f128 == f32 == 2 * 2 * (nst - 1) * 128 * 128 * 4 + state_bytes
+    assert f64 == 2 * 2 * 2 * (nst - 1) * 128 * 128 * 4 + state_bytes
+    # keeping no states for backward shrinks `saved` by exactly the states
+    _, _, s_keep = rb.rattn_workspace_bytes(params(**base))
+    _, _, s_rebuild = rb.rattn_workspace_bytes(params(state_policy=1, **base))
+    assert s_keep - s_rebuild == state_bytes
