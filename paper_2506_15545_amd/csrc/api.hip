@@ -48,8 +48,9 @@ rattn_status fail(rattn_status s, const char* fmt, ...) {
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-// Sequence lengths from this size on that are not a multiple of 128 run on the matrix-core kernels through
-// zero-padded copies (bf16, D = 128); shorter ones stay on the general kernels, where the copies would not pay.
+// Sequence lengths from this size on that are not a multiple of 128 run on the matrix-core kernels (bf16): with
+// D = 128 in place, only the last partial tile of every sequence goes through zero-padded buffers; with D = 64 through
+// zero-padded copies of the whole tensors.  Shorter ones stay on the general kernels.
 constexpr int PAD_MIN_T = 1024;
 
 struct Layout {
@@ -57,6 +58,8 @@ struct Layout {
   rattn::LayerDims dmf;  // what the matrix-core kernels see: dm with T rounded up to 128 when `pad`
   bool pad;
   bool pad_d;                                             // head size 64 widened to 128 (implies pad)
+  bool tails;                                             // pad without pad_d: the pf_* / pb_* areas hold the last
+                                                          // 128-row tile of every sequence only (RaggedTails)
   size_t pf_q, pf_k, pf_v, pf_o, pf_gs, pf_gr;            // padded copies, forward workspace (gains only if pad_d)
   size_t pb_q, pb_k, pb_v, pb_dO, pb_dq, pb_dk, pb_dv;    // padded copies, backward workspace
   size_t pb_gs, pb_gr, pb_dgs, pb_dgr;                    // padded gains and gain gradients (pad_d)
@@ -121,6 +124,7 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
   const rattn::LayerDims& dmf = L->dmf;
   L->fast_fwd = p->kernel_path != RATTN_PATH_GENERAL && rattn::fast_fwd_supported(dmf, p->dtype);
   if (!L->fast_fwd) { L->pad = L->pad_d = false; L->dmf = dm; }
+  L->tails = L->pad && !L->pad_d;
   // `saved` is sized for the padded length
   const size_t nq = (size_t)dm.B * dm.T * dm.Hq * dm.D;
   const size_t nrow = (size_t)dm.B * dm.Hq * dm.T;
@@ -163,11 +167,14 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
     off = 0;
     L->ff_u = off; off += align_up(pl.u_bytes);
     L->ff_states = off; off += align_up(pl.state_bytes);
+    // padded copies of whole tensors, or of the last tile of every sequence
+    const size_t cq = L->tails ? (size_t)dmf.B * 128 * dmf.Hq * 128 * 2 : nq_f * 2;
+    const size_t ckv = L->tails ? (size_t)dmf.B * 128 * dmf.Hkv * 128 * 2 : nkv_f * 2;
     if (L->pad) {
-      L->pf_q = off; off += align_up(nq_f * 2);
-      L->pf_k = off; off += align_up(nkv_f * 2);
-      L->pf_v = off; off += align_up(nkv_f * 2);
-      L->pf_o = off; off += align_up(nq_f * 2);
+      L->pf_q = off; off += align_up(cq);
+      L->pf_k = off; off += align_up(ckv);
+      L->pf_v = off; off += align_up(ckv);
+      L->pf_o = off; off += align_up(cq);
       L->pf_gs = off; off += align_up((size_t)dmf.Hq * 128 * 4);
       L->pf_gr = off; off += align_up((size_t)dmf.Hq * 128 * 4);
     }
@@ -184,14 +191,16 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
     L->fb_states = off; off += align_up(bp.fwd.state_bytes);
     L->fb_rstates = off; off += align_up(bp.rstate_bytes);
     L->fb_dgpart = off; off += align_up((size_t)2 * bp.RB * dmf.Hq * dmf.D * 4);
+    const size_t cq = L->tails ? (size_t)dmf.B * 128 * dmf.Hq * 128 * 2 : nq_f * 2;
+    const size_t ckv = L->tails ? (size_t)dmf.B * 128 * dmf.Hkv * 128 * 2 : nkv_f * 2;
     if (L->pad) {
-      L->pb_q = off; off += align_up(nq_f * 2);
-      L->pb_k = off; off += align_up(nkv_f * 2);
-      L->pb_v = off; off += align_up(nkv_f * 2);
-      L->pb_dO = off; off += align_up(nq_f * 2);
-      L->pb_dq = off; off += align_up(nq_f * 2);
-      L->pb_dk = off; off += align_up(nkv_f * 2);
-      L->pb_dv = off; off += align_up(nkv_f * 2);
+      L->pb_q = off; off += align_up(cq);
+      L->pb_k = off; off += align_up(ckv);
+      L->pb_v = off; off += align_up(ckv);
+      L->pb_dO = off; off += align_up(cq);
+      L->pb_dq = off; off += align_up(cq);
+      L->pb_dk = off; off += align_up(ckv);
+      L->pb_dv = off; off += align_up(ckv);
       L->pb_gs = off; off += align_up((size_t)dmf.Hq * 128 * 4);
       L->pb_gr = off; off += align_up((size_t)dmf.Hq * 128 * 4);
       L->pb_dgs = off; off += align_up((size_t)dmf.Hq * 128 * 4);
@@ -335,6 +344,19 @@ rattn_status rattn_fwd(const rattn_params* p, const void* q, const void* k, cons
     void* of = o;
     const float *gsf = gamma_swa, *grf = gamma_rla;
     const size_t hb = (size_t)L.dm.D * 2, hbp = (size_t)L.dmf.D * 2;  // bytes of one head row, caller's and padded
+    if (L.tails) {
+      const void* src[3] = {q, k, v};
+      void* tl[3] = {w + L.pf_q, w + L.pf_k, w + L.pf_v};
+      const int Hs[3] = {L.dm.Hq, L.dm.Hkv, L.dm.Hkv};
+      rattn::gather_tails(3, src, tl, Hs, L.dm.B, L.dm.T, st);
+      rattn::RaggedTails rt = {L.dm.T, tl[0], tl[1], tl[2], nullptr, w + L.pf_o, nullptr, nullptr, nullptr};
+      rattn::fast_fwd(L.dmf, q, k, v, gamma_swa, gamma_rla, o, sv, (float*)(w + L.ff_u),
+                      sv.states ? sv.states : (void*)(w + L.ff_states), st, 0, nullptr, &rt);
+      const void* otl[1] = {w + L.pf_o};
+      void* odst[1] = {o};
+      rattn::scatter_tails(1, otl, odst, Hs, L.dm.B, L.dm.T, st);
+      return check_launch("rattn_fwd");
+    }
     if (L.pad) {
       rattn::pad_rows(q, w + L.pf_q, L.dm.B, L.dm.T, L.dmf.T, L.dm.Hq, hb, hbp, st);
       rattn::pad_rows(k, w + L.pf_k, L.dm.B, L.dm.T, L.dmf.T, L.dm.Hkv, hb, hbp, st);
@@ -382,7 +404,8 @@ rattn_status rattn_fwd_static(const rattn_params* p, const void* q, const void* 
     __atomic_store_n(&g_scratch_ptr[dev], ws, __ATOMIC_RELEASE);
   }
   // Every part of the scratch that the forward kernels read is written earlier in the same call (chunk products,
-  // then the scanned states, then - for ragged lengths - the padded copies), so nothing has to be cleared.
+  // then the scanned states, and - for ragged lengths or a head size of 64 - the zero-padded copies), so nothing has
+  // to be cleared.
   return rattn_fwd(p, q, k, v, gamma_swa, gamma_rla, o, saved, ws, RATTN_STATIC_SCRATCH_BYTES, stream);
 }
 // END-STATIC-ENTRY
@@ -408,7 +431,17 @@ rattn_status rattn_bwd(const rattn_params* p, const void* q, const void* k, cons
     fw.dxs = w + L.fb_dxs; fw.dxr = w + L.fb_dxr; fw.delta = (float*)(w + L.fb_delta); fw.U = (float*)(w + L.fb_u);
     fw.states = w + L.fb_states; fw.rstates = w + L.fb_rstates; fw.dgpart = (float*)(w + L.fb_dgpart);
     const size_t hb = (size_t)L.dm.D * 2, hbp = (size_t)L.dmf.D * 2;  // bytes of one head row, caller's and padded
-    if (L.pad) {
+    if (L.tails) {
+      const void* src[4] = {q, k, v, dO};
+      void* tl[4] = {w + L.pb_q, w + L.pb_k, w + L.pb_v, w + L.pb_dO};
+      const int Hs[4] = {L.dm.Hq, L.dm.Hkv, L.dm.Hkv, L.dm.Hq};
+      rattn::gather_tails(4, src, tl, Hs, L.dm.B, L.dm.T, st);
+      rattn::RaggedTails rt = {L.dm.T, tl[0], tl[1], tl[2], tl[3], nullptr, w + L.pb_dq, w + L.pb_dk, w + L.pb_dv};
+      rattn::fast_bwd(L.dmf, q, k, v, gamma_swa, gamma_rla, sv, dO, dq, dk, dv, dgamma_swa, dgamma_rla, fw, st, &rt);
+      const void* gtl[3] = {w + L.pb_dq, w + L.pb_dk, w + L.pb_dv};
+      void* gdst[3] = {dq, dk, dv};
+      rattn::scatter_tails(3, gtl, gdst, Hs, L.dm.B, L.dm.T, st);
+    } else if (L.pad) {
       const int B = L.dm.B, T = L.dm.T, Tp = L.dmf.T, Hq = L.dm.Hq, Hkv = L.dm.Hkv;
       rattn::pad_rows(q, w + L.pb_q, B, T, Tp, Hq, hb, hbp, st);
       rattn::pad_rows(k, w + L.pb_k, B, T, Tp, Hkv, hb, hbp, st);

@@ -14,6 +14,7 @@
 #include "common.hpp"
 #include "kernels.hpp"
 #include "mfma.hpp"
+#include <limits.h>
 
 namespace rattn {
 
@@ -29,6 +30,12 @@ struct FastBwdArgs {
   // inputs of the RMS-norm backward in the dq kernel's prologue, which fills dxs, dxr and delta above
   const uint16_t *dO, *xs, *xr;
   const uint16_t* xr_lo;           // low-order part of the saved x_r (identity feature map), NULL otherwise
+  // ragged lengths (see split_rows in mfma.hpp): rows >= Tfull of the caller's q, k, v, dO, dq, dk, dv live in 128-row
+  // tail buffers; Tc = rows per sequence of the caller's tensors.  T above is the padded length: saved tensors, the
+  // workspace tensors (dxs, dxr, delta) and the states are laid out for it.
+  const uint16_t *q_tail, *k_tail, *v_tail, *dO_tail;
+  uint16_t *dq_tail, *dk_tail, *dv_tail;
+  int Tc, Tfull;
   const float *rs, *rr, *gs, *gr;  // gains: NULL = ones
   float* dgpart;                   // gain-gradient partials [2][4 * ntile * B][Hq][128], NULL = not wanted
   float inv_d;                     // 1 / head size the RMS norms average over (1/64 for rows zero-padded from 64)
@@ -214,8 +221,8 @@ __device__ __forceinline__ float sum16(float x) {
 // GAINS: gains other than one and/or gain gradients; the wave's gradient partials (sums over its 32 rows) go to
 // dgp_s / dgp_r (128 floats each) when those are given.
 template <bool GAINS>
-__device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, int hq, size_t row0_off, size_t qstride, size_t stat0,
-                                             unsigned char* stage_s, unsigned char* stage_r, float* dl_stage,
+__device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, int hq, size_t row0_off, const uint16_t* dO_row0,
+                                             size_t qstride, size_t stat0, unsigned char* stage_s, unsigned char* stage_r, float* dl_stage,
                                              float* dgp_s, float* dgp_r, int lane) {
   const int sub = lane >> 4, c = lane & 15;
   uint16_t* dxs_w = const_cast<uint16_t*>(a.dxs);
@@ -233,7 +240,7 @@ __device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, int hq, size_
     const int r = 4 * it + sub;
     const size_t off = row0_off + (size_t)r * qstride + 8 * c;
     float dy[8], xs[8], xr[8];
-    unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(a.dO + off)), dy);
+    unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(dO_row0 + (size_t)r * qstride + 8 * c)), dy);
     unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(a.xs + off)), xs);
     unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(a.xr + off)), xr);
     if (a.xr_lo) {  // wave-uniform
@@ -311,10 +318,13 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
   const int hq = g * G + hh;
   const int t0 = qt * 128;
   const size_t qstride = (size_t)Hq * 128, kstride = (size_t)Hkv * 128;
-  const size_t qtile_off = ((size_t)(b * T + t0) * Hq + hq) * 128;
-  const size_t myrow_off = qtile_off + (size_t)(32 * w + r32) * qstride;
-  const uint16_t* kbase = a.k + ((size_t)b * T * Hkv + g) * 128;
-  const uint16_t* vbase = a.v + ((size_t)b * T * Hkv + g) * 128;
+  const size_t qtile_off = ((size_t)(b * T + t0) * Hq + hq) * 128;   // in the saved / workspace tensors (padded length)
+  // the caller's tensors: this query tile of q, dO, dq; 64-key tiles of k, v
+  const uint16_t* q_myrow = split_rows(a.q, a.q_tail, b, t0, a.Tc, a.Tfull, Hq, hq) + (size_t)(32 * w + r32) * qstride;
+  const uint16_t* dO_tile = split_rows(a.dO, a.dO_tail, b, t0, a.Tc, a.Tfull, Hq, hq);
+  uint16_t* dq_tile = split_rows(a.dq, a.dq_tail, b, t0, a.Tc, a.Tfull, Hq, hq);
+  auto k_rows = [&](int row) { return split_rows(a.k, a.k_tail, b, row, a.Tc, a.Tfull, Hkv, g); };
+  auto v_rows = [&](int row) { return split_rows(a.v, a.v_tail, b, row, a.Tc, a.Tfull, Hkv, g); };
   const int myq = t0 + 32 * w + r32;
   const size_t stat_off = (size_t)(b * Hq + hq) * T + myq;
 
@@ -329,7 +339,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
       dgp_s = a.dgpart + ((size_t)rb * Hq + hq) * 128;
       dgp_r = dgp_s + (size_t)4 * a.ntile * a.B * Hq * 128;
     }
-    rms_bwd_rows<GAINS>(a, hq, qtile_off + (size_t)(32 * w) * qstride, qstride, stat_off - r32,
+    rms_bwd_rows<GAINS>(a, hq, qtile_off + (size_t)(32 * w) * qstride, dO_tile + (size_t)(32 * w) * qstride, qstride,
+                        stat_off - r32,
                         smem + 32768 + 16 * w * ROW_BYTES, has_lin ? smem + 32 * w * ROW_BYTES : nullptr,
                         dl_stage + 32 * w, dgp_s, dgp_r, lane);
   }
@@ -387,9 +398,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
       if (has_state) {
         const uint16_t* sbase = a.states + ((size_t)(b * Hkv + g) * a.nstf + j0 / 128) * 16384;
         tile_load_async<8>(sbase, 128, smem, w * 8, lane);
-        tile_load_async<4>(vbase + (size_t)j0 * kstride, kstride, smem + 32768, w * 4, lane);
+        tile_load_async<4>(v_rows(j0), kstride, smem + 32768, w * 4, lane);
       }
-      tile_load_async<4>(vbase + (size_t)(j0 + 64) * kstride, kstride, smem + 49152, w * 4, lane);
+      tile_load_async<4>(v_rows(j0 + 64), kstride, smem + 49152, w * 4, lane);
       wait_vmem();
       __syncthreads();
       if (has_state) {
@@ -400,8 +411,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
         }
       }
       __syncthreads();
-      if (has_state) tile_load_async<4>(kbase + (size_t)j0 * kstride, kstride, smem, w * 4, lane);
-      tile_load_async<4>(kbase + (size_t)(j0 + 64) * kstride, kstride, smem + 16384, w * 4, lane);
+      if (has_state) tile_load_async<4>(k_rows(j0), kstride, smem, w * 4, lane);
+      tile_load_async<4>(k_rows(j0 + 64), kstride, smem + 16384, w * 4, lane);
       wait_vmem();
       __syncthreads();
       if (has_state) phi_tile_inplace<FM>(smem, 128);
@@ -412,8 +423,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
     }
     __syncthreads();
     if (gap > 0) {
-      tile_load_async<4>(kbase + (size_t)(j0 + 128) * kstride, kstride, smem, w * 4, lane);
-      tile_load_async<4>(vbase + (size_t)(j0 + 128) * kstride, kstride, smem + 32768, w * 4, lane);
+      tile_load_async<4>(k_rows(j0 + 128), kstride, smem, w * 4, lane);
+      tile_load_async<4>(v_rows(j0 + 128), kstride, smem + 32768, w * 4, lane);
       wait_vmem();
       __syncthreads();
       phi_tile_inplace<FM>(smem, 64);
@@ -424,7 +435,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
     float qf[64];
     {
       bf16x4_t qraw[16];
-      load_row_clayout(a.q + myrow_off, h, qraw);
+      load_row_clayout(q_myrow, h, qraw);
       phi_row_clayout<FM>(qraw, qf);
     }
     phi_jacobian<FM>(acc, qf);
@@ -433,14 +444,14 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
   // ---- softmax branch
   if (!has_lin) __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the staged rows are in registers
   bf16x8_t qop[8];
-  load_bop(a.q + myrow_off, h, qop);
+  load_bop(q_myrow, h, qop);
   const float lse2 = a.lse[stat_off] * LOG2E;
   const int kt_lo = max(0, t0 - W);
   const int ntiles = (t0 + 128 - kt_lo) / 64;
   {
     const int kt0 = kt_lo + 64 * (ntiles - 1);
-    tile_load_async<4>(kbase + (size_t)kt0 * kstride, kstride, smem, w * 4, lane);
-    tile_load_async<4>(vbase + (size_t)kt0 * kstride, kstride, smem + 32768, w * 4, lane);
+    tile_load_async<4>(k_rows(kt0), kstride, smem, w * 4, lane);
+    tile_load_async<4>(v_rows(kt0), kstride, smem + 32768, w * 4, lane);
     wait_vmem();
     __syncthreads();
   }
@@ -452,8 +463,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
     const int cur = n & 1;
     if (n + 1 < ntiles) {
       const int ktn = kt_lo + 64 * (it - 1);
-      tile_load_async_s<4>(kbase + (size_t)ktn * kstride, kstride, smem + (cur ^ 1) * 16384, w * 4, dma_lane);
-      tile_load_async_s<4>(vbase + (size_t)ktn * kstride, kstride, smem + 32768 + (cur ^ 1) * 16384, w * 4, dma_lane);
+      tile_load_async_s<4>(k_rows(ktn), kstride, smem + (cur ^ 1) * 16384, w * 4, dma_lane);
+      tile_load_async_s<4>(v_rows(ktn), kstride, smem + 32768 + (cur ^ 1) * 16384, w * 4, dma_lane);
     }
     const unsigned char* kt = smem + cur * 16384;
     const unsigned char* vt = smem + 32768 + cur * 16384;
@@ -475,7 +486,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
     for (int i = 0; i < 16; ++i) vals[dt][i] = acc[dt][i];
-  store_tile_transposed(smem, vals, a.dq + qtile_off, qstride, w, lane);
+  store_tile_transposed(smem, vals, dq_tile, qstride, w, lane);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -562,12 +573,14 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
   const int s0 = kti * 128;
   const int Tp = T - W;
   const size_t qstride = (size_t)Hq * 128, kstride = (size_t)Hkv * 128;
-  const size_t ktile_off = ((size_t)(b * T + s0) * Hkv + g) * 128;
-  const size_t myrow_off = ktile_off + (size_t)(32 * w + r32) * kstride;
+  // this key tile in the caller's k, v, dk, dv (the last, partial tile of a ragged length lives in the tail buffers)
+  const size_t myrow = (size_t)(32 * w + r32) * kstride;
+  const uint16_t* k_myrow = split_rows(a.k, a.k_tail, b, s0, a.Tc, a.Tfull, Hkv, g) + myrow;
+  const uint16_t* v_myrow = split_rows(a.v, a.v_tail, b, s0, a.Tc, a.Tfull, Hkv, g) + myrow;
   const int mykey = s0 + 32 * w + r32;
 
   bf16x8_t xop[8];  // V-role: K rows (phi(K) rows during the linear branch); K-role: V rows
-  load_bop((krole ? a.v : a.k) + myrow_off, h, xop);
+  load_bop(krole ? v_myrow : k_myrow, h, xop);
   f32x16_t acc[4] = {{0}, {0}, {0}, {0}};  // V-role: dV^T; K-role: dK^T
   // what each role needs of its K rows right after the linear branch, fetched now so that no global load sits on the
   // path between the two branches: the K-role the row in accumulator layout (softmax Jacobian), the V-role a copy of
@@ -587,12 +600,13 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
   const unsigned lds_q = (unsigned)(size_t)RATTN_LDS(smem) + w8 * 2048;
   const unsigned lds_st = (unsigned)(size_t)RATTN_LDS(smem + DKV_STAT_OFF) + (krole ? 1024 : 0);
   const float* stat_base = (krole ? a.delta : a.lse) + (size_t)(b * Hq + g * G) * T + s0;  // lane adds 16 * ip bytes
-  const size_t tile_g = ((size_t)(b * T + s0) * Hq + g * G) * 128;
+  const size_t tile_g = ((size_t)(b * T + s0) * Hq + g * G) * 128;   // workspace tensors (padded length)
   int is_h = 0, is_n = 0, is_buf = 0;  // head, tile and slot of the next tile to request
   auto issue = [&]() {
     const size_t qoff = tile_g + (size_t)is_n * 64 * qstride + (size_t)is_h * 128;
-    dma16s(a.q + qoff, lane_g0, lds_q + is_buf * DKV_SLOT);
-    dma16s(a.q + qoff, lane_g1, lds_q + is_buf * DKV_SLOT + 1024);
+    const uint16_t* qsrc = split_rows(a.q, a.q_tail, b, s0 + 64 * is_n, a.Tc, a.Tfull, Hq, g * G + is_h);
+    dma16s(qsrc, lane_g0, lds_q + is_buf * DKV_SLOT);
+    dma16s(qsrc, lane_g1, lds_q + is_buf * DKV_SLOT + 1024);
     dma16s(a.dxs + qoff, lane_g0, lds_q + is_buf * DKV_SLOT + 16384);
     dma16s(a.dxs + qoff, lane_g1, lds_q + is_buf * DKV_SLOT + 16384 + 1024);
     if (w == 0)  // one wave of each role: the row statistics that role consumes (lanes 16.. fetch duplicates)
@@ -616,7 +630,7 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
     const int np = (has_pre ? 1 : 0) + (has_main ? 1 : 0), NV = G * np;
     if (krole) {
       bf16x4_t kraw[16];
-      load_row_clayout(a.k + myrow_off, h, kraw);
+      load_row_clayout(k_myrow, h, kraw);
 #pragma unroll
       for (int j = 0; j < 8; ++j) kkeep[j] = __builtin_shufflevector(kraw[2 * j], kraw[2 * j + 1], 0, 1, 2, 3, 4, 5, 6, 7);
     }
@@ -628,11 +642,14 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
     auto issue_pass = [&](int vh, unsigned char* qb, unsigned char* db) {
       const bool pre = pass_is_pre(vh);
       const int row0 = s0 + W - (pre ? 64 : 0), nrow = pre ? 64 : nq;
-      const size_t qoff = ((size_t)(b * T + row0) * Hq + g * G + vh / np) * 128;
-      tile_load_async<2>(a.q + qoff, qstride, qb, w8 * 2, lane);
+      const size_t qoff = ((size_t)(b * T + row0) * Hq + g * G + vh / np) * 128;   // workspace tensor (padded length)
+      tile_load_async<2>(split_rows(a.q, a.q_tail, b, row0, a.Tc, a.Tfull, Hq, g * G + vh / np), qstride, qb, w8 * 2, lane);
       tile_load_async<2>(a.dxr + qoff, qstride, db, w8 * 2, lane);
       if (nrow == 128) {
-        tile_load_async<2>(a.q + qoff, qstride, qb, 16 + w8 * 2, lane);
+        // rows 64..127 of the pass: their own source (row0 is a multiple of 64, the half tile may be the ragged tail);
+        // the loader adds 64 row strides for these blocks, so the base is given 64 rows back (never dereferenced there)
+        const uint16_t* q64 = split_rows(a.q, a.q_tail, b, row0 + 64, a.Tc, a.Tfull, Hq, g * G + vh / np);
+        tile_load_async<2>(q64 - (size_t)64 * qstride, qstride, qb, 16 + w8 * 2, lane);
         tile_load_async<2>(a.dxr + qoff, qstride, db, 16 + w8 * 2, lane);
       }
     };
@@ -835,7 +852,8 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
       const int which = id >> 11, r = (id >> 4) & 127, pch = id & 15;
       const int c = pch ^ swz(r);
       const u32x4_t val = *reinterpret_cast<const u32x4_t*>(smem + which * 32768 + r * ROW_BYTES + (pch << 4));
-      uint16_t* dst = (which ? a.dk : a.dv) + ktile_off;
+      uint16_t* dst = which ? split_rows(a.dk, a.dk_tail, b, s0, a.Tc, a.Tfull, Hkv, g)
+                            : split_rows(a.dv, a.dv_tail, b, s0, a.Tc, a.Tfull, Hkv, g);
       __builtin_nontemporal_store(val, reinterpret_cast<u32x4_t*>(dst + (size_t)r * kstride + c * 8));
     }
   }
@@ -845,7 +863,7 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
 
 void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, const float* gs, const float* gr,
               const SavedPtrs& sv, const void* dO, void* dq, void* dk, void* dv, float* dgs, float* dgr,
-              const FastBwdWs& ws, hipStream_t st) {
+              const FastBwdWs& ws, hipStream_t st, const RaggedTails* tails) {
   const FastBwdPlan pl = fast_bwd_plan(dm);
   // The RMS-norm backward runs as the prologue of the dq kernel (each wave on its own rows); the variant with
   // gains also leaves per-wave partials of the gain gradients, summed afterwards in a fixed order.
@@ -855,9 +873,15 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
   a.dxs = (const uint16_t*)ws.dxs; a.dxr = (const uint16_t*)ws.dxr;
   a.lse = sv.lse; a.delta = ws.delta;
   // chunk states of the forward pass: kept in `saved`, or (state policy "rebuild") built again here from k and v
-  if (!sv.states && pl.fwd.nstf > 0) rla_forward_states(dm, pl.fwd, k, v, ws.U, ws.states, st);
+  if (!sv.states && pl.fwd.nstf > 0) rla_forward_states(dm, pl.fwd, k, v, ws.U, ws.states, st, nullptr, tails);
   a.states = (const uint16_t*)(sv.states ? sv.states : ws.states); a.rstates = (const uint16_t*)ws.rstates;
   a.dq = (uint16_t*)dq; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv;
+  a.q_tail = tails ? (const uint16_t*)tails->q : nullptr; a.k_tail = tails ? (const uint16_t*)tails->k : nullptr;
+  a.v_tail = tails ? (const uint16_t*)tails->v : nullptr; a.dO_tail = tails ? (const uint16_t*)tails->dO : nullptr;
+  a.dq_tail = tails ? (uint16_t*)tails->dq : nullptr; a.dk_tail = tails ? (uint16_t*)tails->dk : nullptr;
+  a.dv_tail = tails ? (uint16_t*)tails->dv : nullptr;
+  a.Tc = tails ? tails->Tc : dm.T;
+  a.Tfull = tails ? tails->Tc / 128 * 128 : INT_MAX;
   a.B = dm.B; a.T = dm.T; a.Hq = dm.Hq; a.Hkv = dm.Hkv; a.G = dm.G; a.W = pl.fwd.W; a.gap = pl.fwd.gap;
   a.nstf = pl.fwd.nstf; a.nk = pl.nk; a.ntile = dm.T / 128;
   a.scale = dm.scale; a.scale_log2 = dm.scale * LOG2E;
@@ -888,7 +912,7 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
     ProfScope ps("dgamma_reduce_kernel", st);
     dgamma_reduce_kernel<<<dim3(HD / 32, 2), 256, 0, st>>>(ws.dgpart, dgs, dgr, pl.RB, HD);
   }
-  rla_reverse_states(dm, pl, q, ws.dxr, ws.U, ws.rstates, st);
+  rla_reverse_states(dm, pl, q, ws.dxr, ws.U, ws.rstates, st, tails);
   // the dk/dv kernel needs more LDS than a launch gets by default: raised once per instantiation
   static const bool lds_attr = [] {
     const void* fns[] = {reinterpret_cast<const void*>(bwd_dkv_kernel<FM_SOFTMAX>),

@@ -18,6 +18,7 @@
 #include "common.hpp"
 #include "kernels.hpp"
 #include "mfma.hpp"
+#include <limits.h>
 
 namespace rattn {
 
@@ -27,6 +28,11 @@ struct FastFwdArgs {
   const uint16_t *q, *k, *v;
   const float *gs, *gr;
   uint16_t *o, *xs_out, *xr_out;
+  // ragged lengths (see split_rows): rows >= Tfull of q, k, v, o live in 128-row tail buffers; Tcq / Tck = rows per
+  // sequence of the caller's q, o / k, v tensors (the saved tensors and the states are laid out for the padded T)
+  const uint16_t *q_tail, *k_tail, *v_tail;
+  uint16_t* o_tail;
+  int Tcq, Tck, Tfull;
   uint16_t* xr_lo_out;  // low-order part of the saved x_r (identity feature map only, else null)
   float *lse_out, *rs_out, *rr_out;
   const uint16_t* states;  // [B,Hkv,nstf,128 (value d),128 (feature f)] bf16: S^T at key position base+128*i
@@ -206,9 +212,12 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
   const int hq = g * G + hh;
   const int t0 = qt * 128;
   const size_t qstride = (size_t)Hq * 128, kstride = (size_t)Hkv * 128;
-  const size_t qtile_off = ((size_t)(b * Tq + t0 - 128 * a.qt0) * Hq + hq) * 128;
-  const uint16_t* kbase = a.k + ((size_t)b * T * Hkv + g) * 128;
-  const uint16_t* vbase = a.v + ((size_t)b * T * Hkv + g) * 128;
+  const size_t qtile_off = ((size_t)(b * Tq + t0 - 128 * a.qt0) * Hq + hq) * 128;  // in the saved tensors
+  const uint16_t* q_tile = split_rows(a.q, a.q_tail, b, t0 - 128 * a.qt0, a.Tcq, a.Tfull, Hq, hq);
+  uint16_t* o_tile = split_rows(a.o, a.o_tail, b, t0 - 128 * a.qt0, a.Tcq, a.Tfull, Hq, hq);
+  // first row of a 64-key tile of this KV head
+  auto k_rows = [&](int row) { return split_rows(a.k, a.k_tail, b, row, a.Tck, a.Tfull, Hkv, g); };
+  auto v_rows = [&](int row) { return split_rows(a.v, a.v_tail, b, row, a.Tck, a.Tfull, Hkv, g); };
   const int myq = t0 + 32 * w + r32;
   const size_t stat_off = (size_t)(b * Hq + hq) * Tq + myq - 128 * a.qt0;
 
@@ -219,17 +228,17 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
   const int ntiles = (t0 + 128 - kt_lo) / 64;  // >= 2
   const DmaLane dl = make_dma_lane(lane, kstride);
   auto load_k = [&](int n) {
-    tile_load_async_s<4>(kbase + (size_t)(kt_lo + 64 * (ntiles - 1 - n)) * kstride, kstride, smem + (n & 1) * 16384, w * 4, dl);
+    tile_load_async_s<4>(k_rows(kt_lo + 64 * (ntiles - 1 - n)), kstride, smem + (n & 1) * 16384, w * 4, dl);
   };
   auto load_v = [&](int n) {
-    tile_load_async_s<4>(vbase + (size_t)(kt_lo + 64 * (ntiles - 1 - n)) * kstride, kstride, smem + 32768 + (n & 1) * 16384, w * 4, dl);
+    tile_load_async_s<4>(v_rows(kt_lo + 64 * (ntiles - 1 - n)), kstride, smem + 32768 + (n & 1) * 16384, w * 4, dl);
   };
   load_k(0);
   load_v(0);
   load_k(1);
   bf16x8_t qop[8];
   {
-    const uint16_t* qp = a.q + qtile_off + (size_t)(32 * w + r32) * qstride + 8 * h;
+    const uint16_t* qp = q_tile + (size_t)(32 * w + r32) * qstride + 8 * h;
 #pragma unroll
     for (int dk = 0; dk < 8; ++dk) qop[dk] = *reinterpret_cast<const bf16x8_t*>(qp + 16 * dk);
   }
@@ -355,8 +364,8 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
     }
     __syncthreads();
     if (GAP) {
-      tile_load_async<4>(kbase + (size_t)(j0 + 128) * kstride, kstride, smem, w * 4, lane);
-      tile_load_async<4>(vbase + (size_t)(j0 + 128) * kstride, kstride, smem + 32768, w * 4, lane);
+      tile_load_async<4>(k_rows(j0 + 128), kstride, smem, w * 4, lane);
+      tile_load_async<4>(v_rows(j0 + 128), kstride, smem + 32768, w * 4, lane);
       wait_vmem();
       __syncthreads();
       phi_tiles_inplace<FM>(smem, nullptr);
@@ -435,16 +444,17 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
           }
         }
     }
-    store_tile_transposed(smem, vals, a.o + qtile_off, qstride, w, lane);
+    store_tile_transposed(smem, vals, o_tile, qstride, w, lane);
   }
 }
 
 }  // namespace
 
 void fast_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, const float* gs, const float* gr,
-              void* o, const SavedPtrs& sv, float* U, void* states, hipStream_t st, int qt0, const float* state0) {
+              void* o, const SavedPtrs& sv, float* U, void* states, hipStream_t st, int qt0, const float* state0,
+              const RaggedTails* tails) {
   const FastFwdPlan pl = fast_fwd_plan(dm);
-  if (pl.nstf > 0) rla_forward_states(dm, pl, k, v, U, states, st, state0);
+  if (pl.nstf > 0) rla_forward_states(dm, pl, k, v, U, states, st, state0, tails);
   FastFwdArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
   a.gs = gs; a.gr = gr;
@@ -454,6 +464,12 @@ void fast_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
   a.states = (const uint16_t*)states;
   a.B = dm.B; a.T = dm.T; a.Hq = dm.Hq; a.Hkv = dm.Hkv; a.G = dm.G; a.W = pl.W; a.gap = pl.gap; a.nstf = pl.nstf;
   a.ntile = dm.T / 128; a.qt0 = qt0;
+  // the caller's tensors: q and o hold the computed tiles only; with tails (always qt0 == 0) Tc rows per sequence
+  a.q_tail = tails ? (const uint16_t*)tails->q : nullptr; a.k_tail = tails ? (const uint16_t*)tails->k : nullptr;
+  a.v_tail = tails ? (const uint16_t*)tails->v : nullptr; a.o_tail = tails ? (uint16_t*)tails->o : nullptr;
+  a.Tcq = tails ? tails->Tc : dm.T - 128 * qt0;
+  a.Tck = tails ? tails->Tc : dm.T;
+  a.Tfull = tails ? tails->Tc / 128 * 128 : INT_MAX;
   a.scale_log2 = dm.scale * LOG2E; a.eps = dm.eps;
   ProfScope ps("fwd_fused_kernel", st);
   const dim3 grid((a.ntile - qt0) * dm.Hq * dm.B);

@@ -71,6 +71,19 @@ inline int feature_map_variant(const LayerDims& dm) {
   return dm.Dv == 64 ? 3 : 0;
 }
 
+// Ragged sequence lengths on the matrix-core kernels (bf16, D = 128): the kernels work in 128-row tiles over the
+// length rounded up (LayerDims::T), the caller's tensors hold Tc rows per sequence.  Tiles below 128 * (Tc / 128) are
+// read and written in place; the last, partial tile of every sequence goes through [B,128,H,128] buffers that the host
+// layer fills (inputs, zero past row Tc) before and copies back (results, rows below Tc) after the kernels.  The saved
+// and workspace tensors are laid out for the rounded-up length.  Null where a function takes a RaggedTails*: every
+// tensor holds LayerDims::T rows itself.
+struct RaggedTails {
+  int Tc;
+  const void *q, *k, *v, *dO;   // dO: backward only
+  void *o;                      // forward only
+  void *dq, *dk, *dv;           // backward only
+};
+
 // MFMA forward path (bf16, D = 128, T % 128 == 0, any W >= 8)
 struct FastFwdPlan {
   int W;        // window the tiles and states are laid out for: min(W, T) rounded up to a multiple of 64
@@ -89,11 +102,12 @@ FastFwdPlan fast_fwd_plan(const LayerDims& dm);
 // do not see it, so the caller uses it only when no computed tile is of that kind.
 void fast_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, const float* gs, const float* gr,
               void* o, const SavedPtrs& sv, float* U, void* states, hipStream_t st, int qt0 = 0,
-              const float* state0 = nullptr);
+              const float* state0 = nullptr, const RaggedTails* tails = nullptr);
 
 // linear-branch chunk states for the MFMA paths (bf16 [d][f] per state, fp32 scratch U per chunk)
 void rla_forward_states(const LayerDims& dm, const FastFwdPlan& pl, const void* k, const void* v, float* U,
-                        void* states, hipStream_t st, const float* state0 = nullptr);
+                        void* states, hipStream_t st, const float* state0 = nullptr,
+                        const RaggedTails* tails = nullptr);
 // MFMA backward path (same shape class as the MFMA forward)
 struct FastBwdPlan {
   FastFwdPlan fwd;
@@ -113,10 +127,10 @@ FastBwdPlan fast_bwd_plan(const LayerDims& dm);
 // reverse-time states R_i = sum over t' >= 128(i+1) and over the group's heads of phi(q_{t'+W})^T dxr_{t'+W},
 // i in [0, nk), nk = ceil((T-W)/128); stored transposed [d][f] bf16.  U needs (nk-1) chunks.
 void rla_reverse_states(const LayerDims& dm, const FastBwdPlan& pl, const void* q, const void* dxr, float* U,
-                        void* rstates, hipStream_t st);
+                        void* rstates, hipStream_t st, const RaggedTails* tails = nullptr);
 void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, const float* gs, const float* gr,
               const SavedPtrs& sv, const void* dO, void* dq, void* dk, void* dv, float* dgs, float* dgr,
-              const FastBwdWs& ws, hipStream_t st);
+              const FastBwdWs& ws, hipStream_t st, const RaggedTails* tails = nullptr);
 
 // prefill -> decode hand-over: rings of the last min(T, W) tokens and the state of all keys before them
 struct ExportPlan {
@@ -145,6 +159,11 @@ void pad_rows(const void* src, void* dst, int B, int T, int Tp, int H, size_t he
               hipStream_t st);
 void unpad_rows(const void* src, void* dst, int B, int T, int Tp, int H, size_t head_bytes, size_t head_bytes_padded,
                 hipStream_t st);
+
+// rows 128 * (T / 128) .. of up to four [B,T,H,128] bf16 tensors <-> their [B,128,H,128] tail buffers (RaggedTails):
+// gather fills the buffers (zero from row T on), scatter copies the rows below T back.  n tensors, H[i] heads each.
+void gather_tails(int n, const void* const* src, void* const* tail, const int* H, int B, int T, hipStream_t st);
+void scatter_tails(int n, const void* const* tail, void* const* dst, const int* H, int B, int T, hipStream_t st);
 
 // launches the matrix-core probe loop; returns the FLOPs it issues
 double probe_mfma(float* sink, int iters, int blocks, hipStream_t st);

@@ -195,6 +195,16 @@ __device__ __forceinline__ float half_max(float x) {
 // 2^x on the transcendental unit (v_exp_f32): 2^-inf = 0, no denormal fix-up code
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Ragged sequence lengths.  The kernels work on whole 128-row tiles of a padded length; a caller tensor [B, Tc, H, 128]
+// whose length Tc is not a whole number of tiles is read (or written) in two parts: rows below Tfull = 128 * (Tc / 128)
+// in place, the last, partial tile through a zero-padded 128-row copy [B, 128, H, 128] in the workspace.  A tile or
+// half tile never straddles Tfull.  Without a ragged tail, Tfull is INT_MAX and the tail pointer is never used.
+template <typename P>
+__device__ __forceinline__ P* split_rows(P* main, P* tail, int b, int row, int Tc, int Tfull, int H, int h) {
+  return row < Tfull ? main + ((size_t)(b * (size_t)Tc + row) * H + h) * 128
+                     : tail + ((size_t)(b * (size_t)128 + (row - Tfull)) * H + h) * 128;
+}
+
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 

@@ -4,6 +4,8 @@
 //  * a head size of 64: rows are widened to 128 features with zeros, which add nothing to any dot product; the
 //    kernels are told that only 64 features carry data (RMS norms, softmax feature map).
 // Tensors are [B, T, H, D]; the padded copy is [B, Tp, H, Dp] with zeros at t >= T and in features >= D.
+// With D = 128 only the last, partial tile of every sequence is copied (tail buffers, see RaggedTails); the kernels
+// address everything in front of it in place.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -37,6 +39,30 @@ __global__ __launch_bounds__(256) void unpad_rows_kernel(const uint4* __restrict
   }
 }
 
+struct TailSet {
+  const uint4* src[4];
+  uint4* dst[4];
+  int H[4];
+};
+
+// blockIdx.y = tensor; one thread per 16 bytes of a [B,128,H,16 vectors] tail buffer.  GATHER: buffer <- rows
+// Tfull + r of the [B,T,H,128] bf16 tensor, zero where Tfull + r >= T; else tensor rows < T <- buffer.
+template <bool GATHER>
+__global__ __launch_bounds__(256) void tail_rows_kernel(TailSet s, int B, int T, int Tfull) {
+  const int i = blockIdx.y, H = s.H[i];
+  const long long total = (long long)B * 128 * H * 16;
+  for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long long)gridDim.x * 256) {
+    const int c = (int)(e & 15);
+    long long r = e >> 4;
+    const int h = (int)(r % H); r /= H;
+    const int row = (int)(r & 127), b = (int)(r >> 7);
+    const bool live = Tfull + row < T;
+    const long long full = (((long long)b * T + Tfull + row) * H + h) * 16 + c;
+    if (GATHER) s.dst[i][e] = live ? s.src[i][full] : make_uint4(0u, 0u, 0u, 0u);
+    else if (live) s.dst[i][full] = s.src[i][e];
+  }
+}
+
 int blocks_for(long long total) {
   const long long n = (total + 255) / 256;
   return (int)(n < 16384 ? (n > 0 ? n : 1) : 16384);
@@ -56,6 +82,22 @@ void unpad_rows(const void* src, void* dst, int B, int T, int Tp, int H, size_t 
   const int hv = (int)(head_bytes / 16), hvp = (int)(head_bytes_padded / 16);
   ProfScope ps("unpad_rows_kernel", st);
   unpad_rows_kernel<<<blocks_for((long long)B * T * H * hv), 256, 0, st>>>((const uint4*)src, (uint4*)dst, B, T, Tp, H, hv, hvp);
+}
+
+void gather_tails(int n, const void* const* src, void* const* tail, const int* H, int B, int T, hipStream_t st) {
+  TailSet s = {};
+  int Hmax = 1;
+  for (int i = 0; i < n && i < 4; ++i) { s.src[i] = (const uint4*)src[i]; s.dst[i] = (uint4*)tail[i]; s.H[i] = H[i]; Hmax = H[i] > Hmax ? H[i] : Hmax; }
+  ProfScope ps("tail_rows_kernel(gather)", st);
+  tail_rows_kernel<true><<<dim3(blocks_for((long long)B * 128 * Hmax * 16), n), 256, 0, st>>>(s, B, T, T / 128 * 128);
+}
+
+void scatter_tails(int n, const void* const* tail, void* const* dst, const int* H, int B, int T, hipStream_t st) {
+  TailSet s = {};
+  int Hmax = 1;
+  for (int i = 0; i < n && i < 4; ++i) { s.src[i] = (const uint4*)tail[i]; s.dst[i] = (uint4*)dst[i]; s.H[i] = H[i]; Hmax = H[i] > Hmax ? H[i] : Hmax; }
+  ProfScope ps("tail_rows_kernel(scatter)", st);
+  tail_rows_kernel<false><<<dim3(blocks_for((long long)B * 128 * Hmax * 16), n), 256, 0, st>>>(s, B, T, T / 128 * 128);
 }
 
 }  // namespace rattn

@@ -5,6 +5,7 @@
 #include "common.hpp"
 #include "kernels.hpp"
 #include "mfma.hpp"
+#include <limits.h>
 
 namespace rattn {
 
@@ -14,7 +15,11 @@ struct ChunkArgs {
   const uint16_t* a;   // rows that go through phi  (k, or q for the reverse states)
   const uint16_t* b;   // rows multiplied in        (v, or dx_r)
   float* U;            // [B,Hkv,nchunks,128,128] fp32, U^T = B^T phi(A)
-  int T, H, GA;        // heads in a/b, heads summed per kv head
+  // rows per sequence of a and of b as laid out in memory; rows >= Tfull_a / Tfull_b come from the 128-row tail
+  // buffers instead (ragged lengths, see split_rows; INT_MAX and null when the tensor holds every row itself)
+  const uint16_t *a_tail, *b_tail;
+  int Ta, Tb, Tfull_a, Tfull_b;
+  int H, GA;           // heads in a/b, heads summed per kv head
   int tok_off;         // token index = t' + tok_off
   int first_lo, first_n, rest_lo, ckeys, tok_end;  // chunk 0 = [first_lo, +first_n); chunk c > 0 = ckeys tokens from
                                                    // rest_lo + ckeys (c-1); every chunk is clipped at tok_end
@@ -34,13 +39,16 @@ __global__ __launch_bounds__(256, 2) void rla_chunk_kernel(ChunkArgs p) {
   const size_t rstride = (size_t)p.H * 128;
   f32x16_t acc[4] = {{0}, {0}, {0}, {0}};
   for (int ga = 0; ga < p.GA; ++ga) {
-    const size_t off = ((size_t)(b * p.T + lo + p.tok_off) * p.H + g * p.GA + ga) * 128;
+    const int row = lo + p.tok_off, hd = g * p.GA + ga;   // chunks start at multiples of 64 rows
     if (ga > 0) __syncthreads();
-    tile_load_async<4>(p.a + off, rstride, At, w * 4, lane);
-    tile_load_async<4>(p.b + off, rstride, Bt, w * 4, lane);
+    tile_load_async<4>(split_rows(p.a, p.a_tail, b, row, p.Ta, p.Tfull_a, p.H, hd), rstride, At, w * 4, lane);
+    tile_load_async<4>(split_rows(p.b, p.b_tail, b, row, p.Tb, p.Tfull_b, p.H, hd), rstride, Bt, w * 4, lane);
     if (ntok == 128) {
-      tile_load_async<4>(p.a + off, rstride, At, 16 + w * 4, lane);
-      tile_load_async<4>(p.b + off, rstride, Bt, 16 + w * 4, lane);
+      // rows 64..127 have their own source (they may be the ragged tail); the loader adds 64 row strides for these
+      // blocks, so the base is given 64 rows back (never dereferenced there)
+      const size_t back = (size_t)64 * rstride;
+      tile_load_async<4>(split_rows(p.a, p.a_tail, b, row + 64, p.Ta, p.Tfull_a, p.H, hd) - back, rstride, At, 16 + w * 4, lane);
+      tile_load_async<4>(split_rows(p.b, p.b_tail, b, row + 64, p.Tb, p.Tfull_b, p.H, hd) - back, rstride, Bt, 16 + w * 4, lane);
     }
     wait_vmem();
     __syncthreads();
@@ -143,13 +151,16 @@ void launch_chunk_kernel(int fm, dim3 grid, const ChunkArgs& p, hipStream_t st) 
 }  // namespace
 
 void rla_forward_states(const LayerDims& dm, const FastFwdPlan& pl, const void* k, const void* v, float* U,
-                        void* states, hipStream_t st, const float* state0) {
+                        void* states, hipStream_t st, const float* state0, const RaggedTails* tails) {
   if (pl.nstf <= 0) return;
   const int head = pl.base > 0 ? 1 : 0;  // products in front of state 0: the 64 keys before it when it sits at key 64
   if (pl.nchunks > 0) {
     ChunkArgs p;
     p.a = (const uint16_t*)k; p.b = (const uint16_t*)v; p.U = U;
-    p.T = dm.T; p.H = dm.Hkv; p.GA = 1; p.tok_off = 0;
+    p.a_tail = tails ? (const uint16_t*)tails->k : nullptr; p.b_tail = tails ? (const uint16_t*)tails->v : nullptr;
+    p.Ta = p.Tb = tails ? tails->Tc : dm.T;
+    p.Tfull_a = p.Tfull_b = tails ? tails->Tc / 128 * 128 : INT_MAX;
+    p.H = dm.Hkv; p.GA = 1; p.tok_off = 0;
     p.ckeys = pl.ckeys;
     p.first_lo = 0; p.first_n = head ? 64 : pl.ckeys; p.rest_lo = p.first_n; p.tok_end = 1 << 30;
     ProfScope ps("rla_chunk_kernel", st);
@@ -162,13 +173,16 @@ void rla_forward_states(const LayerDims& dm, const FastFwdPlan& pl, const void* 
 }
 
 void rla_reverse_states(const LayerDims& dm, const FastBwdPlan& pl, const void* q, const void* dxr, float* U,
-                        void* rstates, hipStream_t st) {
+                        void* rstates, hipStream_t st, const RaggedTails* tails) {
   if (pl.nk <= 0) return;
   const int W = pl.fwd.W, Tp = dm.T - W, ck = pl.fwd.ckeys;
   if (pl.nrchunks > 0) {
     ChunkArgs p;
     p.a = (const uint16_t*)q; p.b = (const uint16_t*)dxr; p.U = U;
-    p.T = dm.T; p.H = dm.Hq; p.GA = dm.G; p.tok_off = W;
+    p.a_tail = tails ? (const uint16_t*)tails->q : nullptr; p.b_tail = nullptr;   // dx_r is a workspace tensor
+    p.Ta = tails ? tails->Tc : dm.T; p.Tb = dm.T;
+    p.Tfull_a = tails ? tails->Tc / 128 * 128 : INT_MAX; p.Tfull_b = INT_MAX;
+    p.H = dm.Hq; p.GA = dm.G; p.tok_off = W;
     p.ckeys = ck;
     p.first_lo = 128; p.first_n = ck; p.rest_lo = 128 + ck; p.tok_end = Tp;
     ProfScope ps("rla_chunk_kernel(rev)", st);

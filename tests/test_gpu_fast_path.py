@@ -279,10 +279,13 @@ def test_fast_bwd_is_deterministic():
         assert torch.equal(x1, x2)
 
 
-@pytest.mark.parametrize("B,T,Hq,Hkv,W", [(1, 1100, 2, 1, 128), (2, 1025, 4, 2, 513), (1, 1279, 3, 1, 1279)])
-def test_ragged_length_runs_on_padded_copies(B, T, Hq, Hkv, W):
-    """Sequence lengths >= 1024 that are no multiple of 128 go through the matrix-core kernels on zero-padded
-    copies (the layer is causal; zero rows of dO add nothing to any gradient): same bars as the aligned cases."""
+@pytest.mark.parametrize("B,T,Hq,Hkv,W", [(1, 1100, 2, 1, 128), (2, 1025, 4, 2, 513), (1, 1279, 3, 1, 1279),
+                                          (2, 1217, 6, 2, 192), (1, 1500, 2, 2, 100), (1, 2000, 4, 1, 512)])
+def test_ragged_length_runs_on_the_matrix_cores(B, T, Hq, Hkv, W):
+    """Sequence lengths >= 1024 that are no multiple of 128 run on the matrix-core kernels in place; only the last,
+    partial tile of every sequence goes through zero-padded buffers (the layer is causal; zero rows of dO add nothing
+    to any gradient): same bars as the aligned cases.  Tail lengths 1 .. 127, both state alignments, a window that is
+    no multiple of 64, several sequences per batch (the batch stride is the true length)."""
     D = 128
     x = synth.make_random_layer(B, T, Hq, Hkv, D, "bf16", 2300 + T + W, with_dO=True, with_gains=True)
     scale = 1.0 / math.sqrt(D)
@@ -295,7 +298,8 @@ def test_ragged_length_runs_on_padded_copies(B, T, Hq, Hkv, W):
     torch.cuda.synchronize()
     names = [n for n, _ in rb.rattn_profile_records()]
     rb.rattn_profile_enable(False)
-    assert "fwd_fused_kernel" in names and "bwd_dkv_kernel" in names and "pad_rows_kernel" in names
+    assert "fwd_fused_kernel" in names and "bwd_dkv_kernel" in names and "tail_rows_kernel(gather)" in names
+    assert "pad_rows_kernel" not in names   # no copies of whole tensors
     kw = dict(scale=scale, gamma_swa=np64(gs), gamma_rla=np64(gr))
     ref = orc.fwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), W, **kw)
     gmax = max(float(gs.abs().max()), float(gr.abs().max()), 1.0)
@@ -310,6 +314,30 @@ def test_ragged_length_runs_on_padded_copies(B, T, Hq, Hkv, W):
         else:
             rms = math.sqrt(float(np.mean(refb[n] ** 2)))
             assert float(np.max(np.abs(np64(g_) - refb[n]))) / rms <= 2e-2, n
+
+
+@pytest.mark.parametrize("ck,policy", [(128, "keep"), (64, "rebuild")])
+def test_ragged_length_full_tiles_match_the_truncated_sequence(ck, policy):
+    """The layer is causal and the kernels work tile by tile: every row in front of the last, partial tile is
+    bit-identical to the same call on the sequence cut at that tile boundary, and the gradients of a dO that is zero
+    from there on are those of the cut sequence, bit for bit."""
+    B, T, Hq, Hkv, D, W = 2, 1300, 4, 2, 128, 256
+    Tf = T // 128 * 128
+    x = synth.make_random_layer(B, T, Hq, Hkv, D, "bf16", 4411, with_dO=True)
+    q, k, v, dO = x["q"].cuda(), x["k"].cuda(), x["v"].cuda(), x["dO"].cuda()
+    dO[:, Tf:] = 0
+    kw = dict(softmax_scale=0.09, chunk=ck, state_policy=policy)
+    print(f"ragged vs cut sequence, chunk {ck}, states {policy}", flush=True)
+    o, saved = rb.rattn_fwd(q, k, v, W, save_for_bwd=True, **kw)
+    g = rb.rattn_bwd(q, k, v, saved, dO, W, want_dgamma=False, **kw)
+    qc, kc, vc, dOc = (a[:, :Tf].contiguous() for a in (q, k, v, dO))
+    oc, savedc = rb.rattn_fwd(qc, kc, vc, W, save_for_bwd=True, **kw)
+    gc = rb.rattn_bwd(qc, kc, vc, savedc, dOc, W, want_dgamma=False, **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(o[:, :Tf], oc)
+    for n, a, c in zip(("dq", "dk", "dv"), g[:3], gc[:3]):
+        assert torch.equal(a[:, :Tf], c), n
+        assert float(a[:, Tf:].abs().max()) == 0.0, n   # rows that no query with a gradient reads
 
 
 def test_side_stream_matches_default_stream():

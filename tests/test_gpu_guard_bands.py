@@ -1,6 +1,6 @@
 """Out-of-bounds writes: every buffer the library writes (outputs, `saved`, workspace, gradients, rings, state) is
 carved out of a larger allocation with 4 KiB of a known byte pattern in front of and behind it; after the call the
-pattern must be intact.  Shapes: a 3B-layer-shaped case, a ragged length (padded copies in the workspace), windows that
+pattern must be intact.  Shapes: a 3B-layer-shaped case, a ragged length (tail buffers in the workspace), windows that
 are no tile multiples (the extra key tile of the linear branch), the general kernels, chunked prefill on both routes,
 prefill export and decode.  Nothing here provokes a fault: all sizes are the ones the library itself reports."""
 import ctypes
@@ -47,7 +47,7 @@ def guarded_like(t, name):
 LAYER_CASES = [
     # B, T, Hq, Hkv, D, W, dtype, path
     (1, 1024, 6, 2, 128, 512, "bf16", "auto"),     # the benchmark layer's head ratio and window
-    (2, 1100, 2, 1, 128, 300, "bf16", "auto"),     # ragged: padded copies of q, k, v, o, dO, dq, dk, dv in the workspace
+    (2, 1100, 2, 1, 128, 300, "bf16", "auto"),     # ragged: the last partial tile of q, k, v, o, dO, dq, dk, dv goes through the workspace
     (1, 640, 4, 2, 128, 513, "bf16", "auto"),      # window = 512 earlier tokens + the current one
     (1, 384, 3, 1, 128, 100, "bf16", "auto"),      # gap > 0, states at the 64 alignment
     (1, 256, 2, 1, 128, 250, "bf16", "auto"),      # window rounds up to T
