@@ -73,7 +73,7 @@ def measured_traffic(kernel, workload):
             rows = json.loads(f.read().split("---JSON---", 1)[1])
     except (OSError, IndexError, ValueError):
         return None, info
-    from paper_2506_15545_amd import profile_summary
+    import profile_summary
     info["kernel_sources_of_summary"] = rows.get("_kernel_sources")
     info["stale"] = rows.get("_kernel_sources") != profile_summary.kernel_sources_digest()
     return rows.get(kernel, {}).get("hbm_bytes_per_launch"), info

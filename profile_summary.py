@@ -3,10 +3,10 @@
 
 Runs on the CPU over directories a profiling run left behind; it launches nothing.
 
-    python -m paper_2506_15545_amd.profile_summary stats   <rocprofv3 -d dir> <out.txt> "<command>"
-    python -m paper_2506_15545_amd.profile_summary traffic <FETCH_SIZE dir> <WRITE_SIZE dir> <out.txt> \
+    python profile_summary.py stats   <rocprofv3 -d dir> <out.txt> "<command>"
+    python profile_summary.py traffic <FETCH_SIZE dir> <WRITE_SIZE dir> <out.txt> \
            <workload> "<fetch command>" "<write command>"
-    python -m paper_2506_15545_amd.profile_summary mfma    <SQ counters dir> <out.txt> "<command>"
+    python profile_summary.py mfma    <SQ counters dir> <out.txt> "<command>"
 
 `stats` lists calls / average / min / max duration per kernel from the `--kernel-trace --stats` run.
 `traffic` averages the FETCH_SIZE and WRITE_SIZE readings per dispatch of every kernel and scales them by
@@ -36,7 +36,7 @@ CAL_BYTES = 256 * 2 ** 20
 def kernel_sources_digest():
     """sha256 over the library's kernel sources (csrc/*, sorted by name): written into every summary, so that a
     reader (and bench.py) can tell whether a summary was taken from the kernels that are in the tree now."""
-    d = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc")
+    d = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2506_15545_amd", "csrc")
     h = hashlib.sha256()
     for name in sorted(os.listdir(d)):
         if name.endswith((".hip", ".hpp")):
@@ -44,6 +44,8 @@ def kernel_sources_digest():
             with open(os.path.join(d, name), "rb") as f:
                 h.update(f.read())
     return h.hexdigest()[:16]
+
+
 ALIASES = {"decode_kernel_2pass": "decode_kernel"}   # the name bench.py reports the decode launch under
 WORKLOAD_KERNELS = {"decode_b128_w512": ("decode_kernel",)}
 
