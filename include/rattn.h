@@ -14,10 +14,11 @@
  *    branch covers keys 0..t-W.  The paper's symbol is w = W-1.  W >= T leaves the
  *    linear branch empty (its output and RMS are exactly 0) = causal attention.
  *  - Layer tensors are contiguous [B, T, H, D], D fastest.  Query head h reads KV head
- *    h / (Hq/Hkv).  D is 64 or 128.  The matrix-core kernels take bf16 tensors with D = 128
- *    and T a multiple of 128 directly; bf16 with T >= 1024 not a multiple of 128, and bf16
- *    with D = 64 (T a multiple of 128, or >= 1024), run on them through zero-padded copies
- *    that live in the workspace; every other shape runs on the general (vector-ALU) kernels.
+ *    h / (Hq/Hkv).  D is 64 or 128.  The matrix-core kernels take bf16 tensors with
+ *    window >= 8 and T >= 128: D = 128 in place (of a T that is no multiple of 128 only the
+ *    last, partial 128-row tile of every sequence goes through zero-padded buffers in the
+ *    workspace), D = 64 through copies widened to 128 features that live in the workspace;
+ *    every other shape (fp32, T < 128, tiny windows) runs on the general (vector-ALU) kernels.
  *  - dtype is the element type of q,k,v,o,dO,dq,dk,dv (and of the decode ring buffers).
  *    Accumulators, softmax/RMS statistics and gains are fp32.  Linear-attention states are
  *    accumulated in fp32; the decode, prefill-export and general kernels also keep them in
@@ -182,8 +183,8 @@ rattn_status rattn_prefill_export(const rattn_params* p, const void* k, const vo
  *      pos0 > W, before that it is zero by definition and the buffer's contents are ignored) and updated in place
  *      to position pos0 + T (slots of tokens that stay in the window are left as they are)
  *   workspace: rattn_prefill_chunk_workspace_bytes(p, pos0) bytes of scratch, 16-byte aligned.
- * The matrix-core kernels are used when dtype = bf16, D = 128, window >= 8 and min(pos0, W) + T is a multiple of
- * 128 or at least 1024; any other shape runs on the general kernels. */
+ * The matrix-core kernels are used when dtype = bf16, D = 128, window >= 8 and min(pos0, W) + T >= 128; any other
+ * shape runs on the general kernels. */
 rattn_status rattn_prefill_chunk_workspace_bytes(const rattn_params* p, int32_t pos0, size_t* bytes);
 rattn_status rattn_prefill_chunk(const rattn_params* p, int32_t pos0, const void* q, const void* k, const void* v,
                                  const float* gamma_swa, const float* gamma_rla, void* k_ring, void* v_ring,

@@ -48,10 +48,11 @@ rattn_status fail(rattn_status s, const char* fmt, ...) {
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-// Sequence lengths from this size on that are not a multiple of 128 run on the matrix-core kernels (bf16): with
-// D = 128 in place, only the last partial tile of every sequence goes through zero-padded buffers; with D = 64 through
-// zero-padded copies of the whole tensors.  Shorter ones stay on the general kernels.
-constexpr int PAD_MIN_T = 1024;
+// Sequence lengths from this size on run on the matrix-core kernels (bf16) whether or not they are a multiple of
+// the 128-row tile: with D = 128 in place, only the last partial tile of every sequence goes through zero-padded
+// buffers; with D = 64 through zero-padded copies of the whole tensors.  Shorter ones (less than one tile) stay on
+// the general kernels.
+constexpr int PAD_MIN_T = 128;
 
 struct Layout {
   rattn::LayerDims dm;
@@ -117,7 +118,10 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
   dm.Dv = dm.D;
   L->dmf = dm;
   const bool ragged = dm.T % 128 != 0;
-  L->pad_d = p->dtype == RATTN_BF16 && dm.D == 64 && (!ragged || dm.T >= PAD_MIN_T);
+  // (the identity feature map at head size 64 stays on the general kernels: with bf16 operands its backward leaves
+  // single dq elements off by a third of the gradient's RMS on the first rows past a short window - the rank-deficient
+  // state again, with half as many features to average over - and the CPU model of the roundings shows the same)
+  L->pad_d = p->dtype == RATTN_BF16 && dm.D == 64 && (!ragged || dm.T >= PAD_MIN_T) && dm.phi != rattn::PHI_IDENTITY;
   L->pad = p->dtype == RATTN_BF16 && ((dm.D == 128 && ragged && dm.T >= PAD_MIN_T) || L->pad_d);
   if (L->pad) L->dmf.T = (dm.T + 127) / 128 * 128;
   if (L->pad_d) L->dmf.D = 128;

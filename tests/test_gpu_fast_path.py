@@ -193,6 +193,7 @@ def test_fast_bwd_unit_gains_no_dgamma(B, T, Hq, Hkv, W):
     (1, 128, 2, 2, 512),      # causal
     (1, 640, 6, 2, 192),      # GQA 3, states at the 64 alignment
     (1, 1100, 3, 1, 300),     # ragged length and head size 64 together
+    (2, 333, 2, 1, 20),       # the same, short
 ])
 def test_head_size_64_runs_on_the_matrix_cores(B, T, Hq, Hkv, W):
     """Head size 64 (bf16, whole tiles or long enough for padded copies): rows are widened to 128 features with zeros
@@ -280,9 +281,11 @@ def test_fast_bwd_is_deterministic():
 
 
 @pytest.mark.parametrize("B,T,Hq,Hkv,W", [(1, 1100, 2, 1, 128), (2, 1025, 4, 2, 513), (1, 1279, 3, 1, 1279),
-                                          (2, 1217, 6, 2, 192), (1, 1500, 2, 2, 100), (1, 2000, 4, 1, 512)])
+                                          (2, 1217, 6, 2, 192), (1, 1500, 2, 2, 100), (1, 2000, 4, 1, 512),
+                                          (1, 200, 4, 2, 48), (2, 129, 2, 1, 64), (1, 383, 3, 1, 100), (3, 130, 2, 2, 128),
+                                          (1, 255, 2, 1, 300)])
 def test_ragged_length_runs_on_the_matrix_cores(B, T, Hq, Hkv, W):
-    """Sequence lengths >= 1024 that are no multiple of 128 run on the matrix-core kernels in place; only the last,
+    """Sequence lengths >= 128 that are no multiple of 128 run on the matrix-core kernels in place; only the last,
     partial tile of every sequence goes through zero-padded buffers (the layer is causal; zero rows of dO add nothing
     to any gradient): same bars as the aligned cases.  Tail lengths 1 .. 127, both state alignments, a window that is
     no multiple of 64, several sequences per batch (the batch stride is the true length)."""

@@ -90,10 +90,13 @@ def test_layer_f32(fm, B, T, Hq, Hkv, D, W, chunk):
 
 
 @pytest.mark.parametrize("fm", MAPS)
-@pytest.mark.parametrize("B,T,Hq,Hkv,D,W", [(1, 256, 4, 2, 128, 64), (2, 333, 2, 1, 64, 20), (1, 1100, 2, 1, 128, 100)])
+@pytest.mark.parametrize("B,T,Hq,Hkv,D,W", [(1, 256, 4, 2, 128, 64), (2, 333, 2, 1, 64, 20), (1, 1100, 2, 1, 128, 100),
+                                              (2, 100, 2, 1, 64, 20), (1, 90, 2, 2, 128, 30)])
 def test_layer_bf16(fm, B, T, Hq, Hkv, D, W):
-    # head size 128 in whole tiles (or long enough for padded copies): both maps run on the matrix-core kernels
-    layer_case(fm, B, T, Hq, Hkv, D, W, "bf16", 950 + T, mfma=(D == 128))
+    # from one 128-row tile on, both maps run on the matrix-core kernels (ragged lengths, head size 64 included);
+    # shorter sequences on the general kernels
+    # (the identity map at head size 64 stays on the general kernels: see make_layout in csrc/api.hip)
+    layer_case(fm, B, T, Hq, Hkv, D, W, "bf16", 950 + T, mfma=(T >= 128 and not (fm == "identity" and D == 64)))
 
 
 @pytest.mark.parametrize("B,T,Hq,Hkv,W", [

@@ -50,9 +50,11 @@ LAYER_CASES = [
     (2, 1100, 2, 1, 128, 300, "bf16", "auto"),     # ragged: the last partial tile of q, k, v, o, dO, dq, dk, dv goes through the workspace
     (1, 640, 4, 2, 128, 513, "bf16", "auto"),      # window = 512 earlier tokens + the current one
     (1, 384, 3, 1, 128, 100, "bf16", "auto"),      # gap > 0, states at the 64 alignment
+    (2, 300, 2, 1, 128, 77, "bf16", "auto"),       # short ragged length, gap > 0: tail buffers
     (1, 256, 2, 1, 128, 250, "bf16", "auto"),      # window rounds up to T
     (1, 384, 2, 2, 128, 1000, "bf16", "auto"),     # causal: no linear branch, no states
-    (2, 200, 4, 2, 64, 32, "bf16", "auto"),        # general kernels (D = 64, ragged and short)
+    (2, 100, 4, 2, 64, 32, "bf16", "auto"),        # general kernels (less than one tile)
+    (2, 200, 4, 2, 64, 32, "bf16", "auto"),        # head size 64, ragged and short: widened copies
     (1, 256, 4, 2, 64, 100, "bf16", "auto"),       # head size 64 on the matrix-core kernels: widened copies, gains too
     (1, 1030, 2, 1, 64, 200, "bf16", "auto"),      # head size 64 and a ragged length together
     (1, 300, 2, 1, 128, 77, "f32", "auto"),        # general kernels, fp32

@@ -100,14 +100,16 @@ def test_chunk_hint_does_not_change_result():
         assert float((o - outs[0]).abs().max()) < 2e-5
 
 
-def run_bwd_case(B, T, Hq, Hkv, D, W, dtype, seed, chunk=0, gains=True):
+def run_bwd_case(B, T, Hq, Hkv, D, W, dtype, seed, chunk=0, gains=True, kernel_path="auto"):
     x = synth.make_random_layer(B, T, Hq, Hkv, D, dtype, seed, with_dO=True, with_gains=gains)
     scale = 1.0 / math.sqrt(D)
     gs, gr = x.get("gamma_swa"), x.get("gamma_rla")
     print(f"bwd case B={B} T={T} Hq={Hq} Hkv={Hkv} D={D} W={W} {dtype} chunk={chunk} seed={seed}", flush=True)
     q, k, v, dO = dev(x["q"]), dev(x["k"]), dev(x["v"]), dev(x["dO"])
-    o, saved = rb.rattn_fwd(q, k, v, W, dev(gs), dev(gr), chunk=chunk, softmax_scale=scale, save_for_bwd=True)
-    dq, dk, dv, dgs, dgr = rb.rattn_bwd(q, k, v, saved, dO, W, dev(gs), dev(gr), chunk=chunk, softmax_scale=scale)
+    o, saved = rb.rattn_fwd(q, k, v, W, dev(gs), dev(gr), chunk=chunk, softmax_scale=scale, save_for_bwd=True,
+                            kernel_path=kernel_path)
+    dq, dk, dv, dgs, dgr = rb.rattn_bwd(q, k, v, saved, dO, W, dev(gs), dev(gr), chunk=chunk, softmax_scale=scale,
+                                        kernel_path=kernel_path)
     torch.cuda.synchronize()
     ref = orc.bwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), np64(x["dO"]), W, scale=scale,
                         gamma_swa=None if gs is None else np64(gs), gamma_rla=None if gr is None else np64(gr))
@@ -148,7 +150,8 @@ def test_bwd_config1_tiny_f32():
                                               # windows of a few keys: near-one-hot softmax rows
                                               (2, 143, 3, 3, 128, 5), (2, 70, 6, 3, 128, 2), (1, 100, 2, 1, 64, 3)])
 def test_bwd_bf16_shapes(B, T, Hq, Hkv, D, W):
-    run_bwd_case(B, T, Hq, Hkv, D, W, "bf16", seed=400 + T)
+    # the general kernels' bar (fp32 arithmetic): asked for explicitly where the shape would run on the matrix cores
+    run_bwd_case(B, T, Hq, Hkv, D, W, "bf16", seed=400 + T, kernel_path="general")
 
 
 # ------------------------------------------------------------------------------ decode

@@ -32,8 +32,8 @@ def test_static_entry_matches_workspace_entry_on_two_calls_in_a_row():
     cases = [
         (2, 2048, 8, 2, 128, 256, 31),    # matrix-core path, 14 chunk states per KV head
         (1, 640, 4, 2, 128, 192, 32),     # smaller: reuses the front of the dirty buffer; states at the 64 alignment
-        (1, 1100, 2, 1, 128, 300, 33),    # ragged length: padded copies of q, k, v, o live in the scratch too
-        (1, 200, 4, 2, 64, 32, 34),       # general kernels (D = 64): fp32 chunk states in the scratch
+        (1, 1100, 2, 1, 128, 300, 33),    # ragged length: the tail buffers of q, k, v, o live in the scratch too
+        (1, 100, 4, 2, 64, 32, 34),       # general kernels (less than one tile): fp32 chunk states in the scratch
     ]
     for (B, T, Hq, Hkv, D, W, seed) in cases:
         print(f"static entry case B={B} T={T} Hq={Hq} Hkv={Hkv} D={D} W={W}", flush=True)
@@ -53,8 +53,8 @@ def test_static_entry_matches_workspace_entry_on_two_calls_in_a_row():
         assert torch.cuda.memory_allocated() == before
         # same kernels on the same inputs: the bits agree (stronger than the parity tolerance)
         assert torch.equal(o, o_ref)
-        n = 2 * B * T * Hq * D * (2 if D == 128 and (T % 128 == 0 or T >= 1024) else 4)
-        if T % 128 == 0 or D == 64:  # pre-norm branch outputs (for padded lengths the layout is for the padded T)
+        n = 2 * B * T * Hq * D * (2 if T >= 128 else 4)
+        if T % 128 == 0 or T < 128:  # pre-norm branch outputs (for ragged lengths the layout is for the padded T)
             assert torch.equal(saved[:n], saved_ref[:n])
         # and without saving
         o2 = torch.full_like(q, float("nan"))
