@@ -228,11 +228,18 @@ def main():
         return e0.elapsed_time(e1) / n
 
     # What this device sustains on nothing but matrix-core instructions, and on a plain copy: context for the fractions
-    # of the published peaks below.  These probes run first: the device needs some tens of milliseconds of work to
-    # reach its steady clocks (the first 20 steps after idling take 1.01 ms each, later ones 0.92), more than a short
-    # warm-up of the step itself provides.
+    # of the published peaks below.  These probes run first, the matrix-core loop last: the device needs some tens of
+    # milliseconds of work to reach its steady clocks (the first 20 steps after idling take 1.0 ms each, later ones
+    # 0.91; after 100 ms of the matrix-core loop 0.91 at once), more than a short warm-up of the step itself provides.
     machine = None
     if not args.no_other_workloads:
+        src = torch.zeros(512 * 2 ** 20 // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)
+        copy_ms = min(timed(lambda: torch.add(src, 1.0, out=dst), 100) for _ in range(3))   # best of 3 rounds, ~17 ms each
+        copy_gbps = 2 * src.numel() * 4 / (copy_ms * 1e-3) / 1e9
+        del src, dst
         sink = torch.zeros(64, dtype=torch.float32, device="cuda")
         rb.rattn_probe_mfma(sink, 8000, 2048)
         torch.cuda.synchronize()
@@ -244,13 +251,6 @@ def main():
             e1.record()
             torch.cuda.synchronize()
             mfma_tflops = max(mfma_tflops, probe_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
-        src = torch.zeros(512 * 2 ** 20 // 4, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            torch.add(src, 1.0, out=dst)
-        copy_ms = min(timed(lambda: torch.add(src, 1.0, out=dst), 100) for _ in range(3))   # best of 3 rounds, ~17 ms each
-        copy_gbps = 2 * src.numel() * 4 / (copy_ms * 1e-3) / 1e9
-        del src, dst
         machine = {"mfma_loop_tflops": mfma_tflops, "copy_GBps": copy_gbps}
 
     for _ in range(args.warmup):
