@@ -225,6 +225,10 @@ __device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, int hq, size_
                                              size_t qstride, size_t stat0, unsigned char* stage_s, unsigned char* stage_r, float* dl_stage,
                                              float* dgp_s, float* dgp_r, int lane) {
   const int sub = lane >> 4, c = lane & 15;
+  // A query tile none of whose rows has a key beyond its window (the first tiles of a sequence; every tile of a
+  // causal layer, W >= T) has x_r = 0: the forward does not store it, no later kernel reads its d x_r, and neither
+  // is touched here.  The caller passes `stage_r` exactly for the tiles that have a linear branch (wave-uniform).
+  const bool with_r = stage_r != nullptr;
   uint16_t* dxs_w = const_cast<uint16_t*>(a.dxs);
   uint16_t* dxr_w = const_cast<uint16_t*>(a.dxr);
   float* delta_w = const_cast<float*>(a.delta);
@@ -242,8 +246,11 @@ __device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, int hq, size_
     float dy[8], xs[8], xr[8];
     unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(dO_row0 + (size_t)r * qstride + 8 * c)), dy);
     unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(a.xs + off)), xs);
-    unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(a.xr + off)), xr);
-    if (a.xr_lo) {  // wave-uniform
+    if (with_r) unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(a.xr + off)), xr);
+    else
+#pragma unroll
+      for (int e = 0; e < 8; ++e) xr[e] = 0.f;
+    if (with_r && a.xr_lo) {  // wave-uniform
       float lo[8];
       unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(a.xr_lo + off)), lo);
 #pragma unroll
@@ -277,7 +284,7 @@ __device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, int hq, size_
 #pragma unroll
     for (int e = 0; e < 8; ++e) dl = fmaf(av[e], xs[e], dl);
     __builtin_nontemporal_store(apk, reinterpret_cast<bf16x8_t*>(dxs_w + off));
-    __builtin_nontemporal_store(cpk, reinterpret_cast<bf16x8_t*>(dxr_w + off));
+    if (with_r) __builtin_nontemporal_store(cpk, reinterpret_cast<bf16x8_t*>(dxr_w + off));
     {  // staged in two 16-row pieces, see dxs_stage_addr
       const int R = r & 15;
       *reinterpret_cast<bf16x8_t*>(stage_s + (r >> 4) * 16384 + R * ROW_BYTES + ((c ^ swz(R)) << 4)) = apk;

@@ -398,8 +398,9 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) vals[dt][i] = xr[dt][i];
-    store_tile_transposed(smem, vals, a.xr_out + qtile_off, qstride, w, lane);
-    if (FM == FM_IDENTITY && a.xr_lo_out) {  // what the bf16 value above leaves of x_r, as a second bf16 tensor
+    // (a tile without residual keys has x_r = 0, which backward knows from the tile's position: not stored)
+    if (has_lin) store_tile_transposed(smem, vals, a.xr_out + qtile_off, qstride, w, lane);
+    if (has_lin && FM == FM_IDENTITY && a.xr_lo_out) {  // what the bf16 value above leaves of x_r, as a second bf16 tensor
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt)
 #pragma unroll

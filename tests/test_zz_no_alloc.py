@@ -53,8 +53,8 @@ def test_static_entry_matches_workspace_entry_on_two_calls_in_a_row():
         assert torch.cuda.memory_allocated() == before
         # same kernels on the same inputs: the bits agree (stronger than the parity tolerance)
         assert torch.equal(o, o_ref)
-        n = 2 * B * T * Hq * D * (2 if T >= 128 else 4)
-        if T % 128 == 0 or T < 128:  # pre-norm branch outputs (for ragged lengths the layout is for the padded T)
+        n = B * T * Hq * D * (2 if T >= 128 else 4)
+        if T % 128 == 0 or T < 128:  # pre-norm output of the softmax branch (ragged lengths: laid out for the padded T)
             assert torch.equal(saved[:n], saved_ref[:n])
         # and without saving
         o2 = torch.full_like(q, float("nan"))
