@@ -91,6 +91,30 @@ def test_layer3b_literal_window_513():
             pm.assert_grad_bf16(np64(group(cfg, got, b, g)), ref[name], f"{cfg.name} {name}[{b},{g}]")
 
 
+def test_layer3b_ragged_length_4000():
+    """The 3B-shaped layer at T = 4000 (31 whole tiles + 32 rows; what `bench.py` times as the ragged workload):
+    the rows in front of the partial tile are bit-identical to the call on the sequence cut there, and one group is
+    compared with the oracle over all 4000 rows (forward and backward)."""
+    import dataclasses
+    cfg = dataclasses.replace(synth.CONFIGS["layer3b_t4096_w512"], name="layer3b_t4000_w512", T=4000)
+    q, k, v, dO = synth.make_layer_inputs(cfg, with_dO=True)
+    Tf = cfg.T // 128 * 128
+    print("layer3b at T = 4000: forward + backward on the GPU", flush=True)
+    qd, kd, vd, dOd = q.cuda(), k.cuda(), v.cuda(), dO.cuda()
+    o, saved = rb.rattn_fwd(qd, kd, vd, cfg.W, softmax_scale=cfg.scale, save_for_bwd=True)
+    dq, dk, dv, _, _ = rb.rattn_bwd(qd, kd, vd, saved, dOd, cfg.W, softmax_scale=cfg.scale, want_dgamma=False)
+    oc = rb.rattn_fwd(qd[:, :Tf].contiguous(), kd[:, :Tf].contiguous(), vd[:, :Tf].contiguous(), cfg.W,
+                      softmax_scale=cfg.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(o[:, :Tf], oc)
+    b, g = 2, 5
+    for _ in check_fwd_groups(cfg, q, k, v, o, [(b, g)]):
+        print(f"  oracle bwd batch {b} kv-group {g}", flush=True)
+        ref = orc.bwd_dense(*[np64(group(cfg, t, b, g)) for t in (q, k, v, dO)], cfg.W, scale=cfg.scale)
+        for name, got in (("dq", dq), ("dk", dk), ("dv", dv)):
+            pm.assert_grad_bf16(np64(group(cfg, got, b, g)), ref[name], f"{cfg.name} {name}[{b},{g}]")
+
+
 def test_layer3b_relu_feature_map():
     """The 3B-shaped layer with the ablation's ReLU feature map (Sec. 4.5) on the matrix-core kernels: forward and
     backward of the whole tensor, one group checked against the oracle."""
