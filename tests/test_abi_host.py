@@ -199,3 +199,27 @@ def test_matrix_core_chunk_size_defaults_to_128_keys():
     _, _, s_keep = rb.rattn_workspace_bytes(params(**base))
     _, _, s_rebuild = rb.rattn_workspace_bytes(params(state_policy=1, **base))
     assert s_keep - s_rebuild == state_bytes
+
+
+def test_ragged_lengths_cost_tail_buffers_not_copies():
+    """A bf16, D = 128 length that is no multiple of 128 runs in place on the matrix-core kernels: on top of the
+    scratch of the length rounded up, the workspace holds one 128-row buffer per tensor that passes through the
+    kernels (forward q, k, v, o; backward q, k, v, dO, dq, dk, dv) and `saved` is that of the rounded-up length.
+    A head size of 64 pays whole widened copies instead; lengths below one tile stay on the general kernels."""
+    B, Hq, Hkv = 2, 6, 2
+    base = dict(B=B, Hq=Hq, Hkv=Hkv, D=128, window=256, dtype=rb.RATTN_BF16)
+    f_al, b_al, s_al = rb.rattn_workspace_bytes(params(T=2048, **base))
+    f_rg, b_rg, s_rg = rb.rattn_workspace_bytes(params(T=2000, **base))
+    tail_q, tail_kv = B * 128 * Hq * 128 * 2, B * 128 * Hkv * 128 * 2
+    gains = 2 * Hq * 128 * 4                        # two widened gain rows per head (used at D = 64 only)
+    assert s_rg == s_al
+    assert f_rg == f_al + 2 * tail_q + 2 * tail_kv + gains
+    assert b_rg == b_al + 3 * tail_q + 4 * tail_kv + 2 * gains
+    # D = 64: whole tensors, widened to 128 features, forward and backward
+    f64, b64, _ = rb.rattn_workspace_bytes(params(T=2048, **dict(base, D=64)))
+    full_q, full_kv = B * 2048 * Hq * 128 * 2, B * 2048 * Hkv * 128 * 2
+    assert f64 == f_al + 2 * full_q + 2 * full_kv + gains
+    assert b64 == b_al + 3 * full_q + 4 * full_kv + 2 * gains
+    # less than one tile: general kernels (fp32 branch outputs in `saved`)
+    _, _, s_small = rb.rattn_workspace_bytes(params(T=100, **base))
+    assert s_small >= 2 * B * 100 * Hq * 128 * 4
