@@ -485,11 +485,12 @@ def main():
             other[c_.name] = run_layer(c_, True)
         # The paper's search over what is stored of the chunk states and over the chunk size (Sec. 3.2, Fig. 3: best
         # setting ~15 % faster than storing every state at C = 256), on the matrix-core kernels: chunk states kept in
-        # `saved` for backward or rebuilt there, chunk products of 128 or 64 keys; both benchmark layers, fwd + bwd
+        # `saved` for backward (all of them, m = 1; every 2nd or 4th, m = 2, 4) or rebuilt there, chunk products of 128
+        # or 64 keys; both benchmark layers, fwd + bwd
         search = {}
         for c_ in (cfg, synth.CONFIGS["layer12b_t8192_w512"]):
             rows = {}
-            for pol in ("keep", "rebuild"):
+            for pol in ("keep", "every2", "every4", "rebuild"):
                 for ck in (128, 64):
                     r_ = run_layer(c_, True, chunk=ck, state_policy=pol)
                     rows[f"{pol}_C{ck}"] = {"fwd_ms": r_["fwd_ms"], "bwd_ms": r_["bwd_ms"],

@@ -83,11 +83,17 @@ typedef enum { RATTN_PATH_AUTO = 0, RATTN_PATH_GENERAL = 1 } rattn_kernel_path;
 
 /* The paper's kernel stores chunk states only every m-th chunk and recomputes the others to save accelerator memory,
  * "storing more leads to faster backward passes ... at a higher memory cost" (Sec. 3.2, Fig. 3); it searches over m and
- * the chunk size C.  Here the two ends of that trade are selectable: KEEP stores every chunk state (one per 128 keys,
- * bf16) in `saved` so that backward reads them; REBUILD stores none and backward builds them again from k and v (any
- * subset in between would cost the same rebuild).  The chunk size of the state-building kernels is the `chunk`
- * parameter: 64 selects 64-key chunk products (two per stored state), anything else 128-key products. */
-typedef enum { RATTN_STATES_KEEP = 0, RATTN_STATES_REBUILD = 1 } rattn_state_policy;
+ * the chunk size C.  Here the same trade is selectable: KEEP stores every chunk state (one per 128 keys, bf16) in
+ * `saved` so that backward reads them (m = 1); KEEP_EVERY_2ND / _4TH store states 0, m, 2m, ... and backward forms only
+ * the chunk products that lead to the states in between, continuing from the stored ones (m = 2, 4); REBUILD stores
+ * none and backward builds all of them again from k and v.  The chunk size of the state-building kernels is the `chunk`
+ * parameter: 64 selects 64-key chunk products (two per state), anything else 128-key products. */
+typedef enum {
+  RATTN_STATES_KEEP = 0,
+  RATTN_STATES_REBUILD = 1,
+  RATTN_STATES_KEEP_EVERY_2ND = 2,
+  RATTN_STATES_KEEP_EVERY_4TH = 4
+} rattn_state_policy;
 
 /* Sizes in bytes of the scratch `workspace` rattn_fwd / rattn_bwd need and of the opaque
  * `saved` buffer rattn_fwd fills for rattn_bwd.  Any of the three out pointers (HOST) may

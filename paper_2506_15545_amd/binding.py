@@ -16,8 +16,9 @@ RATTN_F32, RATTN_BF16 = 0, 1
 FEATURE_MAPS = {"softmax": 0, "relu": 1, "identity": 2}
 # rattn_kernel_path: "auto" lets the library choose, "general" forces the general kernels (tests)
 KERNEL_PATHS = {"auto": 0, "general": 1}
-# rattn_state_policy: keep the chunk states in `saved` for backward, or rebuild them there (Sec. 3.2 trade-off)
-STATE_POLICIES = {"keep": 0, "rebuild": 1}
+# rattn_state_policy: keep the chunk states in `saved` for backward (all, every 2nd, every 4th), or rebuild them
+# there (Sec. 3.2 trade-off)
+STATE_POLICIES = {"keep": 0, "rebuild": 1, "every2": 2, "every4": 4}
 _DTYPES = {torch.float32: RATTN_F32, torch.bfloat16: RATTN_BF16}
 
 EXPORTS = ["rattn_workspace_bytes", "rattn_fwd", "rattn_fwd_static", "rattn_bwd", "rattn_decode_step",

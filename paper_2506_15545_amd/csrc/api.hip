@@ -67,7 +67,8 @@ struct Layout {
   size_t esize;
   // saved
   size_t sv_xs, sv_xr, sv_lse, sv_rs, sv_rr, sv_states, sv_xr_lo, saved_bytes;
-  bool has_xr_lo, keep_states;
+  bool has_xr_lo;
+  int state_stride;   // chunk states kept in `saved`: 0 = none, 1 = all, m = every m-th
   // generic forward / backward workspace
   size_t gf_states, gen_fwd_bytes;
   size_t gb_states, gb_rstates, gb_dxs, gb_dxr, gb_delta, gb_dgpart, gen_bwd_bytes;
@@ -95,7 +96,8 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
     return fail(RATTN_ERR_UNSUPPORTED, "unknown feature_map %d", p->feature_map);
   if (p->kernel_path != RATTN_PATH_AUTO && p->kernel_path != RATTN_PATH_GENERAL)
     return fail(RATTN_ERR_UNSUPPORTED, "unknown kernel_path %d", p->kernel_path);
-  if (p->state_policy != RATTN_STATES_KEEP && p->state_policy != RATTN_STATES_REBUILD)
+  if (p->state_policy != RATTN_STATES_KEEP && p->state_policy != RATTN_STATES_REBUILD &&
+      p->state_policy != RATTN_STATES_KEEP_EVERY_2ND && p->state_policy != RATTN_STATES_KEEP_EVERY_4TH)
     return fail(RATTN_ERR_UNSUPPORTED, "unknown state_policy %d", p->state_policy);
   if (!(p->rms_eps > 0.f)) return fail(RATTN_ERR_INVALID_ARG, "rms_eps must be > 0");
   if (!(p->softmax_scale == p->softmax_scale) || p->softmax_scale == 0.f)
@@ -143,8 +145,12 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
   L->sv_rs = off; off += align_up(nrow_f * 4);
   L->sv_rr = off; off += align_up(nrow_f * 4);
   L->sv_states = off;
-  L->keep_states = L->fast_fwd && p->state_policy == RATTN_STATES_KEEP;
-  if (L->keep_states) off += align_up(rattn::fast_fwd_plan(dmf).state_bytes);
+  L->state_stride = !L->fast_fwd || p->state_policy == RATTN_STATES_REBUILD ? 0
+                    : p->state_policy == RATTN_STATES_KEEP ? 1 : p->state_policy;
+  if (L->state_stride > 0) {
+    const int nstf = rattn::fast_fwd_plan(dmf).nstf;
+    off += align_up((size_t)dmf.B * dmf.Hkv * ((nstf + L->state_stride - 1) / L->state_stride) * 128 * 128 * 2);
+  }
   L->has_xr_lo = L->fast_fwd && dm.phi == rattn::PHI_IDENTITY;
   L->sv_xr_lo = off;
   if (L->has_xr_lo) off += align_up(nq_f * L->esize);
@@ -218,12 +224,12 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
 }
 
 rattn::SavedPtrs saved_views(const Layout& L, void* saved) {
-  rattn::SavedPtrs sv = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, !L.fast_fwd, nullptr};
+  rattn::SavedPtrs sv = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, !L.fast_fwd, nullptr, 0};
   if (saved) {
     char* s = (char*)saved;
     sv.xs = s + L.sv_xs; sv.xr = s + L.sv_xr;
     sv.lse = (float*)(s + L.sv_lse); sv.rs = (float*)(s + L.sv_rs); sv.rr = (float*)(s + L.sv_rr);
-    if (L.keep_states) sv.states = s + L.sv_states;
+    if (L.state_stride > 0) { sv.states = s + L.sv_states; sv.state_stride = L.state_stride; }
     if (L.has_xr_lo) sv.xr_lo = s + L.sv_xr_lo;
   }
   return sv;
@@ -355,7 +361,7 @@ rattn_status rattn_fwd(const rattn_params* p, const void* q, const void* k, cons
       rattn::gather_tails(3, src, tl, Hs, L.dm.B, L.dm.T, st);
       rattn::RaggedTails rt = {L.dm.T, tl[0], tl[1], tl[2], nullptr, w + L.pf_o, nullptr, nullptr, nullptr};
       rattn::fast_fwd(L.dmf, q, k, v, gamma_swa, gamma_rla, o, sv, (float*)(w + L.ff_u),
-                      sv.states ? sv.states : (void*)(w + L.ff_states), st, 0, nullptr, &rt);
+                      sv.states && sv.state_stride <= 1 ? sv.states : (void*)(w + L.ff_states), st, 0, nullptr, &rt);
       const void* otl[1] = {w + L.pf_o};
       void* odst[1] = {o};
       rattn::scatter_tails(1, otl, odst, Hs, L.dm.B, L.dm.T, st);
@@ -372,7 +378,7 @@ rattn_status rattn_fwd(const rattn_params* p, const void* q, const void* k, cons
       }
     }
     rattn::fast_fwd(L.dmf, qf, kf, vf, gsf, grf, of, sv, (float*)(w + L.ff_u),
-                    sv.states ? sv.states : (void*)(w + L.ff_states), st);
+                    sv.states && sv.state_stride <= 1 ? sv.states : (void*)(w + L.ff_states), st);
     if (L.pad) rattn::unpad_rows(of, o, L.dm.B, L.dm.T, L.dmf.T, L.dm.Hq, hb, hbp, st);
   } else
     rattn::generic_fwd(L.dm, p->dtype, q, k, v, gamma_swa, gamma_rla, o, sv, (float*)((char*)workspace + L.gf_states), st);
@@ -568,7 +574,7 @@ rattn_status rattn_prefill_chunk(const rattn_params* p, int32_t pos0, const void
   // state) the carried state enters as the initial value of the state scan.  Only K and V are gathered.
   if (C.L2.fast_fwd && !C.L2.pad && C.R % 128 == 0 && (!carried || p->window % 128 == 0)) {
     rattn::chunk_concat(dm, p->dtype, p->T, C.R, pos0, nullptr, k, v, k_ring, v_ring, nullptr, w + C.kc, w + C.vc, st);
-    rattn::SavedPtrs none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, false, nullptr};
+    rattn::SavedPtrs none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, false, nullptr, 0};
     rattn::fast_fwd(dm, q, w + C.kc, w + C.vc, gamma_swa, gamma_rla, o, none, (float*)(w + C.fwdws + C.L2.ff_u),
                     w + C.fwdws + C.L2.ff_states, st, C.R / 128, carried ? state : nullptr);
     rattn::prefill_export(dm, p->dtype, w + C.kc, w + C.vc, k_ring, v_ring, state, (float*)(w + C.partial), st,

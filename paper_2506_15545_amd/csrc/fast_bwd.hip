@@ -880,8 +880,12 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
   a.dxs = (const uint16_t*)ws.dxs; a.dxr = (const uint16_t*)ws.dxr;
   a.lse = sv.lse; a.delta = ws.delta;
   // chunk states of the forward pass: kept in `saved`, or (state policy "rebuild") built again here from k and v
-  if (!sv.states && pl.fwd.nstf > 0) rla_forward_states(dm, pl.fwd, k, v, ws.U, ws.states, st, nullptr, tails);
-  a.states = (const uint16_t*)(sv.states ? sv.states : ws.states); a.rstates = (const uint16_t*)ws.rstates;
+  // (or, with a state stride, every m-th kept and the ones in between built again from those)
+  const bool all_kept = sv.states && sv.state_stride <= 1;
+  if (!all_kept && pl.fwd.nstf > 0)
+    rla_forward_states(dm, pl.fwd, k, v, ws.U, ws.states, st, nullptr, tails, nullptr,
+                       sv.state_stride > 1 ? sv.states : nullptr, sv.state_stride);
+  a.states = (const uint16_t*)(all_kept ? sv.states : ws.states); a.rstates = (const uint16_t*)ws.rstates;
   a.dq = (uint16_t*)dq; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv;
   a.q_tail = tails ? (const uint16_t*)tails->q : nullptr; a.k_tail = tails ? (const uint16_t*)tails->k : nullptr;
   a.v_tail = tails ? (const uint16_t*)tails->v : nullptr; a.dO_tail = tails ? (const uint16_t*)tails->dO : nullptr;

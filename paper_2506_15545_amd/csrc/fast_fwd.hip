@@ -455,7 +455,10 @@ void fast_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
               void* o, const SavedPtrs& sv, float* U, void* states, hipStream_t st, int qt0, const float* state0,
               const RaggedTails* tails) {
   const FastFwdPlan pl = fast_fwd_plan(dm);
-  if (pl.nstf > 0) rla_forward_states(dm, pl, k, v, U, states, st, state0, tails);
+  // `states` receives every chunk state; with a state stride the stored subset also goes to `saved`
+  if (pl.nstf > 0)
+    rla_forward_states(dm, pl, k, v, U, states, st, state0, tails, sv.state_stride > 1 ? sv.states : nullptr, nullptr,
+                       sv.state_stride);
   FastFwdArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
   a.gs = gs; a.gr = gr;

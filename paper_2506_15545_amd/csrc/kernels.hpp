@@ -46,6 +46,9 @@ struct SavedPtrs {
                  // to bf16, so that backward reads x^r to 16 significant bits.  With features of size ~1 the first
                  // rows past the window (state of rank 1, 2, ...) turn the backward through the second RMS norm into
                  // a cancellation that a bf16 x^r alone resolves to only ~10 % of the gradient's RMS
+  int state_stride;  // `states` holds every chunk state (0 or 1) or states 0, m, 2m, ... only (m = 2, 4): the
+                     // forward then works on the full set in its workspace and backward rebuilds the states in
+                     // between from the stored ones (Sec. 3.2: store every m-th state, recompute the others)
 };
 
 struct GenericBwdWs {
@@ -105,9 +108,13 @@ void fast_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
               const float* state0 = nullptr, const RaggedTails* tails = nullptr);
 
 // linear-branch chunk states for the MFMA paths (bf16 [d][f] per state, fp32 scratch U per chunk)
+// With m > 1: `subset_out` (forward) also receives states 0, m, 2m, ...; `restart` (backward) holds those states from
+// the forward pass: only the chunk products that lead to a state in between are formed, and the scan restarts from
+// every stored state.
 void rla_forward_states(const LayerDims& dm, const FastFwdPlan& pl, const void* k, const void* v, float* U,
                         void* states, hipStream_t st, const float* state0 = nullptr,
-                        const RaggedTails* tails = nullptr);
+                        const RaggedTails* tails = nullptr, void* subset_out = nullptr, const void* restart = nullptr,
+                        int m = 1);
 // MFMA backward path (same shape class as the MFMA forward)
 struct FastBwdPlan {
   FastFwdPlan fwd;

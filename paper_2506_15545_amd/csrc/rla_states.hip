@@ -21,6 +21,8 @@ struct ChunkArgs {
   int Ta, Tb, Tfull_a, Tfull_b;
   int H, GA;           // heads in a/b, heads summed per kv head
   int tok_off;         // token index = t' + tok_off
+  int skip_m, skip_head, skip_per;  // skip_m > 1: product c leads from state i = (c - skip_head) / skip_per to i + 1 and is
+                                    // left out when that state is a stored one ((i + 1) % skip_m == 0) or c < skip_head
   int first_lo, first_n, rest_lo, ckeys, tok_end;  // chunk 0 = [first_lo, +first_n); chunk c > 0 = ckeys tokens from
                                                    // rest_lo + ckeys (c-1); every chunk is clipped at tok_end
 };
@@ -32,6 +34,7 @@ __global__ __launch_bounds__(256, 2) void rla_chunk_kernel(ChunkArgs p) {
   unsigned char* At = smem;
   unsigned char* Bt = smem + 32768;
   const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z, nchunks = gridDim.x, Hkv = gridDim.y;
+  if (p.skip_m > 1 && (c < p.skip_head || ((c - p.skip_head) / p.skip_per + 1) % p.skip_m == 0)) return;  // block-uniform
   const int lane = lane_id(), w = wave_id();
   const int r32 = lane & 31, h = lane >> 5;
   const int lo = c == 0 ? p.first_lo : p.rest_lo + p.ckeys * (c - 1);
@@ -80,10 +83,14 @@ __global__ __launch_bounds__(256, 2) void rla_chunk_kernel(ChunkArgs p) {
 //   reverse: state[n-1] = 0; state[i] = state[i+1] + products per*i .. per*i + per - 1 (those that exist)
 // grid (16, Hkv, B), 256 threads, 4 elements per thread.
 // init (forward only, may be NULL): a state that precedes chunk 0, fp32 [B,Hkv,f,d] (not transposed).
+// Forward scan with m > 1: `subset` (may be NULL) also receives states 0, m, 2m, ... ([B,Hkv,ceil(nst/m),128,128]);
+// `restart` (may be NULL) holds such a subset, and the running sum is replaced by the stored state at every multiple
+// of m (the products that lead to a stored state are then never used and need not exist).
 template <bool REV, int PER>
 __global__ __launch_bounds__(256) void rla_scan_kernel(const float* __restrict__ U, uint16_t* __restrict__ states,
                                                        int nchunks, int nst, int head,
-                                                       const float* __restrict__ init) {
+                                                       const float* __restrict__ init, uint16_t* __restrict__ subset,
+                                                       const uint16_t* __restrict__ restart, int m) {
   const int g = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
   const int e4 = (blockIdx.x * 256 + threadIdx.x) * 4;
   const float* Ub = U + (size_t)(b * Hkv + g) * nchunks * 16384 + e4;
@@ -94,9 +101,17 @@ __global__ __launch_bounds__(256) void rla_scan_kernel(const float* __restrict__
     const int f = e4 & 127;
     acc = make_float4(ib[(size_t)f * 128], ib[(size_t)(f + 1) * 128], ib[(size_t)(f + 2) * 128], ib[(size_t)(f + 3) * 128]);
   }
+  const int nsub = (!REV && m > 1) ? (nst + m - 1) / m : 0;
+  const size_t sub0 = (size_t)(b * Hkv + g) * nsub * 16384 + e4;
   auto put = [&](int i) {
+    if (!REV && restart && i % m == 0) {  // continue from the state the forward pass stored
+      const bf16x4_t s = *reinterpret_cast<const bf16x4_t*>(restart + sub0 + (size_t)(i / m) * 16384);
+      acc = make_float4((float)s[0], (float)s[1], (float)s[2], (float)s[3]);
+    }
     f32x4_t f = {acc.x, acc.y, acc.z, acc.w};
-    *reinterpret_cast<bf16x4_t*>(Sb + (size_t)i * 16384) = __builtin_convertvector(f, bf16x4_t);
+    const bf16x4_t o = __builtin_convertvector(f, bf16x4_t);
+    *reinterpret_cast<bf16x4_t*>(Sb + (size_t)i * 16384) = o;
+    if (!REV && subset && i % m == 0) *reinterpret_cast<bf16x4_t*>(subset + sub0 + (size_t)(i / m) * 16384) = o;
   };
   auto ld = [&](int c) {  // product c, or zero when it does not exist
     return (c >= 0 && c < nchunks) ? *reinterpret_cast<const float4*>(Ub + (size_t)c * 16384) : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -106,14 +121,15 @@ __global__ __launch_bounds__(256) void rla_scan_kernel(const float* __restrict__
   // loads of a group are in flight together (the additions keep their fixed order).
   constexpr int GRP = 4;
   if (!REV) {
-    for (int c = 0; c < head; ++c) add(ld(c));
+    if (!restart)
+      for (int c = 0; c < head; ++c) add(ld(c));
     // state i is stored, then products head + PER*i .. + PER - 1 are added to reach state i + 1
     for (int i0 = 0; i0 < nst; i0 += GRP) {
       float4 u[GRP][PER];
 #pragma unroll
       for (int j = 0; j < GRP; ++j)
 #pragma unroll
-        for (int r = 0; r < PER; ++r) u[j][r] = (i0 + j + 1 < nst) ? ld(head + PER * (i0 + j) + r) : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int r = 0; r < PER; ++r) u[j][r] = (i0 + j + 1 < nst && !(restart && (i0 + j + 1) % m == 0)) ? ld(head + PER * (i0 + j) + r) : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
       for (int j = 0; j < GRP; ++j) {
         if (i0 + j < nst) put(i0 + j);
@@ -151,8 +167,10 @@ void launch_chunk_kernel(int fm, dim3 grid, const ChunkArgs& p, hipStream_t st) 
 }  // namespace
 
 void rla_forward_states(const LayerDims& dm, const FastFwdPlan& pl, const void* k, const void* v, float* U,
-                        void* states, hipStream_t st, const float* state0, const RaggedTails* tails) {
+                        void* states, hipStream_t st, const float* state0, const RaggedTails* tails, void* subset_out,
+                        const void* restart, int m) {
   if (pl.nstf <= 0) return;
+  if (m < 2) { m = 1; subset_out = nullptr; restart = nullptr; }
   const int head = pl.base > 0 ? 1 : 0;  // products in front of state 0: the 64 keys before it when it sits at key 64
   if (pl.nchunks > 0) {
     ChunkArgs p;
@@ -163,13 +181,18 @@ void rla_forward_states(const LayerDims& dm, const FastFwdPlan& pl, const void* 
     p.H = dm.Hkv; p.GA = 1; p.tok_off = 0;
     p.ckeys = pl.ckeys;
     p.first_lo = 0; p.first_n = head ? 64 : pl.ckeys; p.rest_lo = p.first_n; p.tok_end = 1 << 30;
+    p.skip_m = restart ? m : 0; p.skip_head = head; p.skip_per = 128 / pl.ckeys;
     ProfScope ps("rla_chunk_kernel", st);
     launch_chunk_kernel(feature_map_variant(dm), dim3(pl.nchunks, dm.Hkv, dm.B), p, st);
   }
   ProfScope ps("rla_scan_kernel", st);
   const dim3 sgrid(16, dm.Hkv, dm.B);
-  if (pl.ckeys == 64) rla_scan_kernel<false, 2><<<sgrid, 256, 0, st>>>(U, (uint16_t*)states, pl.nchunks, pl.nstf, head, state0);
-  else rla_scan_kernel<false, 1><<<sgrid, 256, 0, st>>>(U, (uint16_t*)states, pl.nchunks, pl.nstf, head, state0);
+  if (pl.ckeys == 64)
+    rla_scan_kernel<false, 2><<<sgrid, 256, 0, st>>>(U, (uint16_t*)states, pl.nchunks, pl.nstf, head, state0,
+                                                     (uint16_t*)subset_out, (const uint16_t*)restart, m);
+  else
+    rla_scan_kernel<false, 1><<<sgrid, 256, 0, st>>>(U, (uint16_t*)states, pl.nchunks, pl.nstf, head, state0,
+                                                     (uint16_t*)subset_out, (const uint16_t*)restart, m);
 }
 
 void rla_reverse_states(const LayerDims& dm, const FastBwdPlan& pl, const void* q, const void* dxr, float* U,
@@ -185,13 +208,14 @@ void rla_reverse_states(const LayerDims& dm, const FastBwdPlan& pl, const void* 
     p.H = dm.Hq; p.GA = dm.G; p.tok_off = W;
     p.ckeys = ck;
     p.first_lo = 128; p.first_n = ck; p.rest_lo = 128 + ck; p.tok_end = Tp;
+    p.skip_m = 0; p.skip_head = 0; p.skip_per = 1;
     ProfScope ps("rla_chunk_kernel(rev)", st);
     launch_chunk_kernel(feature_map_variant(dm), dim3(pl.nrchunks, dm.Hkv, dm.B), p, st);
   }
   ProfScope ps("rla_scan_kernel(rev)", st);
   const dim3 sgrid(16, dm.Hkv, dm.B);
-  if (ck == 64) rla_scan_kernel<true, 2><<<sgrid, 256, 0, st>>>(U, (uint16_t*)rstates, pl.nrchunks, pl.nk, 0, nullptr);
-  else rla_scan_kernel<true, 1><<<sgrid, 256, 0, st>>>(U, (uint16_t*)rstates, pl.nrchunks, pl.nk, 0, nullptr);
+  if (ck == 64) rla_scan_kernel<true, 2><<<sgrid, 256, 0, st>>>(U, (uint16_t*)rstates, pl.nrchunks, pl.nk, 0, nullptr, nullptr, nullptr, 1);
+  else rla_scan_kernel<true, 1><<<sgrid, 256, 0, st>>>(U, (uint16_t*)rstates, pl.nrchunks, pl.nk, 0, nullptr, nullptr, nullptr, 1);
 }
 
 }  // namespace rattn

@@ -42,7 +42,7 @@ int main() {
       {0, 0, RATTN_ERR_INVALID_ARG}, {1, 0, RATTN_ERR_INVALID_ARG}, {2, 3, RATTN_ERR_INVALID_ARG},
       {4, 96, RATTN_ERR_UNSUPPORTED}, {5, 0, RATTN_ERR_INVALID_ARG}, {6, -1, RATTN_ERR_INVALID_ARG},
       {7, 7, RATTN_ERR_UNSUPPORTED}, {11, 3, RATTN_ERR_UNSUPPORTED}, {12, 2, RATTN_ERR_UNSUPPORTED},
-      {13, 2, RATTN_ERR_UNSUPPORTED},
+      {13, 3, RATTN_ERR_UNSUPPORTED}, {13, -1, RATTN_ERR_UNSUPPORTED},
       {0, 70000, RATTN_ERR_UNSUPPORTED}, {1, 2000000000, RATTN_ERR_UNSUPPORTED}};
   for (auto& c : bad) {
     rattn_params q = p;
@@ -58,9 +58,10 @@ int main() {
                      {65535, 8000, 1, 1, 128, 9, 1}, {1, 300, 65535, 65535, 64, 1000000, 0}, {2, 127, 8, 1, 128, 64, 1}};
   for (auto& sh : shapes) {
     rattn_params q = params(sh[0], sh[1], sh[2], sh[3], sh[4], sh[5], sh[6]);
-    for (int variant = 0; variant < 4; ++variant) {
+    for (int variant = 0; variant < 8; ++variant) {
+      const int policies[4] = {RATTN_STATES_KEEP, RATTN_STATES_REBUILD, RATTN_STATES_KEEP_EVERY_2ND, RATTN_STATES_KEEP_EVERY_4TH};
       q.kernel_path = variant & 1;
-      q.state_policy = variant >> 1;
+      q.state_policy = policies[variant >> 1];
       q.chunk = variant == 2 ? 64 : 0;
       rattn_status st = rattn_workspace_bytes(&q, &f, &b, &s);
       CHECK(st == RATTN_OK || st == RATTN_ERR_UNSUPPORTED);

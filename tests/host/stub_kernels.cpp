@@ -17,7 +17,7 @@ void generic_bwd(const LayerDims&, int, const void*, const void*, const void*, c
 void fast_fwd(const LayerDims&, const void*, const void*, const void*, const float*, const float*, void*,
               const SavedPtrs&, float*, void*, hipStream_t, int, const float*, const RaggedTails*) { ++g_stub_launches; }
 void rla_forward_states(const LayerDims&, const FastFwdPlan&, const void*, const void*, float*, void*, hipStream_t,
-                        const float*, const RaggedTails*) { ++g_stub_launches; }
+                        const float*, const RaggedTails*, void*, const void*, int) { ++g_stub_launches; }
 void rla_reverse_states(const LayerDims&, const FastBwdPlan&, const void*, const void*, float*, void*, hipStream_t,
                         const RaggedTails*) { ++g_stub_launches; }
 void fast_bwd(const LayerDims&, const void*, const void*, const void*, const float*, const float*, const SavedPtrs&,

@@ -48,7 +48,7 @@ def test_workspace_sizes_scale_with_shape():
 @pytest.mark.parametrize("kw,code", [
     (dict(B=0), -1), (dict(T=0), -1), (dict(Hq=3, Hkv=2), -1), (dict(window=0), -1), (dict(chunk=-1), -1),
     (dict(rms_eps=0.0), -1), (dict(softmax_scale=0.0), -1), (dict(D=96), -2), (dict(dtype=7), -2),
-    (dict(feature_map=3), -2), (dict(feature_map=-1), -2), (dict(kernel_path=2), -2), (dict(state_policy=2), -2),
+    (dict(feature_map=3), -2), (dict(feature_map=-1), -2), (dict(kernel_path=2), -2), (dict(state_policy=3), -2), (dict(state_policy=-1), -2),
     (dict(B=60000, T=10000), -2),      # more rows than 32-bit row indexing covers
     (dict(B=70000), -2), (dict(Hq=70000, Hkv=70000), -2),   # grid dimensions
 ])
@@ -199,6 +199,11 @@ def test_matrix_core_chunk_size_defaults_to_128_keys():
     _, _, s_keep = rb.rattn_workspace_bytes(params(**base))
     _, _, s_rebuild = rb.rattn_workspace_bytes(params(state_policy=1, **base))
     assert s_keep - s_rebuild == state_bytes
+    # every 2nd / 4th state kept (states 0, m, 2m, ...)
+    _, _, s2 = rb.rattn_workspace_bytes(params(state_policy=2, **base))
+    _, _, s4 = rb.rattn_workspace_bytes(params(state_policy=4, **base))
+    assert s2 - s_rebuild == state_bytes // nst * ((nst + 1) // 2)
+    assert s4 - s_rebuild == state_bytes // nst * ((nst + 3) // 4)
 
 
 def test_ragged_lengths_cost_tail_buffers_not_copies():

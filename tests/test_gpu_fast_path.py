@@ -238,12 +238,15 @@ def test_head_size_64_runs_on_the_matrix_cores(B, T, Hq, Hkv, W):
     assert float((o.float() - o_gen.float()).abs().max()) <= 4e-2 * gmax
 
 
-@pytest.mark.parametrize("policy,chunk", [("keep", 64), ("rebuild", 0), ("rebuild", 64)])
+@pytest.mark.parametrize("policy,chunk", [("keep", 64), ("rebuild", 0), ("rebuild", 64), ("every2", 0), ("every4", 0),
+                                          ("every2", 64)])
 @pytest.mark.parametrize("B,T,Hq,Hkv,W", [(1, 1024, 3, 1, 192), (2, 512, 4, 2, 128), (1, 1024, 2, 1, 513), (1, 896, 2, 1, 320)])
 def test_state_policy_and_chunk_size_variants(policy, chunk, B, T, Hq, Hkv, W):
     """The two tunables of the linear-branch state pipeline (Sec. 3.2: which chunk states are stored, chunk size C):
-    states kept in `saved` or rebuilt in backward, chunk products of 64 or 128 keys.  Every variant against the oracle
-    to the same bars as the default; rebuilding changes no bit; `saved` shrinks by the states when they are not kept."""
+    all states kept in `saved`, every 2nd or 4th kept and the ones in between rebuilt in backward from those, or all
+    rebuilt; chunk products of 64 or 128 keys.  Every variant against the oracle to the same bars as the default;
+    rebuilding everything changes no bit (continuing from a stored, i.e. rounded, state moves the rebuilt states by a
+    rounding); `saved` shrinks by the states that are not kept."""
     D = 128
     x = synth.make_random_layer(B, T, Hq, Hkv, D, "bf16", 3300 + T + W, with_dO=True)
     scale = 1.0 / math.sqrt(D)
@@ -257,7 +260,7 @@ def test_state_policy_and_chunk_size_variants(policy, chunk, B, T, Hq, Hkv, W):
     names = [n for n, _ in rb.rattn_profile_records()]
     rb.rattn_profile_enable(False)
     assert "bwd_dkv_kernel" in names
-    assert ("rla_chunk_kernel" in names) == (policy == "rebuild")     # forward states rebuilt only under that policy
+    assert ("rla_chunk_kernel" in names) == (policy != "keep")        # forward states (re)built in backward
     ref = orc.fwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), W, scale=scale)
     pm.assert_out_bf16(np64(o), ref["o"])
     refb = orc.bwd_dense(np64(x["q"]), np64(x["k"]), np64(x["v"]), np64(x["dO"]), W, scale=scale)
@@ -269,10 +272,14 @@ def test_state_policy_and_chunk_size_variants(policy, chunk, B, T, Hq, Hkv, W):
     g0 = rb.rattn_bwd(q, k, v, saved0, dO, W, want_dgamma=False, softmax_scale=scale, chunk=chunk)
     assert torch.equal(o, o0)
     for a_, b_ in zip((dq, dk, dv), g0[:3]):
-        assert torch.equal(a_, b_)
-    if policy == "rebuild":
-        nst = T // 128 - (min(W, T) + 63) // 64 * 64 // 128 - ((min(W, T) + 63) // 64 * 64 % 128 > 0)
-        assert saved0.numel() - saved.numel() >= max(nst, 0) * B * Hkv * 128 * 128 * 2
+        if policy in ("keep", "rebuild"):
+            assert torch.equal(a_, b_)
+        else:   # a few states differ by one rounding: the gradients move by far less than their tolerance
+            af, bf = a_.float(), b_.float()   # (one bf16 step of the stored value on top of the RMS-relative slack)
+            assert bool(((af - bf).abs() <= 2e-2 * float(bf.pow(2).mean().sqrt()) + 2.0 ** -7 * bf.abs()).all())
+    nst = max(T // 128 - (min(W, T) + 63) // 64 * 64 // 128 - ((min(W, T) + 63) // 64 * 64 % 128 > 0), 0)
+    kept = {"keep": nst, "rebuild": 0, "every2": (nst + 1) // 2, "every4": (nst + 3) // 4}[policy]
+    assert saved0.numel() - saved.numel() == (nst - kept) * B * Hkv * 128 * 128 * 2
 
 
 def test_fast_bwd_is_deterministic():
