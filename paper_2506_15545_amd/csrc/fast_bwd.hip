@@ -239,24 +239,44 @@ __device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, int hq, size_
     g2[e] = (GAINS && a.gr) ? a.gr[hq * 128 + 8 * c + e] : 1.f;
     dg1[e] = dg2[e] = 0.f;
   }
+  // All rows are requested before the first is worked on: the loads below and the stores further down go through
+  // pointers the compiler cannot tell apart, so inside one loop every iteration's loads would wait behind the
+  // previous iteration's stores - eight memory round trips in a row instead of one.
+  bf16x8_t dy_raw[8], xs_raw[8], xr_raw[8];
+  float rs_row[8], rr_row[8];
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int r = 4 * it + sub;
+    const size_t off = row0_off + (size_t)r * qstride + 8 * c;
+    dy_raw[it] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(dO_row0 + (size_t)r * qstride + 8 * c));
+    xs_raw[it] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(a.xs + off));
+    rs_row[it] = a.rs[stat0 + r];
+    rr_row[it] = a.rr[stat0 + r];
+  }
+  if (with_r) {
+#pragma unroll
+    for (int it = 0; it < 8; ++it)
+      xr_raw[it] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(
+          a.xr + row0_off + (size_t)(4 * it + sub) * qstride + 8 * c));
+  } else {
+#pragma unroll
+    for (int it = 0; it < 8; ++it) xr_raw[it] = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+  }
 #pragma unroll
   for (int it = 0; it < 8; ++it) {
     const int r = 4 * it + sub;
     const size_t off = row0_off + (size_t)r * qstride + 8 * c;
     float dy[8], xs[8], xr[8];
-    unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(dO_row0 + (size_t)r * qstride + 8 * c)), dy);
-    unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(a.xs + off)), xs);
-    if (with_r) unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(a.xr + off)), xr);
-    else
-#pragma unroll
-      for (int e = 0; e < 8; ++e) xr[e] = 0.f;
-    if (with_r && a.xr_lo) {  // wave-uniform
+    unpack_bf16x8(dy_raw[it], dy);
+    unpack_bf16x8(xs_raw[it], xs);
+    unpack_bf16x8(xr_raw[it], xr);
+    if (with_r && a.xr_lo) {  // wave-uniform (identity feature map only)
       float lo[8];
       unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(a.xr_lo + off)), lo);
 #pragma unroll
       for (int e = 0; e < 8; ++e) xr[e] += lo[e];
     }
-    const float r_s = a.rs[stat0 + r], r_r = a.rr[stat0 + r];
+    const float r_s = rs_row[it], r_r = rr_row[it];
     float m1 = 0.f, m2 = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
