@@ -347,7 +347,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
   const size_t qstride = (size_t)Hq * 128, kstride = (size_t)Hkv * 128;
   const size_t qtile_off = ((size_t)(b * T + t0) * Hq + hq) * 128;   // in the saved / workspace tensors (padded length)
   // the caller's tensors: this query tile of q, dO, dq; 64-key tiles of k, v
-  const uint16_t* q_myrow = split_rows(a.q, a.q_tail, b, t0, a.Tc, a.Tfull, Hq, hq) + (size_t)(32 * w + r32) * qstride;
+  const uint16_t* q_tile = split_rows(a.q, a.q_tail, b, t0, a.Tc, a.Tfull, Hq, hq);
   const uint16_t* dO_tile = split_rows(a.dO, a.dO_tail, b, t0, a.Tc, a.Tfull, Hq, hq);
   uint16_t* dq_tile = split_rows(a.dq, a.dq_tail, b, t0, a.Tc, a.Tfull, Hq, hq);
   auto k_rows = [&](int row) { return split_rows(a.k, a.k_tail, b, row, a.Tc, a.Tfull, Hkv, g); };
@@ -459,19 +459,13 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
       for (int u = 4; u <= min(5, u_hi); ++u) intra_unit(smem, smem + 32768, u & 1, u);
       __syncthreads();
     }
-    float qf[64];
-    {
-      bf16x4_t qraw[16];
-      load_row_clayout(q_myrow, h, qraw);
-      phi_row_clayout<FM>(qraw, qf);
-    }
-    phi_jacobian<FM>(acc, qf);
   }
 
   // ---- softmax branch
+  // The first key tile and the work-group's q tile are requested together: q goes into the two tile buffers the
+  // key sweep does not need yet (rows 0..63 and 64..127), and every wave takes its own rows from there in both of the
+  // layouts it needs, instead of two more round trips to global memory for row pieces.
   if (!has_lin) __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the staged rows are in registers
-  bf16x8_t qop[8];
-  load_bop(q_myrow, h, qop);
   const float lse2 = a.lse[stat_off] * LOG2E;
   const int kt_lo = max(0, t0 - W);
   const int ntiles = (t0 + 128 - kt_lo) / 64;
@@ -479,8 +473,29 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
     const int kt0 = kt_lo + 64 * (ntiles - 1);
     tile_load_async<4>(k_rows(kt0), kstride, smem, w * 4, lane);
     tile_load_async<4>(v_rows(kt0), kstride, smem + 32768, w * 4, lane);
+    tile_load_async<4>(q_tile, qstride, smem + 16384, w * 4, lane);
+    tile_load_async<4>(q_tile + (size_t)64 * qstride, qstride, smem + 49152, w * 4, lane);
     wait_vmem();
     __syncthreads();
+  }
+  bf16x8_t qop[8];
+  {
+    const unsigned char* qhalf = smem + ((w >> 1) ? 49152 : 16384);
+    const int R0 = 32 * (w & 1);
+    if (has_lin) {  // phi(q) and its Jacobian close the linear branch
+      const int row = R0 + r32;
+      const unsigned char* rowp = qhalf + row * ROW_BYTES + 8 * h;
+      bf16x4_t qraw[16];
+#pragma unroll
+      for (int j = 0; j < 16; ++j) qraw[j] = *reinterpret_cast<const bf16x4_t*>(rowp + ((j ^ swz(row)) << 4));
+      float qf[64];
+      phi_row_clayout<FM>(qraw, qf);
+      phi_jacobian<FM>(acc, qf);
+    }
+#pragma unroll
+    for (int c = 0; c < 8; ++c) qop[c] = lds_row(qhalf, lo, R0, c);
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    __syncthreads();  // the sweep's second tile load reuses the q buffers
   }
   const int qa = t0 + 32 * w, qb = qa + 31;
   const DmaLane dma_lane = make_dma_lane(lane, kstride);
