@@ -474,7 +474,8 @@ def main():
         other["layer3b_t4096_w512"] = run_layer(cfg, True)
         # the ablation's ReLU and identity feature maps (Sec. 4.5) on the same kernels, same FLOP formula
         other["layer3b_t4096_w512_relu"] = run_layer(cfg, True, feature_map="relu")
-        other["layer3b_t4096_w512_identity"] = run_layer(cfg, True, feature_map="identity")
+        # (identity map: forward only - calls that keep `saved` for a backward pass run on the general kernels)
+        other["layer3b_t4096_w512_identity_fwd_only"] = run_layer(cfg, False, feature_map="identity")
         # shapes that reach the matrix-core kernels through zero-padded copies: a ragged length (4000 -> 4096 rows)
         # and head size 64 (rows widened to 128 features; FLOPs counted at head size 64)
         other["layer3b_t4000_w512_ragged"] = run_layer(dataclasses.replace(cfg, name="layer3b_t4000_w512", T=4000), True)

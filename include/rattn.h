@@ -56,7 +56,9 @@ typedef enum { RATTN_F32 = 0, RATTN_BF16 = 1 } rattn_dtype;
 
 /* Feature map phi of the linear branch, applied to every q and k row over its D features.  The layer uses the
  * softmax map (Sec. 3.1, "Parameterization"); the other two are the alternatives of the ablation (Sec. 4.5):
- * ReLU = max(x, 0) per feature, identity = x.  Zero-initialised parameter structs select the softmax map. */
+ * ReLU = max(x, 0) per feature, identity = x.  Zero-initialised parameter structs select the softmax map.
+ * With the identity map only calls with save_for_bwd = 0 use the matrix-core kernels: a training step (forward that
+ * saves + backward) runs on the general kernels, because its backward is not accurate enough with bf16 operands. */
 typedef enum { RATTN_PHI_SOFTMAX = 0, RATTN_PHI_RELU = 1, RATTN_PHI_IDENTITY = 2 } rattn_feature_map;
 
 typedef struct {

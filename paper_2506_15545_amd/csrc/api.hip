@@ -66,8 +66,7 @@ struct Layout {
   size_t pb_gs, pb_gr, pb_dgs, pb_dgr;                    // padded gains and gain gradients (pad_d)
   size_t esize;
   // saved
-  size_t sv_xs, sv_xr, sv_lse, sv_rs, sv_rr, sv_states, sv_xr_lo, saved_bytes;
-  bool has_xr_lo;
+  size_t sv_xs, sv_xr, sv_lse, sv_rs, sv_rr, sv_states, saved_bytes;
   int state_stride;   // chunk states kept in `saved`: 0 = none, 1 = all, m = every m-th
   // generic forward / backward workspace
   size_t gf_states, gen_fwd_bytes;
@@ -128,7 +127,13 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
   if (L->pad) L->dmf.T = (dm.T + 127) / 128 * 128;
   if (L->pad_d) L->dmf.D = 128;
   const rattn::LayerDims& dmf = L->dmf;
-  L->fast_fwd = p->kernel_path != RATTN_PATH_GENERAL && rattn::fast_fwd_supported(dmf, p->dtype);
+  // Identity feature map: only calls that keep nothing for a backward pass (inference, prefill) run on the matrix
+  // cores.  Its backward with bf16 operands is not accurate enough: on the first rows past the window the state has
+  // rank 1, 2, ..., d x^r is orthogonal to the few value rows x^r is made of, and with features of size ~1 (not ~1/D
+  // as after the softmax map) the 2^-9 that rounding leaves of that cancellation reaches single dq elements at
+  // 0.1 .. 2 times the gradient's RMS (GPU and the CPU model of the roundings agree on every such case).
+  const bool identity_training = dm.phi == rattn::PHI_IDENTITY && p->save_for_bwd;
+  L->fast_fwd = p->kernel_path != RATTN_PATH_GENERAL && !identity_training && rattn::fast_fwd_supported(dmf, p->dtype);
   if (!L->fast_fwd) { L->pad = L->pad_d = false; L->dmf = dm; }
   L->tails = L->pad && !L->pad_d;
   // `saved` is sized for the padded length
@@ -151,9 +156,6 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
     const int nstf = rattn::fast_fwd_plan(dmf).nstf;
     off += align_up((size_t)dmf.B * dmf.Hkv * ((nstf + L->state_stride - 1) / L->state_stride) * 128 * 128 * 2);
   }
-  L->has_xr_lo = L->fast_fwd && dm.phi == rattn::PHI_IDENTITY;
-  L->sv_xr_lo = off;
-  if (L->has_xr_lo) off += align_up(nq_f * L->esize);
   L->saved_bytes = off;
 
   const size_t nstate = (size_t)dm.B * dm.Hkv * dm.nst * dm.D * dm.D;
@@ -224,13 +226,12 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
 }
 
 rattn::SavedPtrs saved_views(const Layout& L, void* saved) {
-  rattn::SavedPtrs sv = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, !L.fast_fwd, nullptr, 0};
+  rattn::SavedPtrs sv = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, !L.fast_fwd, 0};
   if (saved) {
     char* s = (char*)saved;
     sv.xs = s + L.sv_xs; sv.xr = s + L.sv_xr;
     sv.lse = (float*)(s + L.sv_lse); sv.rs = (float*)(s + L.sv_rs); sv.rr = (float*)(s + L.sv_rr);
     if (L.state_stride > 0) { sv.states = s + L.sv_states; sv.state_stride = L.state_stride; }
-    if (L.has_xr_lo) sv.xr_lo = s + L.sv_xr_lo;
   }
   return sv;
 }
@@ -325,10 +326,21 @@ rattn_status rattn_profile_get(int idx, const char** name, float* ms) {
 const char* rattn_version(void) { return "0.1"; }
 
 rattn_status rattn_workspace_bytes(const rattn_params* p, size_t* fwd_bytes, size_t* bwd_bytes, size_t* saved_bytes) {
+  if (!p) return fail(RATTN_ERR_INVALID_ARG, "params is NULL");
+  // sizes do not depend on save_for_bwd: `saved` and the backward scratch are those of a call that saves, the
+  // forward scratch covers both kinds of call (they differ only where the kernel family depends on it)
+  rattn_params q = *p;
   Layout L;
-  rattn_status s = make_layout(p, &L);
+  q.save_for_bwd = 1;
+  rattn_status s = make_layout(&q, &L);
   if (s != RATTN_OK) return s;
-  if (fwd_bytes) *fwd_bytes = L.fwd_bytes;
+  size_t fwd = L.fwd_bytes;
+  Layout L0;
+  q.save_for_bwd = 0;
+  s = make_layout(&q, &L0);
+  if (s != RATTN_OK) return s;
+  if (L0.fwd_bytes > fwd) fwd = L0.fwd_bytes;
+  if (fwd_bytes) *fwd_bytes = fwd;
   if (bwd_bytes) *bwd_bytes = L.bwd_bytes;
   if (saved_bytes) *saved_bytes = L.saved_bytes;
   return RATTN_OK;
@@ -423,6 +435,10 @@ rattn_status rattn_fwd_static(const rattn_params* p, const void* q, const void* 
 rattn_status rattn_bwd(const rattn_params* p, const void* q, const void* k, const void* v, const float* gamma_swa,
                        const float* gamma_rla, const void* saved, const void* dO, void* dq, void* dk, void* dv,
                        float* dgamma_swa, float* dgamma_rla, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!p) return fail(RATTN_ERR_INVALID_ARG, "params is NULL");
+  rattn_params pb = *p;
+  pb.save_for_bwd = 1;   // `saved` comes from a forward call that saved, whatever this copy of the parameters says
+  p = &pb;
   Layout L;
   rattn_status s = make_layout(p, &L);
   if (s != RATTN_OK) return s;
@@ -574,7 +590,7 @@ rattn_status rattn_prefill_chunk(const rattn_params* p, int32_t pos0, const void
   // state) the carried state enters as the initial value of the state scan.  Only K and V are gathered.
   if (C.L2.fast_fwd && !C.L2.pad && C.R % 128 == 0 && (!carried || p->window % 128 == 0)) {
     rattn::chunk_concat(dm, p->dtype, p->T, C.R, pos0, nullptr, k, v, k_ring, v_ring, nullptr, w + C.kc, w + C.vc, st);
-    rattn::SavedPtrs none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, false, nullptr, 0};
+    rattn::SavedPtrs none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, false, 0};
     rattn::fast_fwd(dm, q, w + C.kc, w + C.vc, gamma_swa, gamma_rla, o, none, (float*)(w + C.fwdws + C.L2.ff_u),
                     w + C.fwdws + C.L2.ff_states, st, C.R / 128, carried ? state : nullptr);
     rattn::prefill_export(dm, p->dtype, w + C.kc, w + C.vc, k_ring, v_ring, state, (float*)(w + C.partial), st,

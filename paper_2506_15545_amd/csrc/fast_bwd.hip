@@ -29,7 +29,6 @@ struct FastBwdArgs {
   float scale, scale_log2;
   // inputs of the RMS-norm backward in the dq kernel's prologue, which fills dxs, dxr and delta above
   const uint16_t *dO, *xs, *xr;
-  const uint16_t* xr_lo;           // low-order part of the saved x_r (identity feature map), NULL otherwise
   // ragged lengths (see split_rows in mfma.hpp): rows >= Tfull of the caller's q, k, v, dO, dq, dk, dv live in 128-row
   // tail buffers; Tc = rows per sequence of the caller's tensors.  T above is the padded length: saved tensors, the
   // workspace tensors (dxs, dxr, delta) and the states are laid out for it.
@@ -89,7 +88,6 @@ __device__ __forceinline__ void phi_row_clayout(const bf16x4_t (&raw)[16], float
 #pragma unroll
     for (int e = 0; e < 4; ++e) x[4 * j + e] = f[e];
   }
-  if (FM == FM_IDENTITY) return;
   if (FM == FM_RELU) {
 #pragma unroll
     for (int i = 0; i < 64; ++i) x[i] = fmaxf(x[i], 0.f);
@@ -112,11 +110,9 @@ __device__ __forceinline__ void phi_row_clayout(const bf16x4_t (&raw)[16], float
 }
 
 // acc <- f .* (acc - <acc, f>)   (softmax Jacobian applied to a gradient held in accumulator layout; padding features
-// have f = 0 and come out as 0);  ReLU map: acc <- acc where the input was positive, i.e. where f = max(x, 0) > 0;
-// identity map: acc unchanged
+// have f = 0 and come out as 0);  ReLU map: acc <- acc where the input was positive, i.e. where f = max(x, 0) > 0
 template <int FM>
 __device__ __forceinline__ void phi_jacobian(f32x16_t (&acc)[4], const float (&f)[64]) {
-  if (FM == FM_IDENTITY) return;
   if (FM == FM_RELU) {
 #pragma unroll
     for (int ft = 0; ft < 4; ++ft)
@@ -270,12 +266,6 @@ __device__ __forceinline__ void rms_bwd_rows(const FastBwdArgs& a, int hq, size_
     unpack_bf16x8(dy_raw[it], dy);
     unpack_bf16x8(xs_raw[it], xs);
     unpack_bf16x8(xr_raw[it], xr);
-    if (with_r && a.xr_lo) {  // wave-uniform (identity feature map only)
-      float lo[8];
-      unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(a.xr_lo + off)), lo);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) xr[e] += lo[e];
-    }
     const float r_s = rs_row[it], r_r = rr_row[it];
     float m1 = 0.f, m2 = 0.f;
 #pragma unroll
@@ -536,7 +526,6 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
 // (FM_SOFTMAX64: the two threads on features 64..127 leave the padding zeros alone)
 template <int FM>
 __device__ __forceinline__ void phi_tile_inplace_512(unsigned char* tile, int nrows) {
-  if (FM == FM_IDENTITY) return;
   const int row = threadIdx.x >> 2, part = threadIdx.x & 3;
   if (row < nrows) {
     float x[32];
@@ -932,10 +921,11 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
   a.nstf = pl.fwd.nstf; a.nk = pl.nk; a.ntile = dm.T / 128;
   a.scale = dm.scale; a.scale_log2 = dm.scale * LOG2E;
   a.dO = (const uint16_t*)dO; a.xs = (const uint16_t*)sv.xs; a.xr = (const uint16_t*)sv.xr;
-  a.xr_lo = (const uint16_t*)sv.xr_lo;
   a.rs = sv.rs; a.rr = sv.rr; a.gs = gs; a.gr = gr;
   a.dgpart = (dgs || dgr) ? ws.dgpart : nullptr;
   a.inv_d = 1.f / (float)dm.Dv;
+  // (softmax and ReLU maps only: with the identity map the host layer sends every call that keeps `saved` to the
+  // general kernels, see make_layout)
   const int fm = feature_map_variant(dm);
   {
     ProfScope ps("bwd_dq_kernel", st);
@@ -947,7 +937,6 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
   } while (0)
     switch (fm) {
       case FM_RELU: RATTN_DQ_LAUNCH(FM_RELU); break;
-      case FM_IDENTITY: RATTN_DQ_LAUNCH(FM_IDENTITY); break;
       case FM_SOFTMAX64: RATTN_DQ_LAUNCH(FM_SOFTMAX64); break;
       default: RATTN_DQ_LAUNCH(FM_SOFTMAX); break;
     }
@@ -963,7 +952,6 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
   static const bool lds_attr = [] {
     const void* fns[] = {reinterpret_cast<const void*>(bwd_dkv_kernel<FM_SOFTMAX>),
                          reinterpret_cast<const void*>(bwd_dkv_kernel<FM_RELU>),
-                         reinterpret_cast<const void*>(bwd_dkv_kernel<FM_IDENTITY>),
                          reinterpret_cast<const void*>(bwd_dkv_kernel<FM_SOFTMAX64>)};
     bool ok = true;
     for (const void* f : fns) ok &= hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS_BYTES) == hipSuccess;
@@ -974,7 +962,6 @@ void fast_bwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
   const dim3 kgrid(a.ntile * dm.Hkv * dm.B);
   switch (fm) {
     case FM_RELU: bwd_dkv_kernel<FM_RELU><<<kgrid, 512, DKV_LDS_BYTES, st>>>(a); break;
-    case FM_IDENTITY: bwd_dkv_kernel<FM_IDENTITY><<<kgrid, 512, DKV_LDS_BYTES, st>>>(a); break;
     case FM_SOFTMAX64: bwd_dkv_kernel<FM_SOFTMAX64><<<kgrid, 512, DKV_LDS_BYTES, st>>>(a); break;
     default: bwd_dkv_kernel<FM_SOFTMAX><<<kgrid, 512, DKV_LDS_BYTES, st>>>(a); break;
   }

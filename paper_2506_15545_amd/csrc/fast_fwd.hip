@@ -33,7 +33,6 @@ struct FastFwdArgs {
   const uint16_t *q_tail, *k_tail, *v_tail;
   uint16_t* o_tail;
   int Tcq, Tck, Tfull;
-  uint16_t* xr_lo_out;  // low-order part of the saved x_r (identity feature map only, else null)
   float *lse_out, *rs_out, *rr_out;
   const uint16_t* states;  // [B,Hkv,nstf,128 (value d),128 (feature f)] bf16: S^T at key position base+128*i
   int B, T, Hq, Hkv, G, W, gap, nstf, ntile;  // W: window rounded up to 64; true window = W - gap
@@ -400,13 +399,6 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
       for (int i = 0; i < 16; ++i) vals[dt][i] = xr[dt][i];
     // (a tile without residual keys has x_r = 0, which backward knows from the tile's position: not stored)
     if (has_lin) store_tile_transposed(smem, vals, a.xr_out + qtile_off, qstride, w, lane);
-    if (has_lin && FM == FM_IDENTITY && a.xr_lo_out) {  // what the bf16 value above leaves of x_r, as a second bf16 tensor
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) vals[dt][i] = xr[dt][i] - (float)(__bf16)xr[dt][i];
-      store_tile_transposed(smem, vals, a.xr_lo_out + qtile_off, qstride, w, lane);
-    }
     if (h == 0) {
       a.lse_out[stat_off] = lse_val;
       a.rs_out[stat_off] = rs_val;
@@ -463,7 +455,6 @@ void fast_fwd(const LayerDims& dm, const void* q, const void* k, const void* v, 
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
   a.gs = gs; a.gr = gr;
   a.o = (uint16_t*)o; a.xs_out = (uint16_t*)sv.xs; a.xr_out = (uint16_t*)sv.xr;
-  a.xr_lo_out = (uint16_t*)sv.xr_lo;
   a.lse_out = sv.lse; a.rs_out = sv.rs; a.rr_out = sv.rr;
   a.states = (const uint16_t*)states;
   a.B = dm.B; a.T = dm.T; a.Hq = dm.Hq; a.Hkv = dm.Hkv; a.G = dm.G; a.W = pl.W; a.gap = pl.gap; a.nstf = pl.nstf;

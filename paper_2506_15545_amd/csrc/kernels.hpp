@@ -42,10 +42,6 @@ struct SavedPtrs {
   float* rr;
   void* states;  // null on the general path
   bool f32;      // x^s, x^r are stored as fp32 whatever the tensor dtype
-  void* xr_lo;   // matrix-core path with the identity feature map only (else null): x^r - bf16(x^r), itself rounded
-                 // to bf16, so that backward reads x^r to 16 significant bits.  With features of size ~1 the first
-                 // rows past the window (state of rank 1, 2, ...) turn the backward through the second RMS norm into
-                 // a cancellation that a bf16 x^r alone resolves to only ~10 % of the gradient's RMS
   int state_stride;  // `states` holds every chunk state (0 or 1) or states 0, m, 2m, ... only (m = 2, 4): the
                      // forward then works on the full set in its workspace and backward rebuilds the states in
                      // between from the stored ones (Sec. 3.2: store every m-th state, recompute the others)

@@ -10,8 +10,7 @@ Rounding points (everything else is carried in fp32 by the kernels, float64 here
             phi(q), phi(k) (operands of every linear-branch product); the masked intra-chunk products
             C = phi(q) phi(k)^T (operand of C V); the chunk states (fp32 prefix sum, stored as bf16 operands,
             one per 128 keys, first state at key (W_r mod 128), W_r = window rounded up to 64);
-            the saved branch outputs x^s, x^r (identity feature map: x^r as a pair of bf16 numbers, i.e. to 16
-            significant bits); the output o (one rounding of the fp32 sum).
+            the saved branch outputs x^s, x^r; the output o (one rounding of the fp32 sum).
   backward  dx^s, dx^r (results of the RMS-norm backward, computed from the saved bf16 x^s, x^r);
             delta = <bf16(dx^s), saved x^s>;  dS = P (dP - delta) scale;  P again as operand of dV;
             dC = (dx^r V^T) masked; C again as operand of dV; the reverse-time states
@@ -108,8 +107,6 @@ def model_fwd_bwd(q, k, v, dO, W, scale=1.0, eps=1e-6, gamma_swa=None, gamma_rla
                 r_r = 1.0 / np.sqrt(np.mean(x_r * x_r, axis=1) + eps)
                 out["o"][b, :, h] = r_out(gs[h] * x_s * r_s[:, None] + gr[h] * x_r * r_r[:, None])
                 xs_sv = r_sv(x_s); xr_sv = r_sv(x_r)
-                if feature_map == "identity":   # x^r is saved as a bf16 pair (value + what the rounding left)
-                    xr_sv = xr_sv + r_sv(x_r - xr_sv)
                 out["xs"][b, :, h] = xs_sv; out["xr"][b, :, h] = xr_sv
                 if not with_bwd:
                     continue
