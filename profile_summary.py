@@ -70,6 +70,7 @@ def stats(d, out, command):
             rows[short_name(r["Name"])] = r
     with open(out, "w") as fo:
         fo.write(f"command: {command}\n")
+        fo.write(f"kernel sources (sha256 of csrc/*.hip, *.hpp): {kernel_sources_digest()}\n")
         fo.write("source: rocprofv3 kernel_stats.csv (durations in microseconds)\n\n")
         fo.write(f"{'kernel':34s} {'calls':>7s} {'avg_us':>10s} {'min_us':>10s} {'max_us':>10s} {'share_%':>8s}\n")
         for n, r in rows.items():
