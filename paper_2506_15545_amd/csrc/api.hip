@@ -115,14 +115,11 @@ rattn_status make_layout(const rattn_params* p, Layout* L) {
   L->esize = p->dtype == RATTN_F32 ? 4 : 2;
 
   // What the matrix-core kernels would see: the sequence length rounded up to whole 128-row tiles (ragged lengths from
-  // PAD_MIN_T on) and a head size of 64 widened to 128, both through zero-padded copies in the workspace
+  // PAD_MIN_T on: tail buffers) and a head size of 64 widened to 128 (zero-padded copies in the workspace)
   dm.Dv = dm.D;
   L->dmf = dm;
   const bool ragged = dm.T % 128 != 0;
-  // (the identity feature map at head size 64 stays on the general kernels: with bf16 operands its backward leaves
-  // single dq elements off by a third of the gradient's RMS on the first rows past a short window - the rank-deficient
-  // state again, with half as many features to average over - and the CPU model of the roundings shows the same)
-  L->pad_d = p->dtype == RATTN_BF16 && dm.D == 64 && (!ragged || dm.T >= PAD_MIN_T) && dm.phi != rattn::PHI_IDENTITY;
+  L->pad_d = p->dtype == RATTN_BF16 && dm.D == 64 && (!ragged || dm.T >= PAD_MIN_T);
   L->pad = p->dtype == RATTN_BF16 && ((dm.D == 128 && ragged && dm.T >= PAD_MIN_T) || L->pad_d);
   if (L->pad) L->dmf.T = (dm.T + 127) / 128 * 128;
   if (L->pad_d) L->dmf.D = 128;

@@ -102,8 +102,8 @@ def test_layer_f32(fm, B, T, Hq, Hkv, D, W, chunk):
                                               (2, 100, 2, 1, 64, 20), (1, 90, 2, 2, 128, 30)])
 def test_layer_bf16(fm, B, T, Hq, Hkv, D, W):
     # from one 128-row tile on, the matrix-core kernels (ragged lengths, head size 64 included); shorter sequences on
-    # the general kernels (identity map: matrix cores for forward-only calls, and not at head size 64)
-    layer_case(fm, B, T, Hq, Hkv, D, W, "bf16", 950 + T, mfma=(T >= 128 and not (fm == "identity" and D == 64)))
+    # the general kernels (identity map: matrix cores for forward-only calls)
+    layer_case(fm, B, T, Hq, Hkv, D, W, "bf16", 950 + T, mfma=(T >= 128))
 
 
 @pytest.mark.parametrize("B,T,Hq,Hkv,W", [
