@@ -174,20 +174,6 @@ __device__ __forceinline__ void sweep_step(const unsigned char* smem, const Lane
   s_cur = s_next;
 }
 
-// 8-byte stores straight from accumulator layout (used where LDS still holds live tiles)
-__device__ __forceinline__ void store_tile_direct(const f32x16_t (&acc)[4], uint16_t* dst, size_t row_stride, int w,
-                                                  int lane) {
-  const int r32 = lane & 31, h = lane >> 5;
-  uint16_t* rowp = dst + (size_t)(32 * w + r32) * row_stride + 4 * h;
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int i4 = 0; i4 < 4; ++i4) {
-      f32x4_t f = {acc[dt][4 * i4], acc[dt][4 * i4 + 1], acc[dt][4 * i4 + 2], acc[dt][4 * i4 + 3]};
-      *reinterpret_cast<bf16x4_t*>(rowp + 32 * dt + 8 * i4) = __builtin_convertvector(f, bf16x4_t);
-    }
-}
-
 // GAP: the window is not a multiple of 64 (a.gap > 0); the aligned case compiles without the extra key tile.
 // FM: feature map of the linear branch (FM_* in mfma.hpp).
 template <bool GAP, int FM>
@@ -196,7 +182,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
   const int lane = lane_id(), w = wave_id();
   const int r32 = lane & 31, h = lane >> 5;
   const LaneOff lo = make_lane_off(lane);
-  const int T = a.T, W = a.W, Hq = a.Hq, Hkv = a.Hkv, G = a.G;
+  const int W = a.W, Hq = a.Hq, Hkv = a.Hkv, G = a.G;
 
   // work id: consecutive ids share a KV head (its G query heads, then the next query tile); each XCD
   // (blockIdx % 8) gets one contiguous range of ids so K/V tiles are reused out of its own L2
@@ -296,9 +282,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
   const int j0 = t0 - W;
   const bool has_lin = j0 > -128 || (GAP && j0 == -128);
   if (a.xs_out) {
-    if (has_lin) {
-      store_tile_direct(oacc, a.xs_out + qtile_off, qstride, w, lane);
-    } else {
+    if (!has_lin) {   // (with a linear branch LDS still holds the tiles that branch works on: x_s is stored after it)
       float vals[4][16];
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt)
@@ -398,7 +382,16 @@ __global__ __launch_bounds__(256, 2) void fwd_fused_kernel(FastFwdArgs a) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) vals[dt][i] = xr[dt][i];
     // (a tile without residual keys has x_r = 0, which backward knows from the tile's position: not stored)
-    if (has_lin) store_tile_transposed(smem, vals, a.xr_out + qtile_off, qstride, w, lane);
+    if (has_lin) {
+      store_tile_transposed(smem, vals, a.xr_out + qtile_off, qstride, w, lane);
+      // x_s = (x_s r_s) / r_s: the accumulators hold the normalised rows by now
+      const float inv_rs = 1.f / rs_val;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) vals[dt][i] = oacc[dt][i] * inv_rs;
+      store_tile_transposed(smem, vals, a.xs_out + qtile_off, qstride, w, lane);
+    }
     if (h == 0) {
       a.lse_out[stat_off] = lse_val;
       a.rs_out[stat_off] = rs_val;
