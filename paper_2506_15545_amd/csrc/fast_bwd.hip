@@ -14,6 +14,7 @@
 #include "common.hpp"
 #include "kernels.hpp"
 #include "mfma.hpp"
+#include <type_traits>
 #include <limits.h>
 
 namespace rattn {
@@ -490,9 +491,11 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
   const int qa = t0 + 32 * w, qb = qa + 31;
   const DmaLane dma_lane = make_dma_lane(lane, kstride);
   const int Wm = W - gap;  // the true window: element masks and sub-tile skipping
-  for (int n = 0; n < ntiles; ++n) {
+  // one key tile; the buffer index is a compile-time constant so that every LDS address of the sub-tile code is a
+  // per-lane register plus an immediate (the loop below is unrolled by two for that)
+  auto tile_step = [&](int n, auto cur_c) {
+    constexpr int cur = decltype(cur_c)::value;
     const int it = ntiles - 1 - n;
-    const int cur = n & 1;
     if (n + 1 < ntiles) {
       const int ktn = kt_lo + 64 * (it - 1);
       tile_load_async_s<4>(k_rows(ktn), kstride, smem + (cur ^ 1) * 16384, w * 4, dma_lane);
@@ -512,6 +515,14 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(FastBwdArgs a) {
     }
     wait_vmem();
     __syncthreads();
+  };
+  {
+    int n = 0;
+    for (; n + 1 < ntiles; n += 2) {
+      tile_step(n, std::integral_constant<int, 0>{});
+      tile_step(n + 1, std::integral_constant<int, 1>{});
+    }
+    if (n < ntiles) tile_step(n, std::integral_constant<int, 0>{});
   }
   float vals[4][16];
 #pragma unroll
