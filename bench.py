@@ -287,8 +287,35 @@ def main():
     rb.rattn_profile_enable(False)
     fwd_ms = timed(fwd_only, args.steps)
     bwd_ms = timed(bwd_only, args.steps)
-
     fl = layer_flops(cfg.B, cfg.T, cfg.Hq, cfg.Hkv, cfg.D, cfg.W)
+    fl_fwd_bwd = (fl["fwd"], fl["bwd"])
+
+    # single calls, one event pair each: median of 100, plain and with 512 MiB written between the calls (more than L2
+    # and the memory-side cache hold, so every call starts from HBM); reported, never part of `value`
+    per_call = None
+    if not args.no_other_workloads:
+        def single_calls(fn, scrub, n=100):
+            pairs = []
+            for _ in range(n):
+                if scrub is not None:
+                    scrub.zero_()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                fn()
+                e1.record()
+                pairs.append((e0, e1))
+            torch.cuda.synchronize()
+            ts = sorted(a.elapsed_time(b) for a, b in pairs)
+            return ts[n // 2], ts[0]
+        scrub = torch.empty(512 * 2 ** 20, dtype=torch.uint8, device="cuda")
+        per_call = {"calls": 100, "scrub_MiB": 512}
+        for name, fn, flops in (("fwd", fwd_only, fl_fwd_bwd[0]), ("bwd", bwd_only, fl_fwd_bwd[1])):
+            med, best = single_calls(fn, None)
+            med_s, _ = single_calls(fn, scrub)
+            per_call[name] = {"median_ms": med, "min_ms": best, "median_ms_scrubbed": med_s,
+                              "tflops_median": flops / (med * 1e-3) / 1e12, "tokens_per_s_median": cfg.B * cfg.T / (med * 1e-3)}
+        del scrub
+
     total = fl["fwd"] + fl["bwd"]
     value = total / (ms_per_step * 1e-3) / 1e12
 
@@ -329,6 +356,7 @@ def main():
                 "frac_mfma_peak": fl["fwd"] / (fwd_ms * 1e-3) / PEAK_BF16_MFMA},
         "bwd": {"ms": bwd_ms, "tflops": fl["bwd"] / (bwd_ms * 1e-3) / 1e12,
                 "frac_mfma_peak": fl["bwd"] / (bwd_ms * 1e-3) / PEAK_BF16_MFMA},
+        "per_call": per_call,
         "kernels": kernels,
         "roofline": roofline,
         "roofline_lowest_kernel": lowest,
