@@ -798,80 +798,87 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(FastBwdArgs a) {
   } else if (issued == 1 && nsteps > 1) {
     issue();  // tile 0 is already visible; tile 1 has all of step 0 to arrive
   }
-  int n = 0;
-  for (int step = 0; step < nsteps; ++step, buf = buf == 2 ? 0 : buf + 1, n = n + 1 == n_qt ? 0 : n + 1) {
-    const unsigned char* qtile = smem + buf * DKV_SLOT;
-    const unsigned char* dxt = qtile + 16384;
-    const float* stat_lds = reinterpret_cast<const float*>(smem + DKV_STAT_OFF + buf * 2048 + (krole ? 1024 : 0));
+  // The loop exists once per role (the role is fixed per wave): with the role a compile-time constant the code between
+  // two barriers has no role branches in it, which the instruction scheduler needs to overlap a chain with its reads.
+  auto tile_loop = [&](auto role) {
+    constexpr bool KR = decltype(role)::value;
+    int n = 0;
+    for (int step = 0; step < nsteps; ++step, buf = buf == 2 ? 0 : buf + 1, n = n + 1 == n_qt ? 0 : n + 1) {
+      const unsigned char* qtile = smem + buf * DKV_SLOT;
+      const unsigned char* dxt = qtile + 16384;
+      const float* stat_lds = reinterpret_cast<const float*>(smem + DKV_STAT_OFF + buf * 2048 + (KR ? 1024 : 0));
 #pragma unroll
-    for (int qs = 0; qs < 2; ++qs) {
-      const int qa = s0 + 64 * n + 32 * qs;
-      const bool need = qa + 31 >= ka && qa <= ka + 31 + Wm - 1;
-      const bool full = qa >= ka + 31 && qa + 31 <= ka + Wm - 1;
-      f32x4_t* px = reinterpret_cast<f32x4_t*>(pex + (w * 2 + qs) * 4096 + lane * 16);  // [i4][lane] x 16 bytes
-      f32x16_t s = {0};
-      float stat[16];
-      if (need) {
-        const unsigned char* rows = krole ? dxt : qtile;
+      for (int qs = 0; qs < 2; ++qs) {
+        const int qa = s0 + 64 * n + 32 * qs;
+        const bool need = qa + 31 >= ka && qa <= ka + 31 + Wm - 1;
+        const bool full = qa >= ka + 31 && qa + 31 <= ka + Wm - 1;
+        f32x4_t* px = reinterpret_cast<f32x4_t*>(pex + (w * 2 + qs) * 4096 + lane * 16);  // [i4][lane] x 16 bytes
+        f32x16_t s = {0};
+        float stat[16];
+        if (need) {
+          const unsigned char* rows = KR ? dxt : qtile;
 #pragma unroll
-        for (int c = 0; c < 8; ++c) s = mfma32(lds_row(rows, lo, 32 * qs, c), xop[c], s);
-        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);  // operand reads run four ahead of the chain
+          for (int c = 0; c < 8; ++c) s = mfma32(lds_row(rows, lo, 32 * qs, c), xop[c], s);
+          __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);  // operand reads run four ahead of the chain
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          const f32x4_t f = *reinterpret_cast<const f32x4_t*>(stat_lds + 32 * qs + 8 * i4 + 4 * h);
-          stat[4 * i4] = f[0]; stat[4 * i4 + 1] = f[1]; stat[4 * i4 + 2] = f[2]; stat[4 * i4 + 3] = f[3];
-        }
-        if (!krole) {
-          if (!full) {
-            const unsigned dist0 = (unsigned)(qa + 4 * h - mykey);  // 0 <= query - key < W, one compare per element
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-              s[i] = (dist0 + (unsigned)(8 * (i >> 2) + (i & 3)) < (unsigned)Wm) ? s[i] : -INFINITY;
+          for (int i = 0; i < 4; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
           }
-#pragma unroll
-          for (int i = 0; i < 16; ++i) s[i] = fast_exp2(__builtin_fmaf(s[i], a.scale_log2, -stat[i] * LOG2E));
-#pragma unroll
-          for (int i4 = 0; i4 < 4; ++i4) px[i4 * 64] = f32x4_t{s[4 * i4], s[4 * i4 + 1], s[4 * i4 + 2], s[4 * i4 + 3]};
-        }
-      }
-      if (qs == 1) {  // this wave's share of tile step+1 has landed (tile step+2 may still be in flight)
-        if (step + 2 < nsteps) {
-          if (w == 0) wait_vmcnt<5>();
-          else wait_vmcnt<4>();
-        } else {
-          wait_vmcnt<0>();
-        }
-      }
-      __syncthreads();  // P of this sub-tile is in LDS
-      if (qs == 0 && step + 2 < nsteps) issue();
-      if (need) {
-        float x[16];
-        if (!krole) {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) x[i] = s[i];
-        } else {
+          __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
 #pragma unroll
           for (int i4 = 0; i4 < 4; ++i4) {
-            const f32x4_t pv = px[i4 * 64];
+            const f32x4_t f = *reinterpret_cast<const f32x4_t*>(stat_lds + 32 * qs + 8 * i4 + 4 * h);
+            stat[4 * i4] = f[0]; stat[4 * i4 + 1] = f[1]; stat[4 * i4 + 2] = f[2]; stat[4 * i4 + 3] = f[3];
+          }
+          if (!KR) {
+            if (!full) {
+              const unsigned dist0 = (unsigned)(qa + 4 * h - mykey);  // 0 <= query - key < W, one compare per element
 #pragma unroll
-            for (int e = 0; e < 4; ++e) x[4 * i4 + e] = pv[e] * (s[4 * i4 + e] - stat[4 * i4 + e]) * a.scale;
+              for (int i = 0; i < 16; ++i)
+                s[i] = (dist0 + (unsigned)(8 * (i >> 2) + (i & 3)) < (unsigned)Wm) ? s[i] : -INFINITY;
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s[i] = fast_exp2(__builtin_fmaf(s[i], a.scale_log2, -stat[i] * LOG2E));
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) px[i4 * 64] = f32x4_t{s[4 * i4], s[4 * i4 + 1], s[4 * i4 + 2], s[4 * i4 + 3]};
           }
         }
-        const bf16x8_t xo[2] = {pack_bf16x8(&x[0]), pack_bf16x8(&x[8])};
-        const unsigned char* cols = krole ? qtile : dxt;
+        if (qs == 1) {  // this wave's share of tile step+1 has landed (tile step+2 may still be in flight)
+          if (step + 2 < nsteps) {
+            if (w == 0) wait_vmcnt<5>();
+            else wait_vmcnt<4>();
+          } else {
+            wait_vmcnt<0>();
+          }
+        }
+        __syncthreads();  // P of this sub-tile is in LDS
+        if (qs == 0 && step + 2 < nsteps) issue();
+        if (need) {
+          float x[16];
+          if (!KR) {
 #pragma unroll
-        for (int mf = 0; mf < 2; ++mf)
+            for (int i = 0; i < 16; ++i) x[i] = s[i];
+          } else {
 #pragma unroll
-          for (int dt = 0; dt < 4; ++dt) acc[dt] = mfma32(lds_trp(cols, lo, 32 * qs + 16 * mf, dt), xo[mf], acc[dt]);
+            for (int i4 = 0; i4 < 4; ++i4) {
+              const f32x4_t pv = px[i4 * 64];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) x[4 * i4 + e] = pv[e] * (s[4 * i4 + e] - stat[4 * i4 + e]) * a.scale;
+            }
+          }
+          const bf16x8_t xo[2] = {pack_bf16x8(&x[0]), pack_bf16x8(&x[8])};
+          const unsigned char* cols = KR ? qtile : dxt;
+#pragma unroll
+          for (int mf = 0; mf < 2; ++mf)
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) acc[dt] = mfma32(lds_trp(cols, lo, 32 * qs + 16 * mf, dt), xo[mf], acc[dt]);
+        }
       }
     }
-  }
+  };
+  if (krole) tile_loop(std::true_type{});
+  else tile_loop(std::false_type{});
   __syncthreads();
   // ---- dV^T (V-role) and dK^T (K-role) leave through LDS as two row-major tiles
   {
